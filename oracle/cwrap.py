@@ -1,0 +1,203 @@
+"""ctypes loader for the C oracle (``mvue_oracle.c``).  TEST INFRASTRUCTURE ONLY.
+
+Only the tests, ``__graft_entry__.smoke()`` and the ``cpu_baseline`` leg of
+``bench.py`` may import this module; the product package never does.
+
+Arrays: f32 tensors are ``numpy.float32``; bf16 tensors are ``numpy.uint16`` bit
+patterns.  The compressed operand is ``vals[T/16, O, 8]`` + ``meta[T/16, O]``
+(uint16), the group format described at the top of the C file.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+import subprocess
+from typing import Optional, Tuple
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "mvue_oracle.c")
+_LIB = os.path.join(_HERE, "libmvue_oracle.so")
+
+DT_F32, DT_BF16 = 0, 1
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc (no contraction, no fast-math, OpenMP over independent blocks)."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-std=c11", "-O2", "-ffp-contract=off", "-fno-fast-math", "-fopenmp",
+               "-fPIC", "-shared", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        _lib = C.CDLL(build())
+        vp, i64, u64, u32, i32, dbl = C.c_void_p, C.c_int64, C.c_uint64, C.c_uint32, C.c_int, C.c_double
+        _lib.oracle_philox4x32_10.argtypes = [vp, vp, vp]
+        _lib.oracle_philox4x32_10.restype = None
+        _lib.oracle_block_u24.argtypes = [u64, u32, u64]
+        _lib.oracle_block_u24.restype = u32
+        _lib.oracle_select_1of2.argtypes = [vp, C.c_float, vp, vp]
+        _lib.oracle_select_1of2.restype = None
+        _lib.oracle_select_2of4.argtypes = [vp, C.c_float, vp, vp, vp]
+        _lib.oracle_select_2of4.restype = None
+        _lib.oracle_enumerate_1of2.argtypes = [vp, vp, vp, vp]
+        _lib.oracle_enumerate_1of2.restype = None
+        _lib.oracle_enumerate_2of4.argtypes = [vp, vp, vp, vp]
+        _lib.oracle_enumerate_2of4.restype = None
+        for f in (_lib.oracle_prune_1of2, _lib.oracle_prune_2of4):
+            f.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64]
+            f.restype = i32
+        _lib.oracle_nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp]
+        _lib.oracle_nm_compress.restype = i64
+        _lib.oracle_nm_decompress.argtypes = [vp, vp, i64, i64, i32, vp, i64]
+        _lib.oracle_nm_decompress.restype = None
+        _lib.oracle_update_gemm.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, dbl, vp, vp, vp]
+        _lib.oracle_update_gemm.restype = None
+        _lib.oracle_update_gemm_entries.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp, i64, vp, vp]
+        _lib.oracle_update_gemm_entries.restype = None
+        _lib.oracle_num_threads.argtypes = []
+        _lib.oracle_num_threads.restype = i32
+    return _lib
+
+
+def _p(a: Optional[np.ndarray]):
+    return None if a is None else a.ctypes.data_as(C.c_void_p)
+
+
+def _dt(a: np.ndarray) -> int:
+    if a.dtype == np.float32:
+        return DT_F32
+    if a.dtype == np.uint16:
+        return DT_BF16
+    raise TypeError(f"oracle tensors are float32 or uint16 (bf16 bits), got {a.dtype}")
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def philox4x32_10(ctr, key) -> np.ndarray:
+    c = np.asarray(ctr, dtype=np.uint32).copy()
+    k = np.asarray(key, dtype=np.uint32).copy()
+    out = np.zeros(4, dtype=np.uint32)
+    lib().oracle_philox4x32_10(_p(c), _p(k), _p(out))
+    return out
+
+
+def block_u24(seed: int, stream_id: int, blk: int) -> int:
+    return int(lib().oracle_block_u24(seed, stream_id, blk))
+
+
+def select_1of2(x, eps: float) -> Tuple[int, float]:
+    xa = np.asarray(x, dtype=np.float32).copy()
+    k = C.c_int(0)
+    v = C.c_float(0)
+    lib().oracle_select_1of2(_p(xa), C.c_float(eps), C.byref(k), C.byref(v))
+    return k.value, v.value
+
+
+def select_2of4(x, eps: float):
+    xa = np.asarray(x, dtype=np.float32).copy()
+    pos = np.zeros(2, dtype=np.int32)
+    val = np.zeros(2, dtype=np.float32)
+    wc = C.c_int(0)
+    lib().oracle_select_2of4(_p(xa), C.c_float(eps), _p(pos), _p(val), C.byref(wc))
+    return (int(pos[0]), int(pos[1])), (float(val[0]), float(val[1])), wc.value
+
+
+def enumerate_1of2(x):
+    xa = np.asarray(x, dtype=np.float32).copy()
+    counts = np.zeros(2, dtype=np.uint64)
+    mean = np.zeros(2)
+    second = np.zeros(2)
+    lib().oracle_enumerate_1of2(_p(xa), _p(counts), _p(mean), _p(second))
+    return counts, mean, second
+
+
+PAIR_ORDER = [(0, 1), (0, 2), (0, 3), (1, 2), (1, 3), (2, 3)]
+
+
+def enumerate_2of4(x):
+    xa = np.asarray(x, dtype=np.float32).copy()
+    counts = np.zeros(6, dtype=np.uint64)
+    mean = np.zeros(4)
+    second = np.zeros(4)
+    lib().oracle_enumerate_2of4(_p(xa), _p(counts), _p(mean), _p(second))
+    return counts, mean, second
+
+
+def _prune(fn, g: np.ndarray, seed: int, stream_id: int, want_dense: bool, logical_O: Optional[int] = None):
+    assert g.ndim == 2
+    T, O = g.shape
+    ld = g.strides[0] // g.itemsize
+    assert g.strides[1] == g.itemsize
+    vals = np.zeros((T // 16, O, 8), dtype=g.dtype)
+    meta = np.zeros((T // 16, O), dtype=np.uint16)
+    dense = np.zeros((T, O), dtype=g.dtype) if want_dense else None
+    rc = fn(_p(g), T, O, ld, _dt(g), seed, stream_id, _p(vals), _p(meta), _p(dense), O)
+    if rc != 0:
+        raise ValueError("oracle: shape not representable (T must be a multiple of 16)")
+    return vals, meta, dense
+
+
+def prune_1of2(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
+    return _prune(lib().oracle_prune_1of2, g, seed, stream_id, want_dense)
+
+
+def prune_2of4(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
+    return _prune(lib().oracle_prune_2of4, g, seed, stream_id, want_dense)
+
+
+def nm_compress(dense: np.ndarray, n: int, m: int):
+    T, O = dense.shape
+    ld = dense.strides[0] // dense.itemsize
+    vals = np.zeros((T // 16, O, 8), dtype=dense.dtype)
+    meta = np.zeros((T // 16, O), dtype=np.uint16)
+    bad = lib().oracle_nm_compress(_p(dense), T, O, ld, _dt(dense), n, m, _p(vals), _p(meta))
+    if bad < 0:
+        raise ValueError("oracle: bad shape or (n, m)")
+    return vals, meta, int(bad)
+
+
+def nm_decompress(vals: np.ndarray, meta: np.ndarray) -> np.ndarray:
+    G, O, _ = vals.shape
+    dense = np.zeros((G * 16, O), dtype=vals.dtype)
+    lib().oracle_nm_decompress(_p(vals), _p(meta), G * 16, O, _dt(vals), _p(dense), O)
+    return dense
+
+
+def update_gemm(vals: np.ndarray, meta: np.ndarray, h: np.ndarray, beta: float = 0.0,
+                dW_in: Optional[np.ndarray] = None):
+    """fp64 dW[O x I] and the absolute-value sum used to scale error bounds."""
+    G, O, _ = vals.shape
+    T, I = h.shape
+    assert T == G * 16 and h.dtype == vals.dtype
+    ldh = h.strides[0] // h.itemsize
+    dW = np.zeros((O, I), dtype=np.float64)
+    absdW = np.zeros((O, I), dtype=np.float64)
+    if dW_in is not None:
+        dW_in = np.ascontiguousarray(dW_in, dtype=np.float32)
+    lib().oracle_update_gemm(_p(vals), _p(meta), _p(h), ldh, T, O, I, _dt(vals), float(beta), _p(dW_in),
+                             _p(dW), _p(absdW))
+    return dW, absdW
+
+
+def update_gemm_entries(vals: np.ndarray, meta: np.ndarray, h: np.ndarray, oi: np.ndarray):
+    G, O, _ = vals.shape
+    T, I = h.shape
+    assert T == G * 16 and h.dtype == vals.dtype
+    ldh = h.strides[0] // h.itemsize
+    oi = np.ascontiguousarray(oi, dtype=np.int64).reshape(-1, 2)
+    out = np.zeros(len(oi))
+    out_abs = np.zeros(len(oi))
+    lib().oracle_update_gemm_entries(_p(vals), _p(meta), _p(h), ldh, T, O, I, _dt(vals), _p(oi), len(oi),
+                                     _p(out), _p(out_abs))
+    return out, out_abs

@@ -1,0 +1,429 @@
+/*
+ * mvue_oracle.c -- CPU ORACLE.  TEST INFRASTRUCTURE ONLY.
+ *
+ * A plain, slow, host-only statement of what the MVUE N:M prune -> compress ->
+ * update-GEMM path computes, written from the paper (arXiv 2203.10991).  It shares
+ * no code with the HIP library and must never be linked, imported or called by
+ * the product path: only the tests, the smoke check and the benchmark's
+ * cpu_baseline leg use it.
+ *
+ *   - MVUE 1:2 estimator ............ Sec. 4.1, eq. (6) ("our_method_main"); sampling by a
+ *                                      uniform threshold: App. B.1, "Part 1".
+ *   - optimal MVUE 2:4 .............. Sec. 4.2 (optimality conditions, eqs. (12),(14)) and
+ *                                      App. A.2 (pair probabilities p_ij, cases 1-3).
+ *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T.
+ *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
+ *                                      fixes Philox4x32-10 (Salmon et al., SC'11) as a pure
+ *                                      function of (seed, stream, block index).
+ *   - compressed format ............. not in the paper ("footprint ... up to x2", abstract);
+ *                                      defined below.
+ *
+ * Decision arithmetic is IEEE binary32 with one rounding per written operation
+ * (compile with -ffp-contract=off, no fast-math): the paper measures in FP32
+ * (Table 2 caption) and the device takes the same decisions in the same
+ * precision.  The GEMM is the plain definition in binary64.
+ *
+ * Compressed N:M operand ("group format").  Tokens (rows of g, the GEMM reduction
+ * axis) are cut into groups of 16 = 4 quads.  For group G and column o
+ *     vals[(G*O + o)*8 + 2*i + s]   s-th kept value (ascending position) of quad i, i=0..3
+ *     meta[ G*O + o ]  (uint16)     bits [4i+1:4i] = position of kept 0, bits [4i+3:4i+2] = kept 1
+ * with position in 0..3 inside the quad and kept0 < kept1.  A 1:2 tensor is stored
+ * the same way: quad i holds pairs 2i and 2i+1, so kept0 in {0,1}, kept1 in {2,3}.
+ *
+ * Parity pins: every function here is pinned by tests/test_oracle_*.py (published
+ * Philox known answers, closed-form probabilities/variances, exhaustive enumeration of
+ * all 2^24 thresholds, brute-force minimum variance, library GEMM).
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+
+enum { DT_F32 = 0, DT_BF16 = 1 };
+
+/* ------------------------------------------------------------------------- */
+/* storage types                                                              */
+/* ------------------------------------------------------------------------- */
+static float bits_to_float(uint32_t b) { float f; memcpy(&f, &b, 4); return f; }
+static uint32_t float_to_bits(float f) { uint32_t b; memcpy(&b, &f, 4); return b; }
+
+/* bf16 -> binary32 is exact: bf16 is the upper half of a binary32. */
+static float bf16_widen(uint16_t h) { return bits_to_float((uint32_t)h << 16); }
+
+/* binary32 -> bf16, round to nearest, ties to even (finite inputs; NaN kept quiet). */
+static uint16_t bf16_round(float f)
+{
+    uint32_t b = float_to_bits(f);
+    if ((b & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((b >> 16) | 0x0040u);
+    uint32_t lower = b & 0xffffu, upper = b >> 16;
+    if (lower > 0x8000u || (lower == 0x8000u && (upper & 1u))) upper += 1u;
+    return (uint16_t)upper;
+}
+
+static float load_elem(const void *p, int dt, int64_t idx)
+{
+    return dt == DT_F32 ? ((const float *)p)[idx] : bf16_widen(((const uint16_t *)p)[idx]);
+}
+/* Store with the storage type's rounding; returns the value as stored. */
+static float store_elem(void *p, int dt, int64_t idx, float v)
+{
+    if (dt == DT_F32) { ((float *)p)[idx] = v; return v; }
+    uint16_t h = bf16_round(v);
+    ((uint16_t *)p)[idx] = h;
+    return bf16_widen(h);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Philox4x32-10 (Salmon, Moraes, Dror, Shaw: "Parallel random numbers: as    */
+/* easy as 1, 2, 3", SC'11).  Ten rounds; the key is bumped between rounds.   */
+/* ------------------------------------------------------------------------- */
+void oracle_philox4x32_10(const uint32_t ctr[4], const uint32_t key[2], uint32_t out[4])
+{
+    uint32_t c0 = ctr[0], c1 = ctr[1], c2 = ctr[2], c3 = ctr[3];
+    uint32_t k0 = key[0], k1 = key[1];
+    for (int round = 0; round < 10; ++round) {
+        if (round > 0) { k0 += 0x9E3779B9u; k1 += 0xBB67AE85u; }
+        uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        uint32_t n1 = (uint32_t)p1;
+        uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        uint32_t n3 = (uint32_t)p0;
+        c0 = n0; c1 = n1; c2 = n2; c3 = n3;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+/*
+ * The uniform of block `blk` (App. B.1: one eps ~ U[0,1) per block).  Four blocks share one
+ * Philox call: counter = (blk/4 low, blk/4 high, stream, 0), key = seed, the block takes
+ * output word blk%4 and its top 24 bits, so eps = u24 / 2^24 is exact in binary32.
+ */
+uint32_t oracle_block_u24(uint64_t seed, uint32_t stream_id, uint64_t blk)
+{
+    uint64_t c = blk >> 2;
+    uint32_t ctr[4] = { (uint32_t)c, (uint32_t)(c >> 32), stream_id, 0u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    return out[blk & 3u] >> 8;
+}
+
+static float u24_to_eps(uint32_t u24) { return (float)u24 * 0x1p-24f; }
+
+/* ------------------------------------------------------------------------- */
+/* MVUE 1:2 (Sec. 4.1, eq. (6)).                                              */
+/*   keep a1 w.p. |a1|/(|a1|+|a2|) and emit sign(a1)(|a1|+|a2|); else a2.      */
+/* Threshold form (App. B.1): keep a1 iff eps < p1, evaluated without the     */
+/* division as  eps*(|a1|+|a2|) < |a1|.  A zero is never preferred to a        */
+/* non-zero partner (p in {0,1}); an all-zero pair keeps position 0.           */
+/* ------------------------------------------------------------------------- */
+void oracle_select_1of2(const float x[2], float eps, int *kept, float *value)
+{
+    float m0 = fabsf(x[0]), m1 = fabsf(x[1]);
+    float s = m0 + m1;
+    float t = eps * s;
+    int k = (m1 == 0.0f || t < m0) ? 0 : 1;
+    *kept = k;
+    *value = copysignf(s, x[k]);
+}
+
+/* ------------------------------------------------------------------------- */
+/* optimal MVUE 2:4 (Sec. 4.2 + App. A.2).                                    */
+/* Magnitudes are ranked a1<=a2<=a3<=a4 (the appendix assumes this order      */
+/* w.l.o.g.); among equal magnitudes the element at the higher position ranks  */
+/* lower.  One eps walks the cumulative pair probabilities in the order        */
+/* p13,p14,p23,p24,p34 (p12 = 0 in every case):                                */
+/*   case 1  a4 <= 2a1+a3 ........ denominators 2(a1+a2+a3+a4)                  */
+/*   case 2  a4 <= a1+a2+a3 ...... same probabilities written over 2(a1+..+a4)  */
+/*   case 3  otherwise ............ a4 kept w.p. 1, partner i w.p. a_i/(a1+a2+a3)*/
+/* Kept magnitudes follow theta_i = a_i/p_i (eq. (8)): with p_i = 2a_i/sum     */
+/* (eq. (12)) that is sum/2; in case 3 (eq. (14)) a4 is unchanged and the      */
+/* partner becomes a1+a2+a3.  Signs are those of the inputs.                   */
+/* ------------------------------------------------------------------------- */
+void oracle_select_2of4(const float x[4], float eps, int pos[2], float value[2], int *which_case)
+{
+    /* rank: insertion sort on (magnitude asc, position desc) */
+    int r[4] = { 3, 2, 1, 0 };           /* already "position descending" for all-equal */
+    float m[4];
+    for (int i = 0; i < 4; ++i) m[i] = fabsf(x[i]);
+    for (int i = 1; i < 4; ++i) {
+        int cur = r[i], j = i - 1;
+        while (j >= 0 && m[r[j]] > m[cur]) { r[j + 1] = r[j]; --j; }
+        r[j + 1] = cur;
+    }
+    const float a1 = m[r[0]], a2 = m[r[1]], a3 = m[r[2]], a4 = m[r[3]];
+    const float s12 = a1 + a2;
+    const float s123 = s12 + a3;
+    const float s = s123 + a4;
+
+    int ra, rb;            /* ranks (0-based) of the kept pair, ra < rb */
+    float va, vb;          /* their output magnitudes */
+    const float two_a1_a3 = 2.0f * a1 + a3;
+    if (a4 <= two_a1_a3 || a4 <= s123) {
+        const int c1case = (a4 <= two_a1_a3);
+        const float t = eps * (2.0f * s);
+        const float c13 = c1case ? (two_a1_a3 - a4) : 0.0f;              /* 2S*p13 */
+        const float c14 = 4.0f * a1;                                     /* 2S*(p13+p14) */
+        const float n23 = c1case ? ((2.0f * a2 + a3) - a4)               /* 2S*p23, case 1 */
+                                 : (2.0f * (s123 - a4));                 /* 2S*p23, case 2 */
+        const float c23 = c14 + n23;
+        const float c24 = 4.0f * s12;                                    /* 2S*(1-p34) */
+        if (t < c13)      { ra = 0; rb = 2; }
+        else if (t < c14) { ra = 0; rb = 3; }
+        else if (t < c23) { ra = 1; rb = 2; }
+        else if (t < c24) { ra = 1; rb = 3; }
+        else              { ra = 2; rb = 3; }
+        va = vb = 0.5f * s;
+        *which_case = c1case ? 1 : 2;
+    } else {
+        const float t = eps * s123;
+        if (t < a1)       ra = 0;
+        else if (t < s12) ra = 1;
+        else              ra = 2;
+        rb = 3;
+        va = s123;
+        vb = a4;
+        *which_case = 3;
+    }
+    int pa = r[ra], pb = r[rb];
+    float fa = copysignf(va, x[pa]), fb = copysignf(vb, x[pb]);
+    if (pa < pb) { pos[0] = pa; pos[1] = pb; value[0] = fa; value[1] = fb; }
+    else         { pos[0] = pb; pos[1] = pa; value[0] = fb; value[1] = fa; }
+}
+
+/* ------------------------------------------------------------------------- */
+/* exhaustive enumeration over all 2^24 thresholds (test support)              */
+/* ------------------------------------------------------------------------- */
+/* counts[k]: how many u24 keep position k; mean[k]: average output at position k (binary64). */
+void oracle_enumerate_1of2(const float x[2], uint64_t counts[2], double mean[2], double second[2])
+{
+    counts[0] = counts[1] = 0; mean[0] = mean[1] = 0; second[0] = second[1] = 0;
+    for (uint32_t u = 0; u < (1u << 24); ++u) {
+        int k; float v;
+        oracle_select_1of2(x, u24_to_eps(u), &k, &v);
+        counts[k] += 1; mean[k] += (double)v; second[k] += (double)v * (double)v;
+    }
+    for (int k = 0; k < 2; ++k) { mean[k] /= 16777216.0; second[k] /= 16777216.0; }
+}
+
+/* pair_counts[6] in the order (0,1),(0,2),(0,3),(1,2),(1,3),(2,3) of *positions*. */
+void oracle_enumerate_2of4(const float x[4], uint64_t pair_counts[6], double mean[4], double second[4])
+{
+    static const int pair_id[4][4] = { {-1,0,1,2}, {0,-1,3,4}, {1,3,-1,5}, {2,4,5,-1} };
+    for (int i = 0; i < 6; ++i) pair_counts[i] = 0;
+    for (int i = 0; i < 4; ++i) { mean[i] = 0; second[i] = 0; }
+    for (uint32_t u = 0; u < (1u << 24); ++u) {
+        int pos[2], wc; float v[2];
+        oracle_select_2of4(x, u24_to_eps(u), pos, v, &wc);
+        pair_counts[pair_id[pos[0]][pos[1]]] += 1;
+        for (int s = 0; s < 2; ++s) { mean[pos[s]] += (double)v[s]; second[pos[s]] += (double)v[s] * (double)v[s]; }
+    }
+    for (int i = 0; i < 4; ++i) { mean[i] /= 16777216.0; second[i] /= 16777216.0; }
+}
+
+/* ------------------------------------------------------------------------- */
+/* tensor-level prune + compress.  g is [T x O], row stride ldg (elements);    */
+/* blocks run along T.  Block index for the random source:                     */
+/*     blk = (t / M) * O + o     (M = 2 or 4; O = logical columns)              */
+/* Outputs in the group format; `dense` (nullable) receives theta(g), [T x O]  */
+/* with row stride ldd, pruned positions +0.                                    */
+/* Returns 0, or -1 for shapes the format cannot hold (T % 16 != 0).            */
+/* ------------------------------------------------------------------------- */
+int oracle_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                      uint64_t seed, uint32_t stream_id,
+                      void *vals, uint16_t *meta, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {          /* quad i = pairs 2i, 2i+1 */
+                for (int s = 0; s < 2; ++s) {
+                    int64_t pr = G * 8 + i * 2 + s;           /* pair row */
+                    int64_t t0 = pr * 2;
+                    float x[2] = { load_elem(g, dt, t0 * ldg + o), load_elem(g, dt, (t0 + 1) * ldg + o) };
+                    uint32_t u = oracle_block_u24(seed, stream_id, (uint64_t)pr * (uint64_t)O + (uint64_t)o);
+                    int k; float v;
+                    oracle_select_1of2(x, u24_to_eps(u), &k, &v);
+                    float stored = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + s, v);
+                    md |= (uint16_t)((2 * s + k) << (4 * i + 2 * s));
+                    if (dense) {
+                        store_elem(dense, dt, (t0 + k) * ldd + o, stored);
+                        store_elem(dense, dt, (t0 + 1 - k) * ldd + o, 0.0f);
+                    }
+                }
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+int oracle_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                      uint64_t seed, uint32_t stream_id,
+                      void *vals, uint16_t *meta, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {
+                int64_t q = G * 4 + i, t0 = q * 4;
+                float x[4];
+                for (int k = 0; k < 4; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                uint32_t u = oracle_block_u24(seed, stream_id, (uint64_t)q * (uint64_t)O + (uint64_t)o);
+                int pos[2], wc; float v[2];
+                oracle_select_2of4(x, u24_to_eps(u), pos, v, &wc);
+                float st0 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 0, v[0]);
+                float st1 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 1, v[1]);
+                md |= (uint16_t)((pos[0] | (pos[1] << 2)) << (4 * i));
+                if (dense) {
+                    for (int k = 0; k < 4; ++k) store_elem(dense, dt, (t0 + k) * ldd + o, 0.0f);
+                    store_elem(dense, dt, (t0 + pos[0]) * ldd + o, st0);
+                    store_elem(dense, dt, (t0 + pos[1]) * ldd + o, st1);
+                }
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* deterministic compression of a tensor that already is n:m sparse along T.   */
+/* Kept positions = non-zero positions, padded with the lowest-index zero       */
+/* positions of the block (pair for 1:2, quad for 2:4); values are copied       */
+/* bit for bit.  Returns the number of blocks holding more than n non-zeros     */
+/* (their output is unspecified), or -1 for a bad shape / (n,m).                */
+/* ------------------------------------------------------------------------- */
+int64_t oracle_nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dt, int n, int m,
+                           void *vals, uint16_t *meta)
+{
+    if (T % 16 || !((n == 1 && m == 2) || (n == 2 && m == 4))) return -1;
+    int64_t bad = 0;
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {
+                int64_t t0 = (G * 4 + i) * 4;
+                int keep[2], nk = 0;
+                if (m == 4) {
+                    int nzc = 0, taken[4] = {0, 0, 0, 0};
+                    for (int k = 0; k < 4; ++k) if (load_elem(dense, dt, (t0 + k) * ld + o) != 0.0f) { taken[k] = 1; ++nzc; }
+                    if (nzc > 2) ++bad;
+                    for (int k = 0; k < 4 && nzc < 2; ++k) if (!taken[k]) { taken[k] = 1; ++nzc; }
+                    for (int k = 0; k < 4 && nk < 2; ++k) if (taken[k]) keep[nk++] = k;
+                } else {
+                    for (int s = 0; s < 2; ++s) {
+                        int z0 = load_elem(dense, dt, (t0 + 2 * s) * ld + o) != 0.0f;
+                        int z1 = load_elem(dense, dt, (t0 + 2 * s + 1) * ld + o) != 0.0f;
+                        if (z0 && z1) ++bad;
+                        keep[nk++] = 2 * s + ((z1 && !z0) ? 1 : 0);
+                    }
+                }
+                for (int s = 0; s < 2; ++s) {
+                    int64_t src = (t0 + keep[s]) * ld + o, dst = (G * O + o) * 8 + 2 * i + s;
+                    if (dt == DT_F32) ((float *)vals)[dst] = ((const float *)dense)[src];
+                    else ((uint16_t *)vals)[dst] = ((const uint16_t *)dense)[src];
+                }
+                md |= (uint16_t)((keep[0] | (keep[1] << 2)) << (4 * i));
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return bad;
+}
+
+/* expand the group format back to a dense [T x O] tensor (row stride ldd), pruned positions +0 */
+void oracle_nm_decompress(const void *vals, const uint16_t *meta, int64_t T, int64_t O, int dt,
+                          void *dense, int64_t ldd)
+{
+    for (int64_t G = 0; G < T / 16; ++G)
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = meta[G * O + o];
+            for (int i = 0; i < 4; ++i) {
+                int64_t t0 = (G * 4 + i) * 4;
+                for (int k = 0; k < 4; ++k) {
+                    int64_t dst = (t0 + k) * ldd + o;
+                    if (dt == DT_F32) ((float *)dense)[dst] = 0.0f; else ((uint16_t *)dense)[dst] = 0;
+                }
+                for (int s = 0; s < 2; ++s) {
+                    int k = (md >> (4 * i + 2 * s)) & 3;
+                    int64_t src = (G * O + o) * 8 + 2 * i + s, dst = (t0 + k) * ldd + o;
+                    if (dt == DT_F32) ((float *)dense)[dst] = ((const float *)vals)[src];
+                    else ((uint16_t *)dense)[dst] = ((const uint16_t *)vals)[src];
+                }
+            }
+        }
+}
+
+/* ------------------------------------------------------------------------- */
+/* update GEMM, eq. (3), oriented [O x I]:                                      */
+/*     dW[o][i] = beta*dW_in[o][i] + sum_t gt[t][o] * h[t][i]                    */
+/* with gt the decompressed operand, every product and sum in binary64, t       */
+/* ascending.  absdW[o][i] = sum_t |gt[t][o]| |h[t][i]| (the scale a rounding     */
+/* error bound is stated against); nullable.                                     */
+/* ------------------------------------------------------------------------- */
+void oracle_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
+                        int64_t T, int64_t O, int64_t I, int dt, double beta, const float *dW_in,
+                        double *dW, double *absdW)
+{
+    #pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t o = 0; o < O; ++o) {
+        double *row = dW + o * I, *arow = absdW ? absdW + o * I : NULL;
+        for (int64_t i = 0; i < I; ++i) {
+            row[i] = (beta != 0.0 && dW_in) ? beta * (double)dW_in[o * I + i] : 0.0;
+            if (arow) arow[i] = 0.0;
+        }
+        for (int64_t t = 0; t < T; ++t) {
+            /* element (t, o) of the decompressed operand */
+            int64_t G = t / 16; int qi = (int)((t % 16) / 4), k = (int)(t % 4);
+            uint16_t md = meta[G * O + o];
+            double gv = 0.0;
+            for (int s = 0; s < 2; ++s)
+                if (((md >> (4 * qi + 2 * s)) & 3) == k)
+                    gv = (double)load_elem(vals, dt, (G * O + o) * 8 + 2 * qi + s);
+            for (int64_t i = 0; i < I; ++i) {
+                double hv = (double)load_elem(h, dt, t * ldh + i);
+                row[i] += gv * hv;
+                if (arow) arow[i] += fabs(gv) * fabs(hv);
+            }
+        }
+    }
+}
+
+/* the same sum for a list of n (o,i) entries: oi = {o0,i0,o1,i1,...} */
+void oracle_update_gemm_entries(const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
+                                int64_t T, int64_t O, int64_t I, int dt,
+                                const int64_t *oi, int64_t n, double *out, double *out_abs)
+{
+    (void)I;
+    #pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t e = 0; e < n; ++e) {
+        int64_t o = oi[2 * e], i = oi[2 * e + 1];
+        double acc = 0.0, aacc = 0.0;
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t G = t / 16; int qi = (int)((t % 16) / 4), k = (int)(t % 4);
+            uint16_t md = meta[G * O + o];
+            double gv = 0.0;
+            for (int s = 0; s < 2; ++s)
+                if (((md >> (4 * qi + 2 * s)) & 3) == k)
+                    gv = (double)load_elem(vals, dt, (G * O + o) * 8 + 2 * qi + s);
+            double hv = (double)load_elem(h, dt, t * ldh + i);
+            acc += gv * hv; aacc += fabs(gv) * fabs(hv);
+        }
+        out[e] = acc;
+        if (out_abs) out_abs[e] = aacc;
+    }
+}
+
+/* threads the parallel loops will use (for the benchmark's report) */
+#ifdef _OPENMP
+#include <omp.h>
+int oracle_num_threads(void) { return omp_get_max_threads(); }
+#else
+int oracle_num_threads(void) { return 1; }
+#endif
