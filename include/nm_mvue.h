@@ -1,0 +1,126 @@
+/*
+ * nm_mvue.h -- C ABI of the MI355X (gfx950) library for minimum-variance unbiased N:M
+ * pruning of neural gradients and the weight-update GEMM that consumes the pruned
+ * operand (arXiv 2203.10991).
+ *
+ * Conventions
+ *   g   [T x O]  neural gradient of a layer, row-major, row stride ldg (elements).  T = tokens
+ *                (batch x positions, or N*H*W of a convolution written as im2col): the
+ *                reduction axis of the update GEMM.  N:M blocks run ALONG T, so a block is M
+ *                consecutive rows of one column.
+ *   h   [T x I]  layer input (the other GEMM operand), row-major, row stride ldh.
+ *   dW  [O x I]  binary32, row-major, row stride lddw:  dW = theta(g)^T h   (eq. (3)).
+ *
+ * Compressed operand ("group format"; the paper fixes none, it only counts the 2x footprint).
+ * Tokens are cut into groups of 16 (= 4 quads = what one lane of a CDNA4 sparse-MFMA
+ * instruction holds of the sparse operand).  For group G = t/16 and column o:
+ *   vals[(G*O + o)*8 + 2*i + s]   s-th kept value (ascending position) of quad i (i = 0..3)
+ *   meta[ G*O + o ]   (uint16)    bits [4i+1:4i]   = position (0..3) of kept value 0 of quad i
+ *                                 bits [4i+3:4i+2] = position of kept value 1, kept0 < kept1
+ * vals has T/2 * O elements of the tensor's dtype, meta T/16 * O uint16; both contiguous.
+ * A 1:2-pruned tensor is stored in the same format (quad i = pairs 2i, 2i+1; kept0 in {0,1},
+ * kept1 in {2,3}), i.e. as the 2:4 pattern it also is.
+ *
+ * All pointers are DEVICE pointers owned by the caller unless stated otherwise.  The library
+ * allocates nothing, frees nothing and never synchronises: every call validates its
+ * arguments on the host, enqueues its kernels on `hip_stream` (a hipStream_t; NULL = the
+ * null stream) and returns.  Outputs must not overlap inputs.
+ *
+ * Errors: every entry point returns an nm_status (0 = ok).  Validation happens before any
+ * device work, so a non-zero return means nothing was enqueued.  nm_last_error() gives a
+ * thread-local message for the last failing call on the calling thread.
+ *
+ * Shape rules (ragged sizes are rejected; zero-padding by the caller is exact because an
+ * all-zero block stays zero):  T % 16 == 0, O % 8 == 0, I % 8 == 0 (GEMM), ldg/ldd/ldh/lddw
+ * such that every row starts 16-byte aligned, base pointers 16-byte aligned.  T, O or I equal
+ * to 0 is accepted and does nothing (dW is still scaled by beta).
+ */
+#ifndef NM_MVUE_H
+#define NM_MVUE_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    NM_OK = 0,
+    NM_ERR_NULL = 1,        /* a required pointer is NULL */
+    NM_ERR_SHAPE = 2,       /* negative / ragged size, leading dimension smaller than the row */
+    NM_ERR_DTYPE = 3,       /* dtype is not an nm_dtype */
+    NM_ERR_ALIGN = 4,       /* pointer or row stride not 16-byte aligned */
+    NM_ERR_ALIAS = 5,       /* an output range overlaps an input range */
+    NM_ERR_WORKSPACE = 6,   /* workspace missing or smaller than nm_update_gemm_workspace() */
+    NM_ERR_UNSUPPORTED = 7, /* valid request this build does not implement */
+    NM_ERR_LAUNCH = 8       /* the HIP runtime refused the launch (message has the HIP error) */
+} nm_status;
+
+typedef enum { NM_F32 = 0, NM_BF16 = 1 } nm_dtype;
+
+/*
+ * MVUE 1:2 prune + compress (Sec. 4.1, eq. (6); threshold sampling of App. B.1).
+ * For every pair (a1, a2) = (g[2r][o], g[2r+1][o]) keeps a1 with probability
+ * |a1|/(|a1|+|a2|) and emits sign(a_kept)*(|a1|+|a2|), rounded to nearest-even in `dtype`.
+ * The uniform of pair row r, column o is Philox4x32-10 with key = seed, counter =
+ * (blk/4 low, blk/4 high, stream_id, 0), word blk%4, top 24 bits, blk = r*O + o; the
+ * result is a pure function of (g, T, O, dtype, seed, stream_id), whatever ldg or the launch.
+ *   vals, meta   out, group format above.
+ *   dense_out    out, optional (NULL = skip): theta(g) as a dense [T x O] tensor, stride ldd,
+ *                pruned positions +0.
+ */
+int mvue_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                    uint64_t seed, uint32_t stream_id,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
+
+/*
+ * MVUE 2:4 prune + compress.  mode 0 = the optimal estimator (Sec. 4.2 conditions, eqs. (12)
+ * and (14); pair probabilities of App. A.2, cases 1-3), one uniform per quad, blk = (t/4)*O + o.
+ * Kept values are a_i/p_i (eq. (8)): (a1+a2+a3+a4)/2 when no element dominates, otherwise the
+ * dominant element unchanged and its partner a1+a2+a3; signs are those of the inputs.
+ * mode 1 (approx-MVUE of Sec. 4.4) returns NM_ERR_UNSUPPORTED in this build.
+ * Arguments as mvue_prune_1of2.
+ */
+int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                    uint64_t seed, uint32_t stream_id, int mode,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
+
+/*
+ * Deterministic compression of a dense [T x O] tensor that already is n:m sparse along T
+ * ((n,m) = (1,2) or (2,4)) into the group format: the "x2 footprint" of the abstract.
+ * Kept positions are the non-zero positions, padded with the lowest-index zero positions of
+ * the block; values are copied bit for bit.  With the dense_out of a prune call as input it
+ * reproduces that call's vals and meta exactly.
+ *   bad_blocks   optional device int32 counter (NULL = do not count): incremented once per
+ *                block that holds more than n non-zeros (such a block keeps its first n).
+ *                The caller zeroes it and reads it after synchronising.
+ */
+int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, int n, int m,
+                void *vals, uint16_t *meta, int32_t *bad_blocks, void *hip_stream);
+
+/*
+ * Update GEMM (eq. (3)):  dW[O x I] = beta*dW + decompress(vals, meta)^T h,  beta in {0, 1},
+ * accumulation in binary32.  NM_BF16 runs on sparse MFMA (4:2 along the reduction axis) and
+ * skips the pruned half of the products; NM_F32 has no sparse matrix instruction on gfx950
+ * and expands the operand on the fly for dense fp32 MFMA.
+ *   workspace    device scratch of at least nm_update_gemm_workspace(T,O,I,dtype) bytes
+ *                (split-K partial sums); may be NULL when that size is 0.
+ */
+int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
+                   float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, int dtype, float beta,
+                   void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/* Bytes of workspace nm_update_gemm needs for this problem (0 when it runs in one pass). */
+size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
+
+/* Message of the last error on this thread ("" if none).  Static storage; do not free. */
+const char *nm_last_error(void);
+
+/* Build identification, e.g. "nm_mvue 0.1 gfx950". */
+const char *nm_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* NM_MVUE_H */

@@ -1,0 +1,8 @@
+"""MVUE N:M pruning of neural gradients + sparse update GEMM for MI355X (gfx950).
+
+``api`` is the thin binding of the C ABI (``include/nm_mvue.h``); ``synth`` draws the seeded
+synthetic workloads; ``build`` compiles the HIP library in-tree.
+"""
+from . import synth  # noqa: F401
+from .api import (NmError, alloc_compressed, load, mvue_prune_1of2, mvue_prune_2of4, nm_compress,  # noqa: F401
+                  nm_update_gemm, nm_update_gemm_workspace)

@@ -1,0 +1,151 @@
+"""Thin Python binding of libnm_mvue (the C ABI declared in include/nm_mvue.h).
+
+Argument marshalling only: torch supplies device memory and the current HIP stream, every
+step of the path runs in the library's kernels.  There is no fallback: if the shared library
+is missing, or a call returns an error status, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Optional, Tuple
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libnm_mvue.so")
+
+NM_F32, NM_BF16 = 0, 1
+_lib = None
+
+
+class NmError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"nm_status {status}: {message}")
+        self.status = status
+
+
+def load():
+    """Load libnm_mvue.so (built in-tree by ``python -m paper_2203_10991_amd.build``)."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(LIB_PATH):
+        raise ImportError(f"{LIB_PATH} is not built: run `python -m paper_2203_10991_amd.build` (needs hipcc)")
+    lib = C.CDLL(LIB_PATH)
+    vp, i64, u64, u32, i32, f32, sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_size_t
+    lib.mvue_prune_1of2.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
+    lib.mvue_prune_2of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, i64, vp]
+    lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
+    lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
+    lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
+    for f in (lib.mvue_prune_1of2, lib.mvue_prune_2of4, lib.nm_compress, lib.nm_update_gemm):
+        f.restype = i32
+    lib.nm_update_gemm_workspace.restype = sz
+    lib.nm_last_error.restype = C.c_char_p
+    lib.nm_version.restype = C.c_char_p
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc != 0:
+        raise NmError(rc, load().nm_last_error().decode())
+
+
+def _dtype_code(t: torch.Tensor) -> int:
+    if t.dtype == torch.float32:
+        return NM_F32
+    if t.dtype == torch.bfloat16:
+        return NM_BF16
+    raise TypeError(f"nm_mvue tensors are float32 or bfloat16, got {t.dtype}")
+
+
+def _stream(t: torch.Tensor) -> int:
+    return torch.cuda.current_stream(t.device).cuda_stream
+
+
+def _rowmajor(t: torch.Tensor, what: str) -> int:
+    if t.dim() != 2 or (t.shape[1] > 1 and t.stride(1) != 1):
+        raise ValueError(f"{what} must be a 2-D tensor with unit column stride")
+    return t.stride(0) if t.shape[0] > 1 else max(t.shape[1], t.stride(0))
+
+
+def _ptr(t: Optional[torch.Tensor]):
+    return None if t is None else t.data_ptr()
+
+
+def alloc_compressed(T: int, O: int, dtype: torch.dtype, device) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Buffers of the group format: vals[T/16, O, 8] and meta[T/16, O] (int16 holds the uint16 words)."""
+    return (torch.empty((T // 16, O, 8), dtype=dtype, device=device),
+            torch.empty((T // 16, O), dtype=torch.int16, device=device))
+
+
+def _prune(which: str, g, seed, stream_id, mode, vals, meta, dense_out, want_dense):
+    lib = load()
+    if not g.is_cuda:
+        raise ValueError("g must live on the GPU")
+    T, O = g.shape
+    ldg = _rowmajor(g, "g")
+    if vals is None or meta is None:
+        vals, meta = alloc_compressed(T - T % 16, O, g.dtype, g.device)
+    if dense_out is None and want_dense:
+        dense_out = torch.empty((T, O), dtype=g.dtype, device=g.device)
+    ldd = _rowmajor(dense_out, "dense_out") if dense_out is not None else 0
+    if which == "1of2":
+        rc = lib.mvue_prune_1of2(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, _ptr(vals), _ptr(meta),
+                                 _ptr(dense_out), ldd, _stream(g))
+    else:
+        rc = lib.mvue_prune_2of4(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, _ptr(vals), _ptr(meta),
+                                 _ptr(dense_out), ldd, _stream(g))
+    _check(rc)
+    return vals, meta, dense_out
+
+
+def mvue_prune_1of2(g: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=None, meta=None, dense_out=None,
+                    want_dense: bool = False):
+    """MVUE 1:2 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
+    return _prune("1of2", g, seed, stream_id, 0, vals, meta, dense_out, want_dense)
+
+
+def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, vals=None, meta=None,
+                    dense_out=None, want_dense: bool = False):
+    """Optimal MVUE 2:4 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
+    return _prune("2of4", g, seed, stream_id, mode, vals, meta, dense_out, want_dense)
+
+
+def nm_compress(dense: torch.Tensor, n: int, m: int, vals=None, meta=None, bad_blocks: Optional[torch.Tensor] = None):
+    """Compress an n:m-sparse dense tensor into the group format.  Returns (vals, meta)."""
+    lib = load()
+    T, O = dense.shape
+    ld = _rowmajor(dense, "dense")
+    if vals is None or meta is None:
+        vals, meta = alloc_compressed(T - T % 16, O, dense.dtype, dense.device)
+    _check(lib.nm_compress(_ptr(dense), T, O, ld, _dtype_code(dense), n, m, _ptr(vals), _ptr(meta),
+                           _ptr(bad_blocks), _stream(dense)))
+    return vals, meta
+
+
+def nm_update_gemm_workspace(T: int, O: int, I: int, dtype: torch.dtype) -> int:
+    return int(load().nm_update_gemm_workspace(T, O, I, NM_F32 if dtype == torch.float32 else NM_BF16))
+
+
+def nm_update_gemm(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: Optional[torch.Tensor] = None,
+                   beta: float = 0.0, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dW[O x I] = beta*dW + decompress(vals, meta)^T h  (binary32 output)."""
+    lib = load()
+    G, O, _ = vals.shape
+    T, I = h.shape
+    if T != G * 16:
+        raise ValueError(f"h has {T} rows, the compressed operand covers {G * 16}")
+    ldh = _rowmajor(h, "h")
+    if dW is None:
+        dW = torch.empty((O, I), dtype=torch.float32, device=h.device)
+    lddw = _rowmajor(dW, "dW")
+    need = nm_update_gemm_workspace(T, O, I, h.dtype)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=h.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.nm_update_gemm(_ptr(vals), _ptr(meta), _ptr(h), ldh, _ptr(dW), lddw, T, O, I, _dtype_code(h),
+                              float(beta), _ptr(workspace), wbytes, _stream(h)))
+    return dW

@@ -1,0 +1,163 @@
+// C ABI of libnm_mvue: host-side argument validation and kernel dispatch.
+// Every check runs before any device work; no allocation, no synchronisation.
+#include <hip/hip_runtime.h>
+#include <stdarg.h>
+#include <stdint.h>
+#include <stdio.h>
+
+#include "../../include/nm_mvue.h"
+#include "nm_internal.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(int code, const char *fmt, ...)
+{
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(g_err, sizeof g_err, fmt, ap);
+    va_end(ap);
+    return code;
+}
+
+inline int64_t esize(int dt) { return dt == NM_F32 ? 4 : 2; }
+inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
+
+struct Range { uintptr_t lo, hi; const char *name; };
+inline Range range_of(const void *p, int64_t bytes, const char *name)
+{
+    return Range{(uintptr_t)p, (uintptr_t)p + (bytes > 0 ? (uintptr_t)bytes : 0), name};
+}
+inline bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi && a.lo != a.hi && b.lo != b.hi; }
+
+// shape / dtype / pointer checks shared by the two prune calls and nm_compress
+int check_tensor(const char *fn, const void *g, int64_t T, int64_t O, int64_t ld, int dt, const char *what)
+{
+    if (dt != NM_F32 && dt != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dt);
+    if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
+    if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16 (pad with zero rows)", fn, (long long)T);
+    if (O % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld is not a multiple of 8 (pad with zero columns)", fn, (long long)O);
+    if (T == 0 || O == 0) return NM_OK;
+    if (!g) return fail(NM_ERR_NULL, "%s: %s is NULL", fn, what);
+    if (ld < O) return fail(NM_ERR_SHAPE, "%s: row stride %lld of %s is smaller than O=%lld", fn, (long long)ld, what, (long long)O);
+    if (!aligned16(g) || (ld * esize(dt)) % 16)
+        return fail(NM_ERR_ALIGN, "%s: %s needs a 16-byte aligned base and row stride", fn, what);
+    return NM_OK;
+}
+
+int check_outputs(const char *fn, const void *in, int64_t T, int64_t O, int64_t ld, int dt, const void *vals,
+                  const void *meta, const void *dense, int64_t ldd)
+{
+    if (T == 0 || O == 0) return NM_OK;
+    if (!vals) return fail(NM_ERR_NULL, "%s: vals is NULL", fn);
+    if (!meta) return fail(NM_ERR_NULL, "%s: meta is NULL", fn);
+    if (!aligned16(vals) || !aligned16(meta)) return fail(NM_ERR_ALIGN, "%s: vals and meta need 16-byte aligned bases", fn);
+    const int64_t es = esize(dt);
+    Range rin = range_of(in, ((T - 1) * ld + O) * es, "input");
+    Range rv = range_of(vals, T / 2 * O * es, "vals");
+    Range rm = range_of(meta, T / 16 * O * 2, "meta");
+    if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm))
+        return fail(NM_ERR_ALIAS, "%s: input, vals and meta must not overlap", fn);
+    if (dense) {
+        if (ldd < O) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld", fn, (long long)ldd, (long long)O);
+        if (!aligned16(dense) || (ldd * es) % 16) return fail(NM_ERR_ALIGN, "%s: dense_out needs a 16-byte aligned base and row stride", fn);
+        Range rd = range_of(dense, ((T - 1) * ldd + O) * es, "dense_out");
+        if (overlap(rd, rin) || overlap(rd, rv) || overlap(rd, rm))
+            return fail(NM_ERR_ALIAS, "%s: dense_out must not overlap g, vals or meta", fn);
+    }
+    return NM_OK;
+}
+
+int launched(const char *fn, hipError_t e)
+{
+    if (e != hipSuccess) return fail(NM_ERR_LAUNCH, "%s: HIP launch failed: %s", fn, hipGetErrorString(e));
+    g_err[0] = 0;
+    return NM_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+int mvue_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream)
+{
+    const char *fn = "mvue_prune_1of2";
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
+    return launched(fn, nm::launch_prune(dtype, 2, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
+                                         (hipStream_t)hip_stream));
+}
+
+int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                    int mode, void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream)
+{
+    const char *fn = "mvue_prune_2of4";
+    if (mode == 1) return fail(NM_ERR_UNSUPPORTED, "%s: mode 1 (approx-MVUE) is not built", fn);
+    if (mode != 0) return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d", fn, mode);
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
+    return launched(fn, nm::launch_prune(dtype, 4, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
+                                         (hipStream_t)hip_stream));
+}
+
+int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, int n, int m, void *vals,
+                uint16_t *meta, int32_t *bad_blocks, void *hip_stream)
+{
+    const char *fn = "nm_compress";
+    if (!((n == 1 && m == 2) || (n == 2 && m == 4)))
+        return fail(NM_ERR_UNSUPPORTED, "%s: (n,m)=(%d,%d); only 1:2 and 2:4 exist in the group format", fn, n, m);
+    if (int rc = check_tensor(fn, dense, T, O, ld, dtype, "dense")) return rc;
+    if (int rc = check_outputs(fn, dense, T, O, ld, dtype, vals, meta, nullptr, 0)) return rc;
+    return launched(fn, nm::launch_compress(dtype, m, dense, T, O, ld, vals, meta, bad_blocks, (hipStream_t)hip_stream));
+}
+
+size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype)
+{
+    if (T < 0 || O < 0 || I < 0 || (dtype != NM_F32 && dtype != NM_BF16)) return 0;
+    return nm::update_gemm_workspace(dtype, T, O, I);
+}
+
+int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW, int64_t lddw,
+                   int64_t T, int64_t O, int64_t I, int dtype, float beta, void *workspace, size_t workspace_bytes,
+                   void *hip_stream)
+{
+    const char *fn = "nm_update_gemm";
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16", fn, (long long)T);
+    if (O % 8 || I % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld and I=%lld must be multiples of 8", fn, (long long)O, (long long)I);
+    if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
+    if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
+    const int64_t es = esize(dtype);
+    if (!dW) return fail(NM_ERR_NULL, "%s: dW is NULL", fn);
+    if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
+    if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
+    Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    if (T > 0) {
+        if (!vals || !meta || !h) return fail(NM_ERR_NULL, "%s: vals, meta and h must not be NULL", fn);
+        if (ldh < I) return fail(NM_ERR_SHAPE, "%s: ldh=%lld is smaller than I=%lld", fn, (long long)ldh, (long long)I);
+        if (!aligned16(vals) || !aligned16(meta) || !aligned16(h) || (ldh * es) % 16)
+            return fail(NM_ERR_ALIGN, "%s: vals, meta, h need 16-byte aligned bases (and h a 16-byte row stride)", fn);
+        Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
+        Range rh = range_of(h, ((T - 1) * ldh + I) * es, "h");
+        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rh)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+    }
+    const size_t need = nm::update_gemm_workspace(dtype, T, O, I);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
+        Range rw = range_of(workspace, (int64_t)need, "workspace");
+        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+    }
+    return launched(fn, nm::launch_update_gemm(dtype, vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace,
+                                               workspace_bytes, (hipStream_t)hip_stream));
+}
+
+const char *nm_last_error(void) { return g_err; }
+
+const char *nm_version(void) { return "nm_mvue 0.1 gfx950"; }
+
+}  // extern "C"

@@ -1,0 +1,23 @@
+// Internal declarations shared by the translation units of libnm_mvue (not part of the ABI).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#define NM_DT_F32 0
+#define NM_DT_BF16 1
+
+namespace nm {
+
+hipError_t launch_prune(int dt, int m, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+                        uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st);
+
+hipError_t launch_compress(int dt, int m, const void *d, int64_t T, int64_t O, int64_t ld, void *vals,
+                           uint16_t *meta, int32_t *bad, hipStream_t st);
+
+// dW = beta*dW + decompress(vals, meta)^T h
+hipError_t launch_update_gemm(int dt, const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
+                              float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, float beta,
+                              void *workspace, size_t workspace_bytes, hipStream_t st);
+size_t update_gemm_workspace(int dt, int64_t T, int64_t O, int64_t I);
+
+}  // namespace nm

@@ -1,0 +1,420 @@
+// Fused MVUE prune + compress kernels for gfx950 (wave64).
+//
+// One thread owns one 16-token group of VEC columns (VEC = one 16-byte load: 8 bf16 or
+// 4 fp32 columns).  Blocks (pairs / quads) run along the token axis, i.e. down the rows of
+// the thread's own column, so no cross-lane exchange is needed: 16 coalesced 16-byte row
+// loads in, 128 contiguous bytes of kept values + VEC 16-bit index words out.
+//
+// The decision arithmetic is binary32 with one rounding per operation (compiled with
+// -ffp-contract=off) so that masks are reproducible bit for bit from (g, seed, stream).
+//
+//   MVUE 1:2 ........ Sec. 4.1, eq. (6); threshold sampling as in App. B.1
+//   optimal 2:4 ..... Sec. 4.2 (eqs. (8), (12), (14)) and App. A.2 (cases 1-3)
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "nm_internal.h"
+
+namespace nm {
+
+// ------------------------------------------------------------------------------------
+// Philox4x32-10 (Salmon et al., SC'11).  Key words are wave-uniform (scalar registers).
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
+}
+
+__device__ __forceinline__ float word_to_eps(uint32_t word)
+{
+    return (float)(word >> 8) * 0x1p-24f;      // 24-bit uniform in [0,1), exact
+}
+
+// ------------------------------------------------------------------------------------
+// element access inside a 16-byte row vector
+// ------------------------------------------------------------------------------------
+template <int DT> struct Row;
+template <> struct Row<NM_DT_F32> {
+    static constexpr int VEC = 4;
+    static __device__ __forceinline__ float get(const uint4 &v, int c)
+    {
+        const uint32_t w = c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w;
+        return __uint_as_float(w);
+    }
+};
+template <> struct Row<NM_DT_BF16> {
+    static constexpr int VEC = 8;
+    static __device__ __forceinline__ float get(const uint4 &v, int c)
+    {
+        const uint32_t w = (c >> 1) == 0 ? v.x : (c >> 1) == 1 ? v.y : (c >> 1) == 2 ? v.z : v.w;
+        return __uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
+    }
+};
+
+// binary32 -> bf16 bits, round to nearest even (finite inputs)
+__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
+{
+    const uint32_t b = __float_as_uint(f);
+    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
+}
+
+// ------------------------------------------------------------------------------------
+// MVUE 1:2 on one pair: returns kept position (0/1) and the kept value (unrounded).
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void select_1of2(float x0, float x1, uint32_t word, uint32_t &kept, float &value)
+{
+    const float m0 = fabsf(x0), m1 = fabsf(x1);
+    const float s = m0 + m1;
+    const float t = word_to_eps(word) * s;
+    const bool keep0 = (m1 == 0.0f) | (t < m0);       // a zero never wins against a non-zero
+    kept = keep0 ? 0u : 1u;
+    value = copysignf(s, keep0 ? x0 : x1);
+}
+
+// ------------------------------------------------------------------------------------
+// optimal MVUE 2:4 on one quad.
+// Ranking key: magnitude bits, then a reversed one-hot position code (position 0 -> 8 ...
+// position 3 -> 1) so that among equal magnitudes the higher position ranks lower, then the
+// sign (never decisive: codes are unique).  bf16 magnitudes leave the low 16 bits free, so
+// the key fits 32 bits; fp32 uses a 64-bit key.
+// ------------------------------------------------------------------------------------
+template <int DT> struct Key;
+template <> struct Key<NM_DT_BF16> {
+    typedef uint32_t type;
+    static __device__ __forceinline__ type make(float x, int pos)
+    {
+        const uint32_t b = __float_as_uint(x);
+        return (b << 1) | ((8u >> pos) << 1) | (b >> 31);      // magnitude in [31:17], code [4:1], sign [0]
+    }
+    static __device__ __forceinline__ float mag(type k) { return __uint_as_float((k >> 1) & 0x7fff0000u); }
+    static __device__ __forceinline__ uint32_t tag(type k) { return k & 0x1fu; }
+};
+template <> struct Key<NM_DT_F32> {
+    typedef uint64_t type;
+    static __device__ __forceinline__ type make(float x, int pos)
+    {
+        const uint32_t b = __float_as_uint(x);
+        return ((uint64_t)(b & 0x7fffffffu) << 8) | ((8u >> pos) << 1) | (b >> 31);
+    }
+    static __device__ __forceinline__ float mag(type k) { return __uint_as_float((uint32_t)(k >> 8)); }
+    static __device__ __forceinline__ uint32_t tag(type k) { return (uint32_t)k & 0x1fu; }
+};
+
+template <typename K> __device__ __forceinline__ void order2(K &a, K &b)
+{
+    const K lo = a < b ? a : b;
+    const K hi = a < b ? b : a;
+    a = lo;
+    b = hi;
+}
+
+// out0/out1: kept values in ascending position; nib = pos0 | pos1 << 2
+template <int DT>
+__device__ __forceinline__ void select_2of4(float x0, float x1, float x2, float x3, uint32_t word,
+                                            float &out0, float &out1, uint32_t &nib)
+{
+    typedef Key<DT> KT;
+    typename KT::type k1 = KT::make(x0, 0), k2 = KT::make(x1, 1), k3 = KT::make(x2, 2), k4 = KT::make(x3, 3);
+    order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
+    const float a1 = KT::mag(k1), a2 = KT::mag(k2), a3 = KT::mag(k3), a4 = KT::mag(k4);
+    const uint32_t t1 = KT::tag(k1), t2 = KT::tag(k2), t3 = KT::tag(k3), t4 = KT::tag(k4);
+
+    const float s12 = a1 + a2;
+    const float s123 = s12 + a3;
+    const float s = s123 + a4;
+    const float u = 2.0f * a1 + a3;
+    const bool case1 = a4 <= u;
+    const bool case12 = case1 | (a4 <= s123);              // else case 3: a4 dominates
+
+    // cumulative thresholds on t = eps * D.  Cases 1-2: D = 2(a1+a2+a3+a4), walk p13,p14,p23,p24,p34.
+    // Case 3: D = a1+a2+a3, partner of a4 is a1 / a2 / a3; expressed in the same chain.
+    const float eps = word_to_eps(word);
+    const float t = eps * (case12 ? 2.0f * s : s123);
+    const float c13 = case1 ? (u - a4) : 0.0f;
+    const float c14 = case12 ? 4.0f * a1 : a1;
+    const float n23 = case1 ? ((2.0f * a2 + a3) - a4) : (2.0f * (s123 - a4));
+    const float c23 = case12 ? (c14 + n23) : a1;
+    const float c24 = case12 ? 4.0f * s12 : s12;
+
+    uint32_t ta, tb;
+    if (t < c13)      { ta = t1; tb = t3; }
+    else if (t < c14) { ta = t1; tb = t4; }
+    else if (t < c23) { ta = t2; tb = t3; }
+    else if (t < c24) { ta = t2; tb = t4; }
+    else              { ta = t3; tb = t4; }
+    if (!case12) tb = t4;
+
+    const float ma = case12 ? 0.5f * s : s123;              // a_i / p_i
+    const float mb = case12 ? 0.5f * s : a4;
+    const float va = __uint_as_float(__float_as_uint(ma) | (ta << 31));
+    const float vb = __uint_as_float(__float_as_uint(mb) | (tb << 31));
+    const uint32_t pa = (uint32_t)__clz((int)ta) - 27u;      // code 8,4,2,1 (<<1) -> position 0..3
+    const uint32_t pb = (uint32_t)__clz((int)tb) - 27u;
+    const bool swap = pa > pb;
+    out0 = swap ? vb : va;
+    out1 = swap ? va : vb;
+    nib = swap ? (pb | (pa << 2)) : (pa | (pb << 2));
+}
+
+// ------------------------------------------------------------------------------------
+// the fused kernel
+// ------------------------------------------------------------------------------------
+template <int DT, int M>     // M = 2: MVUE 1:2, M = 4: optimal MVUE 2:4
+__global__ __launch_bounds__(256) void prune_compress_kernel(
+    const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
+    uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals_, uint16_t *__restrict__ meta_, void *__restrict__ dense_, int64_t ldd)
+{
+    constexpr int VEC = Row<DT>::VEC;
+    constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
+    const int64_t ncg = O / VEC;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_groups * ncg) return;
+    const int64_t G = n / ncg;
+    const int64_t col0 = (n - G * ncg) * VEC;
+
+    const char *gp = (const char *)g_ + ((G * 16) * ldg + col0) * ESZ;
+    uint4 rows[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
+
+    float kept[VEC][8];          // kept values per column, slot order of the group format
+    uint32_t md[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) md[c] = 0;
+
+    constexpr int BLOCK_ROWS = 16 / M;       // pair rows (8) or quad rows (4) in the group
+#pragma unroll
+    for (int b = 0; b < BLOCK_ROWS; ++b) {
+        const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
+        uint32_t words[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            const uint64_t ctr = (blk0 >> 2) + q;
+            uint32_t w4[4];
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 0u, key0, key1, w4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
+        }
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            if (M == 2) {
+                uint32_t k; float v;
+                select_1of2(Row<DT>::get(rows[2 * b], c), Row<DT>::get(rows[2 * b + 1], c), words[c], k, v);
+                kept[c][b] = v;
+                md[c] |= ((uint32_t)((b & 1) << 1) | k) << (2 * b);
+            } else {
+                float v0, v1; uint32_t nib;
+                select_2of4<DT>(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
+                                Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c),
+                                words[c], v0, v1, nib);
+                kept[c][2 * b] = v0;
+                kept[c][2 * b + 1] = v1;
+                md[c] |= nib << (4 * b);
+            }
+        }
+    }
+
+    // ---- kept values: 8 per column, VEC columns contiguous = 128 bytes per thread
+    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;
+    if (DT == NM_DT_F32) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            ((float4 *)vp)[2 * c] = make_float4(kept[c][0], kept[c][1], kept[c][2], kept[c][3]);
+            ((float4 *)vp)[2 * c + 1] = make_float4(kept[c][4], kept[c][5], kept[c][6], kept[c][7]);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            uint4 o;
+            o.x = bf16_bits_rne(kept[c][0]) | (bf16_bits_rne(kept[c][1]) << 16);
+            o.y = bf16_bits_rne(kept[c][2]) | (bf16_bits_rne(kept[c][3]) << 16);
+            o.z = bf16_bits_rne(kept[c][4]) | (bf16_bits_rne(kept[c][5]) << 16);
+            o.w = bf16_bits_rne(kept[c][6]) | (bf16_bits_rne(kept[c][7]) << 16);
+            ((uint4 *)vp)[c] = o;
+        }
+    }
+    // ---- index words
+    uint16_t *mp = meta_ + (G * O + col0);
+    if (VEC == 8) {
+        uint4 o;
+        o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
+        o.z = md[4 % VEC] | (md[5 % VEC] << 16); o.w = md[6 % VEC] | (md[7 % VEC] << 16);
+        *(uint4 *)mp = o;
+    } else {
+        uint2 o;
+        o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
+        *(uint2 *)mp = o;
+    }
+
+    // ---- optional dense theta(g)
+    if (dense_) {
+        char *dp = (char *)dense_ + ((G * 16) * ldd + col0) * ESZ;
+#pragma unroll
+        for (int r = 0; r < 16; ++r) {
+            const int q = r >> 2, p = r & 3;             // quad and position inside it
+            uint32_t w[VEC];
+#pragma unroll
+            for (int c = 0; c < VEC; ++c) {
+                const uint32_t nib = (md[c] >> (4 * q)) & 0xfu;
+                const float v = (nib & 3u) == (uint32_t)p ? kept[c][2 * q]
+                              : (nib >> 2) == (uint32_t)p ? kept[c][2 * q + 1] : 0.0f;
+                w[c] = DT == NM_DT_F32 ? __float_as_uint(v) : bf16_bits_rne(v);
+            }
+            uint4 o;
+            if (DT == NM_DT_F32) { o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3]; }
+            else {
+                o.x = w[0] | (w[1] << 16); o.y = w[2] | (w[3] << 16);
+                o.z = w[4 % VEC] | (w[5 % VEC] << 16); o.w = w[6 % VEC] | (w[7 % VEC] << 16);
+            }
+            *(uint4 *)(dp + (int64_t)r * ldd * ESZ) = o;
+        }
+    }
+}
+
+// ------------------------------------------------------------------------------------
+// nm_compress: dense n:m tensor -> group format.  Same thread tiling as above.
+// ------------------------------------------------------------------------------------
+template <int DT, int M>
+__global__ __launch_bounds__(256) void compress_kernel(
+    const void *__restrict__ d_, int64_t n_groups, int64_t O, int64_t ld,
+    void *__restrict__ vals_, uint16_t *__restrict__ meta_, int32_t *__restrict__ bad)
+{
+    constexpr int VEC = Row<DT>::VEC;
+    constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
+    const int64_t ncg = O / VEC;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_groups * ncg) return;
+    const int64_t G = n / ncg;
+    const int64_t col0 = (n - G * ncg) * VEC;
+    const char *gp = (const char *)d_ + ((G * 16) * ld + col0) * ESZ;
+    uint4 rows[16];
+#pragma unroll
+    for (int r = 0; r < 16; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ld * ESZ);
+
+    float kept[VEC][8];
+    uint32_t md[VEC];
+    int nbad = 0;
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) {
+        md[c] = 0;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            float x[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) x[p] = Row<DT>::get(rows[4 * i + p], c);
+            uint32_t p0, p1;
+            if (M == 4) {
+                const uint32_t nz = (x[0] != 0.0f ? 1u : 0u) | (x[1] != 0.0f ? 2u : 0u) |
+                                    (x[2] != 0.0f ? 4u : 0u) | (x[3] != 0.0f ? 8u : 0u);
+                uint32_t taken = nz;
+                if (__popc(taken) > 2) ++nbad;
+                if (__popc(taken) < 2) taken |= (~taken) & (uint32_t)(-(int)(~taken & 0xfu)) & 0xfu;   // lowest zero
+                if (__popc(taken) < 2) taken |= (~taken) & (uint32_t)(-(int)(~taken & 0xfu)) & 0xfu;
+                p0 = (uint32_t)__ffs((int)taken) - 1u;
+                taken &= taken - 1u;
+                p1 = (uint32_t)__ffs((int)taken) - 1u;
+            } else {
+                const bool n0 = x[0] != 0.0f, n1 = x[1] != 0.0f, n2 = x[2] != 0.0f, n3 = x[3] != 0.0f;
+                nbad += (n0 & n1) + (n2 & n3);
+                p0 = (n1 & !n0) ? 1u : 0u;
+                p1 = (n3 & !n2) ? 3u : 2u;
+            }
+            kept[c][2 * i] = p0 == 0 ? x[0] : p0 == 1 ? x[1] : p0 == 2 ? x[2] : x[3];
+            kept[c][2 * i + 1] = p1 == 0 ? x[0] : p1 == 1 ? x[1] : p1 == 2 ? x[2] : x[3];
+            md[c] |= (p0 | (p1 << 2)) << (4 * i);
+        }
+    }
+    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;
+    if (DT == NM_DT_F32) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            ((float4 *)vp)[2 * c] = make_float4(kept[c][0], kept[c][1], kept[c][2], kept[c][3]);
+            ((float4 *)vp)[2 * c + 1] = make_float4(kept[c][4], kept[c][5], kept[c][6], kept[c][7]);
+        }
+    } else {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {           // values are bf16 already: the upper half is exact
+            uint4 o;
+            o.x = (__float_as_uint(kept[c][0]) >> 16) | (__float_as_uint(kept[c][1]) & 0xffff0000u);
+            o.y = (__float_as_uint(kept[c][2]) >> 16) | (__float_as_uint(kept[c][3]) & 0xffff0000u);
+            o.z = (__float_as_uint(kept[c][4]) >> 16) | (__float_as_uint(kept[c][5]) & 0xffff0000u);
+            o.w = (__float_as_uint(kept[c][6]) >> 16) | (__float_as_uint(kept[c][7]) & 0xffff0000u);
+            ((uint4 *)vp)[c] = o;
+        }
+    }
+    uint16_t *mp = meta_ + (G * O + col0);
+    if (VEC == 8) {
+        uint4 o;
+        o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
+        o.z = md[4 % VEC] | (md[5 % VEC] << 16); o.w = md[6 % VEC] | (md[7 % VEC] << 16);
+        *(uint4 *)mp = o;
+    } else {
+        uint2 o;
+        o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
+        *(uint2 *)mp = o;
+    }
+    if (bad && nbad) atomicAdd(bad, nbad);
+}
+
+// ------------------------------------------------------------------------------------
+// launchers (called from the C ABI after validation)
+// ------------------------------------------------------------------------------------
+template <int DT, int M>
+static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed, uint32_t stream_id,
+                                 void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
+{
+    const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
+    if (threads == 0) return hipSuccess;
+    const int64_t blocks = (threads + 255) / 256;
+    hipLaunchKernelGGL((prune_compress_kernel<DT, M>), dim3((unsigned)blocks), dim3(256), 0, st,
+                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune(int dt, int m, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+                        uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
+{
+    if (dt == NM_DT_F32)
+        return m == 2 ? launch_prune_t<NM_DT_F32, 2>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
+                      : launch_prune_t<NM_DT_F32, 4>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st);
+    return m == 2 ? launch_prune_t<NM_DT_BF16, 2>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
+                  : launch_prune_t<NM_DT_BF16, 4>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st);
+}
+
+template <int DT, int M>
+static hipError_t launch_compress_t(const void *d, int64_t T, int64_t O, int64_t ld, void *vals, uint16_t *meta,
+                                    int32_t *bad, hipStream_t st)
+{
+    const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
+    if (threads == 0) return hipSuccess;
+    hipLaunchKernelGGL((compress_kernel<DT, M>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       d, groups, O, ld, vals, meta, bad);
+    return hipGetLastError();
+}
+
+hipError_t launch_compress(int dt, int m, const void *d, int64_t T, int64_t O, int64_t ld, void *vals,
+                           uint16_t *meta, int32_t *bad, hipStream_t st)
+{
+    if (dt == NM_DT_F32)
+        return m == 2 ? launch_compress_t<NM_DT_F32, 2>(d, T, O, ld, vals, meta, bad, st)
+                      : launch_compress_t<NM_DT_F32, 4>(d, T, O, ld, vals, meta, bad, st);
+    return m == 2 ? launch_compress_t<NM_DT_BF16, 2>(d, T, O, ld, vals, meta, bad, st)
+                  : launch_compress_t<NM_DT_BF16, 4>(d, T, O, ld, vals, meta, bad, st);
+}
+
+}  // namespace nm

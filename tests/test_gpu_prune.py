@@ -1,0 +1,166 @@
+"""GPU parity: fused prune+compress and nm_compress against the CPU oracle, bit for bit,
+through the C ABI (python binding = argument marshalling only)."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2203_10991_amd import synth
+from gpu_util import DEV, first_mismatch, to_dev, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def nm():
+    import paper_2203_10991_amd as p
+    p.load()
+    assert torch.cuda.is_available()
+    return p
+
+
+def _prune_pair(nm, oracle, nmode):
+    return (nm.mvue_prune_1of2, oracle.prune_1of2) if nmode == "1:2" else (nm.mvue_prune_2of4, oracle.prune_2of4)
+
+
+def _bits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def check_case(nm, oracle, g_host, nmode, seed, stream):
+    gpu_fn, cpu_fn = _prune_pair(nm, oracle, nmode)
+    v, m, d = gpu_fn(to_dev(g_host), seed=seed, stream_id=stream, want_dense=True)
+    torch.cuda.synchronize()
+    ov, om, od = cpu_fn(g_host, seed, stream, want_dense=True)
+    hv, hm, hd = to_host(v), to_host(m), to_host(d)
+    assert first_mismatch(hm, om) is None, ("meta", first_mismatch(hm, om))
+    assert first_mismatch(_bits(hv), _bits(ov)) is None, ("vals", first_mismatch(_bits(hv), _bits(ov)))
+    assert first_mismatch(_bits(hd), _bits(od)) is None, ("dense", first_mismatch(_bits(hd), _bits(od)))
+    return v, m, d
+
+
+SHAPES = [(16, 8), (16 * 37, 8 * 29), (16 * 5, 8 * 64 + 8), (16 * 64, 1024)]
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_fused_prune_bit_exact(nm, oracle, dtype, nmode, shape):
+    T, O = shape
+    print(f"case dtype={dtype} nm={nmode} T={T} O={O}", flush=True)
+    w = synth.Workload("t", T, O, 8, dtype, nmode, 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O)
+    v, m, d = check_case(nm, oracle, g, nmode, seed=0x1234567 + (1 << 40), stream=3)
+    # compress(dense theta(g)) reproduces the fused outputs
+    n, mm = (1, 2) if nmode == "1:2" else (2, 4)
+    bad = torch.zeros(1, dtype=torch.int32, device=DEV)
+    v2, m2 = nm.nm_compress(d, n, mm, bad_blocks=bad)
+    torch.cuda.synchronize()
+    assert int(bad.item()) == 0
+    assert torch.equal(m2, m) and torch.equal(v2.view(torch.int16 if dtype == "bf16" else torch.int32),
+                                              v.view(torch.int16 if dtype == "bf16" else torch.int32))
+    # determinism
+    gpu_fn, _ = _prune_pair(nm, oracle, nmode)
+    v3, m3, _ = gpu_fn(to_dev(g), seed=0x1234567 + (1 << 40), stream_id=3)
+    assert torch.equal(m3, m) and torch.equal(v3.view(torch.int16 if dtype == "bf16" else torch.int32),
+                                              v.view(torch.int16 if dtype == "bf16" else torch.int32))
+    # another stream id gives another mask
+    _, m4, _ = gpu_fn(to_dev(g), seed=0x1234567 + (1 << 40), stream_id=4)
+    if T * O >= 1024:
+        assert not torch.equal(m4, m)
+
+
+@pytest.mark.parametrize("nmode", ["1:2", "2:4"])
+def test_row_stride_and_preallocated_outputs(nm, oracle, nmode):
+    T, O = 16 * 9, 8 * 13
+    w = synth.Workload("t", T, O, 8, "bf16", nmode, 0.0, 2.0, 0.2)
+    g = synth.make_g(w, seed=5)
+    big = torch.zeros((T, O + 24), dtype=torch.bfloat16, device=DEV)
+    big[:, :O] = to_dev(g)
+    gpu_fn, cpu_fn = _prune_pair(nm, oracle, nmode)
+    dense_big = torch.full((T, O + 8), 7.0, dtype=torch.bfloat16, device=DEV)
+    v, m, d = gpu_fn(big[:, :O], seed=9, stream_id=1, dense_out=dense_big[:, :O])
+    torch.cuda.synchronize()
+    ov, om, od = cpu_fn(g, 9, 1, want_dense=True)
+    assert np.array_equal(to_host(m), om) and np.array_equal(to_host(v), ov)
+    assert np.array_equal(to_host(dense_big[:, :O]), od)
+    assert bool((dense_big[:, O:] == 7.0).all())                  # nothing written outside the view
+
+
+def _edge_tensor(dtype):
+    """zeros, negative zeros, ties, dominant elements, denormals and huge values in every position"""
+    base = [0.0, -0.0, 1.0, -1.0, 1.0, 2.0, 3.0, 4.0, 1e-3, 1e3, 7.0, 7.0, 0.5, 0.25, 0.125, 9.0,
+            1e-40, 3e-39, 1.2e-38, 2e-38, 1e37, 2e37, 3e37, 1.5e37, 5.0, 0.0, 0.0, -2.0]
+    rng = np.random.default_rng(0)
+    T, O = 64, 256
+    g = rng.choice(np.array(base, dtype=np.float32), size=(T, O))
+    g[:16, :8] = 0.0
+    g[16:32, :8] = np.float32(-0.0)
+    return g if dtype == "f32" else synth.f32_to_bf16_bits(g)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4"])
+def test_edge_values_bit_exact(nm, oracle, dtype, nmode):
+    for seed in range(4):
+        check_case(nm, oracle, _edge_tensor(dtype), nmode, seed, 0)
+
+
+def test_empty_and_error_paths_on_device(nm):
+    g = torch.zeros((0, 64), dtype=torch.bfloat16, device=DEV)
+    v, m, _ = nm.mvue_prune_2of4(g)
+    assert v.shape == (0, 64, 8) and m.shape == (0, 64)
+    with pytest.raises(nm.NmError) as e:
+        nm.mvue_prune_2of4(torch.zeros((24, 64), dtype=torch.bfloat16, device=DEV))
+    assert e.value.status == 2
+    with pytest.raises(nm.NmError) as e:
+        nm.mvue_prune_2of4(torch.zeros((32, 64), dtype=torch.bfloat16, device=DEV), mode=1)
+    assert e.value.status == 7
+
+
+def test_compress_counts_bad_blocks(nm, oracle):
+    rng = np.random.default_rng(3)
+    d = (rng.standard_normal((64, 64)) * (rng.random((64, 64)) < 0.45)).astype(np.float32)
+    for n, m in ((2, 4), (1, 2)):
+        ov, om, obad = oracle.nm_compress(d, n, m)
+        bad = torch.zeros(1, dtype=torch.int32, device=DEV)
+        v, mt = nm.nm_compress(to_dev(d), n, m, bad_blocks=bad)
+        torch.cuda.synchronize()
+        assert int(bad.item()) == obad and obad > 0
+        # blocks that are valid agree bit for bit; over-full blocks keep their first n on both sides
+        assert np.array_equal(to_host(mt), om) and np.array_equal(to_host(v).view(np.uint32), ov.view(np.uint32))
+
+
+def test_unbiased_over_10k_seeds_on_first_256_elements(nm, oracle):
+    """Config 1 recipe (fp32, 1:2): g[0, :256] and their pair partners g[1, :256]; E[theta(g)] = g."""
+    w = synth.WORKLOADS["c1_fp32_1of2"]
+    g = synth.make_g(w, seed=0, rows=(0, 512))[:16, :256].copy()
+    gd = to_dev(g)
+    n = 10000
+    acc = torch.zeros((2, 256), dtype=torch.float64, device=DEV)
+    dense = torch.empty_like(gd)
+    vals, meta = nm.alloc_compressed(16, 256, gd.dtype, DEV)
+    for seed in range(n):
+        nm.mvue_prune_1of2(gd, seed=seed, stream_id=0, vals=vals, meta=meta, dense_out=dense)
+        acc += dense[:2].double()
+        if seed % 500 == 0:                                       # bit-exact against the oracle along the way
+            _, _, od = oracle.prune_1of2(g, seed, 0, want_dense=True)
+            assert np.array_equal(to_host(dense).view(np.uint32), od.view(np.uint32))
+    mean = (acc / n).cpu().numpy()
+    a = np.abs(g[:2].astype(np.float64))
+    var = a[0] * a[1]
+    live = var > 0
+    z = (mean - g[:2])[:, live] / np.sqrt(var[live] / n)
+    assert np.abs(z).max() < 4.5
+    assert abs((z[0] ** 2).sum() - live.sum()) < 5 * np.sqrt(2 * live.sum())
+    assert np.array_equal(mean[:, ~live], g[:2][:, ~live].astype(np.float64))   # zero partner: reproduced exactly
+
+
+@pytest.mark.parametrize("name,T", [("c1_fp32_1of2", None), ("c2_mlp_1of2", 2048), ("c3_conv_2of4", 16384),
+                                    ("c4_vit_qkv_2of4", 1600), ("c4_vit_fc2_1of2", 1600), ("c5_decoder_mlp_2of4", 256)])
+def test_config_recipes_bit_exact(nm, oracle, name, T):
+    w = synth.WORKLOADS[name]
+    if T is not None:
+        w = synth.scaled(w, T=T)
+    print(f"case {w.name} T={w.T} O={w.O}", flush=True)
+    g = synth.make_g(w, seed=0)
+    check_case(nm, oracle, g, w.nm, 0, 0)
