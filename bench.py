@@ -1,0 +1,158 @@
+#!/usr/bin/env python3
+"""Benchmark of the hot path on one MI355X: MVUE 2:4 prune+compress of g, then the sparse
+update GEMM dW = theta(g)^T h, on the large decoder-MLP workload (inputs resident in HBM).
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload NAME] [--no-cpu-baseline]
+
+Prints ONE JSON line.  A step = one pass of the whole path (prune+compress kernel, GEMM kernel)
+over one synthetic batch.  `value` is the job's dense-equivalent GEMM rate over the whole step;
+`roofline` describes the dominant kernel (the GEMM, against the sparse-MFMA peak),
+`roofline_prune` the prune kernel (against HBM), both from HIP events recorded on the launch
+stream around every kernel of the timed region.  `cpu_baseline` times the CPU oracle on a
+bounded slice of the same workload.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
+DENSE_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
+SPARSE_PEAK_TFLOPS = 2.0 * DENSE_BF16_PEAK_TFLOPS   # 4:2 sparse MFMA skips half the products: dense-equivalent peak
+
+
+def read_traffic(workload: str, kernel: str):
+    """HBM bytes per launch measured with rocprofv3 --pmc (FETCH_SIZE / WRITE_SIZE), if a summary is committed."""
+    path = os.path.join(ROOT, "profiles", f"traffic_{workload}.txt")
+    if not os.path.exists(path):
+        return None
+    for ln in open(path):
+        parts = ln.split()
+        if len(parts) >= 2 and parts[0] == f"{kernel}_hbm_bytes_per_launch":
+            return float(parts[1])
+    return None
+
+
+def cpu_baseline(w):
+    """The oracle, as it stands, on a slice of the workload: first 8192 tokens x 2048 out x 4096 in."""
+    from oracle import cwrap as oracle
+    from paper_2203_10991_amd import synth
+    s = synth.scaled(w, T=min(w.T, 8192), O=min(w.O, 2048), I=min(w.I, 4096), name=w.name + "_slice")
+    g, h = synth.make_g(s, 0), synth.make_h(s, 0)
+    prune = oracle.prune_1of2 if s.nm == "1:2" else oracle.prune_2of4
+    t0 = time.perf_counter()
+    v, m, _ = prune(g, 0, 0)
+    t1 = time.perf_counter()
+    oracle.update_gemm(v, m, h)
+    t2 = time.perf_counter()
+    return {
+        "value": s.flops_dense_equiv / (t2 - t0) / 1e12, "unit": "TFLOP/s (dense-equivalent, prune+GEMM step)",
+        "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"first {s.T} tokens x {s.O} out x {s.I} in of {w.name}: prune {t1 - t0:.2f} s "
+                  f"({s.prune_bytes / (t1 - t0) / 1e9:.2f} GB/s), fp64 GEMM {t2 - t1:.2f} s "
+                  f"({s.flops_dense_equiv / (t2 - t1) / 1e9:.1f} GFLOP/s dense-equivalent)",
+        "prune_GBps": s.prune_bytes / (t1 - t0) / 1e9,
+        "gemm_TFLOPs": s.flops_dense_equiv / (t2 - t1) / 1e12,
+    }
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c5_decoder_mlp_2of4")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--pmc-calibration", action="store_true",
+                    help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc byte counters")
+    args = ap.parse_args()
+    if args.gpus != 1 or int(os.environ.get("WORLD_SIZE", "1")) != 1:
+        print("bench.py: this build runs on ONE GPU (the path shards along tokens with one all-reduce of dW; "
+              "that is design only). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2203_10991_amd as nm
+    from paper_2203_10991_amd import synth
+
+    nm.load()                                   # no fallback: fails loudly if the HIP library is not built
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        sys.exit(3)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    w = synth.WORKLOADS[args.workload]
+    g, h = synth.make_device(w, seed=0, device=dev)
+    prune = nm.mvue_prune_1of2 if w.nm == "1:2" else nm.mvue_prune_2of4
+    vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, dev)
+    dW = torch.empty((w.O, w.I), dtype=torch.float32, device=dev)
+    need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+    def step(seed, evs=None):
+        if evs: evs[0].record()
+        prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
+        if evs: evs[1].record()
+        nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+        if evs: evs[2].record()
+
+    for i in range(args.warmup):
+        step(i)
+    torch.cuda.synchronize()
+    events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
+    t0 = time.perf_counter()
+    for i in range(args.steps):
+        step(args.warmup + i, events[i])
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ms_step = wall * 1e3 / args.steps
+    prune_ms = sum(e[0].elapsed_time(e[1]) for e in events) / args.steps
+    gemm_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
+
+    flops = w.flops_dense_equiv
+    prune_gbps = w.prune_bytes / (prune_ms * 1e-3) / 1e9
+    gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
+    out = {
+        "metric": "MVUE prune GB/s (% HBM peak) + sparse dW GEMM TFLOP/s (% SMFMAC peak)",
+        "value": flops / (ms_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s (dense-equivalent 2*T*O*I over the whole prune+GEMM step)",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
+                   "T": w.T, "O": w.O, "I": w.I, "estimator": f"MVUE {w.nm}", "seed": 0},
+        "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
+        "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / SPARSE_PEAK_TFLOPS,
+        "gemm_ms": gemm_ms,
+        "roofline": {"kernel": "update_gemm_smfmac_kernel", "bound": "mfma", "achieved": gemm_tflops,
+                     "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / SPARSE_PEAK_TFLOPS,
+                     "traffic": read_traffic(w.name, "gemm"),
+                     "note": "dense-equivalent flops 2*T*O*I per launch; peak = 2 x published dense bf16 MFMA peak "
+                             "(4:2 sparse MFMA executes half the products)"},
+        "roofline_prune": {"kernel": "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
+                           "traffic": read_traffic(w.name, "prune"),
+                           "note": f"algorithmic bytes {w.prune_bytes} per launch: read g, write T/2 values and T/16 index words per column"},
+    }
+    if args.pmc_calibration:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        dst.copy_(src)                      # reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        del src, dst
+    if not args.no_cpu_baseline:
+        del g, h, vals, meta, dW, ws
+        torch.cuda.empty_cache()
+        out["cpu_baseline"] = cpu_baseline(w)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -19,6 +19,8 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+
 #include "nm_internal.h"
 
 namespace nm {
@@ -30,11 +32,40 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int KT = 64;            // tokens per LDS stage (two 32-token MFMA steps)
-constexpr int LDS_PAD = 32;       // bf16 elements of row padding: row stride = 16 banks mod 64
 
 union Frag16 { bf16x16 v; s16x4 q[4]; };
-union Frag8 { bf16x8 v; uint4 u; };
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+union Frag8 { bf16x8 v; u32x4 u4; };
 
+typedef const __attribute__((address_space(1))) void *gptr_t;
+typedef __attribute__((address_space(3))) void *lptr_t;
+
+// The 16 accumulator blocks of a wave (256 registers) must own the accumulation-register half
+// (AGPRs) of the register file for the whole kernel, with everything else in VGPRs.  Left to
+// itself the compiler keeps accumulators in VGPRs and shuffles blocks to and from AGPRs around
+// every MFMA, so each definition of an accumulator is an asm statement with an AGPR operand:
+//   acc_zero   D = 0*0 + 0 with a dense MFMA (inline-constant C), the only way to write 16 AGPRs at once
+//   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B
+__device__ __forceinline__ void acc_zero(f32x16 &acc)
+{
+    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
+    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
+}
+template <int ABID>
+__device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
+{
+    static_assert(ABID == 0, "index word in the low half");
+    asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+}
+
+// s_waitcnt vmcnt(0) only (expcnt / lgkmcnt left at their maxima)
+__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+
+// LDS image of a stage of h: [KT tokens][TN columns] bf16, rows unpadded (TN*2 bytes).  It is filled by
+// direct global->LDS loads (each wave instruction lands 64 consecutive 16-byte chunks), so bank
+// conflicts of the transposing reads are avoided by a swizzle instead of padding: chunk c of row k
+// lives at chunk position c ^ (4 * (k % 4)).  A transposing read touches, per 16 lanes, the same
+// 32-byte column window of 4 consecutive rows; the swizzle spreads those over distinct banks.
 template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
@@ -42,10 +73,15 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate)
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
-    constexpr int RS = TN + LDS_PAD;                     // LDS row stride in elements
-    constexpr int CHUNKS_PER_ROW = TN / 8;
-    constexpr int CHUNKS_PER_THREAD = KT * CHUNKS_PER_ROW / 256;
-    __shared__ __attribute__((aligned(16))) uint16_t Bs[2][KT * RS];
+    constexpr int CPR = TN / 8;                           // 16-byte chunks per LDS row
+    constexpr int ROWS_PER_DMA = 64 / CPR;                // rows one wave-wide direct load covers
+    constexpr int DMA_PER_WAVE = KT / (4 * ROWS_PER_DMA); // direct loads per wave per stage
+    constexpr int STAGE_BYTES = KT * TN * 2;
+    static_assert(CPR >= 16 && CPR <= 64, "tile width");
+    // two separate arrays (not one array of two stages): the compiler then knows that a direct load
+    // into one buffer cannot alias the LDS reads of the other and leaves those loads in flight
+    __shared__ __attribute__((aligned(1024))) char Bs0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs1[STAGE_BYTES];
 
     // ---- tile assignment.  Workgroups go round-robin over the 8 XCDs (each has its own L2):
     // give every XCD a contiguous run of tiles, walked N-fastest inside bands of 8 M-tiles.
@@ -63,7 +99,8 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     const int tm = band * BAND + in_band % band_rows;
     const int tn = in_band / band_rows;
 
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: keeps LDS bases scalar
     const int wm = wave / WN, wn = wave % WN;
     const int64_t o0 = (int64_t)tm * TM + wm * (AB * 32);
     const int64_t n0 = (int64_t)tn * TN;                 // tile's first column of h / dW
@@ -75,108 +112,133 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
 #pragma unroll
     for (int a = 0; a < AB; ++a)
 #pragma unroll
-        for (int b = 0; b < BB; ++b)
-#pragma unroll
-            for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
+        for (int b = 0; b < BB; ++b) acc_zero(acc[a][b]);
 
-    const int n_iters = (int)((g_end - g_begin + 3) / 4);      // 4 token groups per stage
+    const int n_iters = (int)((g_end - g_begin + 3) / 4);      // stages of 4 token groups; the last may be ragged
 
-    // ---- operand fetch helpers -------------------------------------------------------------
+    // All global reads go through raw buffer descriptors that are re-based to the current stage:
+    // a 32-bit per-lane offset is all a load needs, and whatever lies past the end of the tensor
+    // (the token groups a ragged last stage lacks) reads as zero, so there is no tail code path.
+    // Split-K slabs are whole stages except the last, so a ragged stage only occurs at the tensor's end.
+    auto rsrc = [](const void *base, int64_t bytes) {
+        const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
+        return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)n, 0x00020000);
+    };
+    const int64_t T = n_groups * 16;
+
+    // ---- sparse operand: straight from global memory into MFMA registers ---------------------
+    // Rows >= O are clamped to the last valid row (their outputs are never stored).
     const int kg = lane >> 5;                                  // which 16-token group of a 32-token step
-    Frag8 a_cur[2][AB], a_nxt[2][AB];
-    uint32_t idx_cur[AB], idx_nxt[AB];
-    uint4 stage[CHUNKS_PER_THREAD];
+    uint32_t a_voff[2][AB];                                    // ((2*ks + kg)*O + row)*16: byte offset of the fragment in the stage
+#pragma unroll
+    for (int ks = 0; ks < 2; ++ks)
+#pragma unroll
+        for (int a = 0; a < AB; ++a)
+            a_voff[ks][a] = (uint32_t)((2 * ks + kg) * O + min(o0 + a * 32 + (lane & 31), O - 1)) * 16u;
 
-    auto load_a = [&](int it, Frag8 (&af)[2][AB], uint32_t (&ix)[AB]) {
+    auto load_a = [&](int it, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
+        const int64_t Gs = g_begin + (int64_t)it * 4;
+        const __amdgpu_buffer_rsrc_t rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
+        const __amdgpu_buffer_rsrc_t rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
 #pragma unroll
-        for (int a = 0; a < AB; ++a) {
-            const int64_t o = o0 + a * 32 + (lane & 31);
-            uint32_t m01[2];
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks) {
-                const int64_t G = g_begin + (int64_t)it * 4 + 2 * ks + kg;
-                const bool ok = (G < g_end) & (o < O);
-                const int64_t e = ok ? (G * O + o) : 0;
-                uint4 v = *(const uint4 *)(vals + e * 8);
-                uint32_t m = meta[e];
-                if (!ok) { v = make_uint4(0, 0, 0, 0); m = 0x4444u; }
-                af[ks][a].u = v;
-                m01[ks] = m;
-            }
-            ix[a] = m01[0] | (m01[1] << 16);
-        }
-    };
-    auto load_b = [&](int it) {
-#pragma unroll
-        for (int p = 0; p < CHUNKS_PER_THREAD; ++p) {
-            const int c = tid + 256 * p, row = c / CHUNKS_PER_ROW, cc = c % CHUNKS_PER_ROW;
-            const int64_t t = (g_begin + (int64_t)it * 4) * 16 + row;
-            const int64_t col = n0 + cc * 8;
-            const bool ok = (t < g_end * 16) & (col < I);
-            stage[p] = ok ? *(const uint4 *)(h + t * ldh + col) : make_uint4(0, 0, 0, 0);
-        }
-    };
-    auto store_b = [&](int buf) {
-#pragma unroll
-        for (int p = 0; p < CHUNKS_PER_THREAD; ++p) {
-            const int c = tid + 256 * p, row = c / CHUNKS_PER_ROW, cc = c % CHUNKS_PER_ROW;
-            *(uint4 *)(&Bs[buf][row * RS + cc * 8]) = stage[p];
-        }
-    };
-
-    // lane's LDS read offsets (elements) for the transposing reads
-    const int li = lane & 15, q = lane >> 4;
-    const int b_row0 = 8 * (q >> 1) + (li >> 2);                // + 32*ks + 16*(j>>1) + 4*(j&1)
-    const int b_col0 = wn * (BB * 32) + 16 * (q & 1) + 4 * (li & 3);   // + 32*bn
-
-    if (n_iters > 0) {
-        load_a(0, a_cur, idx_cur);
-        load_b(0);
-        store_b(0);
-    }
-    __syncthreads();
-
-    for (int it = 0; it < n_iters; ++it) {
-        const int buf = it & 1;
-        const bool more = it + 1 < n_iters;
-        if (more) {
-            load_b(it + 1);
-            load_a(it + 1, a_nxt, idx_nxt);
-        }
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks) {
-#pragma unroll
-            for (int b = 0; b < BB; ++b) {
-                Frag16 bf;
-#pragma unroll
-                for (int j = 0; j < 4; ++j) {
-                    const int row = 32 * ks + 16 * (j >> 1) + 4 * (j & 1) + b_row0;
-                    const int col = 32 * b + b_col0;
-                    bf.q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                        (__attribute__((address_space(3))) s16x4 *)(&Bs[buf][row * RS + col]));
-                }
-#pragma unroll
-                for (int a = 0; a < AB; ++a) {
-                    if (ks == 0)
-                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a_cur[0][a].v, bf.v, acc[a][b], (int)idx_cur[a], 0, 0);
-                    else
-                        acc[a][b] = __builtin_amdgcn_smfmac_f32_32x32x32_bf16(a_cur[1][a].v, bf.v, acc[a][b], (int)idx_cur[a], 0, 1);
-                }
-            }
-        }
-        if (more) {
-            store_b(buf ^ 1);
+        for (int ks = 0; ks < 2; ++ks)
 #pragma unroll
             for (int a = 0; a < AB; ++a) {
-                a_cur[0][a] = a_nxt[0][a];
-                a_cur[1][a] = a_nxt[1][a];
-                idx_cur[a] = idx_nxt[a];
+                af[ks][a].u4 = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)a_voff[ks][a], 0, 0);
+                ix[ks][a] = __builtin_amdgcn_raw_buffer_load_b16(rm, (int)(a_voff[ks][a] >> 3), 0, 0);
+            }
+    };
+
+    // ---- dense operand: direct global->LDS loads, swizzled ------------------------------------
+    // direct load d (0..DMA_PER_WAVE-1) of this wave fills rows  wave*KT/4 + d*ROWS_PER_DMA + lane/CPR
+    // and chunk position lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 4*(row%4).
+    constexpr int PHASES = ROWS_PER_DMA >= 4 ? 1 : 4 / ROWS_PER_DMA;
+    uint32_t b_src[PHASES];                                    // byte offsets in the stage, by (d*ROWS_PER_DMA)%4 phase
+    const int dma_row = lane / CPR, dma_pos = lane % CPR;
+#pragma unroll
+    for (int ph = 0; ph < PHASES; ++ph) {
+        const int row_mod4 = (ph * ROWS_PER_DMA + dma_row) & 3;
+        const int64_t col = min(n0 + 8 * (dma_pos ^ (4 * row_mod4)), I - 8);
+        b_src[ph] = (uint32_t)(((int64_t)(wave * (KT / 4) + dma_row) * ldh + col) * 2);
+    }
+    const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh * 2);
+    auto load_b = [&](int it, int buf) {
+        const int64_t t0 = (g_begin + (int64_t)it * 4) * 16;
+        const __amdgpu_buffer_rsrc_t rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
+#pragma unroll
+        for (int d = 0; d < DMA_PER_WAVE; ++d) {
+            char *dst = (buf ? Bs1 : Bs0) + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)dst, 16, (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
+        }
+    };
+    auto fetch = [&](int it, int buf, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
+        load_b(it, buf);
+        load_a(it, af, ix);
+    };
+    // everything of a stage that was fetched into an LDS buffer is visible to the whole workgroup after this
+    auto stage_ready = [&]() {
+        wait_vmcnt0();                                  // this wave's direct loads have landed
+        __syncthreads();
+    };
+
+    // lane's LDS read address pieces for the transposing reads (see the layout note above)
+    const int li = lane & 15, q4 = lane >> 4;
+    const int rd_row = (8 * (q4 >> 1) + (li >> 2)) * (TN * 2);     // + (32*ks + 16*(j>>1) + 4*(j&1)) rows
+    int rd_off[BB];
+#pragma unroll
+    for (int b = 0; b < BB; ++b)
+        rd_off[b] = rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8;
+
+    auto read_b = [&](int buf, int ks, int b, Frag16 &bf) {
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int row_off = (32 * ks + 16 * (j >> 1) + 4 * (j & 1)) * (TN * 2);
+            bf.q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
+                (__attribute__((address_space(3))) s16x4 *)((buf ? Bs1 : Bs0) + row_off + rd_off[b]));
+        }
+    };
+    // one stage: the fragment of h for step (ks, b+1) is requested from LDS before the MFMAs of (ks, b) issue
+    auto compute = [&](int buf, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
+        Frag16 bf[2];
+        read_b(buf, 0, 0, bf[0]);
+#pragma unroll
+        for (int s = 0; s < 2 * BB; ++s) {
+            const int ks = s / BB, b = s % BB;
+            if (s + 1 < 2 * BB) read_b(buf, (s + 1) / BB, (s + 1) % BB, bf[(s + 1) & 1]);
+#pragma unroll
+            for (int a = 0; a < AB; ++a) {
+                if (ks == 0) smfmac_32x32x32<0>(acc[a][b], af[0][a].v, bf[s & 1].v, ix[0][a]);
+                else         smfmac_32x32x32<0>(acc[a][b], af[1][a].v, bf[s & 1].v, ix[1][a]);
             }
         }
-        __syncthreads();
+    };
+
+    // two register sets for the sparse operand and two LDS buffers, alternating by stage parity
+    Frag8 a0[2][AB], a1[2][AB];
+    uint32_t i0[2][AB], i1[2][AB];
+    // Straight-line loop body, two stages per trip.  Stages past the end of the tensor read as
+    // zeros (buffer bounds), so an odd stage count is padded with an all-zero stage and the
+    // fetches that run ahead of the last stage need no guard.  (Split-K slabs other than the last
+    // hold an even number of stages: see make_plan.)
+    const int n_pairs = (n_iters + 1) / 2;
+    if (n_pairs > 0) {
+        fetch(0, 0, a0, i0);
+        stage_ready();
+    }
+    for (int pr = 0; pr < n_pairs; ++pr) {
+        const int it = 2 * pr;
+        fetch(it + 1, 1, a1, i1);
+        compute(0, a0, i0);
+        stage_ready();
+        fetch(it + 2, 0, a0, i0);
+        compute(1, a1, i1);
+        stage_ready();
     }
 
-    // ---- epilogue
+    // ---- epilogue.  The matrix pipeline may still be writing the last accumulators, and the
+    // compiler cannot see MFMAs inside asm statements: idle for longer than an 8-pass
+    // instruction before the first read of an accumulation register.
+    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
 #pragma unroll
     for (int a = 0; a < AB; ++a)
 #pragma unroll
@@ -234,8 +296,8 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
         if (slabs < 1) slabs = 1;
     }
     int64_t gps = (groups + slabs - 1) / slabs;
-    gps = (gps + 3) / 4 * 4;                                           // whole LDS stages
-    if (gps < 4) gps = 4;
+    gps = (gps + 7) / 8 * 8;                                           // whole pairs of LDS stages
+    if (gps < 8) gps = 8;
     p.groups_per_slab = gps;
     p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
     return p;
