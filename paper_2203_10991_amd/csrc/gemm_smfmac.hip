@@ -14,7 +14,7 @@
 //   D  reg r of lane l = row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 //
 // Workgroup = 4 waves (WM x WN), each wave owns AB x BB blocks of 32x32; 64 tokens per LDS
-// stage, double buffered, one barrier per stage.  Split-K over blockIdx.z writes binary32
+// stage, three stages in flight, one barrier per stage.  Split-K over blockIdx.z writes binary32
 // partials that a second kernel sums in a fixed order (deterministic; no atomics).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
@@ -51,15 +51,35 @@ __device__ __forceinline__ void acc_zero(f32x16 &acc)
     const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
 }
-template <int ABID>
+//   LGKM > 0: first wait until at most LGKM-1 LDS reads are outstanding (the fragment's own reads are done)
+template <int LGKM>
 __device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
 {
-    static_assert(ABID == 0, "index word in the low half");
-    asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    if (LGKM == 0)
+        asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    else if (LGKM == 1)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    else
+        asm volatile("s_waitcnt lgkmcnt(4)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
 }
 
-// s_waitcnt vmcnt(0) only (expcnt / lgkmcnt left at their maxima)
-__device__ __forceinline__ void wait_vmcnt0() { __builtin_amdgcn_s_waitcnt(0x0F70); }
+// Transposing LDS read (4 tokens x 16 columns per 16 lanes -> 4 consecutive tokens of one column per
+// lane).  Issued as asm so that the compiler does not order it against the direct global->LDS loads
+// still in flight for later stages: that ordering is explicit (wait_vmcnt + barrier per stage).
+template <int OFFSET>
+__device__ __forceinline__ s16x4 lds_read_tr16(uint32_t addr)
+{
+    s16x4 r;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+
+// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt left at their maxima): at most N vector-memory loads still in flight
+template <int N> __device__ __forceinline__ void wait_vmcnt()
+{
+    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
+    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
+}
 
 // LDS image of a stage of h: [KT tokens][TN columns] bf16, rows unpadded (TN*2 bytes).  It is filled by
 // direct global->LDS loads (each wave instruction lands 64 consecutive 16-byte chunks), so bank
@@ -82,6 +102,7 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     // into one buffer cannot alias the LDS reads of the other and leaves those loads in flight
     __shared__ __attribute__((aligned(1024))) char Bs0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char Bs1[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char Bs2[STAGE_BYTES];
 
     // ---- tile assignment.  Workgroups go round-robin over the 8 XCDs (each has its own L2):
     // give every XCD a contiguous run of tiles, walked N-fastest inside bands of 8 M-tiles.
@@ -167,7 +188,7 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
         const __amdgpu_buffer_rsrc_t rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
 #pragma unroll
         for (int d = 0; d < DMA_PER_WAVE; ++d) {
-            char *dst = (buf ? Bs1 : Bs0) + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2);
+            char *dst = (buf == 0 ? Bs0 : buf == 1 ? Bs1 : Bs2) + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2);
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)dst, 16, (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
         }
     };
@@ -175,10 +196,17 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
         load_b(it, buf);
         load_a(it, af, ix);
     };
-    // everything of a stage that was fetched into an LDS buffer is visible to the whole workgroup after this
-    auto stage_ready = [&]() {
-        wait_vmcnt0();                                  // this wave's direct loads have landed
-        __syncthreads();
+    // Loads a wave issues per stage; with the fetch of stage s+2 issued before stage s is computed,
+    // "stage s+1 has landed" means: at most one stage's worth of this wave's loads still in flight.
+    constexpr int LOADS_PER_STAGE = DMA_PER_WAVE + 4 * AB;
+    auto next_stage_ready = [&]() {
+        wait_vmcnt<LOADS_PER_STAGE>();
+        // ... and every other wave's part of it too.  A bare barrier: __syncthreads() would add a
+        // workgroup release fence, which the compiler implements by draining every direct-to-LDS
+        // load in flight (those of stage s+2 included).  The LDS reads of the stage just computed
+        // were drained by the lgkmcnt(0) of its last fragment, so its buffer may be refilled after this.
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
     };
 
     // lane's LDS read address pieces for the transposing reads (see the layout note above)
@@ -189,50 +217,64 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     for (int b = 0; b < BB; ++b)
         rd_off[b] = rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8;
 
-    auto read_b = [&](int buf, int ks, int b, Frag16 &bf) {
-#pragma unroll
-        for (int j = 0; j < 4; ++j) {
-            const int row_off = (32 * ks + 16 * (j >> 1) + 4 * (j & 1)) * (TN * 2);
-            bf.q[j] = __builtin_amdgcn_ds_read_tr16_b64_v4i16(
-                (__attribute__((address_space(3))) s16x4 *)((buf ? Bs1 : Bs0) + row_off + rd_off[b]));
-        }
-    };
+    const uint32_t lds_base[3] = {(uint32_t)(uintptr_t)(lptr_t)Bs0, (uint32_t)(uintptr_t)(lptr_t)Bs1, (uint32_t)(uintptr_t)(lptr_t)Bs2};
     // one stage: the fragment of h for step (ks, b+1) is requested from LDS before the MFMAs of (ks, b) issue
     auto compute = [&](int buf, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
+        uint32_t addr[BB];
+#pragma unroll
+        for (int b = 0; b < BB; ++b) addr[b] = lds_base[buf] + (uint32_t)rd_off[b];
+        auto read_b = [&](int ks, int b, Frag16 &bf) {
+            constexpr int R = TN * 2;
+            if (ks == 0) {
+                bf.q[0] = lds_read_tr16<0 * R>(addr[b]);  bf.q[1] = lds_read_tr16<4 * R>(addr[b]);
+                bf.q[2] = lds_read_tr16<16 * R>(addr[b]); bf.q[3] = lds_read_tr16<20 * R>(addr[b]);
+            } else {
+                bf.q[0] = lds_read_tr16<32 * R>(addr[b]); bf.q[1] = lds_read_tr16<36 * R>(addr[b]);
+                bf.q[2] = lds_read_tr16<48 * R>(addr[b]); bf.q[3] = lds_read_tr16<52 * R>(addr[b]);
+            }
+        };
         Frag16 bf[2];
-        read_b(buf, 0, 0, bf[0]);
+        read_b(0, 0, bf[0]);
 #pragma unroll
         for (int s = 0; s < 2 * BB; ++s) {
             const int ks = s / BB, b = s % BB;
-            if (s + 1 < 2 * BB) read_b(buf, (s + 1) / BB, (s + 1) % BB, bf[(s + 1) & 1]);
+            const bool last = s + 1 == 2 * BB;
+            if (!last) read_b((s + 1) / BB, (s + 1) % BB, bf[(s + 1) & 1]);
 #pragma unroll
             for (int a = 0; a < AB; ++a) {
-                if (ks == 0) smfmac_32x32x32<0>(acc[a][b], af[0][a].v, bf[s & 1].v, ix[0][a]);
-                else         smfmac_32x32x32<0>(acc[a][b], af[1][a].v, bf[s & 1].v, ix[1][a]);
+                if (a > 0)     smfmac_32x32x32<0>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
+                else if (last) smfmac_32x32x32<1>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
+                else           smfmac_32x32x32<5>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
             }
         }
     };
 
-    // two register sets for the sparse operand and two LDS buffers, alternating by stage parity
-    Frag8 a0[2][AB], a1[2][AB];
-    uint32_t i0[2][AB], i1[2][AB];
-    // Straight-line loop body, two stages per trip.  Stages past the end of the tensor read as
-    // zeros (buffer bounds), so an odd stage count is padded with an all-zero stage and the
-    // fetches that run ahead of the last stage need no guard.  (Split-K slabs other than the last
-    // hold an even number of stages: see make_plan.)
-    const int n_pairs = (n_iters + 1) / 2;
-    if (n_pairs > 0) {
+    // Three register sets for the sparse operand and three LDS buffers, rotating by stage: while
+    // stage s is computed, the loads of stages s+1 and s+2 are in flight (about two stages of MFMA
+    // work, ~2000 cycles, cover the memory latency of a wave that has no sibling on its SIMD).
+    // Straight-line loop body, three stages per trip.  Stages past the end of the tensor read as
+    // zeros (buffer bounds), so the stage count is padded to a multiple of three with all-zero
+    // stages and the fetches that run ahead of the last stage need no guard.  (Split-K slabs other
+    // than the last hold a multiple of three stages: see make_plan.)
+    Frag8 a0[2][AB], a1[2][AB], a2[2][AB];
+    uint32_t i0[2][AB], i1[2][AB], i2[2][AB];
+    const int n_trips = (n_iters + 2) / 3;
+    if (n_trips > 0) {
         fetch(0, 0, a0, i0);
-        stage_ready();
+        fetch(1, 1, a1, i1);
+        next_stage_ready();
     }
-    for (int pr = 0; pr < n_pairs; ++pr) {
-        const int it = 2 * pr;
-        fetch(it + 1, 1, a1, i1);
+    for (int tr = 0; tr < n_trips; ++tr) {
+        const int it = 3 * tr;
+        fetch(it + 2, 2, a2, i2);
         compute(0, a0, i0);
-        stage_ready();
-        fetch(it + 2, 0, a0, i0);
+        next_stage_ready();
+        fetch(it + 3, 0, a0, i0);
         compute(1, a1, i1);
-        stage_ready();
+        next_stage_ready();
+        fetch(it + 4, 1, a1, i1);
+        compute(2, a2, i2);
+        next_stage_ready();
     }
 
     // ---- epilogue.  The matrix pipeline may still be writing the last accumulators, and the
@@ -296,8 +338,8 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
         if (slabs < 1) slabs = 1;
     }
     int64_t gps = (groups + slabs - 1) / slabs;
-    gps = (gps + 7) / 8 * 8;                                           // whole pairs of LDS stages
-    if (gps < 8) gps = 8;
+    gps = (gps + 11) / 12 * 12;                                        // whole trips of three LDS stages
+    if (gps < 12) gps = 12;
     p.groups_per_slab = gps;
     p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
     return p;
