@@ -4,73 +4,97 @@
 // g, i.e. rows of dW), "B" the dense one (h), both reduced over tokens.  Lane layouts, as
 // measured on gfx950 (l = lane):
 //   A  lane holds 8 kept values of row (l%32) for the 16 tokens  16*(l/32) .. +15  of the
-//      32-token step, quad by quad; the 16-bit index word (2 bits per kept value, ABID selects
-//      the half of the index register) is exactly one `meta` word of the group format, and the
-//      8 values are one 16-byte `vals` fragment: both are loaded straight from global memory.
+//      32-token step, quad by quad; the 16-bit index word (2 bits per kept value) is exactly one
+//      `meta` word of the group format and the 8 values are one 16-byte `vals` fragment.
 //   B  lane holds column (l%32); slots 0-7 = tokens 8*(l/32) .. +7, slots 8-15 = tokens
 //      16 + 8*(l/32) .. +7.  h is token-major in memory, so the tile is staged in LDS as
 //      [token][column] and read with ds_read_b64_tr_b16 (a 4-token x 16-column transpose per
 //      16 lanes).
 //   D  reg r of lane l = row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 //
-// Workgroup = 4 waves (WM x WN), each wave owns AB x BB blocks of 32x32; 64 tokens per LDS
-// stage, three stages in flight, one barrier per stage.  Split-K over blockIdx.z writes binary32
-// partials that a second kernel sums in a fixed order (deterministic; no atomics).
+// Workgroup = 4 waves (WM x WN), one per SIMD, each owning AB x BB accumulator blocks of 32x32
+// (256 accumulation registers for the 128x128 wave tile).  The reduction axis advances in stages
+// of 64 tokens.  Every operand byte of a stage -- the h tile, the `vals` fragments and the `meta`
+// words of the tile's rows -- is brought from global memory by direct global->LDS loads, once
+// per workgroup (the per-CU vector-memory path, 64 B/clk, is the scarce resource: loading the
+// sparse operand per wave would fetch it twice).  Three stages are in flight; one barrier per
+// stage.  Split-K over blockIdx.z writes binary32 partials that a second kernel sums in a fixed
+// order (deterministic; no atomics).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
 #include <type_traits>
+#include <utility>
 
 #include "nm_internal.h"
 
 namespace nm {
 
-typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KT = 64;            // tokens per LDS stage (two 32-token MFMA steps)
+constexpr int KT = 64;            // tokens per LDS stage (two 32-token MFMA steps, four 16-token groups)
 
 union Frag16 { bf16x16 v; s16x4 q[4]; };
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 union Frag8 { bf16x8 v; u32x4 u4; };
 
-typedef const __attribute__((address_space(1))) void *gptr_t;
 typedef __attribute__((address_space(3))) void *lptr_t;
 
-// The 16 accumulator blocks of a wave (256 registers) must own the accumulation-register half
-// (AGPRs) of the register file for the whole kernel, with everything else in VGPRs.  Left to
-// itself the compiler keeps accumulators in VGPRs and shuffles blocks to and from AGPRs around
-// every MFMA, so each definition of an accumulator is an asm statement with an AGPR operand:
-//   acc_zero   D = 0*0 + 0 with a dense MFMA (inline-constant C), the only way to write 16 AGPRs at once
-//   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B
+// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
+template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
+{
+    (f(std::integral_constant<int, Is>{}), ...);
+}
+template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
+{
+    static_for_impl(f, std::make_integer_sequence<int, N>{});
+}
+
+// The accumulator blocks of a wave must own the accumulation-register half (AGPRs) of the
+// register file for the whole kernel, with everything else in VGPRs.  Left to itself the compiler
+// keeps accumulators in VGPRs and shuffles blocks to and from AGPRs around every MFMA, so each
+// definition of an accumulator is an asm statement with an AGPR operand:
+//   acc_zero   D = 0*0 + 0 with a dense MFMA (inline-constant C): writes 16 AGPRs at once
+//   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B, optionally preceded by
+//              a wait until at most LGKM LDS reads are outstanding (LGKM < 0: no wait)
 __device__ __forceinline__ void acc_zero(f32x16 &acc)
 {
     const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    asm volatile("v_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
+    // (the compiler does not know this asm is an MFMA: keep the required distance from the VALU moves that write z)
+    asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
 }
-//   LGKM > 0: first wait until at most LGKM-1 LDS reads are outstanding (the fragment's own reads are done)
 template <int LGKM>
 __device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
 {
-    if (LGKM == 0)
+    if constexpr (LGKM < 0)
         asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
-    else if (LGKM == 1)
-        asm volatile("s_waitcnt lgkmcnt(0)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
     else
-        asm volatile("s_waitcnt lgkmcnt(4)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+        asm volatile("s_waitcnt lgkmcnt(%4)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3"
+                     : "+a"(acc) : "v"(a), "v"(b), "v"(idx), "n"(LGKM));
 }
 
-// Transposing LDS read (4 tokens x 16 columns per 16 lanes -> 4 consecutive tokens of one column per
-// lane).  Issued as asm so that the compiler does not order it against the direct global->LDS loads
-// still in flight for later stages: that ordering is explicit (wait_vmcnt + barrier per stage).
-template <int OFFSET>
-__device__ __forceinline__ s16x4 lds_read_tr16(uint32_t addr)
+// LDS reads are issued as asm so that the compiler does not order them against the direct
+// global->LDS loads still in flight for later stages; that ordering is explicit (vmcnt wait +
+// barrier per stage), and so are the waits for the reads themselves (LGKM above).
+template <int OFFSET> __device__ __forceinline__ s16x4 lds_read_tr16(uint32_t addr)     // 4 tokens x 16 columns transposed per 16 lanes
 {
     s16x4 r;
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+template <int OFFSET> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
+{
+    u32x4 r;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+template <int OFFSET> __device__ __forceinline__ uint32_t lds_read_u16(uint32_t addr)
+{
+    uint32_t r;
+    asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
     return r;
 }
 
@@ -81,11 +105,14 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
-// LDS image of a stage of h: [KT tokens][TN columns] bf16, rows unpadded (TN*2 bytes).  It is filled by
-// direct global->LDS loads (each wave instruction lands 64 consecutive 16-byte chunks), so bank
-// conflicts of the transposing reads are avoided by a swizzle instead of padding: chunk c of row k
-// lives at chunk position c ^ (4 * (k % 4)).  A transposing read touches, per 16 lanes, the same
-// 32-byte column window of 4 consecutive rows; the swizzle spreads those over distinct banks.
+// LDS image of one stage (all filled by direct loads, 64 consecutive lanes -> consecutive LDS bytes):
+//   [0, 128*TN)               h tile, [64 tokens][TN columns] bf16, rows unpadded.  Bank conflicts of the
+//                             transposing reads are avoided by a swizzle: 16-byte chunk c of row k sits at
+//                             chunk position c ^ (4*(k%4)) (a transposing read touches, per 16 lanes, the
+//                             same 32-byte column window of 4 consecutive rows).
+//   [128*TN, +64*TM)          vals fragments, [4 token groups][TM rows] x 16 bytes (the layout they have in
+//                             global memory for a fixed group: read back with one ds_read_b128 per fragment)
+//   [.., +8*TM)               meta words, [4 token groups][TM rows] x 2 bytes
 template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
@@ -93,37 +120,60 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate)
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
-    constexpr int CPR = TN / 8;                           // 16-byte chunks per LDS row
-    constexpr int ROWS_PER_DMA = 64 / CPR;                // rows one wave-wide direct load covers
-    constexpr int DMA_PER_WAVE = KT / (4 * ROWS_PER_DMA); // direct loads per wave per stage
-    constexpr int STAGE_BYTES = KT * TN * 2;
+    constexpr int CPR = TN / 8;                           // 16-byte chunks per h row in LDS
+    constexpr int ROWS_PER_DMA = 64 / CPR;                // h rows one wave-wide 16-byte direct load covers
+    constexpr int B_DMA = KT / (4 * ROWS_PER_DMA);        // direct loads per wave per stage: h tile
+    constexpr int A_DMA = TM / 64;                        //   vals: wave w brings token group w, 64 rows per load
+    constexpr int M_DMA = TM >= 128 ? TM / 128 : 1;      //   meta: wave w brings group w, 2 words (4 bytes) per lane;
+    constexpr int M_LANES = TM >= 128 ? 64 : TM / 2;      //   a 64-row tile needs only the first 32 lanes
+    constexpr int LOADS_PER_STAGE = B_DMA + A_DMA + M_DMA;
+    constexpr int A_OFF = 128 * TN, M_OFF = A_OFF + 64 * TM, STAGE_BYTES = (M_OFF + 8 * TM + 1023) / 1024 * 1024;
     static_assert(CPR >= 16 && CPR <= 64, "tile width");
-    // two separate arrays (not one array of two stages): the compiler then knows that a direct load
-    // into one buffer cannot alias the LDS reads of the other and leaves those loads in flight
-    __shared__ __attribute__((aligned(1024))) char Bs0[STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char Bs1[STAGE_BYTES];
-    __shared__ __attribute__((aligned(1024))) char Bs2[STAGE_BYTES];
+    // three separate arrays: one per stage in flight
+    __shared__ __attribute__((aligned(1024))) char S0[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char S1[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char S2[STAGE_BYTES];
 
-    // ---- tile assignment.  Workgroups go round-robin over the 8 XCDs (each has its own L2):
-    // give every XCD a contiguous run of tiles, walked N-fastest inside bands of 8 M-tiles.
-    const int n_tiles = tiles_m * tiles_n;
-    int bid = blockIdx.x;
+    // ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), 32 CUs and one
+    // L2 each.  Preferred map: the whole GPU works on ONE band of M-tiles at a time, XCD x owning the N-tiles
+    // [x*nx, (x+1)*nx): the band's sparse operand is fetched from HBM once (the XCDs find it in the
+    // memory-side cache), every XCD streams only its own columns of h, and the 32 tiles resident on an XCD
+    // (band_rows x nx) share operand strips inside its L2.
+    int tm, tn;
     {
-        const int per_xcd = (n_tiles + 7) / 8;
-        const int remapped = (bid % 8) * per_xcd + bid / 8;
-        if (n_tiles % 8 == 0) bid = remapped;
+        const int n_tiles = tiles_m * tiles_n, bid = blockIdx.x;
+        const int nx = tiles_n / 8;                                    // N-tiles per XCD
+        if (tiles_n % 8 == 0 && nx <= 32) {
+            const int band_rows = 32 / nx > 0 ? 32 / nx : 1;           // M-tiles per band: band_rows * nx ~ 32 CUs
+            const int xcd = bid % 8, slot = bid / 8;                   // slot: this XCD's running tile count
+            const int per_band = band_rows * nx;
+            const int band = slot / per_band, local = slot % per_band;
+            const int rows_here = min(band_rows, tiles_m - band * band_rows);   // last band may be short
+            // in a short band the slots are re-dealt over rows_here rows (all slots of the band stay valid: per XCD
+            // the band holds rows_here*nx tiles, and slots beyond them belong to no tile of this XCD)
+            const int full_bands = tiles_m / band_rows;
+            if (band < full_bands) { tm = band * band_rows + local % band_rows; tn = xcd * nx + local / band_rows; }
+            else {
+                const int l2 = slot - full_bands * per_band;            // index inside the short band
+                tm = full_bands * band_rows + l2 % rows_here; tn = xcd * nx + l2 / rows_here;
+            }
+        } else {
+            // fallback: contiguous run of tiles per XCD when the count divides evenly, N-fastest inside bands of 8 M-tiles
+            int t = bid;
+            if (n_tiles % 8 == 0) t = (bid % 8) * (n_tiles / 8) + bid / 8;
+            constexpr int BAND = 8;
+            const int band = t / (BAND * tiles_n);
+            const int band_rows = min(BAND, tiles_m - band * BAND);
+            const int in_band = t - band * BAND * tiles_n;
+            tm = band * BAND + in_band % band_rows;
+            tn = in_band / band_rows;
+        }
     }
-    constexpr int BAND = 8;
-    const int band = bid / (BAND * tiles_n);
-    const int band_rows = min(BAND, tiles_m - band * BAND);
-    const int in_band = bid - band * BAND * tiles_n;
-    const int tm = band * BAND + in_band % band_rows;
-    const int tn = in_band / band_rows;
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: keeps LDS bases scalar
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t o0 = (int64_t)tm * TM + wm * (AB * 32);
+    const int64_t m0 = (int64_t)tm * TM;                 // tile's first row of dW (= column of g)
     const int64_t n0 = (int64_t)tn * TN;                 // tile's first column of h / dW
     const int64_t g_begin = (int64_t)blockIdx.z * groups_per_slab;
     const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
@@ -138,8 +188,8 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     const int n_iters = (int)((g_end - g_begin + 3) / 4);      // stages of 4 token groups; the last may be ragged
 
     // All global reads go through raw buffer descriptors that are re-based to the current stage:
-    // a 32-bit per-lane offset is all a load needs, and whatever lies past the end of the tensor
-    // (the token groups a ragged last stage lacks) reads as zero, so there is no tail code path.
+    // a 32-bit per-lane offset is all a load needs, and a load from past the end of the tensor (the
+    // token groups a ragged last stage lacks) is dropped by the bounds check instead of faulting.
     // Split-K slabs are whole stages except the last, so a ragged stage only occurs at the tensor's end.
     auto rsrc = [](const void *base, int64_t bytes) {
         const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
@@ -147,34 +197,17 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     };
     const int64_t T = n_groups * 16;
 
-    // ---- sparse operand: straight from global memory into MFMA registers ---------------------
-    // Rows >= O are clamped to the last valid row (their outputs are never stored).
-    const int kg = lane >> 5;                                  // which 16-token group of a 32-token step
-    uint32_t a_voff[2][AB];                                    // ((2*ks + kg)*O + row)*16: byte offset of the fragment in the stage
+    // per-lane source offsets (bytes, relative to the stage).  Rows >= O and columns >= I are clamped
+    // to the last valid ones: their products land in outputs that are never stored.
+    uint32_t a_src[A_DMA], m_src[M_DMA];
 #pragma unroll
-    for (int ks = 0; ks < 2; ++ks)
+    for (int d = 0; d < A_DMA; ++d) a_src[d] = (uint32_t)(wave * O + min(m0 + 64 * d + lane, O - 1)) * 16u;
 #pragma unroll
-        for (int a = 0; a < AB; ++a)
-            a_voff[ks][a] = (uint32_t)((2 * ks + kg) * O + min(o0 + a * 32 + (lane & 31), O - 1)) * 16u;
-
-    auto load_a = [&](int it, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
-        const int64_t Gs = g_begin + (int64_t)it * 4;
-        const __amdgpu_buffer_rsrc_t rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
-        const __amdgpu_buffer_rsrc_t rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
-#pragma unroll
-        for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-            for (int a = 0; a < AB; ++a) {
-                af[ks][a].u4 = __builtin_amdgcn_raw_buffer_load_b128(rv, (int)a_voff[ks][a], 0, 0);
-                ix[ks][a] = __builtin_amdgcn_raw_buffer_load_b16(rm, (int)(a_voff[ks][a] >> 3), 0, 0);
-            }
-    };
-
-    // ---- dense operand: direct global->LDS loads, swizzled ------------------------------------
-    // direct load d (0..DMA_PER_WAVE-1) of this wave fills rows  wave*KT/4 + d*ROWS_PER_DMA + lane/CPR
-    // and chunk position lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 4*(row%4).
+    for (int d = 0; d < M_DMA; ++d) m_src[d] = (uint32_t)(wave * O + min(m0 + 128 * d + 2 * lane, O - 2)) * 2u;
+    // h: direct load d of this wave fills rows  wave*16 + d*ROWS_PER_DMA + lane/CPR  at chunk position
+    // lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 4*(row%4).
     constexpr int PHASES = ROWS_PER_DMA >= 4 ? 1 : 4 / ROWS_PER_DMA;
-    uint32_t b_src[PHASES];                                    // byte offsets in the stage, by (d*ROWS_PER_DMA)%4 phase
+    uint32_t b_src[PHASES];
     const int dma_row = lane / CPR, dma_pos = lane % CPR;
 #pragma unroll
     for (int ph = 0; ph < PHASES; ++ph) {
@@ -183,104 +216,136 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
         b_src[ph] = (uint32_t)(((int64_t)(wave * (KT / 4) + dma_row) * ldh + col) * 2);
     }
     const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh * 2);
-    auto load_b = [&](int it, int buf) {
-        const int64_t t0 = (g_begin + (int64_t)it * 4) * 16;
+
+    auto fetch = [&](int it, char *stage) {
+        const int64_t Gs = g_begin + (int64_t)it * 4, t0 = Gs * 16;
         const __amdgpu_buffer_rsrc_t rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
+        const __amdgpu_buffer_rsrc_t rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
+        const __amdgpu_buffer_rsrc_t rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
 #pragma unroll
-        for (int d = 0; d < DMA_PER_WAVE; ++d) {
-            char *dst = (buf == 0 ? Bs0 : buf == 1 ? Bs1 : Bs2) + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2);
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)dst, 16, (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
-        }
+        for (int d = 0; d < B_DMA; ++d)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2)), 16,
+                                                     (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
+#pragma unroll
+        for (int d = 0; d < A_DMA; ++d)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wave * TM + 64 * d) * 16), 16, (int)a_src[d], 0, 0, 0);
+#pragma unroll
+        for (int d = 0; d < M_DMA; ++d)
+            if (M_LANES == 64 || lane < M_LANES)        // (a sub-dword direct load would still land one dword per lane)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + wave * TM * 2 + d * 256), 4, (int)m_src[d], 0, 0, 0);
     };
-    auto fetch = [&](int it, int buf, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
-        load_b(it, buf);
-        load_a(it, af, ix);
-    };
-    // Loads a wave issues per stage; with the fetch of stage s+2 issued before stage s is computed,
-    // "stage s+1 has landed" means: at most one stage's worth of this wave's loads still in flight.
-    constexpr int LOADS_PER_STAGE = DMA_PER_WAVE + 4 * AB;
-    auto next_stage_ready = [&]() {
+    // "stage `it` has landed" with the fetch of the following stage already issued: at most one
+    // stage's worth of this wave's loads still in flight ...
+    auto stage_ready = [&](int it, char *stage) {
         wait_vmcnt<LOADS_PER_STAGE>();
+        // A direct load whose source lies past the end of the tensor leaves its LDS bytes untouched.
+        // Wave w brought token group w of the stage (its 16 h rows, its vals fragments, its meta
+        // words): if that group does not exist, the wave clears what it would have brought.
+        if (g_begin + (int64_t)it * 4 + wave >= n_groups) {
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            for (int c = lane; c < 16 * CPR; c += 64) *(uint4 *)(stage + wave * 16 * (TN * 2) + c * 16) = z;
+            for (int c = lane; c < TM; c += 64) *(uint4 *)(stage + A_OFF + (wave * TM + c) * 16) = z;
+            for (int c = lane; c < TM / 8; c += 64) *(uint4 *)(stage + M_OFF + wave * TM * 2 + c * 16) = z;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
         // ... and every other wave's part of it too.  A bare barrier: __syncthreads() would add a
         // workgroup release fence, which the compiler implements by draining every direct-to-LDS
-        // load in flight (those of stage s+2 included).  The LDS reads of the stage just computed
-        // were drained by the lgkmcnt(0) of its last fragment, so its buffer may be refilled after this.
+        // load in flight (those of the next stage included).  The LDS reads of the stage just
+        // computed were drained by the lgkmcnt(0) of its last fragment, so its buffer may be
+        // refilled after this.
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
 
-    // lane's LDS read address pieces for the transposing reads (see the layout note above)
-    const int li = lane & 15, q4 = lane >> 4;
-    const int rd_row = (8 * (q4 >> 1) + (li >> 2)) * (TN * 2);     // + (32*ks + 16*(j>>1) + 4*(j&1)) rows
-    int rd_off[BB];
+    // lane's LDS read addresses inside a stage
+    const int li = lane & 15, q4 = lane >> 4, kg = lane >> 5;
+    const int rd_row = (8 * (q4 >> 1) + (li >> 2)) * (TN * 2);     // h: + (32*ks + 16*(j>>1) + 4*(j&1)) rows
+    uint32_t rd_b[BB];
 #pragma unroll
     for (int b = 0; b < BB; ++b)
-        rd_off[b] = rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8;
+        rd_b[b] = (uint32_t)(rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8);
+    const uint32_t rd_a = (uint32_t)(A_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 16);   // + (2*ks*TM + 32*a)*16
+    const uint32_t rd_m = (uint32_t)(M_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 2);    // + (2*ks*TM + 32*a)*2
 
-    const uint32_t lds_base[3] = {(uint32_t)(uintptr_t)(lptr_t)Bs0, (uint32_t)(uintptr_t)(lptr_t)Bs1, (uint32_t)(uintptr_t)(lptr_t)Bs2};
-    // one stage: the fragment of h for step (ks, b+1) is requested from LDS before the MFMAs of (ks, b) issue
-    auto compute = [&](int buf, Frag8 (&af)[2][AB], uint32_t (&ix)[2][AB]) {
-        uint32_t addr[BB];
+    // One stage.  LDS reads are issued in this order (the lgkmcnt waits count on it):
+    //   A/meta of step 0 (2*AB reads), h fragment 0 (4), A/meta of step 1 (2*AB), h fragment 1 (4);
+    //   after the MFMAs of fragment 0: fragment 2; after the MFMAs of fragment s: fragment s+3 (into the
+    //   registers those MFMAs have read).  Two fragments are always in flight ahead of the one consumed.
+    auto compute = [&](char *stage) {
+        const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)stage;
+        uint32_t addr_b[BB];
 #pragma unroll
-        for (int b = 0; b < BB; ++b) addr[b] = lds_base[buf] + (uint32_t)rd_off[b];
-        auto read_b = [&](int ks, int b, Frag16 &bf) {
-            constexpr int R = TN * 2;
-            if (ks == 0) {
-                bf.q[0] = lds_read_tr16<0 * R>(addr[b]);  bf.q[1] = lds_read_tr16<4 * R>(addr[b]);
-                bf.q[2] = lds_read_tr16<16 * R>(addr[b]); bf.q[3] = lds_read_tr16<20 * R>(addr[b]);
-            } else {
-                bf.q[0] = lds_read_tr16<32 * R>(addr[b]); bf.q[1] = lds_read_tr16<36 * R>(addr[b]);
-                bf.q[2] = lds_read_tr16<48 * R>(addr[b]); bf.q[3] = lds_read_tr16<52 * R>(addr[b]);
-            }
+        for (int b = 0; b < BB; ++b) addr_b[b] = base + rd_b[b];
+        const uint32_t addr_a = base + rd_a, addr_m = base + rd_m;
+        Frag8 af[2][AB];
+        uint32_t ix[2][AB];
+        Frag16 bf[3];
+        auto read_a = [&](auto ks_c) {
+            constexpr int ks = decltype(ks_c)::value;
+            static_for<AB>([&](auto a_c) {
+                constexpr int a = decltype(a_c)::value;
+                af[ks][a].u4 = lds_read_b128<(2 * ks * TM + 32 * a) * 16>(addr_a);
+                ix[ks][a] = lds_read_u16<(2 * ks * TM + 32 * a) * 2>(addr_m);
+            });
         };
-        Frag16 bf[2];
-        read_b(0, 0, bf[0]);
-#pragma unroll
-        for (int s = 0; s < 2 * BB; ++s) {
-            const int ks = s / BB, b = s % BB;
-            const bool last = s + 1 == 2 * BB;
-            if (!last) read_b((s + 1) / BB, (s + 1) % BB, bf[(s + 1) & 1]);
-#pragma unroll
-            for (int a = 0; a < AB; ++a) {
-                if (a > 0)     smfmac_32x32x32<0>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
-                else if (last) smfmac_32x32x32<1>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
-                else           smfmac_32x32x32<5>(acc[a][b], af[ks][a].v, bf[s & 1].v, ix[ks][a]);
-            }
-        }
+        auto read_b = [&](auto s_c, Frag16 &f) {
+            constexpr int s = decltype(s_c)::value, ks = s / BB, b = s % BB, R = TN * 2;
+            f.q[0] = lds_read_tr16<(32 * ks + 0) * R>(addr_b[b]);
+            f.q[1] = lds_read_tr16<(32 * ks + 4) * R>(addr_b[b]);
+            f.q[2] = lds_read_tr16<(32 * ks + 16) * R>(addr_b[b]);
+            f.q[3] = lds_read_tr16<(32 * ks + 20) * R>(addr_b[b]);
+        };
+        constexpr int NF = 2 * BB;                          // h fragments per stage
+        read_a(std::integral_constant<int, 0>{});
+        read_b(std::integral_constant<int, 0>{}, bf[0]);
+        read_a(std::integral_constant<int, 1>{});
+        read_b(std::integral_constant<int, 1>{}, bf[1]);
+        static_for<NF>([&](auto s_c) {
+            constexpr int s = decltype(s_c)::value, ks = s / BB, b = s % BB;
+            // reads that may still be outstanding when fragment s is consumed: the two fragments after it;
+            // for the first one, fragment 1 and the A/meta reads of step 1 (the counter holds 15 at most)
+            constexpr int ahead = NF - 1 - s < 2 ? NF - 1 - s : 2;
+            constexpr int pending = s == 0 ? 2 * AB + 4 : 4 * ahead;
+            static_for<AB>([&](auto a_c) {
+                constexpr int a = decltype(a_c)::value;
+                if constexpr (a == 0) smfmac_32x32x32<pending>(acc[a][b], af[ks][a].v, bf[s % 3].v, ix[ks][a]);
+                else                  smfmac_32x32x32<-1>(acc[a][b], af[ks][a].v, bf[s % 3].v, ix[ks][a]);
+            });
+            if constexpr (s == 0 && 2 < NF) read_b(std::integral_constant<int, 2>{}, bf[2]);
+            if constexpr (s + 3 < NF) read_b(std::integral_constant<int, s + 3>{}, bf[s % 3]);
+        });
     };
 
-    // Three register sets for the sparse operand and three LDS buffers, rotating by stage: while
-    // stage s is computed, the loads of stages s+1 and s+2 are in flight (about two stages of MFMA
-    // work, ~2000 cycles, cover the memory latency of a wave that has no sibling on its SIMD).
-    // Straight-line loop body, three stages per trip.  Stages past the end of the tensor read as
-    // zeros (buffer bounds), so the stage count is padded to a multiple of three with all-zero
-    // stages and the fetches that run ahead of the last stage need no guard.  (Split-K slabs other
-    // than the last hold a multiple of three stages: see make_plan.)
-    Frag8 a0[2][AB], a1[2][AB], a2[2][AB];
-    uint32_t i0[2][AB], i1[2][AB], i2[2][AB];
+    // Three LDS stages rotating: while stage s is computed, the loads of stages s+1 and s+2 are in
+    // flight (about two stages of MFMA work, ~2000 cycles, cover the memory latency of a wave that
+    // has no sibling on its SIMD).  Straight-line loop body, three stages per trip.  Stages past the
+    // end of the tensor read as zeros (buffer bounds), so the stage count is padded to a multiple
+    // of three with all-zero stages and the fetches that run ahead of the last stage need no guard.
+    // (Split-K slabs other than the last hold a multiple of three stages: see make_plan.)
     const int n_trips = (n_iters + 2) / 3;
     if (n_trips > 0) {
-        fetch(0, 0, a0, i0);
-        fetch(1, 1, a1, i1);
-        next_stage_ready();
+        fetch(0, S0);
+        fetch(1, S1);
+        stage_ready(0, S0);
     }
     for (int tr = 0; tr < n_trips; ++tr) {
         const int it = 3 * tr;
-        fetch(it + 2, 2, a2, i2);
-        compute(0, a0, i0);
-        next_stage_ready();
-        fetch(it + 3, 0, a0, i0);
-        compute(1, a1, i1);
-        next_stage_ready();
-        fetch(it + 4, 1, a1, i1);
-        compute(2, a2, i2);
-        next_stage_ready();
+        fetch(it + 2, S2);
+        compute(S0);
+        stage_ready(it + 1, S1);
+        fetch(it + 3, S0);
+        compute(S1);
+        stage_ready(it + 2, S2);
+        fetch(it + 4, S1);
+        compute(S2);
+        stage_ready(it + 3, S0);
     }
 
     // ---- epilogue.  The matrix pipeline may still be writing the last accumulators, and the
     // compiler cannot see MFMAs inside asm statements: idle for longer than an 8-pass
     // instruction before the first read of an accumulation register.
     asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    const int64_t o0 = m0 + wm * (AB * 32);
 #pragma unroll
     for (int a = 0; a < AB; ++a)
 #pragma unroll
