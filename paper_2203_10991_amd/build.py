@@ -23,6 +23,8 @@ def sources():
 
 def build(force: bool = True, verbose: bool = False) -> str:
     os.makedirs(OBJ, exist_ok=True)
+    if os.path.exists(LIB):
+        os.remove(LIB)            # never leave a stale library behind a failed build
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
     srcs = sources()
     headers = [os.path.join(CSRC, f) for f in os.listdir(CSRC) if f.endswith(".h")]

@@ -71,6 +71,17 @@ __device__ __forceinline__ uint32_t bf16_bits_rne(float f)
     const uint32_t b = __float_as_uint(f);
     return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
 }
+// two binary32 -> packed bf16 (lo, hi), round to nearest even: one v_cvt_pk_bf16_f32
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
+{
+    const f32x2_t v = {lo, hi};
+    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
+    uint32_t u;
+    __builtin_memcpy(&u, &b, 4);
+    return u;
+}
 
 // ------------------------------------------------------------------------------------
 // MVUE 1:2 on one pair: returns kept position (0/1) and the kept value (unrounded).
@@ -150,6 +161,7 @@ __device__ __forceinline__ void select_2of4(float x0, float x1, float x2, float 
     const float c23 = case12 ? (c14 + n23) : a1;
     const float c24 = case12 ? 4.0f * s12 : s12;
 
+    // the first threshold above t decides the pair: 13, 14, 23, 24, else 34
     uint32_t ta, tb;
     if (t < c13)      { ta = t1; tb = t3; }
     else if (t < c14) { ta = t1; tb = t4; }
@@ -241,10 +253,10 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             uint4 o;
-            o.x = bf16_bits_rne(kept[c][0]) | (bf16_bits_rne(kept[c][1]) << 16);
-            o.y = bf16_bits_rne(kept[c][2]) | (bf16_bits_rne(kept[c][3]) << 16);
-            o.z = bf16_bits_rne(kept[c][4]) | (bf16_bits_rne(kept[c][5]) << 16);
-            o.w = bf16_bits_rne(kept[c][6]) | (bf16_bits_rne(kept[c][7]) << 16);
+            o.x = pack_bf16_rne(kept[c][0], kept[c][1]);
+            o.y = pack_bf16_rne(kept[c][2], kept[c][3]);
+            o.z = pack_bf16_rne(kept[c][4], kept[c][5]);
+            o.w = pack_bf16_rne(kept[c][6], kept[c][7]);
             ((uint4 *)vp)[c] = o;
         }
     }
