@@ -40,10 +40,10 @@ def read_traffic(workload: str, kernel: str):
 
 
 def cpu_baseline(w):
-    """The oracle, as it stands, on a slice of the workload: first 8192 tokens x 2048 out x 4096 in."""
+    """The oracle, as it stands, on a slice of the workload: first 16384 tokens x 4096 out x 4096 in."""
     from oracle import cwrap as oracle
     from paper_2203_10991_amd import synth
-    s = synth.scaled(w, T=min(w.T, 8192), O=min(w.O, 2048), I=min(w.I, 4096), name=w.name + "_slice")
+    s = synth.scaled(w, T=min(w.T, 16384), O=min(w.O, 4096), I=min(w.I, 4096), name=w.name + "_slice")
     g, h = synth.make_g(s, 0), synth.make_h(s, 0)
     prune = oracle.prune_1of2 if s.nm == "1:2" else oracle.prune_2of4
     t0 = time.perf_counter()

@@ -1,0 +1,86 @@
+"""GPU parity at the benchmark's full size (large decoder-MLP workload, MVUE 2:4, bf16), in the launch
+configuration bench.py times.  The tensors are drawn on the device, copied to the host, and the CPU
+oracle computes its own prune output from them:
+  * vals / meta of the whole tensor: bit for bit;
+  * dW: 4096 sampled entries as fp64 dot products over all tokens, one full 256x256 output tile, and a
+    Freivalds identity  dW x  ==  theta(g)^T (h x)  for random x (covers every entry).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2203_10991_amd import synth
+from gpu_util import DEV, to_host
+
+pytestmark = pytest.mark.gpu
+NAME = "c5_decoder_mlp_2of4"
+
+
+@pytest.fixture(scope="module")
+def case(oracle):
+    import paper_2203_10991_amd as nm
+    nm.load()
+    w = synth.WORKLOADS[NAME]
+    print(f"full size {w.name}: T={w.T} O={w.O} I={w.I}", flush=True)
+    g, h = synth.make_device(w, seed=0, device=DEV)
+    vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, DEV)
+    nm.mvue_prune_2of4(g, seed=0, stream_id=0, vals=vals, meta=meta)
+    dW = torch.empty((w.O, w.I), dtype=torch.float32, device=DEV)
+    need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
+    ws = torch.empty(max(need, 16), dtype=torch.uint8, device=DEV)
+    nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+    torch.cuda.synchronize()
+    g_host, h_host = to_host(g), to_host(h)
+    del g
+    print("oracle prune of the full tensor ...", flush=True)
+    ov, om, _ = oracle.prune_2of4(g_host, 0, 0)
+    del g_host
+    return dict(w=w, vals=vals, meta=meta, dW=dW, h=h, h_host=h_host, ov=ov, om=om)
+
+
+def test_full_tensor_masks_and_values_bit_exact(case):
+    assert np.array_equal(to_host(case["meta"]), case["om"])
+    assert np.array_equal(to_host(case["vals"]), case["ov"])
+
+
+def test_sampled_entries_and_one_tile(case, oracle):
+    w, dW = case["w"], case["dW"]
+    rng = np.random.default_rng(0)
+    cols = rng.choice(w.O, size=256, replace=False)
+    oi = np.stack([np.repeat(cols, 16), rng.integers(0, w.I, size=256 * 16)], axis=1)
+    want, wabs = oracle.update_gemm_entries(case["ov"], case["om"], case["h_host"], oi)
+    got = dW[torch.from_numpy(oi[:, 0]).to(DEV), torch.from_numpy(oi[:, 1]).to(DEV)].cpu().numpy().astype(np.float64)
+    rel = np.abs(got - want) / np.maximum(wabs, 1e-300)
+    print(f"4096 sampled entries: max |err|/sum|ab| = {rel.max():.3e}", flush=True)
+    assert rel.max() <= 1e-2
+    # one full 256 x 256 output tile (a ragged place: last tile row, second tile column)
+    o0, i0 = w.O - 256, 256
+    ov = np.ascontiguousarray(case["ov"][:, o0:o0 + 256]); om = np.ascontiguousarray(case["om"][:, o0:o0 + 256])
+    hs = np.ascontiguousarray(case["h_host"][:, i0:i0 + 256])
+    want, wabs = oracle.update_gemm(ov, om, hs)
+    got = dW[o0:o0 + 256, i0:i0 + 256].cpu().numpy().astype(np.float64)
+    rel = np.abs(got - want) / np.maximum(wabs, 1e-300)
+    fro = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"256x256 tile: max |err|/sum|ab| = {rel.max():.3e}, frobenius = {fro:.3e}", flush=True)
+    assert rel.max() <= 1e-2 and fro <= 1e-2
+
+
+def test_freivalds_identity_over_every_entry(case, oracle):
+    w, dW = case["w"], case["dW"]
+    rng = np.random.default_rng(1)
+    hf = synth.bf16_to_f32(case["h_host"])                      # [T, I] float32 (exact)
+    dense = oracle.nm_decompress(case["ov"], case["om"])        # oracle's own operand, [T, O] bf16 bits
+    for trial in range(2):
+        x = rng.choice([-1.0, 1.0], size=w.I)
+        hx = hf.astype(np.float64) @ x                          # [T]
+        want = np.zeros(w.O)
+        scale = np.zeros(w.O)
+        ahx = np.abs(hf).astype(np.float64).sum(1)              # sum_i |h_ti|
+        for a in range(0, w.T, 4096):                           # chunks: never hold an fp64 copy of theta(g)
+            blk = synth.bf16_to_f32(dense[a:a + 4096]).astype(np.float64)
+            want += blk.T @ hx[a:a + 4096]
+            scale += np.abs(blk).T @ ahx[a:a + 4096]
+        got = (dW.double() @ torch.from_numpy(x).to(DEV)).cpu().numpy()
+        rel = np.abs(got - want) / np.maximum(scale, 1e-300)
+        print(f"Freivalds trial {trial}: max |dW x - theta(g)^T h x| / sum|ab| = {rel.max():.3e}", flush=True)
+        assert rel.max() <= 1e-2
