@@ -114,7 +114,7 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //                             global memory for a fixed group: read back with one ds_read_b128 per fragment)
 //   [.., +8*TM)               meta words, [4 token groups][TM rows] x 2 bytes
 template <int WM, int WN, int AB, int BB>
-__global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
+__global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride,       // out + z*slab_stride
     int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate)
@@ -122,10 +122,16 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
     constexpr int CPR = TN / 8;                           // 16-byte chunks per h row in LDS
     constexpr int ROWS_PER_DMA = 64 / CPR;                // h rows one wave-wide 16-byte direct load covers
-    constexpr int B_DMA = KT / (4 * ROWS_PER_DMA);        // direct loads per wave per stage: h tile
-    constexpr int A_DMA = TM / 64;                        //   vals: wave w brings token group w, 64 rows per load
-    constexpr int M_DMA = TM >= 128 ? TM / 128 : 1;      //   meta: wave w brings group w, 2 words (4 bytes) per lane;
-    constexpr int M_LANES = TM >= 128 ? 64 : TM / 2;      //   a 64-row tile needs only the first 32 lanes
+    constexpr int NW = WM * WN;                           // waves: 4 (one per SIMD) or 8 (two per SIMD)
+    constexpr int WPG = NW / 4;                           // waves that share one of the stage's 4 token groups
+    constexpr int B_ROWS = KT / NW;                       // h rows a wave brings per stage
+    constexpr int A_ROWS = TM / WPG;                      // tile rows a wave brings (vals and meta) of its token group
+    constexpr int B_DMA = B_ROWS / ROWS_PER_DMA;          // direct loads per wave per stage: h tile
+    constexpr int A_DMA = A_ROWS / 64;                    //   vals: 64 rows (16 bytes each) per load
+    constexpr int M_DMA = A_ROWS >= 128 ? A_ROWS / 128 : 1;   //   meta: 2 words (4 bytes) per lane;
+    constexpr int M_LANES = A_ROWS >= 128 ? 64 : A_ROWS / 2;  //   a 64-row share needs only the first 32 lanes
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(B_DMA >= 1 && A_DMA >= 1, "tile too small for this wave count");
     constexpr int LOADS_PER_STAGE = B_DMA + A_DMA + M_DMA;
     constexpr int A_OFF = 128 * TN, M_OFF = A_OFF + 64 * TM, STAGE_BYTES = (M_OFF + 8 * TM + 1023) / 1024 * 1024;
     static_assert(CPR >= 16 && CPR <= 64, "tile width");
@@ -152,10 +158,12 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
             // in a short band the slots are re-dealt over rows_here rows (all slots of the band stay valid: per XCD
             // the band holds rows_here*nx tiles, and slots beyond them belong to no tile of this XCD)
             const int full_bands = tiles_m / band_rows;
-            if (band < full_bands) { tm = band * band_rows + local % band_rows; tn = xcd * nx + local / band_rows; }
+            // N-tile index fastest: tiles that share an h strip AND tiles that share a vals strip start within a few
+            // dispatches of each other, so both kinds of sharing are live in the L2 from the first stage on
+            if (band < full_bands) { tm = band * band_rows + local / nx; tn = xcd * nx + local % nx; }
             else {
                 const int l2 = slot - full_bands * per_band;            // index inside the short band
-                tm = full_bands * band_rows + l2 % rows_here; tn = xcd * nx + l2 / rows_here;
+                tm = full_bands * band_rows + l2 / nx; tn = xcd * nx + l2 % nx;
             }
         } else {
             // fallback: contiguous run of tiles per XCD when the count divides evenly, N-fastest inside bands of 8 M-tiles
@@ -199,11 +207,12 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
 
     // per-lane source offsets (bytes, relative to the stage).  Rows >= O and columns >= I are clamped
     // to the last valid ones: their products land in outputs that are never stored.
+    const int wgrp = wave / WPG, wsub = wave % WPG;          // this wave's token group of the stage, and its share of the rows
     uint32_t a_src[A_DMA], m_src[M_DMA];
 #pragma unroll
-    for (int d = 0; d < A_DMA; ++d) a_src[d] = (uint32_t)(wave * O + min(m0 + 64 * d + lane, O - 1)) * 16u;
+    for (int d = 0; d < A_DMA; ++d) a_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 64 * d + lane, O - 1)) * 16u;
 #pragma unroll
-    for (int d = 0; d < M_DMA; ++d) m_src[d] = (uint32_t)(wave * O + min(m0 + 128 * d + 2 * lane, O - 2)) * 2u;
+    for (int d = 0; d < M_DMA; ++d) m_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 128 * d + 2 * lane, O - 2)) * 2u;
     // h: direct load d of this wave fills rows  wave*16 + d*ROWS_PER_DMA + lane/CPR  at chunk position
     // lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 4*(row%4).
     constexpr int PHASES = ROWS_PER_DMA >= 4 ? 1 : 4 / ROWS_PER_DMA;
@@ -213,7 +222,7 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
     for (int ph = 0; ph < PHASES; ++ph) {
         const int row_mod4 = (ph * ROWS_PER_DMA + dma_row) & 3;
         const int64_t col = min(n0 + 8 * (dma_pos ^ (4 * row_mod4)), I - 8);
-        b_src[ph] = (uint32_t)(((int64_t)(wave * (KT / 4) + dma_row) * ldh + col) * 2);
+        b_src[ph] = (uint32_t)(((int64_t)(wave * B_ROWS + dma_row) * ldh + col) * 2);
     }
     const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh * 2);
 
@@ -224,28 +233,28 @@ __global__ __launch_bounds__(256) void update_gemm_smfmac_kernel(
         const __amdgpu_buffer_rsrc_t rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
 #pragma unroll
         for (int d = 0; d < B_DMA; ++d)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * (KT / 4) + d * ROWS_PER_DMA) * (TN * 2)), 16,
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * B_ROWS + d * ROWS_PER_DMA) * (TN * 2)), 16,
                                                      (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
 #pragma unroll
         for (int d = 0; d < A_DMA; ++d)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wave * TM + 64 * d) * 16), 16, (int)a_src[d], 0, 0, 0);
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + 64 * d) * 16), 16, (int)a_src[d], 0, 0, 0);
 #pragma unroll
         for (int d = 0; d < M_DMA; ++d)
             if (M_LANES == 64 || lane < M_LANES)        // (a sub-dword direct load would still land one dword per lane)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + wave * TM * 2 + d * 256), 4, (int)m_src[d], 0, 0, 0);
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + d * 256), 4, (int)m_src[d], 0, 0, 0);
     };
     // "stage `it` has landed" with the fetch of the following stage already issued: at most one
     // stage's worth of this wave's loads still in flight ...
     auto stage_ready = [&](int it, char *stage) {
         wait_vmcnt<LOADS_PER_STAGE>();
         // A direct load whose source lies past the end of the tensor leaves its LDS bytes untouched.
-        // Wave w brought token group w of the stage (its 16 h rows, its vals fragments, its meta
+        // Each wave brought a share of one token group of the stage (h rows, vals fragments, meta
         // words): if that group does not exist, the wave clears what it would have brought.
-        if (g_begin + (int64_t)it * 4 + wave >= n_groups) {
+        if (g_begin + (int64_t)it * 4 + wgrp >= n_groups) {
             const uint4 z = make_uint4(0, 0, 0, 0);
-            for (int c = lane; c < 16 * CPR; c += 64) *(uint4 *)(stage + wave * 16 * (TN * 2) + c * 16) = z;
-            for (int c = lane; c < TM; c += 64) *(uint4 *)(stage + A_OFF + (wave * TM + c) * 16) = z;
-            for (int c = lane; c < TM / 8; c += 64) *(uint4 *)(stage + M_OFF + wave * TM * 2 + c * 16) = z;
+            for (int c = lane; c < B_ROWS * CPR; c += 64) *(uint4 *)(stage + wave * B_ROWS * (TN * 2) + c * 16) = z;
+            for (int c = lane; c < A_ROWS; c += 64) *(uint4 *)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + c) * 16) = z;
+            for (int c = lane; c < A_ROWS / 8; c += 64) *(uint4 *)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + c * 16) = z;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         // ... and every other wave's part of it too.  A bare barrier: __syncthreads() would add a
@@ -429,10 +438,10 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
     if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
-    hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB>), grid, dim3(256), 0, st, (const uint16_t *)vals,   \
+    hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, (const uint16_t *)vals,   \
                        meta, (const uint16_t *)h, ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I,         \
                        p.tiles_m, p.tiles_n, acc_flag)
-    if (p.shape == 0) NM_LAUNCH(2, 2, 4, 4);
+    if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
     else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
     else NM_LAUNCH(1, 4, 2, 2);
 #undef NM_LAUNCH
