@@ -106,6 +106,8 @@ int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, 
  * and expands the operand on the fly for dense fp32 MFMA.
  *   workspace    device scratch of at least nm_update_gemm_workspace(T,O,I,dtype) bytes
  *                (split-K partial sums); may be NULL when that size is 0.
+ * O and ldh may not exceed 2^21 (NM_ERR_UNSUPPORTED): the kernels reach a few hundred rows of h
+ * and a few dozen token groups of vals through 32-bit byte offsets.
  */
 int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
                    float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, int dtype, float beta,

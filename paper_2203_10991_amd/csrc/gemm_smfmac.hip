@@ -12,14 +12,15 @@
 //      16 lanes).
 //   D  reg r of lane l = row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 //
-// Workgroup = 4 waves (WM x WN), one per SIMD, each owning AB x BB accumulator blocks of 32x32
-// (256 accumulation registers for the 128x128 wave tile).  The reduction axis advances in stages
-// of 64 tokens.  Every operand byte of a stage -- the h tile, the `vals` fragments and the `meta`
-// words of the tile's rows -- is brought from global memory by direct global->LDS loads, once
-// per workgroup (the per-CU vector-memory path, 64 B/clk, is the scarce resource: loading the
-// sparse operand per wave would fetch it twice).  Three stages are in flight; one barrier per
-// stage.  Split-K over blockIdx.z writes binary32 partials that a second kernel sums in a fixed
-// order (deterministic; no atomics).
+// Workgroup = WM x WN waves (4: one per SIMD, or 8: two per SIMD), each owning AB x BB accumulator
+// blocks of 32x32 in accumulation registers.  The reduction axis advances in stages of 32 tokens (one
+// MFMA step).  Every operand byte of a stage -- the h tile, the `vals` fragments and the `meta` words
+// of the tile's rows -- is brought from global memory by direct global->LDS loads, once per workgroup
+// (the per-CU vector-memory path, 64 B/clk, is the scarce resource: loading the sparse operand per
+// wave would fetch it once per wave column).  Six stages rotate through LDS, one barrier per stage; the
+// operand registers are double-buffered so that LDS reads of the next stage run under the MFMAs of the
+// current one.  Split-K over blockIdx.z writes binary32 partials that a second kernel sums in a
+// fixed order (deterministic; no atomics).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -36,7 +37,8 @@ typedef float f32x16 __attribute__((ext_vector_type(16)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
-constexpr int KT = 64;            // tokens per LDS stage (two 32-token MFMA steps, four 16-token groups)
+constexpr int KT = 32;            // tokens per LDS stage (one 32-token MFMA step, two 16-token groups)
+constexpr int NS = 6;             // LDS stages: one being consumed, one landed, four in flight
 
 union Frag16 { bf16x16 v; s16x4 q[4]; };
 union Frag8 { bf16x8 v; u32x4 u4; };
@@ -59,21 +61,22 @@ template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
 // definition of an accumulator is an asm statement with an AGPR operand:
 //   acc_zero   D = 0*0 + 0 with a dense MFMA (inline-constant C): writes 16 AGPRs at once
 //   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B, optionally preceded by
-//              a wait until at most LGKM LDS reads are outstanding (LGKM < 0: no wait)
+//              a wait until at most LGKM LDS reads are outstanding (LGKM < 0: no wait); ABID picks the
+//              half of idx that holds the index word
 __device__ __forceinline__ void acc_zero(f32x16 &acc)
 {
     const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     // (the compiler does not know this asm is an MFMA: keep the required distance from the VALU moves that write z)
     asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
 }
-template <int LGKM>
+template <int LGKM, int ABID>
 __device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
 {
-    if constexpr (LGKM < 0)
+    if constexpr (LGKM >= 0) asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(LGKM));
+    if constexpr (ABID == 0)
         asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
     else
-        asm volatile("s_waitcnt lgkmcnt(%4)\n\tv_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3"
-                     : "+a"(acc) : "v"(a), "v"(b), "v"(idx), "n"(LGKM));
+        asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
 }
 
 // LDS reads are issued as asm so that the compiler does not order them against the direct
@@ -91,10 +94,17 @@ template <int OFFSET> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t ad
     asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
     return r;
 }
-template <int OFFSET> __device__ __forceinline__ uint32_t lds_read_u16(uint32_t addr)
+template <int OFFSET> __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr)
 {
     uint32_t r;
-    asm volatile("ds_read_u16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr)
+{
+    u32x2 r;
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
     return r;
 }
 
@@ -106,13 +116,12 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 }
 
 // LDS image of one stage (all filled by direct loads, 64 consecutive lanes -> consecutive LDS bytes):
-//   [0, 128*TN)               h tile, [64 tokens][TN columns] bf16, rows unpadded.  Bank conflicts of the
+//   [0, 64*TN)                h tile, [32 tokens][TN columns] bf16, rows unpadded.  Bank conflicts of the
 //                             transposing reads are avoided by a swizzle: 16-byte chunk c of row k sits at
 //                             chunk position c ^ (4*(k%4)) (a transposing read touches, per 16 lanes, the
 //                             same 32-byte column window of 4 consecutive rows).
-//   [128*TN, +64*TM)          vals fragments, [4 token groups][TM rows] x 16 bytes (the layout they have in
-//                             global memory for a fixed group: read back with one ds_read_b128 per fragment)
-//   [.., +8*TM)               meta words, [4 token groups][TM rows] x 2 bytes
+//   [64*TN, +32*TM)           vals fragments, [2 token groups][TM slots] x 16 bytes, one ds_read_b128 per fragment
+//   [.., +4*TM)               meta words, [2 token groups][TM rows] x 2 bytes
 template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
@@ -123,22 +132,36 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     constexpr int CPR = TN / 8;                           // 16-byte chunks per h row in LDS
     constexpr int ROWS_PER_DMA = 64 / CPR;                // h rows one wave-wide 16-byte direct load covers
     constexpr int NW = WM * WN;                           // waves: 4 (one per SIMD) or 8 (two per SIMD)
-    constexpr int WPG = NW / 4;                           // waves that share one of the stage's 4 token groups
+    constexpr int WPG = NW / 2;                           // waves that share one of the stage's 2 token groups
     constexpr int B_ROWS = KT / NW;                       // h rows a wave brings per stage
     constexpr int A_ROWS = TM / WPG;                      // tile rows a wave brings (vals and meta) of its token group
     constexpr int B_DMA = B_ROWS / ROWS_PER_DMA;          // direct loads per wave per stage: h tile
-    constexpr int A_DMA = A_ROWS / 64;                    //   vals: 64 rows (16 bytes each) per load
+    constexpr int A_DMA = A_ROWS >= 64 ? A_ROWS / 64 : 1;     //   vals: 64 rows (16 bytes each) per load,
+    constexpr int A_LANES = A_ROWS >= 64 ? 64 : A_ROWS;       //   or the first A_ROWS lanes of one
     constexpr int M_DMA = A_ROWS >= 128 ? A_ROWS / 128 : 1;   //   meta: 2 words (4 bytes) per lane;
-    constexpr int M_LANES = A_ROWS >= 128 ? 64 : A_ROWS / 2;  //   a 64-row share needs only the first 32 lanes
+    constexpr int M_LANES = A_ROWS >= 128 ? 64 : A_ROWS / 2;  //   (a sub-dword direct load would still land one dword per lane)
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
-    static_assert(B_DMA >= 1 && A_DMA >= 1, "tile too small for this wave count");
+    static_assert(B_DMA >= 1 && B_ROWS % 4 == 0 && A_ROWS >= 16, "tile too small for this wave count");
     constexpr int LOADS_PER_STAGE = B_DMA + A_DMA + M_DMA;
-    constexpr int A_OFF = 128 * TN, M_OFF = A_OFF + 64 * TM, STAGE_BYTES = (M_OFF + 8 * TM + 1023) / 1024 * 1024;
+    constexpr int A_OFF = 64 * TN, M_OFF = A_OFF + 32 * TM, STAGE_BYTES = (M_OFF + 4 * TM + 1023) / 1024 * 1024;
     static_assert(CPR >= 16 && CPR <= 64, "tile width");
-    // three separate arrays: one per stage in flight
+    static_assert(NS * STAGE_BYTES <= 160 * 1024, "LDS");
+    // separate arrays: one per stage in flight
     __shared__ __attribute__((aligned(1024))) char S0[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char S1[STAGE_BYTES];
     __shared__ __attribute__((aligned(1024))) char S2[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char S3[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char S4[STAGE_BYTES];
+    __shared__ __attribute__((aligned(1024))) char S5[STAGE_BYTES];
+    auto buf = [&](auto u_c) -> char * {
+        constexpr int u = decltype(u_c)::value % NS;
+        if constexpr (u == 0) return S0;
+        else if constexpr (u == 1) return S1;
+        else if constexpr (u == 2) return S2;
+        else if constexpr (u == 3) return S3;
+        else if constexpr (u == 4) return S4;
+        else return S5;
+    };
 
     // ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), 32 CUs and one
     // L2 each.  Preferred map: the whole GPU works on ONE band of M-tiles at a time, XCD x owning the N-tiles
@@ -193,11 +216,11 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
 #pragma unroll
         for (int b = 0; b < BB; ++b) acc_zero(acc[a][b]);
 
-    const int n_iters = (int)((g_end - g_begin + 3) / 4);      // stages of 4 token groups; the last may be ragged
+    const int n_iters = (int)((g_end - g_begin + 1) / 2);      // stages of 2 token groups; the last may be ragged
 
-    // All global reads go through raw buffer descriptors that are re-based to the current stage:
+    // All global reads go through raw buffer descriptors that are re-based as the kernel advances:
     // a 32-bit per-lane offset is all a load needs, and a load from past the end of the tensor (the
-    // token groups a ragged last stage lacks) is dropped by the bounds check instead of faulting.
+    // token group a ragged last stage lacks) is dropped by the bounds check instead of faulting.
     // Split-K slabs are whole stages except the last, so a ragged stage only occurs at the tensor's end.
     auto rsrc = [](const void *base, int64_t bytes) {
         const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
@@ -210,10 +233,17 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const int wgrp = wave / WPG, wsub = wave % WPG;          // this wave's token group of the stage, and its share of the rows
     uint32_t a_src[A_DMA], m_src[M_DMA];
 #pragma unroll
-    for (int d = 0; d < A_DMA; ++d) a_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 64 * d + lane, O - 1)) * 16u;
+    for (int d = 0; d < A_DMA; ++d) {
+        // LDS slot q of a token group holds tile row  slot_row(q): inside each wave-row block of AB*32 rows, the 32 rows
+        // that feed accumulator block a (rows a, AB+a, 2AB+a, ...) are stored next to each other
+        const int q = wsub * A_ROWS + 64 * d + (lane % A_LANES);
+        const int row = (q / (AB * 32)) * (AB * 32) + AB * (q % 32) + (q % (AB * 32)) / 32;
+        a_src[d] = (uint32_t)(wgrp * O + min(m0 + row, O - 1)) * 16u;
+    }
 #pragma unroll
-    for (int d = 0; d < M_DMA; ++d) m_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 128 * d + 2 * lane, O - 2)) * 2u;
-    // h: direct load d of this wave fills rows  wave*16 + d*ROWS_PER_DMA + lane/CPR  at chunk position
+    for (int d = 0; d < M_DMA; ++d)
+        m_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 128 * d + 2 * (lane % M_LANES), O - 2)) * 2u;
+    // h: direct load d of this wave fills rows  wave*B_ROWS + d*ROWS_PER_DMA + lane/CPR  at chunk position
     // lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 4*(row%4).
     constexpr int PHASES = ROWS_PER_DMA >= 4 ? 1 : 4 / ROWS_PER_DMA;
     uint32_t b_src[PHASES];
@@ -226,31 +256,44 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     }
     const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh * 2);
 
-    auto fetch = [&](int it, char *stage) {
-        const int64_t Gs = g_begin + (int64_t)it * 4, t0 = Gs * 16;
-        const __amdgpu_buffer_rsrc_t rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
-        const __amdgpu_buffer_rsrc_t rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
-        const __amdgpu_buffer_rsrc_t rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
+    // Buffer descriptors are re-based once per trip of NS stages (to the trip's first stage, with the exact
+    // number of bytes left in the tensor as the bound); a stage inside or ahead of the trip is reached through
+    // the per-lane offset.  U = stage number relative to the descriptors' stage, at most 2*NS-1.
+    __amdgpu_buffer_rsrc_t rh, rv, rm;
+    auto rebase = [&](int it) {
+        const int64_t Gs = g_begin + (int64_t)it * 2, t0 = Gs * 16;
+        rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
+        rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
+        rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
+    };
+    const uint32_t h_stage = (uint32_t)(KT * ldh * 2), v_stage = (uint32_t)(2 * O * 16), m_stage = (uint32_t)(2 * O * 2);
+    auto fetch = [&](auto u_c, char *stage) {
+        constexpr uint32_t U = decltype(u_c)::value;
 #pragma unroll
         for (int d = 0; d < B_DMA; ++d)
             __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * B_ROWS + d * ROWS_PER_DMA) * (TN * 2)), 16,
-                                                     (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step), 0, 0, 0);
+                                                     (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step + U * h_stage), 0, 0, 0);
 #pragma unroll
         for (int d = 0; d < A_DMA; ++d)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + 64 * d) * 16), 16, (int)a_src[d], 0, 0, 0);
+            if (A_LANES == 64 || lane < A_LANES)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + 64 * d) * 16), 16,
+                                                         (int)(a_src[d] + U * v_stage), 0, 0, 0);
 #pragma unroll
         for (int d = 0; d < M_DMA; ++d)
-            if (M_LANES == 64 || lane < M_LANES)        // (a sub-dword direct load would still land one dword per lane)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + d * 256), 4, (int)m_src[d], 0, 0, 0);
+            if (M_LANES == 64 || lane < M_LANES)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + d * 256), 4,
+                                                         (int)(m_src[d] + U * m_stage), 0, 0, 0);
     };
-    // "stage `it` has landed" with the fetch of the following stage already issued: at most one
-    // stage's worth of this wave's loads still in flight ...
-    auto stage_ready = [&](int it, char *stage) {
-        wait_vmcnt<LOADS_PER_STAGE>();
+    // first stage (relative to the slab) in which this wave's token group lies past the end of the tensor
+    const int first_missing = (int)min((int64_t)0x7fffffff, (n_groups - g_begin - wgrp + 1) / 2);
+    // "stage `it` has landed" while the loads of the IN_FLIGHT stages fetched after it may still be on
+    // their way ...
+    auto stage_ready = [&](auto in_flight_c, int it, char *stage) {
+        wait_vmcnt<decltype(in_flight_c)::value * LOADS_PER_STAGE>();
         // A direct load whose source lies past the end of the tensor leaves its LDS bytes untouched.
         // Each wave brought a share of one token group of the stage (h rows, vals fragments, meta
         // words): if that group does not exist, the wave clears what it would have brought.
-        if (g_begin + (int64_t)it * 4 + wgrp >= n_groups) {
+        if (it >= first_missing) {
             const uint4 z = make_uint4(0, 0, 0, 0);
             for (int c = lane; c < B_ROWS * CPR; c += 64) *(uint4 *)(stage + wave * B_ROWS * (TN * 2) + c * 16) = z;
             for (int c = lane; c < A_ROWS; c += 64) *(uint4 *)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + c) * 16) = z;
@@ -259,101 +302,97 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
         }
         // ... and every other wave's part of it too.  A bare barrier: __syncthreads() would add a
         // workgroup release fence, which the compiler implements by draining every direct-to-LDS
-        // load in flight (those of the next stage included).  The LDS reads of the stage just
-        // computed were drained by the lgkmcnt(0) of its last fragment, so its buffer may be
-        // refilled after this.
+        // load in flight (those of the later stages included).
         __builtin_amdgcn_s_barrier();
         __builtin_amdgcn_sched_barrier(0);
     };
 
     // lane's LDS read addresses inside a stage
     const int li = lane & 15, q4 = lane >> 4, kg = lane >> 5;
-    const int rd_row = (8 * (q4 >> 1) + (li >> 2)) * (TN * 2);     // h: + (32*ks + 16*(j>>1) + 4*(j&1)) rows
+    const int rd_row = (8 * (q4 >> 1) + (li >> 2)) * (TN * 2);     // h: + (16*(j>>1) + 4*(j&1)) rows for read j of a fragment
     uint32_t rd_b[BB];
 #pragma unroll
     for (int b = 0; b < BB; ++b)
         rd_b[b] = (uint32_t)(rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8);
-    const uint32_t rd_a = (uint32_t)(A_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 16);   // + (2*ks*TM + 32*a)*16
-    const uint32_t rd_m = (uint32_t)(M_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 2);    // + (2*ks*TM + 32*a)*2
+    const uint32_t rd_a = (uint32_t)(A_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 16);       // + 32*a*16
+    const uint32_t rd_m = (uint32_t)(M_OFF + (kg * TM + wm * (AB * 32) + AB * (lane & 31)) * 2);   // AB consecutive words
 
-    // One stage.  LDS reads are issued in this order (the lgkmcnt waits count on it):
-    //   A/meta of step 0 (2*AB reads), h fragment 0 (4), A/meta of step 1 (2*AB), h fragment 1 (4);
-    //   after the MFMAs of fragment 0: fragment 2; after the MFMAs of fragment s: fragment s+3 (into the
-    //   registers those MFMAs have read).  Two fragments are always in flight ahead of the one consumed.
-    auto compute = [&](char *stage) {
+    // Operand registers: two sets.  While the MFMAs of a stage read one set, the LDS reads of the next
+    // stage fill the other, so the fragment pipeline never drains at a stage boundary.
+    static_assert(AB == 2 || AB == 4, "AB is 2 or 4");
+    Frag8 af[2][AB];
+    u32x2 ix2[2]; uint32_t ix1[2];          // index words as read, AB consecutive 16-bit words: the one that matches AB is used
+    Frag16 bf[2][BB];
+    constexpr int NR = AB + 1 + 4 * BB;     // LDS reads of one stage per wave
+    constexpr int NM = AB * BB;             // MFMAs of one stage per wave
+    static_assert(NR <= 15, "lgkmcnt is a 4-bit counter");
+    // read number r of a stage, in issue order: AB sparse fragments, the index words, 4 reads per h fragment
+    auto lds_read = [&](auto set_c, auto r_c, char *stage) {
+        constexpr int set = decltype(set_c)::value, r = decltype(r_c)::value, R = TN * 2;
         const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)stage;
-        uint32_t addr_b[BB];
-#pragma unroll
-        for (int b = 0; b < BB; ++b) addr_b[b] = base + rd_b[b];
-        const uint32_t addr_a = base + rd_a, addr_m = base + rd_m;
-        Frag8 af[2][AB];
-        uint32_t ix[2][AB];
-        Frag16 bf[3];
-        auto read_a = [&](auto ks_c) {
-            constexpr int ks = decltype(ks_c)::value;
-            static_for<AB>([&](auto a_c) {
-                constexpr int a = decltype(a_c)::value;
-                af[ks][a].u4 = lds_read_b128<(2 * ks * TM + 32 * a) * 16>(addr_a);
-                ix[ks][a] = lds_read_u16<(2 * ks * TM + 32 * a) * 2>(addr_m);
+        if constexpr (r < AB) af[set][r].u4 = lds_read_b128<32 * r * 16>(base + rd_a);
+        else if constexpr (r == AB) {
+            if constexpr (AB == 4) ix2[set] = lds_read_b64<0>(base + rd_m);
+            else                   ix1[set] = lds_read_b32<0>(base + rd_m);
+        } else {
+            constexpr int j = r - AB - 1, b = j / 4, qd = j % 4;
+            bf[set][b].q[qd] = lds_read_tr16<(16 * (qd >> 1) + 4 * (qd & 1)) * R>(base + rd_b[b]);
+        }
+    };
+    // One stage: its operands are in (or on their way into) register set SET; its MFMAs are
+    // interleaved with the LDS reads of the following stage (from `next`) into the other set.
+    auto consume = [&](auto set_c, char *next) {
+        constexpr int set = decltype(set_c)::value;
+        // every read of this stage was issued during the previous stage.  The wait names the index-word
+        // registers as an operand, so that the compiler cannot move their (its own) uses above it.
+        if constexpr (AB == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ix2[set]));
+        else                   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ix1[set]));
+        static_for<NM>([&](auto m_c) {
+            constexpr int m = decltype(m_c)::value, b = m / AB, a = m % AB;
+            uint32_t idx;
+            if constexpr (AB == 4) idx = ix2[set][a / 2];
+            else                   idx = ix1[set];
+            smfmac_32x32x32<-1, (a & 1)>(acc[a][b], af[set][a].v, bf[set][b].v, idx);
+            static_for<NR>([&](auto r_c) {
+                constexpr int r = decltype(r_c)::value;
+                if constexpr (r >= m * NR / NM && r < (m + 1) * NR / NM) lds_read(std::integral_constant<int, 1 - set>{}, r_c, next);
             });
-        };
-        auto read_b = [&](auto s_c, Frag16 &f) {
-            constexpr int s = decltype(s_c)::value, ks = s / BB, b = s % BB, R = TN * 2;
-            f.q[0] = lds_read_tr16<(32 * ks + 0) * R>(addr_b[b]);
-            f.q[1] = lds_read_tr16<(32 * ks + 4) * R>(addr_b[b]);
-            f.q[2] = lds_read_tr16<(32 * ks + 16) * R>(addr_b[b]);
-            f.q[3] = lds_read_tr16<(32 * ks + 20) * R>(addr_b[b]);
-        };
-        constexpr int NF = 2 * BB;                          // h fragments per stage
-        read_a(std::integral_constant<int, 0>{});
-        read_b(std::integral_constant<int, 0>{}, bf[0]);
-        read_a(std::integral_constant<int, 1>{});
-        read_b(std::integral_constant<int, 1>{}, bf[1]);
-        static_for<NF>([&](auto s_c) {
-            constexpr int s = decltype(s_c)::value, ks = s / BB, b = s % BB;
-            // reads that may still be outstanding when fragment s is consumed: the two fragments after it;
-            // for the first one, fragment 1 and the A/meta reads of step 1 (the counter holds 15 at most)
-            constexpr int ahead = NF - 1 - s < 2 ? NF - 1 - s : 2;
-            constexpr int pending = s == 0 ? 2 * AB + 4 : 4 * ahead;
-            static_for<AB>([&](auto a_c) {
-                constexpr int a = decltype(a_c)::value;
-                if constexpr (a == 0) smfmac_32x32x32<pending>(acc[a][b], af[ks][a].v, bf[s % 3].v, ix[ks][a]);
-                else                  smfmac_32x32x32<-1>(acc[a][b], af[ks][a].v, bf[s % 3].v, ix[ks][a]);
-            });
-            if constexpr (s == 0 && 2 < NF) read_b(std::integral_constant<int, 2>{}, bf[2]);
-            if constexpr (s + 3 < NF) read_b(std::integral_constant<int, s + 3>{}, bf[s % 3]);
         });
     };
 
-    // Three LDS stages rotating: while stage s is computed, the loads of stages s+1 and s+2 are in
-    // flight (about two stages of MFMA work, ~2000 cycles, cover the memory latency of a wave that
-    // has no sibling on its SIMD).  Straight-line loop body, three stages per trip.  Stages past the
-    // end of the tensor read as zeros (buffer bounds), so the stage count is padded to a multiple
-    // of three with all-zero stages and the fetches that run ahead of the last stage need no guard.
-    // (Split-K slabs other than the last hold a multiple of three stages: see make_plan.)
-    const int n_trips = (n_iters + 2) / 3;
+    // Six LDS stages rotating.  During stage j: stage j+1 has landed (its readiness barrier opens the
+    // slot), the loads of stages j+2 .. j+4 are in flight and those of stage j+5 are issued into the
+    // buffer that stage j-1 occupied -- every wave finished reading it before it arrived at this slot's
+    // barrier.  A load therefore has four stages of MFMA work (about two thousand cycles) to land.
+    // Straight-line loop body, six stages per trip.  Stages past the end of the tensor hold zeros
+    // (dropped loads, cleared shares), so the stage count is padded to a multiple of six with
+    // all-zero stages and the fetches and reads that run ahead of the last stage need no guard.
+    // (Split-K slabs other than the last hold a multiple of six stages: see make_plan.)
+    const int n_trips = (n_iters + NS - 1) / NS;
     if (n_trips > 0) {
-        fetch(0, S0);
-        fetch(1, S1);
-        stage_ready(0, S0);
+        rebase(0);
+        static_for<NS - 1>([&](auto u_c) { fetch(u_c, buf(u_c)); });
+        stage_ready(std::integral_constant<int, NS - 2>{}, 0, S0);
+        static_for<NR>([&](auto r_c) { lds_read(std::integral_constant<int, 0>{}, r_c, S0); });
     }
     for (int tr = 0; tr < n_trips; ++tr) {
-        const int it = 3 * tr;
-        fetch(it + 2, S2);
-        compute(S0);
-        stage_ready(it + 1, S1);
-        fetch(it + 3, S0);
-        compute(S1);
-        stage_ready(it + 2, S2);
-        fetch(it + 4, S1);
-        compute(S2);
-        stage_ready(it + 3, S0);
+        const int it = NS * tr;
+        rebase(it);
+        static_for<NS>([&](auto u_c) {
+            constexpr int u = decltype(u_c)::value;
+            stage_ready(std::integral_constant<int, NS - 3>{}, it + u + 1, buf(std::integral_constant<int, u + 1>{}));
+            fetch(std::integral_constant<int, u + NS - 1>{}, buf(std::integral_constant<int, u + NS - 1>{}));
+            consume(std::integral_constant<int, u % 2>{}, buf(std::integral_constant<int, u + 1>{}));
+        });
     }
 
     // ---- epilogue.  The matrix pipeline may still be writing the last accumulators, and the
     // compiler cannot see MFMAs inside asm statements: idle for longer than an 8-pass
     // instruction before the first read of an accumulation register.
-    asm volatile("s_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    // (The reads issued ahead for the stage after the last are drained first: their destination registers are dead.)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
     const int64_t o0 = m0 + wm * (AB * 32);
 #pragma unroll
     for (int a = 0; a < AB; ++a)
@@ -362,7 +401,7 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
             const int64_t col = n0 + wn * (BB * 32) + b * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
-                const int64_t row = o0 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
+                const int64_t row = o0 + AB * (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) + a;   // block a holds rows a, AB+a, ...
                 if (row < O && col < I) {
                     float *p = out + row * ldo + col;
                     *p = accumulate ? (*p + acc[a][b][r]) : acc[a][b][r];
@@ -412,7 +451,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
         if (slabs < 1) slabs = 1;
     }
     int64_t gps = (groups + slabs - 1) / slabs;
-    gps = (gps + 11) / 12 * 12;                                        // whole trips of three LDS stages
+    gps = (gps + 11) / 12 * 12;                                        // whole trips of six LDS stages
     if (gps < 12) gps = 12;
     p.groups_per_slab = gps;
     p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;

@@ -138,6 +138,9 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
     if (T > 0) {
         if (!vals || !meta || !h) return fail(NM_ERR_NULL, "%s: vals, meta and h must not be NULL", fn);
         if (ldh < I) return fail(NM_ERR_SHAPE, "%s: ldh=%lld is smaller than I=%lld", fn, (long long)ldh, (long long)I);
+        // the kernels address a few hundred rows of h, and a few dozen token groups of vals, through 32-bit byte offsets
+        if (ldh > (1 << 21) || O > (1 << 21))
+            return fail(NM_ERR_UNSUPPORTED, "%s: O=%lld and ldh=%lld must not exceed 2^21", fn, (long long)O, (long long)ldh);
         if (!aligned16(vals) || !aligned16(meta) || !aligned16(h) || (ldh * es) % 16)
             return fail(NM_ERR_ALIGN, "%s: vals, meta, h need 16-byte aligned bases (and h a 16-byte row stride)", fn);
         Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
