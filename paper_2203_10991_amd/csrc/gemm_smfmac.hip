@@ -120,8 +120,9 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
 //                             transposing reads are avoided by a swizzle: 16-byte chunk c of row k sits at
 //                             chunk position c ^ (4*(k%4)) (a transposing read touches, per 16 lanes, the
 //                             same 32-byte column window of 4 consecutive rows).
-//   [64*TN, +32*TM)           vals fragments, [2 token groups][TM slots] x 16 bytes, one ds_read_b128 per fragment
-//   [.., +4*TM)               meta words, [2 token groups][TM rows] x 2 bytes
+//   then                      vals fragments, [2 token groups][TM slots] x 16 bytes, one ds_read_b128 per fragment
+//   then                      meta words, [2 token groups][TM rows] x 2 bytes
+//                             (both as one share per wave, padded to a whole 64-lane load)
 template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
@@ -136,14 +137,20 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     constexpr int B_ROWS = KT / NW;                       // h rows a wave brings per stage
     constexpr int A_ROWS = TM / WPG;                      // tile rows a wave brings (vals and meta) of its token group
     constexpr int B_DMA = B_ROWS / ROWS_PER_DMA;          // direct loads per wave per stage: h tile
-    constexpr int A_DMA = A_ROWS >= 64 ? A_ROWS / 64 : 1;     //   vals: 64 rows (16 bytes each) per load,
-    constexpr int A_LANES = A_ROWS >= 64 ? 64 : A_ROWS;       //   or the first A_ROWS lanes of one
-    constexpr int M_DMA = A_ROWS >= 128 ? A_ROWS / 128 : 1;   //   meta: 2 words (4 bytes) per lane;
+    // Every direct load is issued by all 64 lanes (no divergent code in the main loop): a wave's share of the vals
+    // fragments is padded to 64 slots and its share of the meta words to 128; the lanes a short share does not
+    // need fetch duplicates into the padding.
+    constexpr int A_DMA = A_ROWS >= 64 ? A_ROWS / 64 : 1;     //   vals: 64 rows (16 bytes each) per load
+    constexpr int A_LANES = A_ROWS >= 64 ? 64 : A_ROWS;
+    constexpr int A_SLOTS = A_ROWS >= 64 ? A_ROWS : 64;       //   16-byte slots per share in LDS
+    constexpr int M_DMA = A_ROWS >= 128 ? A_ROWS / 128 : 1;   //   meta: 2 words (4 bytes) per lane
     constexpr int M_LANES = A_ROWS >= 128 ? 64 : A_ROWS / 2;  //   (a sub-dword direct load would still land one dword per lane)
+    constexpr int M_SLOTS = A_ROWS >= 128 ? A_ROWS : 128;     //   2-byte slots per share in LDS
     static_assert(NW == 4 || NW == 8, "4 or 8 waves");
     static_assert(B_DMA >= 1 && B_ROWS % 4 == 0 && A_ROWS >= 16, "tile too small for this wave count");
     constexpr int LOADS_PER_STAGE = B_DMA + A_DMA + M_DMA;
-    constexpr int A_OFF = 64 * TN, M_OFF = A_OFF + 32 * TM, STAGE_BYTES = (M_OFF + 4 * TM + 1023) / 1024 * 1024;
+    constexpr int A_OFF = 64 * TN, M_OFF = A_OFF + 2 * WPG * A_SLOTS * 16;
+    constexpr int STAGE_BYTES = (M_OFF + 2 * WPG * M_SLOTS * 2 + 1023) / 1024 * 1024;
     static_assert(CPR >= 16 && CPR <= 64, "tile width");
     static_assert(NS * STAGE_BYTES <= 160 * 1024, "LDS");
     // separate arrays: one per stage in flight
@@ -267,22 +274,22 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
         rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
     };
     const uint32_t h_stage = (uint32_t)(KT * ldh * 2), v_stage = (uint32_t)(2 * O * 16), m_stage = (uint32_t)(2 * O * 2);
-    auto fetch = [&](auto u_c, char *stage) {
+    // direct load number K (of LOADS_PER_STAGE) of the stage U stages past the descriptors' one
+    auto fetch_one = [&](auto u_c, auto k_c, char *stage) {
         constexpr uint32_t U = decltype(u_c)::value;
-#pragma unroll
-        for (int d = 0; d < B_DMA; ++d)
-            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * B_ROWS + d * ROWS_PER_DMA) * (TN * 2)), 16,
-                                                     (int)(b_src[d % PHASES] + (uint32_t)d * b_row_step + U * h_stage), 0, 0, 0);
-#pragma unroll
-        for (int d = 0; d < A_DMA; ++d)
-            if (A_LANES == 64 || lane < A_LANES)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + 64 * d) * 16), 16,
-                                                         (int)(a_src[d] + U * v_stage), 0, 0, 0);
-#pragma unroll
-        for (int d = 0; d < M_DMA; ++d)
-            if (M_LANES == 64 || lane < M_LANES)
-                __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + d * 256), 4,
-                                                         (int)(m_src[d] + U * m_stage), 0, 0, 0);
+        constexpr int K = decltype(k_c)::value;
+        if constexpr (K < B_DMA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * B_ROWS + K * ROWS_PER_DMA) * (TN * 2)), 16,
+                                                     (int)(b_src[K % PHASES] + (uint32_t)K * b_row_step + U * h_stage), 0, 0, 0);
+        else if constexpr (K < B_DMA + A_DMA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wave * A_SLOTS + 64 * (K - B_DMA)) * 16), 16,
+                                                     (int)(a_src[K - B_DMA] + U * v_stage), 0, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + wave * M_SLOTS * 2 + (K - B_DMA - A_DMA) * 256), 4,
+                                                     (int)(m_src[K - B_DMA - A_DMA] + U * m_stage), 0, 0, 0);
+    };
+    auto fetch = [&](auto u_c, char *stage) {
+        static_for<LOADS_PER_STAGE>([&](auto k_c) { fetch_one(u_c, k_c, stage); });
     };
     // first stage (relative to the slab) in which this wave's token group lies past the end of the tensor
     const int first_missing = (int)min((int64_t)0x7fffffff, (n_groups - g_begin - wgrp + 1) / 2);
@@ -296,8 +303,8 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
         if (it >= first_missing) {
             const uint4 z = make_uint4(0, 0, 0, 0);
             for (int c = lane; c < B_ROWS * CPR; c += 64) *(uint4 *)(stage + wave * B_ROWS * (TN * 2) + c * 16) = z;
-            for (int c = lane; c < A_ROWS; c += 64) *(uint4 *)(stage + A_OFF + (wgrp * TM + wsub * A_ROWS + c) * 16) = z;
-            for (int c = lane; c < A_ROWS / 8; c += 64) *(uint4 *)(stage + M_OFF + (wgrp * TM + wsub * A_ROWS) * 2 + c * 16) = z;
+            for (int c = lane; c < A_SLOTS; c += 64) *(uint4 *)(stage + A_OFF + (wave * A_SLOTS + c) * 16) = z;
+            for (int c = lane; c < M_SLOTS / 8; c += 64) *(uint4 *)(stage + M_OFF + wave * M_SLOTS * 2 + c * 16) = z;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         // ... and every other wave's part of it too.  A bare barrier: __syncthreads() would add a
@@ -314,8 +321,12 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
 #pragma unroll
     for (int b = 0; b < BB; ++b)
         rd_b[b] = (uint32_t)(rd_row + (4 * (((wn * BB + b)) ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8);
-    const uint32_t rd_a = (uint32_t)(A_OFF + (kg * TM + wm * (AB * 32) + (lane & 31)) * 16);       // + 32*a*16
-    const uint32_t rd_m = (uint32_t)(M_OFF + (kg * TM + wm * (AB * 32) + AB * (lane & 31)) * 2);   // AB consecutive words
+    // slot q (row r) of token group kg sits in the share of wave  kg*WPG + q/A_ROWS  at position  q % A_ROWS
+    constexpr int A_BLOCK = (A_ROWS >= 64 ? 32 : 64) * 16;       // bytes between the fragments of consecutive accumulator blocks
+    static_assert(A_ROWS % 32 == 0 && (AB * 32) % A_ROWS == 0 || A_ROWS % (AB * 32) == 0, "shares and wave rows nest");
+    const int q0 = wm * (AB * 32), r0 = q0 + AB * (lane & 31);
+    const uint32_t rd_a = (uint32_t)(A_OFF + ((kg * WPG + q0 / A_ROWS) * A_SLOTS + q0 % A_ROWS + (lane & 31)) * 16);   // + a*A_BLOCK
+    const uint32_t rd_m = (uint32_t)(M_OFF + ((kg * WPG + r0 / A_ROWS) * M_SLOTS + r0 % A_ROWS) * 2);                   // AB consecutive words
 
     // Operand registers: two sets.  While the MFMAs of a stage read one set, the LDS reads of the next
     // stage fill the other, so the fragment pipeline never drains at a stage boundary.
@@ -330,7 +341,7 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     auto lds_read = [&](auto set_c, auto r_c, char *stage) {
         constexpr int set = decltype(set_c)::value, r = decltype(r_c)::value, R = TN * 2;
         const uint32_t base = (uint32_t)(uintptr_t)(lptr_t)stage;
-        if constexpr (r < AB) af[set][r].u4 = lds_read_b128<32 * r * 16>(base + rd_a);
+        if constexpr (r < AB) af[set][r].u4 = lds_read_b128<r * A_BLOCK>(base + rd_a);
         else if constexpr (r == AB) {
             if constexpr (AB == 4) ix2[set] = lds_read_b64<0>(base + rd_m);
             else                   ix1[set] = lds_read_b32<0>(base + rd_m);
@@ -341,8 +352,11 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     };
     // One stage: its operands are in (or on their way into) register set SET; its MFMAs are
     // interleaved with the LDS reads of the following stage (from `next`) into the other set.
-    auto consume = [&](auto set_c, char *next) {
+    // The direct loads of the stage FU stages ahead (into `far`) are spread over the MFMAs as well: issued in one
+    // burst they fill the CU's vector-memory queue, and the waves stall on them instead of feeding the matrix pipeline.
+    auto consume = [&](auto set_c, char *next, auto fu_c, char *far) {
         constexpr int set = decltype(set_c)::value;
+        constexpr int NL = LOADS_PER_STAGE;
         // every read of this stage was issued during the previous stage.  The wait names the index-word
         // registers as an operand, so that the compiler cannot move their (its own) uses above it.
         if constexpr (AB == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ix2[set]));
@@ -356,6 +370,10 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
             static_for<NR>([&](auto r_c) {
                 constexpr int r = decltype(r_c)::value;
                 if constexpr (r >= m * NR / NM && r < (m + 1) * NR / NM) lds_read(std::integral_constant<int, 1 - set>{}, r_c, next);
+            });
+            static_for<NL>([&](auto k_c) {
+                constexpr int k = decltype(k_c)::value;
+                if constexpr (k >= m * NL / NM && k < (m + 1) * NL / NM) fetch_one(fu_c, k_c, far);
             });
         });
     };
@@ -381,8 +399,8 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
         static_for<NS>([&](auto u_c) {
             constexpr int u = decltype(u_c)::value;
             stage_ready(std::integral_constant<int, NS - 3>{}, it + u + 1, buf(std::integral_constant<int, u + 1>{}));
-            fetch(std::integral_constant<int, u + NS - 1>{}, buf(std::integral_constant<int, u + NS - 1>{}));
-            consume(std::integral_constant<int, u % 2>{}, buf(std::integral_constant<int, u + 1>{}));
+            consume(std::integral_constant<int, u % 2>{}, buf(std::integral_constant<int, u + 1>{}),
+                    std::integral_constant<int, u + NS - 1>{}, buf(std::integral_constant<int, u + NS - 1>{}));
         });
     }
 
