@@ -171,12 +171,19 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     };
 
     // ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), 32 CUs and one
-    // L2 each.  Preferred map: the whole GPU works on ONE band of M-tiles at a time, XCD x owning the N-tiles
-    // [x*nx, (x+1)*nx): the band's sparse operand is fetched from HBM once (the XCDs find it in the
-    // memory-side cache), every XCD streams only its own columns of h, and the 32 tiles resident on an XCD
-    // (band_rows x nx) share operand strips inside its L2.
+    // L2 each; the 32 tiles resident on an XCD form a block of 8 M-tiles x 4 N-tiles (N fastest), so that
+    // they share operand strips inside its L2 from the first stage on (8 vals strips + 4 h strips feed 32 tiles).
+    // Preferred map, when both tile counts are multiples of 16: the XCDs form a 2 x 4 grid and the whole GPU
+    // works on one 16 x 16 block of tiles at a time.  Of all 8-XCD arrangements this one streams the fewest
+    // bytes per block from HBM (16 vals strips + 16 h strips); strips shared between XCDs meet in the
+    // memory-side cache.  Otherwise: one band of M-tiles at a time, XCD x owning the N-tiles [x*nx, (x+1)*nx).
     int tm, tn;
-    {
+    if (tiles_m % 16 == 0 && tiles_n % 16 == 0) {
+        const int bid = blockIdx.x, xcd = bid % 8, slot = bid / 8;         // slot: this XCD's running tile count
+        const int round = slot / 32, local = slot % 32, bands = tiles_m / 16;
+        tm = (round % bands) * 16 + (xcd / 4) * 8 + local / 4;
+        tn = (round / bands) * 16 + (xcd % 4) * 4 + local % 4;
+    } else {
         const int n_tiles = tiles_m * tiles_n, bid = blockIdx.x;
         const int nx = tiles_n / 8;                                    // N-tiles per XCD
         if (tiles_n % 8 == 0 && nx <= 32) {
@@ -184,9 +191,8 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
             const int xcd = bid % 8, slot = bid / 8;                   // slot: this XCD's running tile count
             const int per_band = band_rows * nx;
             const int band = slot / per_band, local = slot % per_band;
-            const int rows_here = min(band_rows, tiles_m - band * band_rows);   // last band may be short
-            // in a short band the slots are re-dealt over rows_here rows (all slots of the band stay valid: per XCD
-            // the band holds rows_here*nx tiles, and slots beyond them belong to no tile of this XCD)
+            // the last band may be short: its slots are re-dealt over the rows it has (per XCD the band then holds
+            // fewer tiles, and every slot still belongs to exactly one tile)
             const int full_bands = tiles_m / band_rows;
             // N-tile index fastest: tiles that share an h strip AND tiles that share a vals strip start within a few
             // dispatches of each other, so both kinds of sharing are live in the L2 from the first stage on
