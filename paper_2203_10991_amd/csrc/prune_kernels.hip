@@ -98,31 +98,39 @@ __device__ __forceinline__ void select_1of2(float x0, float x1, uint32_t word, u
 
 // ------------------------------------------------------------------------------------
 // optimal MVUE 2:4 on one quad.
-// Ranking key: magnitude bits, then a reversed one-hot position code (position 0 -> 8 ...
-// position 3 -> 1) so that among equal magnitudes the higher position ranks lower, then the
-// sign (never decisive: codes are unique).  bf16 magnitudes leave the low 16 bits free, so
-// the key fits 32 bits; fp32 uses a 64-bit key.
+// Ranking key, most significant first: magnitude bits, then 3 - position (among equal
+// magnitudes the higher position ranks lower), ..., the position itself, the sign.  The last two
+// never decide an order (the code above them is unique); they ride along so that the kept
+// elements' positions and signs come out of the sorted keys.  bf16 magnitudes leave the low
+// 16 bits free, so the key fits 32 bits and is made straight from the packed row word (two
+// columns per word): one merge of the column's half with the position constant, one rotate
+// that moves the sign from the top to bit 0.  fp32 uses a 64-bit key.
 // ------------------------------------------------------------------------------------
 template <int DT> struct Key;
 template <> struct Key<NM_DT_BF16> {
     typedef uint32_t type;
-    static __device__ __forceinline__ type make(float x, int pos)
+    // w: row word holding columns (2j, 2j+1); half: which of the two
+    static __device__ __forceinline__ type make(const uint4 &v, int c, int pos)
     {
-        const uint32_t b = __float_as_uint(x);
-        return (b << 1) | ((8u >> pos) << 1) | (b >> 31);      // magnitude in [31:17], code [4:1], sign [0]
+        const uint32_t w = (c >> 1) == 0 ? v.x : (c >> 1) == 1 ? v.y : (c >> 1) == 2 ? v.z : v.w;
+        const uint32_t code = ((3u - (uint32_t)pos) << 14) | (uint32_t)pos;          // lands in key bits [16:15] and [2:1]
+        const uint32_t d = (c & 1) ? ((w & 0xffff0000u) | code) : ((w << 16) | code);
+        return __builtin_rotateleft32(d, 1);              // magnitude [31:17], 3-pos [16:15], pos [2:1], sign [0]
     }
     static __device__ __forceinline__ float mag(type k) { return __uint_as_float((k >> 1) & 0x7fff0000u); }
-    static __device__ __forceinline__ uint32_t tag(type k) { return k & 0x1fu; }
+    static __device__ __forceinline__ uint32_t pos(type k) { return (k >> 1) & 3u; }
+    static __device__ __forceinline__ float with_sign(float m, type k) { return __uint_as_float(__float_as_uint(m) | (k << 31)); }
 };
 template <> struct Key<NM_DT_F32> {
     typedef uint64_t type;
-    static __device__ __forceinline__ type make(float x, int pos)
+    static __device__ __forceinline__ type make(const uint4 &v, int c, int pos)
     {
-        const uint32_t b = __float_as_uint(x);
-        return ((uint64_t)(b & 0x7fffffffu) << 8) | ((8u >> pos) << 1) | (b >> 31);
+        const uint32_t b = c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w;
+        return ((uint64_t)(b & 0x7fffffffu) << 8) | ((3u - (uint32_t)pos) << 3) | ((uint32_t)pos << 1) | (b >> 31);
     }
     static __device__ __forceinline__ float mag(type k) { return __uint_as_float((uint32_t)(k >> 8)); }
-    static __device__ __forceinline__ uint32_t tag(type k) { return (uint32_t)k & 0x1fu; }
+    static __device__ __forceinline__ uint32_t pos(type k) { return ((uint32_t)k >> 1) & 3u; }
+    static __device__ __forceinline__ float with_sign(float m, type k) { return __uint_as_float(__float_as_uint(m) | ((uint32_t)k << 31)); }
 };
 
 template <typename K> __device__ __forceinline__ void order2(K &a, K &b)
@@ -133,49 +141,45 @@ template <typename K> __device__ __forceinline__ void order2(K &a, K &b)
     b = hi;
 }
 
-// out0/out1: kept values in ascending position; nib = pos0 | pos1 << 2
+// out0/out1: kept values in ascending position; nib = pos0 | pos1 << 2.  Straight-line code: the case
+// analysis and the walk over the pair probabilities are lane masks and selects, no divergent branch.
 template <int DT>
-__device__ __forceinline__ void select_2of4(float x0, float x1, float x2, float x3, uint32_t word,
-                                            float &out0, float &out1, uint32_t &nib)
+__device__ __forceinline__ void select_2of4(typename Key<DT>::type k1, typename Key<DT>::type k2, typename Key<DT>::type k3,
+                                            typename Key<DT>::type k4, uint32_t word, float &out0, float &out1, uint32_t &nib)
 {
     typedef Key<DT> KT;
-    typename KT::type k1 = KT::make(x0, 0), k2 = KT::make(x1, 1), k3 = KT::make(x2, 2), k4 = KT::make(x3, 3);
     order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
     const float a1 = KT::mag(k1), a2 = KT::mag(k2), a3 = KT::mag(k3), a4 = KT::mag(k4);
-    const uint32_t t1 = KT::tag(k1), t2 = KT::tag(k2), t3 = KT::tag(k3), t4 = KT::tag(k4);
 
     const float s12 = a1 + a2;
     const float s123 = s12 + a3;
     const float s = s123 + a4;
-    const float u = 2.0f * a1 + a3;
+    const float u = fmaf(2.0f, a1, a3);                    // 2*a1 is exact: one rounding, as in (2*a1) + a3
     const bool case1 = a4 <= u;
     const bool case12 = case1 | (a4 <= s123);              // else case 3: a4 dominates
 
     // cumulative thresholds on t = eps * D.  Cases 1-2: D = 2(a1+a2+a3+a4), walk p13,p14,p23,p24,p34.
     // Case 3: D = a1+a2+a3, partner of a4 is a1 / a2 / a3; expressed in the same chain.
-    const float eps = word_to_eps(word);
-    const float t = eps * (case12 ? 2.0f * s : s123);
-    const float c13 = case1 ? (u - a4) : 0.0f;
+    const float t = word_to_eps(word) * (case12 ? s + s : s123);
+    const float c13 = u - a4;                                                   // counts in case 1 only
     const float c14 = case12 ? 4.0f * a1 : a1;
-    const float n23 = case1 ? ((2.0f * a2 + a3) - a4) : (2.0f * (s123 - a4));
-    const float c23 = case12 ? (c14 + n23) : a1;
+    const float d34 = s123 - a4;
+    const float n23 = case1 ? (fmaf(2.0f, a2, a3) - a4) : (d34 + d34);
+    const float c23 = 4.0f * a1 + n23;                                          // counts in cases 1-2 only
     const float c24 = case12 ? 4.0f * s12 : s12;
 
-    // the first threshold above t decides the pair: 13, 14, 23, 24, else 34
-    uint32_t ta, tb;
-    if (t < c13)      { ta = t1; tb = t3; }
-    else if (t < c14) { ta = t1; tb = t4; }
-    else if (t < c23) { ta = t2; tb = t3; }
-    else if (t < c24) { ta = t2; tb = t4; }
-    else              { ta = t3; tb = t4; }
-    if (!case12) tb = t4;
+    // the first threshold above t decides the pair: 13, 14, 23, 24, else 34 (case 3: 14, 24, else 34)
+    const bool lt13 = case1 & (t < c13), lt14 = t < c14, lt23 = case12 & (t < c23), lt24 = t < c24;
+    const bool first_is_1 = lt13 | lt14;
+    const bool first_is_2 = lt23 | lt24;
+    const bool second_is_3 = case12 & (lt13 | (!lt14 & lt23));
+    const typename KT::type ka = first_is_1 ? k1 : (first_is_2 ? k2 : k3);
+    const typename KT::type kb = second_is_3 ? k3 : k4;
 
-    const float ma = case12 ? 0.5f * s : s123;              // a_i / p_i
-    const float mb = case12 ? 0.5f * s : a4;
-    const float va = __uint_as_float(__float_as_uint(ma) | (ta << 31));
-    const float vb = __uint_as_float(__float_as_uint(mb) | (tb << 31));
-    const uint32_t pa = (uint32_t)__clz((int)ta) - 27u;      // code 8,4,2,1 (<<1) -> position 0..3
-    const uint32_t pb = (uint32_t)__clz((int)tb) - 27u;
+    const float half_s = 0.5f * s;
+    const float va = KT::with_sign(case12 ? half_s : s123, ka);                // a_i / p_i
+    const float vb = KT::with_sign(case12 ? half_s : a4, kb);
+    const uint32_t pa = KT::pos(ka), pb = KT::pos(kb);
     const bool swap = pa > pb;
     out0 = swap ? vb : va;
     out1 = swap ? va : vb;
@@ -204,12 +208,20 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 #pragma unroll
     for (int r = 0; r < 16; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
 
-    float kept[VEC][8];          // kept values per column, slot order of the group format
+    // kept values per column in the slot order of the group format, as stored: binary32 words, or bf16 pairs
+    // (slots 2i, 2i+1) packed as soon as a block row is decided, which keeps the live registers low
+    constexpr int KW = DT == NM_DT_F32 ? 8 : 4;      // words per column
+    uint32_t kept[VEC][KW];
     uint32_t md[VEC];
 #pragma unroll
     for (int c = 0; c < VEC; ++c) md[c] = 0;
+    auto put2 = [&](int c, int i, float v0, float v1) {      // slots 2i and 2i+1 of column c
+        if constexpr (DT == NM_DT_F32) { kept[c][2 * i] = __float_as_uint(v0); kept[c][2 * i + 1] = __float_as_uint(v1); }
+        else kept[c][i] = pack_bf16_rne(v0, v1);
+    };
 
     constexpr int BLOCK_ROWS = 16 / M;       // pair rows (8) or quad rows (4) in the group
+    float held[VEC];                         // 1:2: the kept value of the even pair row, until its partner is known
 #pragma unroll
     for (int b = 0; b < BLOCK_ROWS; ++b) {
         const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
@@ -227,15 +239,14 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
             if (M == 2) {
                 uint32_t k; float v;
                 select_1of2(Row<DT>::get(rows[2 * b], c), Row<DT>::get(rows[2 * b + 1], c), words[c], k, v);
-                kept[c][b] = v;
+                if (b & 1) put2(c, b >> 1, held[c], v); else held[c] = v;
                 md[c] |= ((uint32_t)((b & 1) << 1) | k) << (2 * b);
             } else {
                 float v0, v1; uint32_t nib;
-                select_2of4<DT>(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
-                                Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c),
+                select_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
+                                Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3),
                                 words[c], v0, v1, nib);
-                kept[c][2 * b] = v0;
-                kept[c][2 * b + 1] = v1;
+                put2(c, b, v0, v1);
                 md[c] |= nib << (4 * b);
             }
         }
@@ -243,23 +254,11 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 
     // ---- kept values: 8 per column, VEC columns contiguous = 128 bytes per thread
     char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;
-    if (DT == NM_DT_F32) {
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            ((float4 *)vp)[2 * c] = make_float4(kept[c][0], kept[c][1], kept[c][2], kept[c][3]);
-            ((float4 *)vp)[2 * c + 1] = make_float4(kept[c][4], kept[c][5], kept[c][6], kept[c][7]);
-        }
-    } else {
+    for (int c = 0; c < VEC; ++c)
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            uint4 o;
-            o.x = pack_bf16_rne(kept[c][0], kept[c][1]);
-            o.y = pack_bf16_rne(kept[c][2], kept[c][3]);
-            o.z = pack_bf16_rne(kept[c][4], kept[c][5]);
-            o.w = pack_bf16_rne(kept[c][6], kept[c][7]);
-            ((uint4 *)vp)[c] = o;
-        }
-    }
+        for (int j = 0; j < KW / 4; ++j)
+            ((uint4 *)vp)[c * (KW / 4) + j] = make_uint4(kept[c][4 * j], kept[c][4 * j + 1], kept[c][4 * j + 2], kept[c][4 * j + 3]);
     // ---- index words
     uint16_t *mp = meta_ + (G * O + col0);
     if (VEC == 8) {
@@ -283,9 +282,10 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 #pragma unroll
             for (int c = 0; c < VEC; ++c) {
                 const uint32_t nib = (md[c] >> (4 * q)) & 0xfu;
-                const float v = (nib & 3u) == (uint32_t)p ? kept[c][2 * q]
-                              : (nib >> 2) == (uint32_t)p ? kept[c][2 * q + 1] : 0.0f;
-                w[c] = DT == NM_DT_F32 ? __float_as_uint(v) : bf16_bits_rne(v);
+                // the stored words of slots 2q and 2q+1 (bf16: the two halves of one word)
+                const uint32_t s0 = DT == NM_DT_F32 ? kept[c][(2 * q) % KW] : (kept[c][q % KW] & 0xffffu);
+                const uint32_t s1 = DT == NM_DT_F32 ? kept[c][(2 * q + 1) % KW] : (kept[c][q % KW] >> 16);
+                w[c] = (nib & 3u) == (uint32_t)p ? s0 : (nib >> 2) == (uint32_t)p ? s1 : 0u;
             }
             uint4 o;
             if (DT == NM_DT_F32) { o.x = w[0]; o.y = w[1]; o.z = w[2]; o.w = w[3]; }
