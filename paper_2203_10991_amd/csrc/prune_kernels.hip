@@ -204,9 +204,12 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
     const int64_t col0 = (n - G * ncg) * VEC;
 
     const char *gp = (const char *)g_ + ((G * 16) * ldg + col0) * ESZ;
+    // The second half of the rows is requested only after the first block row is decided (an opaque copy of the
+    // address keeps those loads from being hoisted): their latency hides under the arithmetic of the rows already
+    // here, and fewer registers are live at once, so one more wave fits each SIMD.
     uint4 rows[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
+    for (int r = 0; r < 8; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
 
     // kept values per column in the slot order of the group format, as stored: binary32 words, or bf16 pairs
     // (slots 2i, 2i+1) packed as soon as a block row is decided, which keeps the live registers low
@@ -224,6 +227,12 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
     float held[VEC];                         // 1:2: the kept value of the even pair row, until its partner is known
 #pragma unroll
     for (int b = 0; b < BLOCK_ROWS; ++b) {
+        if (b == 1) {
+            const char *gp2 = gp;
+            asm volatile("" : "+v"(gp2));               // an address the compiler cannot see through
+#pragma unroll
+            for (int r = 8; r < 16; ++r) rows[r] = *(const uint4 *)(gp2 + (int64_t)r * ldg * ESZ);
+        }
         const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
         uint32_t words[VEC];
 #pragma unroll
@@ -248,6 +257,7 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
                                 words[c], v0, v1, nib);
                 put2(c, b, v0, v1);
                 md[c] |= nib << (4 * b);
+                __builtin_amdgcn_sched_barrier(0);       // one block at a time: interleaving blocks only lengthens live ranges
             }
         }
     }
