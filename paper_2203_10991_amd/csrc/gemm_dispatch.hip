@@ -1,4 +1,4 @@
-// Shape/dtype dispatch of the update GEMM (eq. (3)) over the kernels of this library.
+// Dtype dispatch of the update GEMM (eq. (3)) over the kernels of this library.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -6,16 +6,9 @@
 
 namespace nm {
 
-hipError_t launch_update_gemm_valu(int dt, const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
-                                   float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, hipStream_t st);
-hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
-                                     int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
-                                     hipStream_t st);
-size_t update_gemm_smfmac_workspace(int64_t T, int64_t O, int64_t I);
-
 size_t update_gemm_workspace(int dt, int64_t T, int64_t O, int64_t I)
 {
-    return dt == NM_DT_BF16 ? update_gemm_smfmac_workspace(T, O, I) : 0;
+    return dt == NM_DT_BF16 ? update_gemm_smfmac_workspace(T, O, I) : update_gemm_f32_workspace(T, O, I);
 }
 
 hipError_t launch_update_gemm(int dt, const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
@@ -23,11 +16,10 @@ hipError_t launch_update_gemm(int dt, const void *vals, const uint16_t *meta, co
                               void *workspace, size_t workspace_bytes, hipStream_t st)
 {
     (void)workspace_bytes;
-    // bf16: sparse MFMA.  fp32: gfx950 has no sparse (nor any reduced-precision-free) matrix path for
-    // binary32 inputs with 4:2 structure, so the operand is expanded on the fly on the vector ALU.
-    if (dt == NM_DT_BF16 && T > 0)
-        return launch_update_gemm_smfmac(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);
-    return launch_update_gemm_valu(dt, vals, meta, h, ldh, dW, lddw, T, O, I, beta, st);
+    // bf16: 4:2 sparse MFMA.  binary32: gfx950's sparse matrix instructions take 16- and 8-bit operands only,
+    // so the operand is expanded on its way into LDS and multiplied on the dense fp32 MFMA path.
+    if (dt == NM_DT_BF16) return launch_update_gemm_smfmac(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);
+    return launch_update_gemm_f32(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);
 }
 
 }  // namespace nm

@@ -450,6 +450,16 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
     *(float4 *)(out + o * ldo + i) = s;
 }
 
+// dW = (accumulate ? dW : 0) + sum over the slabs of [slabs][O][I] partial sums (row stride I), in slab order
+hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
+                                int accumulate, hipStream_t st)
+{
+    const int64_t n4 = O * (I / 4);
+    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, slabs, O * I,
+                       dW, lddw, O, I, accumulate);
+    return hipGetLastError();
+}
+
 // ------------------------------------------------------------------------------------
 // host side: tile shape and split-K plan (pure function of the problem size)
 // ------------------------------------------------------------------------------------
@@ -510,12 +520,7 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
 #undef NM_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (p.slabs > 1) {
-        const int64_t n4 = O * (I / 4);
-        hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st,
-                           (const float *)workspace, p.slabs, slab_stride, dW, lddw, O, I, accumulate);
-        e = hipGetLastError();
-    }
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, st);
     return e;
 }
 

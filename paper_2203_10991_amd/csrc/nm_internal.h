@@ -20,4 +20,17 @@ hipError_t launch_update_gemm(int dt, const void *vals, const uint16_t *meta, co
                               void *workspace, size_t workspace_bytes, hipStream_t st);
 size_t update_gemm_workspace(int dt, int64_t T, int64_t O, int64_t I);
 
+// kernels behind launch_update_gemm: sparse MFMA for bf16, dense fp32 MFMA for binary32; both split the reduction
+// axis into slabs for shapes with few output tiles and sum the partials with launch_splitk_reduce
+hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
+                                     int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
+                                     hipStream_t st);
+size_t update_gemm_smfmac_workspace(int64_t T, int64_t O, int64_t I);
+hipError_t launch_update_gemm_f32(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
+                                  int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
+                                  hipStream_t st);
+size_t update_gemm_f32_workspace(int64_t T, int64_t O, int64_t I);
+hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
+                                int accumulate, hipStream_t st);
+
 }  // namespace nm
