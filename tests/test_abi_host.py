@@ -91,4 +91,10 @@ def test_gemm_argument_errors(lib):
     assert gemm(h=P + 0x20004) == NM_ERR_ALIGN
     assert gemm(dW=P + 0x20000) == NM_ERR_ALIAS
     assert gemm(O=0) == NM_OK
+    # the kernels' 32-bit stage offsets bound O and ldh (checked before anything is launched)
+    assert gemm(ldh=(1 << 21) + 8, dW=P + (1 << 40)) == NM_ERR_UNSUPPORTED and b"2^21" in lib.nm_last_error()
+    assert gemm(O=(1 << 21) + 8, dW=P + (1 << 40)) == NM_ERR_UNSUPPORTED
     assert lib.nm_update_gemm_workspace(-1, 8, 8, 1) == 0
+    # binary32 problems with few output tiles split the reduction axis as well
+    assert lib.nm_update_gemm_workspace(1024, 1024, 1024, 0) == 8 * 1024 * 1024 * 4
+    assert gemm(T=1024, O=1024, I=1024, ldh=1024, lddw=1024, dt=0, dW=P + (1 << 40)) == NM_ERR_WORKSPACE
