@@ -52,7 +52,13 @@ def lib():
         _lib.oracle_enumerate_1of2.restype = None
         _lib.oracle_enumerate_2of4.argtypes = [vp, vp, vp, vp]
         _lib.oracle_enumerate_2of4.restype = None
-        for f in (_lib.oracle_prune_1of2, _lib.oracle_prune_2of4):
+        _lib.oracle_block_u24_pair.argtypes = [u64, u32, u64, vp]
+        _lib.oracle_block_u24_pair.restype = None
+        _lib.oracle_select_2of4_approx.argtypes = [vp, C.c_float, C.c_float, vp, vp]
+        _lib.oracle_select_2of4_approx.restype = None
+        _lib.oracle_enumerate_approx_draw.argtypes = [vp, i32, vp]
+        _lib.oracle_enumerate_approx_draw.restype = None
+        for f in (_lib.oracle_prune_1of2, _lib.oracle_prune_2of4, _lib.oracle_prune_2of4_approx):
             f.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64]
             f.restype = i32
         _lib.oracle_nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp]
@@ -134,6 +140,28 @@ def enumerate_2of4(x):
     return counts, mean, second
 
 
+def block_u24_pair(seed: int, stream_id: int, blk: int) -> Tuple[int, int]:
+    u = np.zeros(2, dtype=np.uint32)
+    lib().oracle_block_u24_pair(seed, stream_id, blk, _p(u))
+    return int(u[0]), int(u[1])
+
+
+def select_2of4_approx(x, eps1: float, eps2: float):
+    xa = np.asarray(x, dtype=np.float32).copy()
+    pos = np.zeros(2, dtype=np.int32)
+    val = np.zeros(2, dtype=np.float32)
+    lib().oracle_select_2of4_approx(_p(xa), C.c_float(eps1), C.c_float(eps2), _p(pos), _p(val))
+    return (int(pos[0]), int(pos[1])), (float(val[0]), float(val[1]))
+
+
+def enumerate_approx_draw(x, first: int = -1) -> np.ndarray:
+    """Counts, over all 2^24 uniforms, of the position drawn (second draw when `first` >= 0)."""
+    xa = np.asarray(x, dtype=np.float32).copy()
+    counts = np.zeros(4, dtype=np.uint64)
+    lib().oracle_enumerate_approx_draw(_p(xa), first, _p(counts))
+    return counts
+
+
 def _prune(fn, g: np.ndarray, seed: int, stream_id: int, want_dense: bool, logical_O: Optional[int] = None):
     assert g.ndim == 2
     T, O = g.shape
@@ -154,6 +182,10 @@ def prune_1of2(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: boo
 
 def prune_2of4(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
     return _prune(lib().oracle_prune_2of4, g, seed, stream_id, want_dense)
+
+
+def prune_2of4_approx(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
+    return _prune(lib().oracle_prune_2of4_approx, g, seed, stream_id, want_dense)
 
 
 def nm_compress(dense: np.ndarray, n: int, m: int):

@@ -127,6 +127,30 @@ def marginals_approx_2of4(a) -> np.ndarray:
     return p
 
 
+def pair_probs_approx_2of4(a) -> Dict[Tuple[int, int], float]:
+    """Sec. 4.4: probability that the unordered pair (i, j) is kept = P(i then j) + P(j then i)."""
+    a = np.abs(np.asarray(a, dtype=np.float64))
+    s = a.sum()
+    out = {}
+    for i, j in PAIRS:
+        out[(i, j)] = a[i] / s * a[j] / (s - a[i]) + a[j] / s * a[i] / (s - a[j])
+    return out
+
+
+def marginals_approx_alg1(a) -> np.ndarray:
+    """Alg. 1 (App. B.1) writes the same inclusion probability as  v (1 + q - vv),  v = a/sum, vv = v/(1-v), q = sum vv."""
+    a = np.abs(np.asarray(a, dtype=np.float64))
+    v = a / a.sum()
+    vv = v / (1.0 - v)
+    return v * (1.0 + vv.sum() - vv)
+
+
+def var_approx_2of4(a) -> float:
+    """Block variance (eq. (10)) of approx-MVUE: sum_i a_i^2 (1/p_i - 1) with the marginals of Sec. 4.4."""
+    a = np.abs(np.asarray(a, dtype=np.float64))
+    return var_block(a, marginals_approx_2of4(a))
+
+
 # ---------------------------------------------------------------------------
 # the 1:2 comparison estimators of Table "1:2 ablation" (negative / positive controls)
 # each maps (pairs [n,2], eps [n]) -> theta [n,2]

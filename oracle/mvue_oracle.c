@@ -11,6 +11,9 @@
  *                                      uniform threshold: App. B.1, "Part 1".
  *   - optimal MVUE 2:4 .............. Sec. 4.2 (optimality conditions, eqs. (12),(14)) and
  *                                      App. A.2 (pair probabilities p_ij, cases 1-3).
+ *   - approx-MVUE 2:4 ............... Sec. 4.4: two draws without replacement, each proportional
+ *                                      to magnitude; kept value a_i/p_i with the inclusion
+ *                                      probability p_i of that section.
  *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T.
  *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
  *                                      fixes Philox4x32-10 (Salmon et al., SC'11) as a pure
@@ -192,6 +195,85 @@ void oracle_select_2of4(const float x[4], float eps, int pos[2], float value[2],
     else         { pos[0] = pb; pos[1] = pa; value[0] = fb; value[1] = fa; }
 }
 
+/*
+ * The two uniforms of block `blk` for approx-MVUE 2:4 (Sec. 4.4 draws twice).  Two blocks share
+ * one Philox call: counter = (blk/2 low, blk/2 high, stream, 1) -- the last word separates this
+ * stream from the one-uniform-per-block stream above -- and the block takes output words
+ * 2*(blk%2) and 2*(blk%2)+1, top 24 bits each.
+ */
+void oracle_block_u24_pair(uint64_t seed, uint32_t stream_id, uint64_t blk, uint32_t u[2])
+{
+    uint64_t c = blk >> 1;
+    uint32_t ctr[4] = { (uint32_t)c, (uint32_t)(c >> 32), stream_id, 1u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    u[0] = out[2u * (blk & 1u)] >> 8;
+    u[1] = out[2u * (blk & 1u) + 1u] >> 8;
+}
+
+/* ------------------------------------------------------------------------- */
+/* approx-MVUE 2:4 (Sec. 4.4).                                                 */
+/* One element is drawn with probability a_i / sum, a second one from the      */
+/* remaining three with probability a_j / (sum - a_i); both are kept with the  */
+/* value a_k / p_k, where p_k is the probability that k is one of the two      */
+/* (the section's last equation):                                              */
+/*     p_k = v_k (1 + sum_{l != k} v_l / (1 - v_l)),   v = a / sum             */
+/* so  a_k / p_k = sum / (1 + sum_{l != k} a_l / (sum - a_l)).                 */
+/* No ranking is needed: everything runs in position order.                    */
+/*                                                                             */
+/* Draw (threshold walk, no division): t = eps * total; the element is the     */
+/* first position k whose running sum exceeds t.  If none does (possible only  */
+/* through rounding, or when nothing non-zero is left) it is the last position */
+/* with a non-zero magnitude, and if there is none, the lowest position not    */
+/* taken yet -- so a zero is never drawn while a non-zero remains, and padding */
+/* falls on the lowest-index zeros.  The second draw repeats the first on the  */
+/* block with the drawn element's magnitude set to zero.                       */
+/* "sum - a_l" is formed as the sum of the other three magnitudes (no          */
+/* cancellation when one element dominates), and the sum over l != k likewise  */
+/* (term k replaced by zero).  A zero magnitude contributes no term.           */
+/* ------------------------------------------------------------------------- */
+static int approx_draw(const float m[4], float eps, int taken)
+{
+    const float c0 = m[0], c1 = c0 + m[1], c2 = c1 + m[2], total = c2 + m[3];
+    const float t = eps * total;
+    if (t < c0) return 0;
+    if (t < c1) return 1;
+    if (t < c2) return 2;
+    if (t < total) return 3;
+    for (int k = 3; k >= 0; --k) if (m[k] > 0.0f) return k;
+    for (int k = 0; k < 4; ++k) if (k != taken) return k;
+    return 0;
+}
+
+void oracle_select_2of4_approx(const float x[4], float eps1, float eps2, int pos[2], float value[2])
+{
+    float m[4];
+    for (int k = 0; k < 4; ++k) m[k] = fabsf(x[k]);
+    const int i = approx_draw(m, eps1, -1);
+    float r[4];
+    for (int k = 0; k < 4; ++k) r[k] = (k == i) ? 0.0f : m[k];
+    const int j = approx_draw(r, eps2, i);
+
+    /* values */
+    const float s01 = m[0] + m[1], s23 = m[2] + m[3];
+    const float total = ((m[0] + m[1]) + m[2]) + m[3];
+    const float others[4] = { m[1] + s23, m[0] + s23, s01 + m[3], s01 + m[2] };      /* sum - a_l, without cancellation */
+    float vv[4];
+    for (int l = 0; l < 4; ++l) vv[l] = (m[l] > 0.0f) ? m[l] / others[l] : 0.0f;     /* v_l / (1 - v_l) */
+    float out[2];
+    const int kept[2] = { i, j };
+    for (int e = 0; e < 2; ++e) {
+        const int k = kept[e];
+        float z[4];
+        for (int l = 0; l < 4; ++l) z[l] = (l == k) ? 0.0f : vv[l];
+        const float denom = 1.0f + (((z[0] + z[1]) + z[2]) + z[3]);
+        out[e] = copysignf(total / denom, x[k]);
+    }
+    if (i < j) { pos[0] = i; pos[1] = j; value[0] = out[0]; value[1] = out[1]; }
+    else       { pos[0] = j; pos[1] = i; value[0] = out[1]; value[1] = out[0]; }
+}
+
 /* ------------------------------------------------------------------------- */
 /* exhaustive enumeration over all 2^24 thresholds (test support)              */
 /* ------------------------------------------------------------------------- */
@@ -277,6 +359,47 @@ int oracle_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
                 uint32_t u = oracle_block_u24(seed, stream_id, (uint64_t)q * (uint64_t)O + (uint64_t)o);
                 int pos[2], wc; float v[2];
                 oracle_select_2of4(x, u24_to_eps(u), pos, v, &wc);
+                float st0 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 0, v[0]);
+                float st1 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 1, v[1]);
+                md |= (uint16_t)((pos[0] | (pos[1] << 2)) << (4 * i));
+                if (dense) {
+                    for (int k = 0; k < 4; ++k) store_elem(dense, dt, (t0 + k) * ldd + o, 0.0f);
+                    store_elem(dense, dt, (t0 + pos[0]) * ldd + o, st0);
+                    store_elem(dense, dt, (t0 + pos[1]) * ldd + o, st1);
+                }
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+/* approx-MVUE test support: how often each position is drawn over all 2^24 uniforms.          */
+/* first < 0: the first draw on |x|; otherwise the second draw given that `first` was drawn.   */
+void oracle_enumerate_approx_draw(const float x[4], int first, uint64_t counts[4])
+{
+    float m[4];
+    for (int k = 0; k < 4; ++k) { m[k] = (k == first) ? 0.0f : fabsf(x[k]); counts[k] = 0; }
+    for (uint32_t u = 0; u < (1u << 24); ++u) counts[approx_draw(m, u24_to_eps(u), first)] += 1;
+}
+
+int oracle_prune_2of4_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                             uint64_t seed, uint32_t stream_id,
+                             void *vals, uint16_t *meta, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {
+                int64_t q = G * 4 + i, t0 = q * 4;
+                float x[4];
+                for (int k = 0; k < 4; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                uint32_t u[2];
+                oracle_block_u24_pair(seed, stream_id, (uint64_t)q * (uint64_t)O + (uint64_t)o, u);
+                int pos[2]; float v[2];
+                oracle_select_2of4_approx(x, u24_to_eps(u[0]), u24_to_eps(u[1]), pos, v);
                 float st0 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 0, v[0]);
                 float st1 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 1, v[1]);
                 md |= (uint16_t)((pos[0] | (pos[1] << 2)) << (4 * i));
