@@ -39,13 +39,13 @@ def read_traffic(workload: str, kernel: str):
     return None
 
 
-def cpu_baseline(w):
+def cpu_baseline(w, approx=False):
     """The oracle, as it stands, on a slice of the workload: first 16384 tokens x 4096 out x 4096 in."""
     from oracle import cwrap as oracle
     from paper_2203_10991_amd import synth
     s = synth.scaled(w, T=min(w.T, 16384), O=min(w.O, 4096), I=min(w.I, 4096), name=w.name + "_slice")
     g, h = synth.make_g(s, 0), synth.make_h(s, 0)
-    prune = oracle.prune_1of2 if s.nm == "1:2" else oracle.prune_2of4
+    prune = oracle.prune_1of2 if s.nm == "1:2" else (oracle.prune_2of4_approx if approx else oracle.prune_2of4)
     t0 = time.perf_counter()
     v, m, _ = prune(g, 0, 0)
     t1 = time.perf_counter()
@@ -68,6 +68,8 @@ def main():
     ap.add_argument("--steps", type=int, default=20)
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c5_decoder_mlp_2of4")
+    ap.add_argument("--estimator", default="optimal", choices=["optimal", "approx"],
+                    help="2:4 workloads: the optimal MVUE (Sec. 4.2, default) or approx-MVUE (Sec. 4.4)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc byte counters")
@@ -90,7 +92,11 @@ def main():
     torch.cuda.set_device(0)
     w = synth.WORKLOADS[args.workload]
     g, h = synth.make_device(w, seed=0, device=dev)
-    prune = nm.mvue_prune_1of2 if w.nm == "1:2" else nm.mvue_prune_2of4
+    approx = args.estimator == "approx" and w.nm == "2:4"
+    if w.nm == "1:2":
+        prune = nm.mvue_prune_1of2
+    else:
+        prune = lambda g_, **kw: nm.mvue_prune_2of4(g_, mode=1 if approx else 0, **kw)
     vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, dev)
     dW = torch.empty((w.O, w.I), dtype=torch.float32, device=dev)
     need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
@@ -127,7 +133,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
-                   "T": w.T, "O": w.O, "I": w.I, "estimator": f"MVUE {w.nm}", "seed": 0},
+                   "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0},
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
         "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / SPARSE_PEAK_TFLOPS,
         "gemm_ms": gemm_ms,
@@ -178,7 +184,7 @@ def main():
     if not args.no_cpu_baseline:
         del g, h, vals, meta, dW, ws
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w)
+        out["cpu_baseline"] = cpu_baseline(w, approx)
     print(json.dumps(out))
 
 

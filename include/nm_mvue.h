@@ -79,8 +79,12 @@ int mvue_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
  * and (14); pair probabilities of App. A.2, cases 1-3), one uniform per quad, blk = (t/4)*O + o.
  * Kept values are a_i/p_i (eq. (8)): (a1+a2+a3+a4)/2 when no element dominates, otherwise the
  * dominant element unchanged and its partner a1+a2+a3; signs are those of the inputs.
- * mode 1 (approx-MVUE of Sec. 4.4) returns NM_ERR_UNSUPPORTED in this build.
- * Arguments as mvue_prune_1of2.
+ * mode 1 = approx-MVUE (Sec. 4.4): one element is drawn with probability a_i/sum, a second one
+ * from the remaining three with probability a_j/(sum - a_i) (two uniforms per quad, a counter
+ * stream of their own); both are kept with the value a_k/p_k, p_k the inclusion probability of
+ * that section.  No ranking, six binary32 divisions per quad.  A zero is never drawn while a
+ * non-zero remains; padding falls on the lowest-index zeros.
+ * Any other mode returns NM_ERR_UNSUPPORTED.  Arguments as mvue_prune_1of2.
  */
 int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     uint64_t seed, uint32_t stream_id, int mode,

@@ -86,7 +86,7 @@ int mvue_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
     const char *fn = "mvue_prune_1of2";
     if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
     if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
-    return launched(fn, nm::launch_prune(dtype, 2, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
+    return launched(fn, nm::launch_prune(dtype, 2, 0, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
                                          (hipStream_t)hip_stream));
 }
 
@@ -94,11 +94,11 @@ int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     int mode, void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream)
 {
     const char *fn = "mvue_prune_2of4";
-    if (mode == 1) return fail(NM_ERR_UNSUPPORTED, "%s: mode 1 (approx-MVUE) is not built", fn);
-    if (mode != 0) return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d", fn, mode);
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", fn, mode);
     if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
     if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
-    return launched(fn, nm::launch_prune(dtype, 4, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
+    return launched(fn, nm::launch_prune(dtype, 4, mode, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
                                          (hipStream_t)hip_stream));
 }
 

@@ -8,7 +8,7 @@
 
 namespace nm {
 
-hipError_t launch_prune(int dt, int m, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st);
 
 hipError_t launch_compress(int dt, int m, const void *d, int64_t T, int64_t O, int64_t ld, void *vals,

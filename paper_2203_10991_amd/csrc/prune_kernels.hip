@@ -10,6 +10,7 @@
 //
 //   MVUE 1:2 ........ Sec. 4.1, eq. (6); threshold sampling as in App. B.1
 //   optimal 2:4 ..... Sec. 4.2 (eqs. (8), (12), (14)) and App. A.2 (cases 1-3)
+//   approx 2:4 ...... Sec. 4.4 (two magnitude-proportional draws, kept value a/p)
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -187,9 +188,64 @@ __device__ __forceinline__ void select_2of4(typename Key<DT>::type k1, typename 
 }
 
 // ------------------------------------------------------------------------------------
+// approx-MVUE 2:4 on one quad (Sec. 4.4): one element drawn with probability a_i/sum, a second from
+// the other three with probability a_j/(sum - a_i); both kept with value a_k/p_k, p_k the section's
+// inclusion probability, i.e.  sum / (1 + sum_{l != k} a_l/(sum - a_l)).  No ranking: position order.
+// A draw is a threshold walk over the running sums (t = eps * total, first position whose running
+// sum exceeds t); when none does -- rounding, or nothing non-zero left -- it falls on the last
+// position with a non-zero magnitude, else on the lowest position not taken, so a zero never beats a
+// non-zero and padding falls on the lowest-index zeros.  "sum - a_l" and the sum over l != k are
+// formed from the other terms (no cancellation when one element carries the sum).  The six
+// divisions are IEEE binary32 divisions.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void select_2of4_approx(float x0, float x1, float x2, float x3, uint32_t word1, uint32_t word2,
+                                                   float &out0, float &out1, uint32_t &nib)
+{
+    // Straight-line code: draws are lane masks (one per position), everything else selects.
+    const float m0 = fabsf(x0), m1 = fabsf(x1), m2 = fabsf(x2), m3 = fabsf(x3);
+    const float c1 = m0 + m1, c2 = c1 + m2, total = c2 + m3;
+    // first draw.  (t < total would pick position 3, and so does the fallback whenever m3 > 0; with m3 == 0 the
+    // total equals c2 and the test cannot hold: one expression covers both.)
+    const float t = word_to_eps(word1) * total;
+    const bool w0 = t < m0, w1 = t < c1, w2 = t < c2;                           // walk
+    const bool n0 = m0 > 0.0f, n1 = m1 > 0.0f, n2 = m2 > 0.0f, n3 = m3 > 0.0f;
+    const bool i0 = w0 | (!w1 & !w2 & !n3 & !n2 & !n1);                         // (fallback on position 0: nothing non-zero above it)
+    const bool i1 = !w0 & (w1 | (!w2 & !n3 & !n2 & n1));
+    const bool i2 = !w0 & !w1 & (w2 | (!n3 & n2));
+    const bool i3 = !w0 & !w1 & !w2 & n3;
+    // second draw on the block without the first element
+    const float r0 = i0 ? 0.0f : m0, r1 = i1 ? 0.0f : m1, r2 = i2 ? 0.0f : m2, r3 = i3 ? 0.0f : m3;
+    const float d1 = r0 + r1, d2 = d1 + r2, rest = d2 + r3;
+    const float t2 = word_to_eps(word2) * rest;
+    const bool u0 = t2 < r0, u1 = t2 < d1, u2 = t2 < d2;
+    const bool q0 = r0 > 0.0f, q1 = r1 > 0.0f, q2 = r2 > 0.0f, q3 = r3 > 0.0f;
+    const bool none = !q0 & !q1 & !q2 & !q3;                                    // nothing non-zero left: lowest position not taken
+    const bool fall = !u0 & !u1 & !u2;
+    const bool j0 = u0 | (fall & ((!q3 & !q2 & !q1 & q0) | (none & !i0)));
+    const bool j1 = !u0 & (u1 | (!u2 & ((!q3 & !q2 & q1) | (none & i0))));
+    const bool j2 = !u0 & !u1 & (u2 | (!q3 & q2));
+    const bool j3 = fall & q3;
+    // kept values: sum / (1 + sum over the other three of a_l / (sum - a_l)), "sum - a_l" from the other three
+    const float s23 = m2 + m3;
+    const float o0 = m1 + s23, o1 = m0 + s23, o2 = c1 + m3, o3 = c2;
+    const float e0 = m0 / o0, e1 = m1 / o1, e2 = m2 / o2, e3 = m3 / o3;         // (0/0 of a zero element is discarded below)
+    const float v0 = n0 ? e0 : 0.0f, v1 = n1 ? e1 : 0.0f, v2 = n2 ? e2 : 0.0f, v3 = n3 ? e3 : 0.0f;
+    const float di = 1.0f + ((((i0 ? 0.0f : v0) + (i1 ? 0.0f : v1)) + (i2 ? 0.0f : v2)) + (i3 ? 0.0f : v3));
+    const float dj = 1.0f + ((((j0 ? 0.0f : v0) + (j1 ? 0.0f : v1)) + (j2 ? 0.0f : v2)) + (j3 ? 0.0f : v3));
+    const float xi = i0 ? x0 : i1 ? x1 : i2 ? x2 : x3;
+    const float xj = j0 ? x0 : j1 ? x1 : j2 ? x2 : x3;
+    const float vi = copysignf(total / di, xi), vj = copysignf(total / dj, xj);
+    const uint32_t pi = i0 ? 0u : i1 ? 1u : i2 ? 2u : 3u, pj = j0 ? 0u : j1 ? 1u : j2 ? 2u : 3u;
+    const bool swap = pi > pj;
+    out0 = swap ? vj : vi;
+    out1 = swap ? vi : vj;
+    nib = swap ? (pj | (pi << 2)) : (pi | (pj << 2));
+}
+
+// ------------------------------------------------------------------------------------
 // the fused kernel
 // ------------------------------------------------------------------------------------
-template <int DT, int M>     // M = 2: MVUE 1:2, M = 4: optimal MVUE 2:4
+template <int DT, int M, int EST>     // M = 2: MVUE 1:2; M = 4: MVUE 2:4, EST = 0 the optimal estimator, 1 approx-MVUE
 __global__ __launch_bounds__(256) void prune_compress_kernel(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
     uint32_t key0, uint32_t key1, uint32_t stream_id,
@@ -234,12 +290,15 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
             for (int r = 8; r < 16; ++r) rows[r] = *(const uint4 *)(gp2 + (int64_t)r * ldg * ESZ);
         }
         const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
-        uint32_t words[VEC];
+        // one uniform per block: four blocks share a Philox call (counter blk/4, last counter word 0);
+        // approx-MVUE draws twice: two blocks share a call (counter blk/2, last counter word 1)
+        constexpr int WPB = EST == 1 ? 2 : 1;            // words per block
+        uint32_t words[VEC * WPB];
 #pragma unroll
-        for (int q = 0; q < VEC / 4; ++q) {
-            const uint64_t ctr = (blk0 >> 2) + q;
+        for (int q = 0; q < VEC * WPB / 4; ++q) {
+            const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
             uint32_t w4[4];
-            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 0u, key0, key1, w4);
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
 #pragma unroll
             for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
         }
@@ -252,9 +311,14 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
                 md[c] |= ((uint32_t)((b & 1) << 1) | k) << (2 * b);
             } else {
                 float v0, v1; uint32_t nib;
-                select_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
-                                Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3),
-                                words[c], v0, v1, nib);
+                if constexpr (EST == 1)
+                    select_2of4_approx(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
+                                       Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c),
+                                       words[2 * c], words[2 * c + 1], v0, v1, nib);
+                else
+                    select_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
+                                    Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3),
+                                    words[c], v0, v1, nib);
                 put2(c, b, v0, v1);
                 md[c] |= nib << (4 * b);
                 __builtin_amdgcn_sched_barrier(0);       // one block at a time: interleaving blocks only lengthens live ranges
@@ -396,26 +460,26 @@ __global__ __launch_bounds__(256) void compress_kernel(
 // ------------------------------------------------------------------------------------
 // launchers (called from the C ABI after validation)
 // ------------------------------------------------------------------------------------
-template <int DT, int M>
+template <int DT, int M, int EST>
 static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed, uint32_t stream_id,
                                  void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
 {
     const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     const int64_t blocks = (threads + 255) / 256;
-    hipLaunchKernelGGL((prune_compress_kernel<DT, M>), dim3((unsigned)blocks), dim3(256), 0, st,
+    hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st,
                        g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
     return hipGetLastError();
 }
 
-hipError_t launch_prune(int dt, int m, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+// m = 2: MVUE 1:2;  m = 4: MVUE 2:4 with est = 0 (optimal) or 1 (approx-MVUE)
+hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
 {
-    if (dt == NM_DT_F32)
-        return m == 2 ? launch_prune_t<NM_DT_F32, 2>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
-                      : launch_prune_t<NM_DT_F32, 4>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st);
-    return m == 2 ? launch_prune_t<NM_DT_BF16, 2>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
-                  : launch_prune_t<NM_DT_BF16, 4>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st);
+#define NM_PRUNE(DT, M, EST) launch_prune_t<DT, M, EST>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
+    if (dt == NM_DT_F32) return m == 2 ? NM_PRUNE(NM_DT_F32, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_F32, 4, 1) : NM_PRUNE(NM_DT_F32, 4, 0);
+    return m == 2 ? NM_PRUNE(NM_DT_BF16, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_BF16, 4, 1) : NM_PRUNE(NM_DT_BF16, 4, 0);
+#undef NM_PRUNE
 }
 
 template <int DT, int M>

@@ -64,8 +64,9 @@ def test_prune_argument_errors(lib):
 
 def test_prune_2of4_modes(lib):
     call = lambda mode, **kw: lib.mvue_prune_2of4(P, kw.get("T", 32), 16, 16, 1, 0, 0, mode, P + 0x10000, P + 0x20000, None, 0, None)
-    assert call(1) == NM_ERR_UNSUPPORTED and b"approx" in lib.nm_last_error()
-    assert call(7) == NM_ERR_UNSUPPORTED
+    assert call(2) == NM_ERR_UNSUPPORTED and b"approx" in lib.nm_last_error()
+    assert call(7) == NM_ERR_UNSUPPORTED and call(-1) == NM_ERR_UNSUPPORTED
+    assert call(1, T=24) == NM_ERR_SHAPE
     assert call(0, T=24) == NM_ERR_SHAPE
 
 

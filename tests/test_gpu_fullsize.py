@@ -43,6 +43,23 @@ def test_full_tensor_masks_and_values_bit_exact(case):
     assert np.array_equal(to_host(case["vals"]), case["ov"])
 
 
+def test_full_tensor_approx_mvue_bit_exact(case, oracle):
+    """approx-MVUE (mode 1) on the same full-size tensor: the whole compressed output, bit for bit."""
+    import paper_2203_10991_amd as nm
+    w = case["w"]
+    g, _ = synth.make_device(w, seed=0, device=DEV)            # the same tensor as the fixture's (seeded generator)
+    vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, DEV)
+    nm.mvue_prune_2of4(g, seed=5, stream_id=2, mode=1, vals=vals, meta=meta)
+    torch.cuda.synchronize()
+    g_host = to_host(g)
+    del g
+    print("oracle approx-MVUE prune of the full tensor ...", flush=True)
+    ov, om, _ = oracle.prune_2of4_approx(g_host, 5, 2)
+    del g_host
+    assert np.array_equal(to_host(meta), om)
+    assert np.array_equal(to_host(vals), ov)
+
+
 def test_sampled_entries_and_one_tile(case, oracle):
     w, dW = case["w"], case["dW"]
     rng = np.random.default_rng(0)
