@@ -245,8 +245,9 @@ __device__ __forceinline__ void select_2of4_approx(float x0, float x1, float x2,
 // ------------------------------------------------------------------------------------
 // the fused kernel
 // ------------------------------------------------------------------------------------
-template <int DT, int M, int EST>     // M = 2: MVUE 1:2; M = 4: MVUE 2:4, EST = 0 the optimal estimator, 1 approx-MVUE
-__global__ __launch_bounds__(256) void prune_compress_kernel(
+// M = 2: MVUE 1:2; M = 4: MVUE 2:4, EST = 0 the optimal estimator, 1 approx-MVUE; DENSE: also write theta(g)
+template <int DT, int M, int EST, bool DENSE>
+__device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
     uint32_t key0, uint32_t key1, uint32_t stream_id,
     void *__restrict__ vals_, uint16_t *__restrict__ meta_, void *__restrict__ dense_, int64_t ldd)
@@ -347,7 +348,7 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
     }
 
     // ---- optional dense theta(g)
-    if (dense_) {
+    if constexpr (DENSE) {
         char *dp = (char *)dense_ + ((G * 16) * ldd + col0) * ESZ;
 #pragma unroll
         for (int r = 0; r < 16; ++r) {
@@ -370,6 +371,22 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
             *(uint4 *)(dp + (int64_t)r * ldd * ESZ) = o;
         }
     }
+}
+
+template <int DT, int M, int EST, bool DENSE>
+__global__ __launch_bounds__(256) void prune_compress_kernel(
+    const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals, uint16_t *__restrict__ meta, void *__restrict__ dense, int64_t ldd)
+{
+    prune_compress_body<DT, M, EST, DENSE>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, dense, ldd);
+}
+// The bf16 optimal-2:4 kernel without the dense output needs 98 registers as the compiler would have it, two more
+// than let a fifth wave onto each SIMD; asked for five waves it fits 96 without spilling.
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) void prune_compress_bf16_2of4_kernel(
+    const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals, uint16_t *__restrict__ meta)
+{
+    prune_compress_body<NM_DT_BF16, 4, 0, false>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
 }
 
 // ------------------------------------------------------------------------------------
@@ -467,8 +484,15 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     const int64_t blocks = (threads + 255) / 256;
-    hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st,
-                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
+    if (dense)
+        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0)
+        hipLaunchKernelGGL(prune_compress_bf16_2of4_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
+    else
+        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, false>), dim3((unsigned)blocks), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
     return hipGetLastError();
 }
 
