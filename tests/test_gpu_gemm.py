@@ -56,6 +56,14 @@ def test_update_gemm_matches_fp64_oracle(nm, oracle, dtype, nmode, shape):
     run_case(nm, oracle, synth.Workload(f"s{T}x{O}x{I}_{dtype}_{nmode}", T, O, I, dtype, nmode, 0.0, 2.0, 0.3), seed=T)
 
 
+@pytest.mark.parametrize("T,O,I", [(96, 17 * 256 - 40, 16 * 256),        # 17 x 16 tiles: banded map with a short last band
+                                   (80, 26 * 256, 10 * 256 - 8),         # 26 x 10 tiles: the map for other tile counts
+                                   (112, 16 * 256, 16 * 256)])           # 16 x 16 tiles: the 2 x 4 XCD grid
+def test_large_tile_kernel_and_its_tile_maps(nm, oracle, T, O, I):
+    """Enough output tiles for the 256 x 256 kernel (8 waves), short reductions with a ragged last stage."""
+    run_case(nm, oracle, synth.Workload(f"big{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_beta_one_accumulates(nm, oracle, dtype):
     run_case(nm, oracle, synth.Workload("beta", 16 * 20, 8 * 21, 8 * 19, dtype, "2:4", 0.0, 2.0, 0.3), seed=2, beta=1.0)
