@@ -23,7 +23,9 @@
 // fixed order (deterministic; no atomics).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+#include <stdlib.h>
 
+#include <algorithm>
 #include <type_traits>
 #include <utility>
 
@@ -63,20 +65,32 @@ template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
 //   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B, optionally preceded by
 //              a wait until at most LGKM LDS reads are outstanding (LGKM < 0: no wait); ABID picks the
 //              half of idx that holds the index word
+// IN_VGPR: the block lives in ordinary registers instead (the compiler splits a wave's register budget evenly
+// between the two halves of the file, so a kernel with more than 128 accumulation registers per wave at two waves
+// per SIMD keeps the excess there).
+template <bool IN_VGPR = false>
 __device__ __forceinline__ void acc_zero(f32x16 &acc)
 {
     const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
     // (the compiler does not know this asm is an MFMA: keep the required distance from the VALU moves that write z)
-    asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
+    if constexpr (IN_VGPR) asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=v"(acc) : "v"(z));
+    else                   asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
 }
-template <int LGKM, int ABID>
+template <int LGKM, int ABID, bool IN_VGPR = false>
 __device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
 {
     if constexpr (LGKM >= 0) asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(LGKM));
-    if constexpr (ABID == 0)
-        asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
-    else
-        asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    if constexpr (IN_VGPR) {
+        if constexpr (ABID == 0)
+            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+v"(acc) : "v"(a), "v"(b), "v"(idx));
+        else
+            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+v"(acc) : "v"(a), "v"(b), "v"(idx));
+    } else {
+        if constexpr (ABID == 0)
+            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+        else
+            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    }
 }
 
 // LDS reads are issued as asm so that the compiler does not order them against the direct
@@ -100,6 +114,20 @@ template <int OFFSET> __device__ __forceinline__ uint32_t lds_read_b32(uint32_t 
     asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
     return r;
 }
+// refill forms: the destination is the register the previous value of the same fragment lives in (read-write operand),
+// so a fragment keeps its registers for the whole kernel
+template <int OFFSET> __device__ __forceinline__ void lds_refill_tr16(s16x4 &r, uint32_t addr)
+{
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int OFFSET> __device__ __forceinline__ void lds_refill_b128(u32x4 &r, uint32_t addr)
+{
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int OFFSET> __device__ __forceinline__ void lds_refill_b32(uint32_t &r, uint32_t addr)
+{
+    asm volatile("ds_read_b32 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+}
 typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr)
 {
@@ -115,6 +143,52 @@ template <int N> __device__ __forceinline__ void wait_vmcnt()
     __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
 }
 
+// ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (workgroup id % 8), 32 CUs and one
+// L2 each; the 32 tiles resident on an XCD form a block of 8 M-tiles x 4 N-tiles (N fastest), so that
+// they share operand strips inside its L2 from the first stage on (8 vals strips + 4 h strips feed 32 tiles).
+// Preferred map, when both tile counts are multiples of 16: the XCDs form a 2 x 4 grid and the whole GPU
+// works on one 16 x 16 block of tiles at a time.  Of all 8-XCD arrangements this one streams the fewest
+// bytes per block from HBM (16 vals strips + 16 h strips); strips shared between XCDs meet in the
+// memory-side cache.  Otherwise: one band of M-tiles at a time, XCD x owning the N-tiles [x*nx, (x+1)*nx).
+__device__ __forceinline__ void tile_of_workgroup(int bid_, int tiles_m, int tiles_n, int &tm, int &tn)
+{
+    if (tiles_m % 16 == 0 && tiles_n % 16 == 0) {
+        const int bid = bid_, xcd = bid % 8, slot = bid / 8;         // slot: this XCD's running tile count
+        const int round = slot / 32, local = slot % 32, bands = tiles_m / 16;
+        tm = (round % bands) * 16 + (xcd / 4) * 8 + local / 4;
+        tn = (round / bands) * 16 + (xcd % 4) * 4 + local % 4;
+    } else {
+        const int n_tiles = tiles_m * tiles_n, bid = bid_;
+        const int nx = tiles_n / 8;                                    // N-tiles per XCD
+        if (tiles_n % 8 == 0 && nx <= 32) {
+            const int band_rows = 32 / nx > 0 ? 32 / nx : 1;           // M-tiles per band: band_rows * nx ~ 32 CUs
+            const int xcd = bid % 8, slot = bid / 8;                   // slot: this XCD's running tile count
+            const int per_band = band_rows * nx;
+            const int band = slot / per_band, local = slot % per_band;
+            // the last band may be short: its slots are re-dealt over the rows it has (per XCD the band then holds
+            // fewer tiles, and every slot still belongs to exactly one tile)
+            const int full_bands = tiles_m / band_rows;
+            // N-tile index fastest: tiles that share an h strip AND tiles that share a vals strip start within a few
+            // dispatches of each other, so both kinds of sharing are live in the L2 from the first stage on
+            if (band < full_bands) { tm = band * band_rows + local / nx; tn = xcd * nx + local % nx; }
+            else {
+                const int l2 = slot - full_bands * per_band;            // index inside the short band
+                tm = full_bands * band_rows + l2 / nx; tn = xcd * nx + l2 % nx;
+            }
+        } else {
+            // fallback: contiguous run of tiles per XCD when the count divides evenly, N-fastest inside bands of 8 M-tiles
+            int t = bid;
+            if (n_tiles % 8 == 0) t = (bid % 8) * (n_tiles / 8) + bid / 8;
+            constexpr int BAND = 8;
+            const int band = t / (BAND * tiles_n);
+            const int band_rows = min(BAND, tiles_m - band * BAND);
+            const int in_band = t - band * BAND * tiles_n;
+            tm = band * BAND + in_band % band_rows;
+            tn = in_band / band_rows;
+        }
+    }
+}
+
 // LDS image of one stage (all filled by direct loads, 64 consecutive lanes -> consecutive LDS bytes):
 //   [0, 64*TN)                h tile, [32 tokens][TN columns] bf16, rows unpadded.  Bank conflicts of the
 //                             transposing reads are avoided by a swizzle: 16-byte chunk c of row k sits at
@@ -127,7 +201,8 @@ template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride,       // out + z*slab_stride
-    int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate)
+    int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate,
+    int64_t o_first, int64_t o_end)          // the launch computes rows [o_first, o_end) of dW; tiles_m counts its M-tiles
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
     constexpr int CPR = TN / 8;                           // 16-byte chunks per h row in LDS
@@ -170,54 +245,13 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
         else return S5;
     };
 
-    // ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (blockIdx % 8), 32 CUs and one
-    // L2 each; the 32 tiles resident on an XCD form a block of 8 M-tiles x 4 N-tiles (N fastest), so that
-    // they share operand strips inside its L2 from the first stage on (8 vals strips + 4 h strips feed 32 tiles).
-    // Preferred map, when both tile counts are multiples of 16: the XCDs form a 2 x 4 grid and the whole GPU
-    // works on one 16 x 16 block of tiles at a time.  Of all 8-XCD arrangements this one streams the fewest
-    // bytes per block from HBM (16 vals strips + 16 h strips); strips shared between XCDs meet in the
-    // memory-side cache.  Otherwise: one band of M-tiles at a time, XCD x owning the N-tiles [x*nx, (x+1)*nx).
     int tm, tn;
-    if (tiles_m % 16 == 0 && tiles_n % 16 == 0) {
-        const int bid = blockIdx.x, xcd = bid % 8, slot = bid / 8;         // slot: this XCD's running tile count
-        const int round = slot / 32, local = slot % 32, bands = tiles_m / 16;
-        tm = (round % bands) * 16 + (xcd / 4) * 8 + local / 4;
-        tn = (round / bands) * 16 + (xcd % 4) * 4 + local % 4;
-    } else {
-        const int n_tiles = tiles_m * tiles_n, bid = blockIdx.x;
-        const int nx = tiles_n / 8;                                    // N-tiles per XCD
-        if (tiles_n % 8 == 0 && nx <= 32) {
-            const int band_rows = 32 / nx > 0 ? 32 / nx : 1;           // M-tiles per band: band_rows * nx ~ 32 CUs
-            const int xcd = bid % 8, slot = bid / 8;                   // slot: this XCD's running tile count
-            const int per_band = band_rows * nx;
-            const int band = slot / per_band, local = slot % per_band;
-            // the last band may be short: its slots are re-dealt over the rows it has (per XCD the band then holds
-            // fewer tiles, and every slot still belongs to exactly one tile)
-            const int full_bands = tiles_m / band_rows;
-            // N-tile index fastest: tiles that share an h strip AND tiles that share a vals strip start within a few
-            // dispatches of each other, so both kinds of sharing are live in the L2 from the first stage on
-            if (band < full_bands) { tm = band * band_rows + local / nx; tn = xcd * nx + local % nx; }
-            else {
-                const int l2 = slot - full_bands * per_band;            // index inside the short band
-                tm = full_bands * band_rows + l2 / nx; tn = xcd * nx + l2 % nx;
-            }
-        } else {
-            // fallback: contiguous run of tiles per XCD when the count divides evenly, N-fastest inside bands of 8 M-tiles
-            int t = bid;
-            if (n_tiles % 8 == 0) t = (bid % 8) * (n_tiles / 8) + bid / 8;
-            constexpr int BAND = 8;
-            const int band = t / (BAND * tiles_n);
-            const int band_rows = min(BAND, tiles_m - band * BAND);
-            const int in_band = t - band * BAND * tiles_n;
-            tm = band * BAND + in_band % band_rows;
-            tn = in_band / band_rows;
-        }
-    }
+    tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);       // wave-uniform: keeps LDS bases scalar
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t m0 = (int64_t)tm * TM;                 // tile's first row of dW (= column of g)
+    const int64_t m0 = o_first + (int64_t)tm * TM;       // tile's first row of dW (= column of g)
     const int64_t n0 = (int64_t)tn * TN;                 // tile's first column of h / dW
     const int64_t g_begin = (int64_t)blockIdx.z * groups_per_slab;
     const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
@@ -426,7 +460,255 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = o0 + AB * (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) + a;   // block a holds rows a, AB+a, ...
-                if (row < O && col < I) {
+                if (row < o_end && col < I) {
+                    float *p = out + row * ldo + col;
+                    *p = accumulate ? (*p + acc[a][b][r]) : acc[a][b][r];
+                }
+            }
+        }
+}
+
+// ------------------------------------------------------------------------------------
+// 384 x 256 tile.  What bounds the 256 x 256 kernel on large problems is the path from the L2s to the
+// CUs (0.8 KB of operands per token and tile); a tile that is 1.5 times taller needs 21 % fewer bytes
+// per product.  8 waves as 2 x 4, wave tile 192 x 64 = 6 x 2 accumulator blocks (192 accumulation
+// registers), which leaves 64 ordinary registers per wave: the operand registers are single and are
+// refilled in place -- a fragment of the next stage is read into the registers of the same fragment of
+// the current stage right after the last MFMA that uses them.  MFMA order inside a stage: the six row
+// blocks against column block 0, then against column block 1; so column fragment 0 is refilled after
+// MFMA 6, row fragment a after MFMA 7+a, column fragment 1 after MFMA 12.
+//
+// Rows of a wave's 192-row block are interleaved so that the index words a lane needs are adjacent in
+// the natural `meta` order: accumulator blocks 0-3 hold rows 4m+a of the first 128 rows (m = row inside
+// the block), blocks 4-5 rows 128 + 2m + (a-4).
+// LDS image of a stage: h tile [32][256] bf16 (swizzled as above) | vals [2 groups][384 slots] x 16 B
+// (slot 192*wm + 32*a + m) | meta [2 groups][384 rows] x 2 B; five stages rotate.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
+    const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
+    float *__restrict__ out, int64_t ldo, int64_t slab_stride, int64_t n_groups, int64_t groups_per_slab,
+    int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate, int64_t o_first, int64_t o_end)
+{
+    constexpr int WN = 4, AB = 6, BB = 2, TM = 384, TN = 256, TNS = 5;
+    constexpr int A_OFF = 64 * TN, M_OFF = A_OFF + 2 * TM * 16, STAGE = (M_OFF + 2 * TM * 2 + 1023) / 1024 * 1024;
+    constexpr int LPS = 5;                                   // direct loads per wave and stage: 2 h, 2 vals, 1 meta
+    static_assert(TNS * STAGE <= 160 * 1024, "LDS");
+    __shared__ __attribute__((aligned(1024))) char S[TNS * STAGE];
+
+    int tm, tn;
+    tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = o_first + (int64_t)tm * TM, n0 = (int64_t)tn * TN;
+    const int64_t g_begin = (int64_t)blockIdx.z * groups_per_slab;
+    const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
+    out += (int64_t)blockIdx.z * slab_stride;
+
+    // accumulator blocks of rows a < 4 in accumulation registers (128), a = 4, 5 in ordinary ones (64)
+    f32x16 acc[AB][BB];
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
+        static_for<BB>([&](auto b_c) { acc_zero<(a >= 4)>(acc[a][decltype(b_c)::value]); });
+    });
+
+    const int n_iters = (int)((g_end - g_begin + 1) / 2);      // stages of 2 token groups; the last may be ragged
+    const int n_trips = (n_iters + TNS - 1) / TNS;
+
+    // tile row held by slot q of a token group (see above)
+    auto slot_row = [](int q) {
+        const int blk = q / 192, r = q % 192, a = r / 32, m = r % 32;
+        return blk * 192 + 6 * m + a;
+    };
+    // ---- direct loads.  Wave w brings, of token group w/4 of the stage: 4 rows of h (2 loads), vals slots
+    // [64c, 64c+64) for c = w%4 and c = (w%4 + 4) % 6 (2 loads; chunks 0 and 1 come twice, same bytes to the same
+    // place), meta rows [128c, 128c+128) for c = (w%4) % 3 (1 load).  Per-lane byte offsets inside a stage; the
+    // stage itself is reached through the scalar offset, which the bounds check does not cover: a load for a
+    // token group past the end of the tensor is switched off through the descriptor's size instead.
+    const int wgrp = wave / 4, ws = wave % 4;
+    uint32_t b_src[2], a_src[2], m_src;
+    {
+        constexpr int CPR = TN / 8;                          // 32 chunks of 16 bytes per h row
+        const int dma_row = lane / CPR, dma_pos = lane % CPR;
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {                     // load d covers rows 4*wave + 2*d + dma_row
+            const int row_mod4 = (2 * ph + dma_row) & 3;
+            const int64_t col = min(n0 + 8 * (dma_pos ^ (4 * row_mod4)), I - 8);
+            b_src[ph] = (uint32_t)(((int64_t)(wave * 4 + 2 * ph + dma_row) * ldh + col) * 2);
+        }
+        // vals: slots [96*ws, 96*ws+96) as one 64-lane and one 32-lane load; meta: rows [96*ws, 96*ws+96) as 48 lanes
+#pragma unroll
+        for (int d = 0; d < 2; ++d)
+            a_src[d] = (uint32_t)(wgrp * O + min(m0 + slot_row(96 * ws + 64 * d + (d ? (lane & 31) : lane)), O - 1)) * 16u;
+        m_src = (uint32_t)(wgrp * O + min(m0 + 96 * ws + 2 * (lane % 48), O - 2)) * 2u;
+    }
+    const bool lane_lt32 = lane < 32, lane_lt48 = lane < 48;
+    const uint32_t h_stage = (uint32_t)(KT * ldh * 2), v_stage = (uint32_t)(2 * O * 16), m_stage = (uint32_t)(2 * O * 2);
+    const int first_missing = (int)min((int64_t)0x7fffffff, (n_groups - g_begin - wgrp + 1) / 2);
+    const char *hp = nullptr, *vp = nullptr, *mp = nullptr;   // the tensors at the first stage of the current trip
+    int trip_first = 0;
+    auto rebase = [&](int it) {
+        const int64_t Gs = g_begin + (int64_t)it * 2;
+        hp = (const char *)h + Gs * 16 * ldh * 2;
+        vp = (const char *)vals + Gs * O * 16;
+        mp = (const char *)meta + Gs * O * 2;
+        trip_first = it;
+    };
+    // load K of the stage U stages past the trip's first one, into stage buffer BUF
+    auto fetch_one = [&](auto u_c, auto k_c, auto buf_c) {
+        constexpr uint32_t U = decltype(u_c)::value;
+        constexpr int K = decltype(k_c)::value, BUF = decltype(buf_c)::value % TNS;
+        const int size = trip_first + (int)U < first_missing ? 0x7fffffff : 0;        // 0: every lane out of range, nothing is loaded
+        char *stage = S + BUF * STAGE;
+        if constexpr (K < 2)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)hp, 0, size, 0x00020000),
+                                                     (lptr_t)(stage + (wave * 4 + 2 * K) * (TN * 2)), 16, (int)b_src[K],
+                                                     (int)(U * h_stage), 0, 0);
+        else if constexpr (K == 2)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)vp, 0, size, 0x00020000),
+                                                     (lptr_t)(stage + A_OFF + (wgrp * TM + 96 * ws) * 16), 16,
+                                                     (int)a_src[0], (int)(U * v_stage), 0, 0);
+        else if constexpr (K == 3) {
+            if (lane_lt32)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)vp, 0, size, 0x00020000),
+                                                         (lptr_t)(stage + A_OFF + (wgrp * TM + 96 * ws + 64) * 16), 16,
+                                                         (int)a_src[1], (int)(U * v_stage), 0, 0);
+        } else {
+            if (lane_lt48)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)mp, 0, size, 0x00020000),
+                                                         (lptr_t)(stage + M_OFF + (wgrp * TM + 96 * ws) * 2), 4, (int)m_src,
+                                                         (int)(U * m_stage), 0, 0);
+        }
+    };
+    // "stage `it` has landed" with the loads of IN_FLIGHT later stages still on their way; a wave whose token
+    // group lies past the end of the tensor clears what it would have brought (its loads were switched off)
+    auto stage_ready = [&](auto in_flight_c, int it, auto buf_c) {
+        constexpr int BUF = decltype(buf_c)::value % TNS;
+        wait_vmcnt<decltype(in_flight_c)::value * LPS>();
+        if (it >= first_missing) {
+            // zero kept values make the group's products zero whatever the h rows and index words left in the buffer are
+            // (finite operands of an earlier stage).  Everything the branch needs is made inside it: nothing of it
+            // occupies a register on the common path.
+            char *stage = S + BUF * STAGE;
+            uint32_t zero, ln;
+            asm volatile("v_mov_b32 %0, 0\n\tv_mbcnt_lo_u32_b32 %1, -1, 0\n\tv_mbcnt_hi_u32_b32 %1, -1, %1" : "=v"(zero), "=v"(ln));
+            const uint4 z = make_uint4(zero, zero, zero, zero);
+            *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + ln) * 16) = z;
+            if (ln < 32) *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + 64 + ln) * 16) = z;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- LDS read addresses of the stage being read; they advance by one stage per slot
+    const int li = lane & 15, q4 = lane >> 4, kg = lane >> 5, m = lane & 31;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)S;
+    uint32_t cur_a = lds0 + (uint32_t)(A_OFF + (kg * TM + wm * 192 + m) * 16);                 // + 32*a*16
+    uint32_t cur_m = lds0 + (uint32_t)(M_OFF + (kg * TM + wm * 192 + 6 * m) * 2);              // 6 consecutive words (three reads)
+    // column block b of wave wn is block b*4 + wn of the tile: the swizzle only touches the low two bits of that
+    // number, so the two blocks of a wave are a constant 256 bytes apart in every row
+    uint32_t cur_b = lds0 + (uint32_t)((8 * (q4 >> 1) + (li >> 2)) * (TN * 2) +
+                                       (4 * (wn ^ (li >> 2)) + 2 * (q4 & 1) + ((li & 3) >> 1)) * 16 + (li & 1) * 8);
+    // (asm: the compiler would otherwise keep one copy of every address per stage buffer)
+    auto advance = [&](int bytes) {
+        asm volatile("v_add_u32 %0, %3, %0\n\tv_add_u32 %1, %3, %1\n\tv_add_u32 %2, %3, %2" : "+v"(cur_a), "+v"(cur_m), "+v"(cur_b) : "s"(bytes));
+    };
+
+    Frag8 af[AB];
+    Frag16 bf[BB];
+    uint32_t ix[3] = {0, 0, 0};                              // index words of blocks (0,1), (2,3), (4,5): low and high half
+#pragma unroll
+    for (int a = 0; a < AB; ++a) af[a].u4 = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < BB; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[b].q[j] = s16x4{0, 0, 0, 0};
+    auto read_a = [&](auto a_c) { constexpr int a = decltype(a_c)::value; lds_refill_b128<32 * a * 16>(af[a].u4, cur_a); };
+    auto read_ix = [&](auto j_c) {
+        constexpr int j = decltype(j_c)::value;
+        lds_refill_b32<4 * j>(ix[j], cur_m);
+    };
+    auto read_b = [&](auto b_c) {
+        constexpr int b = decltype(b_c)::value, R = TN * 2;
+        lds_refill_tr16<0 * R + 256 * b>(bf[b].q[0], cur_b);
+        lds_refill_tr16<4 * R + 256 * b>(bf[b].q[1], cur_b);
+        lds_refill_tr16<16 * R + 256 * b>(bf[b].q[2], cur_b);
+        lds_refill_tr16<20 * R + 256 * b>(bf[b].q[3], cur_b);
+    };
+    // LDS reads of one stage, in issue order (the waits below count on it):
+    //   B0 (4 reads) | A0 | A1, ix0 | A2 | A3, ix1 | A4 | A5, ix2, B1 (4)
+    // One stage of MFMAs.  Before MFMA number n (1..12) the reads issued after the ones it needs may still be
+    // outstanding: that count is the wait.  After it: the refill of what it freed, and a share of the direct loads.
+    auto mfma = [&](auto a_c, auto b_c) {
+        constexpr int a = decltype(a_c)::value, b = decltype(b_c)::value;
+        smfmac_32x32x32<-1, (a & 1), (a >= 4)>(acc[a][b], af[a].v, bf[b].v, ix[a / 2]);
+    };
+    auto lgkm_wait = [&](auto n_c, auto) { asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(decltype(n_c)::value)); };
+    using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>; using I4 = std::integral_constant<int, 4>; using I5 = std::integral_constant<int, 5>;
+    auto consume = [&](auto fu_c, auto fbuf_c) {
+        lgkm_wait(std::integral_constant<int, 10>{}, I0{}); mfma(I0{}, I0{});
+        fetch_one(fu_c, I0{}, fbuf_c);
+        mfma(I1{}, I0{});
+        lgkm_wait(std::integral_constant<int, 7>{}, I2{});  mfma(I2{}, I0{});
+        fetch_one(fu_c, I1{}, fbuf_c);
+        mfma(I3{}, I0{});
+        lgkm_wait(std::integral_constant<int, 4>{}, I4{});  mfma(I4{}, I0{});     // (ix2 is the last read before B1)
+        fetch_one(fu_c, I2{}, fbuf_c);
+        mfma(I5{}, I0{});
+        read_b(I0{});
+        asm volatile("s_waitcnt lgkmcnt(4)");
+        mfma(I0{}, I1{}); read_a(I0{});
+        mfma(I1{}, I1{}); read_a(I1{}); read_ix(I0{});
+        fetch_one(fu_c, I3{}, fbuf_c);
+        mfma(I2{}, I1{}); read_a(I2{});
+        mfma(I3{}, I1{}); read_a(I3{}); read_ix(I1{});
+        fetch_one(fu_c, I4{}, fbuf_c);
+        mfma(I4{}, I1{}); read_a(I4{});
+        mfma(I5{}, I1{}); read_a(I5{}); read_ix(I2{}); read_b(I1{});
+    };
+    auto read_all = [&]() {
+        read_b(I0{}); read_a(I0{}); read_a(I1{}); read_ix(I0{}); read_a(I2{}); read_a(I3{}); read_ix(I1{}); read_a(I4{});
+        read_a(I5{}); read_ix(I2{}); read_b(I1{});
+    };
+
+    // Five LDS stages.  Slot j: stage j's operands are in (or on their way into) registers, read during slot j-1;
+    // stage j+1 has landed (the barrier that opens the slot) and is read during the slot; the loads of stages j+2 and
+    // j+3 are in flight, those of stage j+4 are issued into the buffer stage j-1 occupied (every wave finished reading
+    // it before it arrived at this slot's barrier).  Stages past the end of the tensor hold zeros, so the stage count
+    // is padded to a multiple of five and nothing that runs ahead needs a guard.
+    if (n_trips > 0) {
+        rebase(0);
+        static_for<TNS - 1>([&](auto u_c) { static_for<LPS>([&](auto k_c) { fetch_one(u_c, k_c, u_c); }); });
+        stage_ready(std::integral_constant<int, TNS - 2>{}, 0, I0{});
+        read_all();
+        advance(STAGE);
+    }
+    for (int tr = 0; tr < n_trips; ++tr) {
+        const int it = TNS * tr;
+        rebase(it);
+        static_for<TNS>([&](auto u_c) {
+            constexpr int u = decltype(u_c)::value;
+            stage_ready(std::integral_constant<int, TNS - 3>{}, it + u + 1, std::integral_constant<int, u + 1>{});
+            consume(std::integral_constant<int, u + TNS - 1>{}, std::integral_constant<int, u + TNS - 1>{});
+            advance(u == TNS - 2 ? -(TNS - 1) * STAGE : STAGE);       // the reads of the next slot take the stage after
+        });
+    }
+
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int a = 0; a < AB; ++a)
+#pragma unroll
+        for (int b = 0; b < BB; ++b) {
+            const int64_t col = n0 + (b * 4 + wn) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int mr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);               // row inside the accumulator block
+                const int64_t row = m0 + wm * 192 + 6 * mr + a;
+                if (row < o_end && col < I) {
                     float *p = out + row * ldo + col;
                     *p = accumulate ? (*p + acc[a][b][r]) : acc[a][b][r];
                 }
@@ -463,22 +745,42 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
 // ------------------------------------------------------------------------------------
 // host side: tile shape and split-K plan (pure function of the problem size)
 // ------------------------------------------------------------------------------------
-struct Plan { int shape; int tm, tn; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; };
+// tall_rows: rows [0, tall_rows) of dW are computed by the 384 x 256 kernel (tall_tiles_m tile rows), the rest by the
+// kernel of `shape` (tiles_m tile rows); 0 = that kernel alone.
+struct Plan { int shape; int tm, tn; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
+static const bool g_allow_tall = getenv("NM_GEMM_NO_TALL") == nullptr;      // (switch for A/B measurements)
 
 static Plan make_plan(int64_t T, int64_t O, int64_t I)
 {
     Plan p;
     const int64_t groups = T / 16;
     const int CUS = 256;
+    p.tall_rows = 0; p.tall_tiles_m = 0;
     // shape 0: 256x256, shape 1: 128x128, shape 2: 64x256 (few rows)
     if (O <= 64) { p.shape = 2; p.tm = 64; p.tn = 256; }
-    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) { p.shape = 0; p.tm = 256; p.tn = 256; }
+    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
+        p.shape = 0; p.tm = 256; p.tn = 256;
+        // Large problems: the 384 x 256 kernel moves 21 % fewer operand bytes per product and is ~10 % faster per
+        // product, but a GPU-wide round of its tiles takes 1.34 times as long, and a partly filled last round costs
+        // as much as a full one.  So the rows are split: the first mt tile rows go to the tall kernel, the rest to
+        // the 256 x 256 kernel, mt chosen to minimise the summed cost of whole rounds (mt = 0: no tall launch).
+        const int64_t tn = (I + 255) / 256;
+        double best = 1e300;
+        int64_t best_mt = 0;
+        for (int64_t mt = 0; g_allow_tall && mt <= (O + 383) / 384; ++mt) {
+            const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
+            const double cost = 1.34 * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
+            if (cost < best - 1e-9) { best = cost; best_mt = mt; }
+        }
+        p.tall_tiles_m = (int)best_mt;
+        p.tall_rows = std::min<int64_t>(O, best_mt * 384);
+    }
     else { p.shape = 1; p.tm = 128; p.tn = 128; }
-    p.tiles_m = (int)((O + p.tm - 1) / p.tm);
+    p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + p.tn - 1) / p.tn);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     int slabs = 1;
-    if (tiles < CUS && groups >= 64) {
+    if (p.tall_rows == 0 && tiles < CUS && groups >= 64) {
         slabs = (int)((2 * CUS + tiles - 1) / tiles);                 // about two workgroups per CU
         const int64_t max_slabs = groups / 32;                         // at least 512 tokens per slab
         if (slabs > max_slabs) slabs = (int)max_slabs;
@@ -509,15 +811,25 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
     int64_t ldo = lddw, slab_stride = 0;
     int acc_flag = accumulate;
     if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; }
-    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
+    if (p.tall_rows > 0) {
+        dim3 tall_grid((unsigned)(p.tall_tiles_m * p.tiles_n), 1, 1);
+        hipLaunchKernelGGL(update_gemm_smfmac_tall_kernel, tall_grid, dim3(512), 0, st, (const uint16_t *)vals, meta, (const uint16_t *)h,
+                           ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I, p.tall_tiles_m, p.tiles_n, acc_flag,
+                           (int64_t)0, p.tall_rows);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+    }
+    if (p.tiles_m > 0) {
+        dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, (const uint16_t *)vals,   \
                        meta, (const uint16_t *)h, ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I,         \
-                       p.tiles_m, p.tiles_n, acc_flag)
-    if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
-    else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
-    else NM_LAUNCH(1, 4, 2, 2);
+                       p.tiles_m, p.tiles_n, acc_flag, p.tall_rows, O)
+        if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
+        else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
+        else NM_LAUNCH(1, 4, 2, 2);
 #undef NM_LAUNCH
+    }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, st);

@@ -56,11 +56,15 @@ def test_update_gemm_matches_fp64_oracle(nm, oracle, dtype, nmode, shape):
     run_case(nm, oracle, synth.Workload(f"s{T}x{O}x{I}_{dtype}_{nmode}", T, O, I, dtype, nmode, 0.0, 2.0, 0.3), seed=T)
 
 
-@pytest.mark.parametrize("T,O,I", [(96, 17 * 256 - 40, 16 * 256),        # 17 x 16 tiles: banded map with a short last band
-                                   (80, 26 * 256, 10 * 256 - 8),         # 26 x 10 tiles: the map for other tile counts
-                                   (112, 16 * 256, 16 * 256)])           # 16 x 16 tiles: the 2 x 4 XCD grid
-def test_large_tile_kernel_and_its_tile_maps(nm, oracle, T, O, I):
-    """Enough output tiles for the 256 x 256 kernel (8 waves), short reductions with a ragged last stage."""
+@pytest.mark.parametrize("T,O,I", [(112, 16 * 256, 16 * 256),            # 16 x 16 tiles of 256 x 256: the 2 x 4 XCD grid
+                                   (80, 50 * 256 - 40, 8 * 256),         # 50 x 8 tiles: banded map with a short last band
+                                   (80, 25 * 256, 10 * 256 - 8),         # 25 x 10 tiles: the map for other tile counts
+                                   (96, 17 * 256 - 40, 16 * 256),        # 12 x 16 tiles of 384 x 256 alone, ragged last tile row
+                                   (96, 32 * 384, 16 * 256),             # 32 x 16 tiles of 384 x 256 alone
+                                   (80, 16 * 384 + 16 * 256, 16 * 256)]) # rows split: 16 tile rows of 384, then 16 of 256
+def test_large_tile_kernels_and_their_tile_maps(nm, oracle, T, O, I):
+    """Enough output tiles for the 8-wave kernels (256 x 256, 384 x 256, or both on a row split), at short
+    reductions with a ragged last stage.  Which kernel a shape takes follows from the plan's cost rule."""
     run_case(nm, oracle, synth.Workload(f"big{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T)
 
 
