@@ -137,11 +137,12 @@ def main():
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
         "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / SPARSE_PEAK_TFLOPS,
         "gemm_ms": gemm_ms,
-        "roofline": {"kernel": "update_gemm_smfmac_kernel", "bound": "mfma", "achieved": gemm_tflops,
+        "roofline": {"kernel": "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
+                               "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
                      "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / SPARSE_PEAK_TFLOPS,
                      "traffic": read_traffic(w.name, "gemm"),
-                     "note": "dense-equivalent flops 2*T*O*I per launch; peak = 2 x published dense bf16 MFMA peak "
-                             "(4:2 sparse MFMA executes half the products)"},
+                     "note": "dense-equivalent flops 2*T*O*I per call; time = HIP events around the call's kernels; "
+                             "peak = 2 x published dense bf16 MFMA peak (4:2 sparse MFMA executes half the products)"},
         "roofline_prune": {"kernel": "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(w.name, "prune"),

@@ -93,6 +93,26 @@ __device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, co
     }
 }
 
+// An empty statement that "rewrites" an accumulator block: placed after the idle cycles that follow the last MFMA,
+// it makes everything that reads the block later (stores, or copies the compiler makes for them) depend on it, so
+// that none of it can be placed above the wait.  (The compiler cannot see that the asm MFMAs are still in flight.)
+template <bool IN_VGPR = false>
+__device__ __forceinline__ void acc_settled(f32x16 &acc)
+{
+    if constexpr (IN_VGPR) asm volatile("" : "+v"(acc));
+    else                   asm volatile("" : "+a"(acc));
+}
+
+// One accumulator element to global memory, straight from the register it lives in (memory instructions take
+// accumulation registers as data): otherwise the compiler copies whole blocks to ordinary registers first and,
+// short of those, spills accumulators to scratch around the epilogue.
+template <bool IN_VGPR = false>
+__device__ __forceinline__ void store_acc(float *p, float v)
+{
+    if constexpr (IN_VGPR) asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
+    else                   asm volatile("global_store_dword %0, %1, off" : : "v"(p), "a"(v) : "memory");
+}
+
 // LDS reads are issued as asm so that the compiler does not order them against the direct
 // global->LDS loads still in flight for later stages; that ordering is explicit (vmcnt wait +
 // barrier per stage), and so are the waits for the reads themselves (LGKM above).
@@ -450,6 +470,10 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     // (The reads issued ahead for the stage after the last are drained first: their destination registers are dead.)
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int a = 0; a < AB; ++a)
+#pragma unroll
+        for (int b = 0; b < BB; ++b) acc_settled(acc[a][b]);
     __builtin_amdgcn_sched_barrier(0);
     const int64_t o0 = m0 + wm * (AB * 32);
 #pragma unroll
@@ -462,9 +486,11 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
                 const int64_t row = o0 + AB * (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) + a;   // block a holds rows a, AB+a, ...
                 if (row < o_end && col < I) {
                     float *p = out + row * ldo + col;
-                    *p = accumulate ? (*p + acc[a][b][r]) : acc[a][b][r];
+                    if (accumulate) *p = *p + acc[a][b][r];
+                    else store_acc(p, acc[a][b][r]);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);       // one block at a time: keeps the address arithmetic of 16 stores, not of all, live
         }
 }
 
@@ -698,9 +724,14 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
 
     __builtin_amdgcn_sched_barrier(0);
     asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
-    __builtin_amdgcn_sched_barrier(0);
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
 #pragma unroll
-    for (int a = 0; a < AB; ++a)
+        for (int b = 0; b < BB; ++b) acc_settled<(a >= 4)>(acc[a][b]);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
 #pragma unroll
         for (int b = 0; b < BB; ++b) {
             const int64_t col = n0 + (b * 4 + wn) * 32 + (lane & 31);
@@ -710,10 +741,13 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
                 const int64_t row = m0 + wm * 192 + 6 * mr + a;
                 if (row < o_end && col < I) {
                     float *p = out + row * ldo + col;
-                    *p = accumulate ? (*p + acc[a][b][r]) : acc[a][b][r];
+                    if (accumulate) *p = *p + acc[a][b][r];
+                    else store_acc<(a >= 4)>(p, acc[a][b][r]);
                 }
             }
+            __builtin_amdgcn_sched_barrier(0);       // one block at a time
         }
+    });
 }
 
 // out[o][i] = (accumulate ? out : 0) + sum_z part[z][o][i], z ascending
