@@ -73,6 +73,11 @@ def test_beta_one_accumulates(nm, oracle, dtype):
     run_case(nm, oracle, synth.Workload("beta", 16 * 20, 8 * 21, 8 * 19, dtype, "2:4", 0.0, 2.0, 0.3), seed=2, beta=1.0)
 
 
+def test_beta_one_accumulates_in_the_large_tile_kernels(nm, oracle):
+    run_case(nm, oracle, synth.Workload("beta_big", 48, 16 * 384 + 16 * 256 - 16, 16 * 256, "bf16", "2:4", 0.0, 2.0, 0.3),
+             seed=3, beta=1.0)
+
+
 def test_zero_operand_and_empty_reduction(nm):
     v, m = nm.alloc_compressed(64, 64, torch.bfloat16, DEV)
     v.zero_(); m.fill_(0x4E4E)                       # index (2,3) everywhere: valid pattern, zero values
