@@ -143,7 +143,7 @@ def main():
                      "traffic": read_traffic(w.name, "gemm"),
                      "note": "dense-equivalent flops 2*T*O*I per call; time = HIP events around the call's kernels; "
                              "peak = 2 x published dense bf16 MFMA peak (4:2 sparse MFMA executes half the products)"},
-        "roofline_prune": {"kernel": "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
+        "roofline_prune": {"kernel": "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(w.name, "prune"),
                            "note": f"algorithmic bytes {w.prune_bytes} per launch: read g, write T/2 values and T/16 index words per column"},
