@@ -176,6 +176,25 @@ def main():
     except Exception as e:                       # no management interface: the published-peak roofline stands alone
         out["gemm_sclk_MHz_sampled"] = None
         out["gemm_sclk_note"] = repr(e)[:200]
+    # What a plain device-to-device copy moves on this machine (1 GiB read + 1 GiB written per copy, the runtime's own copy
+    # kernel): context for the HBM roofline of the prune kernel, which is priced against the published 8 TB/s.
+    try:
+        src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(10):
+            dst.copy_(src)
+        e1.record()
+        torch.cuda.synchronize()
+        copy_gbps = 10 * 2 * src.numel() * 4 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+        out["roofline_prune"]["device_copy_GBps_measured"] = copy_gbps
+        out["roofline_prune"]["frac_of_device_copy"] = prune_gbps / copy_gbps
+        del src, dst
+    except Exception as e:
+        out["roofline_prune"]["device_copy_GBps_measured"] = None
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)

@@ -69,6 +69,21 @@ def lib():
         _lib.oracle_update_gemm.restype = None
         _lib.oracle_update_gemm_entries.argtypes = [vp, vp, vp, i64, i64, i64, i64, i32, vp, i64, vp, vp]
         _lib.oracle_update_gemm_entries.restype = None
+        u8, flt = C.c_uint8, C.c_float
+        _lib.oracle_e5m2_value.argtypes = [u8]
+        _lib.oracle_e5m2_value.restype = dbl
+        _lib.oracle_e4m3_value.argtypes = [u8]
+        _lib.oracle_e4m3_value.restype = dbl
+        _lib.oracle_sr_e5m2.argtypes = [flt, u32]
+        _lib.oracle_sr_e5m2.restype = u8
+        _lib.oracle_block_r16_pair.argtypes = [u64, u32, u64, vp]
+        _lib.oracle_block_r16_pair.restype = None
+        _lib.oracle_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, flt, vp, vp]
+        _lib.oracle_prune_2of4_q8.restype = i32
+        _lib.oracle_nm_decompress_q8.argtypes = [vp, vp, i64, i64, vp]
+        _lib.oracle_nm_decompress_q8.restype = None
+        _lib.oracle_update_gemm_q8.argtypes = [vp, vp, vp, i64, i64, i64, i64, dbl, vp, i64, vp, vp]
+        _lib.oracle_update_gemm_q8.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -232,4 +247,64 @@ def update_gemm_entries(vals: np.ndarray, meta: np.ndarray, h: np.ndarray, oi: n
     out_abs = np.zeros(len(oi))
     lib().oracle_update_gemm_entries(_p(vals), _p(meta), _p(h), ldh, T, O, I, _dt(vals), _p(oi), len(oi),
                                      _p(out), _p(out_abs))
+    return out, out_abs
+
+
+# ---- 8-bit neural gradients (e5m2, stochastic rounding) on top of 2:4 sparsity; 32-token groups:
+# vals8[T/32, O, 16] uint8 + meta32[T/32, O] uint32
+
+def e5m2_value(code: int) -> float:
+    return float(lib().oracle_e5m2_value(int(code) & 0xFF))
+
+
+def e4m3_value(code: int) -> float:
+    return float(lib().oracle_e4m3_value(int(code) & 0xFF))
+
+
+def sr_e5m2(x: float, r16: int) -> int:
+    return int(lib().oracle_sr_e5m2(C.c_float(float(x)), int(r16) & 0xFFFFFFFF))
+
+
+def block_r16_pair(seed: int, stream_id: int, blk: int) -> Tuple[int, int]:
+    r = np.zeros(2, dtype=np.uint32)
+    lib().oracle_block_r16_pair(int(seed), int(stream_id), int(blk), _p(r))
+    return int(r[0]), int(r[1])
+
+
+def prune_2of4_q8(g: np.ndarray, seed: int = 0, stream_id: int = 0, mode: int = 0, scale: float = 1.0):
+    """g: [T, O] float32 or uint16 (bf16 bits), T % 32 == 0.  Returns (vals8 [T/32, O, 16], meta32 [T/32, O])."""
+    g = np.ascontiguousarray(g)
+    T, O = g.shape
+    vals8 = np.zeros((T // 32, O, 16), dtype=np.uint8)
+    meta32 = np.zeros((T // 32, O), dtype=np.uint32)
+    rc = lib().oracle_prune_2of4_q8(_p(g), T, O, O, _dt(g), int(seed), int(stream_id), int(mode),
+                                    C.c_float(float(scale)), _p(vals8), _p(meta32))
+    if rc != 0:
+        raise ValueError("oracle_prune_2of4_q8: bad shape or mode")
+    return vals8, meta32
+
+
+def nm_decompress_q8(vals8: np.ndarray, meta32: np.ndarray) -> np.ndarray:
+    G, O = meta32.shape
+    dense = np.zeros((G * 32, O), dtype=np.float64)
+    lib().oracle_nm_decompress_q8(_p(np.ascontiguousarray(vals8)), _p(np.ascontiguousarray(meta32)), G * 32, O, _p(dense))
+    return dense
+
+
+def update_gemm_q8(vals8: np.ndarray, meta32: np.ndarray, h8: np.ndarray, alpha: float = 1.0,
+                   oi: Optional[np.ndarray] = None):
+    """h8: [T, I] uint8 (e4m3 codes).  Returns (dW, absdW) as float64: [O, I], or [n] for the entries oi [n, 2]."""
+    G, O = meta32.shape
+    h8 = np.ascontiguousarray(h8)
+    T, I = h8.shape
+    assert T == G * 32
+    if oi is None:
+        n, shape, oip = O * I, (O, I), None
+    else:
+        oi = np.ascontiguousarray(oi, dtype=np.int64)
+        n, shape, oip = oi.shape[0], (oi.shape[0],), _p(oi)
+    out = np.zeros(shape, dtype=np.float64)
+    out_abs = np.zeros(shape, dtype=np.float64)
+    lib().oracle_update_gemm_q8(_p(np.ascontiguousarray(vals8)), _p(np.ascontiguousarray(meta32)), _p(h8), I, T, O, I,
+                                float(alpha), oip, n, _p(out), _p(out_abs))
     return out, out_abs

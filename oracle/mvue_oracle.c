@@ -18,6 +18,9 @@
  *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
  *                                      fixes Philox4x32-10 (Salmon et al., SC'11) as a pure
  *                                      function of (seed, stream, block index).
+ *   - 8-bit neural gradients ........ Sec. 5 (sparsity in all phases + 8-bit quantisation: FP8 neural
+ *                                      gradients) with the unbiasedness requirement of Sec. 3:
+ *                                      stochastic rounding of the kept values to e5m2.
  *   - compressed format ............. not in the paper ("footprint ... up to x2", abstract);
  *                                      defined below.
  *
@@ -35,7 +38,8 @@
  *
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (published
  * Philox known answers, closed-form probabilities/variances, exhaustive enumeration of
- * all 2^24 thresholds, brute-force minimum variance, library GEMM).
+ * all 2^24 thresholds, brute-force minimum variance, library GEMM; the 8-bit path by a library's
+ * float8 decoder and nearest cast, exact rational counts over all 2^16 rounding words, library GEMM).
  */
 #include <math.h>
 #include <stdint.h>
@@ -540,6 +544,169 @@ void oracle_update_gemm_entries(const void *vals, const uint16_t *meta, const vo
         }
         out[e] = acc;
         if (out_abs) out_abs[e] = aacc;
+    }
+}
+
+/* ------------------------------------------------------------------------- */
+/* 8-bit neural gradients on top of 2:4 sparsity (Sec. 5, the "8-bit" rows of    */
+/* the table that combines sparsity in all training phases with quantisation:    */
+/* FP8 neural gradients).  Sec. 3 recalls why the quantiser of a neural gradient */
+/* has to be unbiased: stochastic rounding.  The paper fixes neither the bit     */
+/* layout nor the scale; this build takes                                         */
+/*   gradients   e5m2 (1 sign, 5 exponent, 2 mantissa bits, bias 15, IEEE-like    */
+/*               subnormals; the finite codes are the upper byte of a binary16)   */
+/*   activations e4m3 (1-4-3, bias 7, no infinities, 0x7F/0xFF = NaN, max 448)    */
+/*               -- the 8-bit format the matrix unit multiplies e5m2 with; it     */
+/*               stands in for the paper's INT8 activations                       */
+/* both as defined by the OCP 8-bit floating point specification (OFP8).          */
+/* ------------------------------------------------------------------------- */
+double oracle_e5m2_value(uint8_t c)
+{
+    int sign = c >> 7, e = (c >> 2) & 31, m = c & 3;
+    double v;
+    if (e == 31) v = m ? NAN : INFINITY;
+    else if (e == 0) v = ldexp((double)m, -16);                 /* subnormal: m/4 * 2^-14 */
+    else v = ldexp(1.0 + (double)m / 4.0, e - 15);
+    return sign ? -v : v;
+}
+
+double oracle_e4m3_value(uint8_t c)
+{
+    int sign = c >> 7, e = (c >> 3) & 15, m = c & 7;
+    double v;
+    if (e == 15 && m == 7) v = NAN;
+    else if (e == 0) v = ldexp((double)m, -9);                  /* subnormal: m/8 * 2^-6 */
+    else v = ldexp(1.0 + (double)m / 8.0, e - 7);
+    return sign ? -v : v;
+}
+
+/*
+ * Stochastic rounding of a binary32 value to e5m2 with 16 random bits r16 in [0, 2^16).
+ * lo <= |x| < hi are neighbouring magnitudes of the e5m2 grid and f = (|x| - lo)/(hi - lo):
+ * the result is hi when  r16 + floor(f * 2^16) >= 2^16,  else lo; the sign is kept.  Over a
+ * uniform r16 the mean is lo + (hi - lo) * floor(f 2^16) / 2^16: unbiased up to 2^-16 of a grid
+ * step.  Magnitudes at or above the largest finite value (57344) saturate to it; NaN gives NaN.
+ */
+uint8_t oracle_sr_e5m2(float x, uint32_t r16)
+{
+    uint8_t sign = (uint8_t)(float_to_bits(x) >> 31 << 7);
+    double m = fabs((double)x);
+    if (isnan(x)) return (uint8_t)(sign | 0x7F);
+    if (m >= oracle_e5m2_value(0x7B)) return (uint8_t)(sign | 0x7B);
+    int c = 0;
+    while (oracle_e5m2_value((uint8_t)(c + 1)) <= m) ++c;       /* codes 0..0x7B ascend with magnitude */
+    double lo = oracle_e5m2_value((uint8_t)c), hi = oracle_e5m2_value((uint8_t)(c + 1));
+    double f = (m - lo) / (hi - lo);
+    uint32_t thr = (uint32_t)floor(f * 65536.0);
+    return (uint8_t)(sign | (uint8_t)(c + ((r16 & 0xFFFFu) + thr >= 65536u ? 1 : 0)));
+}
+
+/*
+ * The rounding bits of block `blk`: one Philox call per four blocks, counter = (blk/4 low, blk/4 high,
+ * stream, 2) -- the last word separates this stream from the selection streams above --, the block
+ * takes output word blk%4; its low half rounds the first kept value, its high half the second.
+ */
+void oracle_block_r16_pair(uint64_t seed, uint32_t stream_id, uint64_t blk, uint32_t r[2])
+{
+    uint64_t call = blk >> 2;
+    uint32_t ctr[4] = { (uint32_t)call, (uint32_t)(call >> 32), stream_id, 2u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    r[0] = out[blk & 3] & 0xFFFFu;
+    r[1] = out[blk & 3] >> 16;
+}
+
+/*
+ * 2:4 prune (mode 0: optimal MVUE, Sec. 4.2; mode 1: approx-MVUE, Sec. 4.4) with 8-bit output.
+ * Selection and kept values are exactly those of oracle_prune_2of4 / oracle_prune_2of4_approx
+ * (same random stream, same block index), taken in binary32 before any storage rounding; each
+ * kept value is multiplied by `scale` (one binary32 product) and rounded stochastically to e5m2.
+ * E[q / scale] = theta(g) up to the 2^-16 granularity above, so the estimate stays unbiased (Sec. 3).
+ *
+ * 8-bit group format: groups of 32 tokens = 8 quads.  For group G and column o
+ *     vals8[(G*O + o)*16 + 2*i + s]   s-th kept value (ascending position) of quad i, i = 0..7
+ *     meta32[G*O + o]  (uint32)       bits [4i+1:4i] = position of kept 0, [4i+3:4i+2] = kept 1
+ * Returns 0, or -1 for shapes the format cannot hold (T % 32 != 0) or an unknown mode.
+ */
+int oracle_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                         uint64_t seed, uint32_t stream_id, int mode, float scale,
+                         uint8_t *vals8, uint32_t *meta32)
+{
+    if (T % 32 || T < 0 || O < 0 || (mode != 0 && mode != 1)) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 32; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint32_t md = 0;
+            for (int i = 0; i < 8; ++i) {
+                int64_t q = G * 8 + i, t0 = q * 4;
+                uint64_t blk = (uint64_t)q * (uint64_t)O + (uint64_t)o;
+                float x[4];
+                for (int k = 0; k < 4; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                int pos[2]; float v[2];
+                if (mode == 0) {
+                    int wc;
+                    oracle_select_2of4(x, u24_to_eps(oracle_block_u24(seed, stream_id, blk)), pos, v, &wc);
+                } else {
+                    uint32_t u[2];
+                    oracle_block_u24_pair(seed, stream_id, blk, u);
+                    oracle_select_2of4_approx(x, u24_to_eps(u[0]), u24_to_eps(u[1]), pos, v);
+                }
+                uint32_t r[2];
+                oracle_block_r16_pair(seed, stream_id, blk, r);
+                for (int s = 0; s < 2; ++s) {
+                    float scaled = v[s] * scale;
+                    vals8[(G * O + o) * 16 + 2 * i + s] = oracle_sr_e5m2(scaled, r[s]);
+                }
+                md |= (uint32_t)(pos[0] | (pos[1] << 2)) << (4 * i);
+            }
+            meta32[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+/* expand the 8-bit group format to a dense binary64 [T x O] tensor (decoded e5m2 values, pruned positions 0) */
+void oracle_nm_decompress_q8(const uint8_t *vals8, const uint32_t *meta32, int64_t T, int64_t O, double *dense)
+{
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t o = 0; o < O; ++o) dense[t * O + o] = 0.0;
+    for (int64_t G = 0; G < T / 32; ++G)
+        for (int64_t o = 0; o < O; ++o)
+            for (int i = 0; i < 8; ++i)
+                for (int s = 0; s < 2; ++s) {
+                    int k = (int)((meta32[G * O + o] >> (4 * i + 2 * s)) & 3u);
+                    dense[(G * 32 + 4 * i + k) * O + o] = oracle_e5m2_value(vals8[(G * O + o) * 16 + 2 * i + s]);
+                }
+}
+
+/*
+ * Update GEMM (eq. (3)) on the 8-bit operands, for n entries oi = {o0,i0,o1,i1,...} (n = O*I with
+ * oi == NULL means every entry, row-major):
+ *     out = alpha * sum_t e5m2(gt[t][o]) * e4m3(h8[t][i])        (binary64, t ascending)
+ * alpha undoes the two scales (1 / (scale_g * scale_h)).  out_abs: the same sum over magnitudes.
+ */
+void oracle_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh,
+                           int64_t T, int64_t O, int64_t I, double alpha,
+                           const int64_t *oi, int64_t n, double *out, double *out_abs)
+{
+    #pragma omp parallel for schedule(dynamic, 16)
+    for (int64_t e = 0; e < n; ++e) {
+        int64_t o = oi ? oi[2 * e] : e / I, i = oi ? oi[2 * e + 1] : e % I;
+        double acc = 0.0, aacc = 0.0;
+        (void)O;
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t G = t / 32; int qi = (int)((t % 32) / 4), k = (int)(t % 4);
+            uint32_t md = meta32[G * O + o];
+            double gv = 0.0;
+            for (int s = 0; s < 2; ++s)
+                if ((int)((md >> (4 * qi + 2 * s)) & 3u) == k)
+                    gv = oracle_e5m2_value(vals8[(G * O + o) * 16 + 2 * qi + s]);
+            double hv = oracle_e4m3_value(h8[t * ldh + i]);
+            acc += gv * hv; aacc += fabs(gv) * fabs(hv);
+        }
+        out[e] = alpha * acc;
+        if (out_abs) out_abs[e] = fabs(alpha) * aacc;
     }
 }
 
