@@ -120,6 +120,41 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
 /* Bytes of workspace nm_update_gemm needs for this problem (0 when it runs in one pass). */
 size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
 
+/*
+ * 8-bit neural gradients on top of 2:4 sparsity (Sec. 5: the rows that combine N:M sparsity in all
+ * phases with 8-bit quantisation use FP8 neural gradients; Sec. 3: the quantiser of a neural gradient
+ * has to be unbiased).  The paper fixes neither bit layout nor scale; this library takes OCP e5m2
+ * for the gradients and OCP e4m3 for the activations (the pair gfx950's 8-bit sparse MFMA multiplies).
+ *
+ * mvue_prune_2of4_q8: selection and kept values exactly as mvue_prune_2of4 (same mode, same random
+ * stream: the same seed gives the same mask), taken in binary32; each kept value is multiplied by
+ * `scale` (> 0, finite; one binary32 product) and rounded stochastically to e5m2: with lo <= |x| < hi
+ * neighbours on the e5m2 grid and f = (|x| - lo)/(hi - lo) the result is hi iff
+ * r16 + floor(f * 2^16) >= 2^16, r16 uniform in [0, 2^16); |x| >= 57344 saturates to 57344, the
+ * sign is kept.  E[q]/scale = theta(g) up to 2^-16 of a grid step.  r16: Philox4x32-10, key = seed,
+ * counter = (blk/4 low, blk/4 high, stream_id, 2), word blk%4; low half for the first kept value of
+ * the quad, high half for the second; blk = (t/4)*O + o.
+ * Output, the 8-bit group format (device pointers, 16-byte aligned): tokens in groups of 32 = 8 quads,
+ *     vals8[(G*O + o)*16 + 2*i + s]   s-th kept value (ascending position) of quad i   (T/2 * O bytes)
+ *     meta32[G*O + o]                 bits [4i+1:4i] = position of kept 0, [4i+3:4i+2] = kept 1
+ * T must be a multiple of 32, O of 8.  g: NM_F32 or NM_BF16, row stride ldg.
+ */
+int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                       uint64_t seed, uint32_t stream_id, int mode, float scale,
+                       uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+
+/*
+ * Update GEMM (eq. (3)) on the 8-bit operands:
+ *     dW[O x I] = beta*dW + alpha * decompress(vals8, meta32)^T h8,   beta in {0, 1},
+ * h8 [T x I] e4m3 with row stride ldh (bytes = elements), products exact and accumulation in binary32
+ * on the 8-bit sparse MFMA; alpha undoes the scales of the two operands.  I must be a multiple of 16,
+ * ldh a multiple of 16; limits and workspace as nm_update_gemm (size from nm_update_gemm_q8_workspace).
+ */
+int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh,
+                      float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta,
+                      void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
+
 /* Message of the last error on this thread ("" if none).  Static storage; do not free. */
 const char *nm_last_error(void);
 

@@ -39,9 +39,14 @@ def load():
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
-    for f in (lib.mvue_prune_1of2, lib.mvue_prune_2of4, lib.nm_compress, lib.nm_update_gemm):
+    lib.mvue_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp]
+    lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
+    lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
+    for f in (lib.mvue_prune_1of2, lib.mvue_prune_2of4, lib.nm_compress, lib.nm_update_gemm, lib.mvue_prune_2of4_q8,
+              lib.nm_update_gemm_q8):
         f.restype = i32
     lib.nm_update_gemm_workspace.restype = sz
+    lib.nm_update_gemm_q8_workspace.restype = sz
     lib.nm_last_error.restype = C.c_char_p
     lib.nm_version.restype = C.c_char_p
     _lib = lib
@@ -148,4 +153,54 @@ def nm_update_gemm(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: 
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.nm_update_gemm(_ptr(vals), _ptr(meta), _ptr(h), ldh, _ptr(dW), lddw, T, O, I, _dtype_code(h),
                               float(beta), _ptr(workspace), wbytes, _stream(h)))
+    return dW
+
+
+# ---- 8-bit neural gradients (e5m2, stochastic rounding) on top of 2:4 sparsity
+
+def alloc_compressed_q8(T: int, O: int, device) -> Tuple[torch.Tensor, torch.Tensor]:
+    """Buffers of the 8-bit group format: vals8[T/32, O, 16] (uint8 e5m2 codes) and meta32[T/32, O] (int32 holds the words)."""
+    return (torch.empty((T // 32, O, 16), dtype=torch.uint8, device=device),
+            torch.empty((T // 32, O), dtype=torch.int32, device=device))
+
+
+def mvue_prune_2of4_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, scale: float = 1.0,
+                       vals8=None, meta32=None):
+    """MVUE 2:4 prune of g[T x O] along T with kept values scaled and rounded stochastically to e5m2.  Returns (vals8, meta32)."""
+    lib = load()
+    if not g.is_cuda:
+        raise ValueError("g must live on the GPU")
+    T, O = g.shape
+    ldg = _rowmajor(g, "g")
+    if vals8 is None or meta32 is None:
+        vals8, meta32 = alloc_compressed_q8(T - T % 32, O, g.device)
+    _check(lib.mvue_prune_2of4_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, float(scale),
+                                  _ptr(vals8), _ptr(meta32), _stream(g)))
+    return vals8, meta32
+
+
+def nm_update_gemm_q8_workspace(T: int, O: int, I: int) -> int:
+    return int(load().nm_update_gemm_q8_workspace(T, O, I))
+
+
+def nm_update_gemm_q8(vals8: torch.Tensor, meta32: torch.Tensor, h8: torch.Tensor, dW: Optional[torch.Tensor] = None,
+                      alpha: float = 1.0, beta: float = 0.0, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dW[O x I] = beta*dW + alpha * decompress(vals8, meta32)^T h8; h8 holds e4m3 codes (uint8 or float8_e4m3fn)."""
+    lib = load()
+    G, O, _ = vals8.shape
+    T, I = h8.shape
+    if T != G * 32:
+        raise ValueError(f"h8 has {T} rows, the compressed operand covers {G * 32}")
+    if h8.element_size() != 1:
+        raise TypeError("h8 must be an 8-bit tensor of e4m3 codes")
+    ldh = _rowmajor(h8, "h8")
+    if dW is None:
+        dW = torch.empty((O, I), dtype=torch.float32, device=h8.device)
+    lddw = _rowmajor(dW, "dW")
+    need = nm_update_gemm_q8_workspace(T, O, I)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=h8.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    _check(lib.nm_update_gemm_q8(_ptr(vals8), _ptr(meta32), _ptr(h8), ldh, _ptr(dW), lddw, T, O, I, float(alpha),
+                                 float(beta), _ptr(workspace), wbytes, _stream(h8)))
     return dW

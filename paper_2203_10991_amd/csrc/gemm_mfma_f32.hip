@@ -169,7 +169,7 @@ hipError_t launch_update_gemm_f32(const void *vals, const uint16_t *meta, const 
                        ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I, acc_flag);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, st);
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, 1.0f, st);
     return e;
 }
 

@@ -30,184 +30,12 @@
 #include <utility>
 
 #include "nm_internal.h"
+#include "smfmac_common.h"
 
 namespace nm {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x16 __attribute__((ext_vector_type(16)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
-
 constexpr int KT = 32;            // tokens per LDS stage (one 32-token MFMA step, two 16-token groups)
 constexpr int NS = 6;             // LDS stages: one being consumed, one landed, four in flight
-
-union Frag16 { bf16x16 v; s16x4 q[4]; };
-union Frag8 { bf16x8 v; u32x4 u4; };
-
-typedef __attribute__((address_space(3))) void *lptr_t;
-
-// compile-time loop: f(integral_constant<int, 0>) ... f(integral_constant<int, N-1>)
-template <typename F, int... Is> __device__ __forceinline__ void static_for_impl(F &&f, std::integer_sequence<int, Is...>)
-{
-    (f(std::integral_constant<int, Is>{}), ...);
-}
-template <int N, typename F> __device__ __forceinline__ void static_for(F &&f)
-{
-    static_for_impl(f, std::make_integer_sequence<int, N>{});
-}
-
-// The accumulator blocks of a wave must own the accumulation-register half (AGPRs) of the
-// register file for the whole kernel, with everything else in VGPRs.  Left to itself the compiler
-// keeps accumulators in VGPRs and shuffles blocks to and from AGPRs around every MFMA, so each
-// definition of an accumulator is an asm statement with an AGPR operand:
-//   acc_zero   D = 0*0 + 0 with a dense MFMA (inline-constant C): writes 16 AGPRs at once
-//   smfmac     D += A(4:2 sparse, index word in the low half of idx) * B, optionally preceded by
-//              a wait until at most LGKM LDS reads are outstanding (LGKM < 0: no wait); ABID picks the
-//              half of idx that holds the index word
-// IN_VGPR: the block lives in ordinary registers instead (the compiler splits a wave's register budget evenly
-// between the two halves of the file, so a kernel with more than 128 accumulation registers per wave at two waves
-// per SIMD keeps the excess there).
-template <bool IN_VGPR = false>
-__device__ __forceinline__ void acc_zero(f32x16 &acc)
-{
-    const bf16x8 z = {0, 0, 0, 0, 0, 0, 0, 0};
-    // (the compiler does not know this asm is an MFMA: keep the required distance from the VALU moves that write z)
-    if constexpr (IN_VGPR) asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=v"(acc) : "v"(z));
-    else                   asm volatile("s_nop 4\n\tv_mfma_f32_32x32x16_bf16 %0, %1, %1, 0" : "=a"(acc) : "v"(z));
-}
-template <int LGKM, int ABID, bool IN_VGPR = false>
-__device__ __forceinline__ void smfmac_32x32x32(f32x16 &acc, const bf16x8 &a, const bf16x16 &b, uint32_t idx)
-{
-    if constexpr (LGKM >= 0) asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(LGKM));
-    if constexpr (IN_VGPR) {
-        if constexpr (ABID == 0)
-            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+v"(acc) : "v"(a), "v"(b), "v"(idx));
-        else
-            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+v"(acc) : "v"(a), "v"(b), "v"(idx));
-    } else {
-        if constexpr (ABID == 0)
-            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
-        else
-            asm volatile("v_smfmac_f32_32x32x32_bf16 %0, %1, %2, %3 abid:1" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
-    }
-}
-
-// An empty statement that "rewrites" an accumulator block: placed after the idle cycles that follow the last MFMA,
-// it makes everything that reads the block later (stores, or copies the compiler makes for them) depend on it, so
-// that none of it can be placed above the wait.  (The compiler cannot see that the asm MFMAs are still in flight.)
-template <bool IN_VGPR = false>
-__device__ __forceinline__ void acc_settled(f32x16 &acc)
-{
-    if constexpr (IN_VGPR) asm volatile("" : "+v"(acc));
-    else                   asm volatile("" : "+a"(acc));
-}
-
-// One accumulator element to global memory, straight from the register it lives in (memory instructions take
-// accumulation registers as data): otherwise the compiler copies whole blocks to ordinary registers first and,
-// short of those, spills accumulators to scratch around the epilogue.
-template <bool IN_VGPR = false>
-__device__ __forceinline__ void store_acc(float *p, float v)
-{
-    if constexpr (IN_VGPR) asm volatile("global_store_dword %0, %1, off" : : "v"(p), "v"(v) : "memory");
-    else                   asm volatile("global_store_dword %0, %1, off" : : "v"(p), "a"(v) : "memory");
-}
-
-// LDS reads are issued as asm so that the compiler does not order them against the direct
-// global->LDS loads still in flight for later stages; that ordering is explicit (vmcnt wait +
-// barrier per stage), and so are the waits for the reads themselves (LGKM above).
-template <int OFFSET> __device__ __forceinline__ s16x4 lds_read_tr16(uint32_t addr)     // 4 tokens x 16 columns transposed per 16 lanes
-{
-    s16x4 r;
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-    return r;
-}
-template <int OFFSET> __device__ __forceinline__ u32x4 lds_read_b128(uint32_t addr)
-{
-    u32x4 r;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-    return r;
-}
-template <int OFFSET> __device__ __forceinline__ uint32_t lds_read_b32(uint32_t addr)
-{
-    uint32_t r;
-    asm volatile("ds_read_b32 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-    return r;
-}
-// refill forms: the destination is the register the previous value of the same fragment lives in (read-write operand),
-// so a fragment keeps its registers for the whole kernel
-template <int OFFSET> __device__ __forceinline__ void lds_refill_tr16(s16x4 &r, uint32_t addr)
-{
-    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-}
-template <int OFFSET> __device__ __forceinline__ void lds_refill_b128(u32x4 &r, uint32_t addr)
-{
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-}
-template <int OFFSET> __device__ __forceinline__ void lds_refill_b32(uint32_t &r, uint32_t addr)
-{
-    asm volatile("ds_read_b32 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-}
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_b64(uint32_t addr)
-{
-    u32x2 r;
-    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
-    return r;
-}
-
-// s_waitcnt vmcnt(N) only (expcnt / lgkmcnt left at their maxima): at most N vector-memory loads still in flight
-template <int N> __device__ __forceinline__ void wait_vmcnt()
-{
-    static_assert(N >= 0 && N < 64, "vmcnt is a 6-bit counter");
-    __builtin_amdgcn_s_waitcnt((N & 0xF) | ((N >> 4) << 14) | (7 << 4) | (15 << 8));
-}
-
-// ---- tile assignment.  Workgroups are dealt round-robin to the 8 XCDs (workgroup id % 8), 32 CUs and one
-// L2 each; the 32 tiles resident on an XCD form a block of 8 M-tiles x 4 N-tiles (N fastest), so that
-// they share operand strips inside its L2 from the first stage on (8 vals strips + 4 h strips feed 32 tiles).
-// Preferred map, when both tile counts are multiples of 16: the XCDs form a 2 x 4 grid and the whole GPU
-// works on one 16 x 16 block of tiles at a time.  Of all 8-XCD arrangements this one streams the fewest
-// bytes per block from HBM (16 vals strips + 16 h strips); strips shared between XCDs meet in the
-// memory-side cache.  Otherwise: one band of M-tiles at a time, XCD x owning the N-tiles [x*nx, (x+1)*nx).
-__device__ __forceinline__ void tile_of_workgroup(int bid_, int tiles_m, int tiles_n, int &tm, int &tn)
-{
-    if (tiles_m % 16 == 0 && tiles_n % 16 == 0) {
-        const int bid = bid_, xcd = bid % 8, slot = bid / 8;         // slot: this XCD's running tile count
-        const int round = slot / 32, local = slot % 32, bands = tiles_m / 16;
-        tm = (round % bands) * 16 + (xcd / 4) * 8 + local / 4;
-        tn = (round / bands) * 16 + (xcd % 4) * 4 + local % 4;
-    } else {
-        const int n_tiles = tiles_m * tiles_n, bid = bid_;
-        const int nx = tiles_n / 8;                                    // N-tiles per XCD
-        if (tiles_n % 8 == 0 && nx <= 32) {
-            const int band_rows = 32 / nx > 0 ? 32 / nx : 1;           // M-tiles per band: band_rows * nx ~ 32 CUs
-            const int xcd = bid % 8, slot = bid / 8;                   // slot: this XCD's running tile count
-            const int per_band = band_rows * nx;
-            const int band = slot / per_band, local = slot % per_band;
-            // the last band may be short: its slots are re-dealt over the rows it has (per XCD the band then holds
-            // fewer tiles, and every slot still belongs to exactly one tile)
-            const int full_bands = tiles_m / band_rows;
-            // N-tile index fastest: tiles that share an h strip AND tiles that share a vals strip start within a few
-            // dispatches of each other, so both kinds of sharing are live in the L2 from the first stage on
-            if (band < full_bands) { tm = band * band_rows + local / nx; tn = xcd * nx + local % nx; }
-            else {
-                const int l2 = slot - full_bands * per_band;            // index inside the short band
-                tm = full_bands * band_rows + l2 / nx; tn = xcd * nx + l2 % nx;
-            }
-        } else {
-            // fallback: contiguous run of tiles per XCD when the count divides evenly, N-fastest inside bands of 8 M-tiles
-            int t = bid;
-            if (n_tiles % 8 == 0) t = (bid % 8) * (n_tiles / 8) + bid / 8;
-            constexpr int BAND = 8;
-            const int band = t / (BAND * tiles_n);
-            const int band_rows = min(BAND, tiles_m - band * BAND);
-            const int in_band = t - band * BAND * tiles_n;
-            tm = band * BAND + in_band % band_rows;
-            tn = in_band / band_rows;
-        }
-    }
-}
 
 // LDS image of one stage (all filled by direct loads, 64 consecutive lanes -> consecutive LDS bytes):
 //   [0, 64*TN)                h tile, [32 tokens][TN columns] bf16, rows unpadded.  Bank conflicts of the
@@ -750,29 +578,35 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
     });
 }
 
-// out[o][i] = (accumulate ? out : 0) + sum_z part[z][o][i], z ascending
+// out[o][i] = (accumulate ? out : 0) + alpha * sum_z part[z][o][i], z ascending
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int slabs, int64_t slab_stride,
-                                                           float *__restrict__ out, int64_t ldo, int64_t O, int64_t I, int accumulate)
+                                                           float *__restrict__ out, int64_t ldo, int64_t O, int64_t I, int accumulate,
+                                                           float alpha)
 {
     const int64_t n4 = O * (I / 4);
     const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
     if (idx >= n4) return;
     const int64_t o = idx / (I / 4), i = (idx % (I / 4)) * 4;
-    float4 s = accumulate ? *(const float4 *)(out + o * ldo + i) : make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
     for (int z = 0; z < slabs; ++z) {
         const float4 v = *(const float4 *)(part + (int64_t)z * slab_stride + o * I + i);
         s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
     }
+    s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
+    if (accumulate) {
+        const float4 d = *(const float4 *)(out + o * ldo + i);
+        s.x += d.x; s.y += d.y; s.z += d.z; s.w += d.w;
+    }
     *(float4 *)(out + o * ldo + i) = s;
 }
 
-// dW = (accumulate ? dW : 0) + sum over the slabs of [slabs][O][I] partial sums (row stride I), in slab order
+// dW = (accumulate ? dW : 0) + alpha * sum over the slabs of [slabs][O][I] partial sums (row stride I), in slab order
 hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
-                                int accumulate, hipStream_t st)
+                                int accumulate, float alpha, hipStream_t st)
 {
     const int64_t n4 = O * (I / 4);
     hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, slabs, O * I,
-                       dW, lddw, O, I, accumulate);
+                       dW, lddw, O, I, accumulate, alpha);
     return hipGetLastError();
 }
 
@@ -866,7 +700,7 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
     }
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, st);
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, 1.0f, st);
     return e;
 }
 

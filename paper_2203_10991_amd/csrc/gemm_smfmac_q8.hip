@@ -1,0 +1,373 @@
+// Update GEMM on CDNA4 sparse MFMA with 8-bit operands:
+//     dW[O x I] = beta*dW + alpha * decompress(vals8, meta32)^T h8        (eq. (3); Sec. 5, 8-bit rows)
+// vals8: kept neural-gradient values in e5m2 (32-token group format), h8: activations in e4m3.
+//
+// Instruction: v_smfmac_f32_32x32x64_bf8_fp8.  Lane layouts, as measured on gfx950 (l = lane):
+//   A  lane holds the 16 kept values of row (l%32) for the 32 tokens  32*(l/32) .. +31  of the 64-token
+//      step, quad by quad: one 16-byte `vals8` fragment; the 32-bit index register (2 bits per kept value)
+//      is exactly one `meta32` word of the group format.
+//   B  lane holds column (l%32); bytes 0-15 = tokens 16*(l/32) .. +15, bytes 16-31 = tokens 32 + 16*(l/32) .. +15.
+//      h8 is token-major, so the tile is staged in LDS as [token][column] and read with ds_read_b64_tr_b8:
+//      per 16 lanes, lane j supplies the address of 8 bytes, and lane i receives byte i%8 of the 8 pieces
+//      supplied by lanes i/8, i/8+2, ..., i/8+14.  Lane j supplies token j/2, column half j%2 of a 16-column
+//      chunk: lane i then holds column i of the chunk for 8 consecutive tokens.
+//   D  reg r of lane l = row 8*(r/4) + 4*(l/32) + r%4, column l%32.
+//
+// The kernel has the structure of the 16-bit one (same bytes per stage: a stage is 64 tokens of 1-byte
+// operands instead of 32 tokens of 2-byte ones): every operand byte of a stage reaches the CU once by direct
+// global->LDS loads spread over the stage's MFMAs, six stages rotate through LDS, one bare barrier per stage,
+// operand registers double-buffered, split-K with a deterministic second pass.
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include <algorithm>
+#include <type_traits>
+#include <utility>
+
+#include "nm_internal.h"
+#include "smfmac_common.h"
+
+namespace nm {
+
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x8 __attribute__((ext_vector_type(8)));
+
+constexpr int KT8 = 64;           // tokens per LDS stage (one 64-token MFMA step, two 32-token groups)
+constexpr int NS8 = 6;            // LDS stages
+
+union FragB8 { i32x8 v; u32x2 q[4]; };
+union FragA8 { i32x4 v; u32x4 u4; };
+
+__device__ __forceinline__ void smfmac_32x32x64_bf8_fp8(f32x16 &acc, const i32x4 &a, const i32x8 &b, uint32_t idx)
+{
+    asm volatile("v_smfmac_f32_32x32x64_bf8_fp8 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+}
+// alpha * (one accumulator element) to global memory: the element is copied out of its accumulation register, scaled
+// and stored inside one statement, so that the compiler never holds whole blocks in ordinary registers
+__device__ __forceinline__ void store_acc_scaled(float *p, float v, float alpha)
+{
+    float t;
+    asm volatile("v_accvgpr_read_b32 %0, %2\n\tv_mul_f32 %0, %0, %3\n\tglobal_store_dword %1, %0, off"
+                 : "=&v"(t) : "v"(p), "a"(v), "v"(alpha) : "memory");
+}
+template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
+{
+    u32x2 r;
+    asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+    return r;
+}
+
+// LDS image of one stage (all filled by direct loads, 64 consecutive lanes -> consecutive LDS bytes):
+//   [0, 64*TN)     h8 tile, [64 tokens][TN columns], rows unpadded; 16-byte chunk c of row k sits at chunk position
+//                  c ^ (2*(k%8)): a transposing read touches, per 32 lanes, two neighbouring chunks of 8 consecutive rows
+//   then           vals8 fragments, [2 token groups][TM slots] x 16 bytes
+//   then           meta32 words,   [2 token groups][TM rows]  x 4 bytes
+//                  (both as one share per wave, padded to a whole 64-lane load)
+template <int WM, int WN, int AB, int BB>
+__global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
+    const uint8_t *__restrict__ vals, const uint32_t *__restrict__ meta, const uint8_t *__restrict__ h, int64_t ldh,
+    float *__restrict__ out, int64_t ldo, int64_t slab_stride,
+    int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate, float alpha)
+{
+    constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
+    static_assert(TN == 256, "the h8 swizzle is written for 16 chunks per row");
+    constexpr int CPR = TN / 16;                          // 16-byte chunks per h8 row in LDS
+    constexpr int ROWS_PER_DMA = 64 / CPR;                // h8 rows one wave-wide 16-byte direct load covers (4)
+    constexpr int NW = WM * WN;
+    constexpr int WPG = NW / 2;                           // waves that share one of the stage's 2 token groups
+    constexpr int B_ROWS = KT8 / NW;                      // h8 rows a wave brings per stage
+    constexpr int A_ROWS = TM / WPG;                      // tile rows a wave brings (vals8 and meta32) of its token group
+    constexpr int B_DMA = B_ROWS / ROWS_PER_DMA;
+    constexpr int A_DMA = A_ROWS >= 64 ? A_ROWS / 64 : 1; //   vals8: 64 rows (16 bytes each) per load
+    constexpr int A_LANES = A_ROWS >= 64 ? 64 : A_ROWS;
+    constexpr int A_SLOTS = A_ROWS >= 64 ? A_ROWS : 64;
+    constexpr int M_DMA = A_DMA;                          //   meta32: one word per lane
+    constexpr int M_SLOTS = A_SLOTS;                      //   4-byte slots per share in LDS
+    static_assert(NW == 4 || NW == 8, "4 or 8 waves");
+    static_assert(B_DMA >= 1 && B_ROWS % 8 == 0 && A_ROWS >= 16, "tile too small for this wave count");
+    constexpr int LOADS_PER_STAGE = B_DMA + A_DMA + M_DMA;
+    constexpr int A_OFF = KT8 * TN, M_OFF = A_OFF + 2 * WPG * A_SLOTS * 16;
+    constexpr int STAGE_BYTES = (M_OFF + 2 * WPG * M_SLOTS * 4 + 1023) / 1024 * 1024;
+    static_assert(NS8 * STAGE_BYTES <= 160 * 1024, "LDS");
+    __shared__ __attribute__((aligned(1024))) char S[NS8 * STAGE_BYTES];
+    auto buf = [&](auto u_c) -> char * { return S + (decltype(u_c)::value % NS8) * STAGE_BYTES; };
+
+    int tm, tn;
+    tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = (int64_t)tm * TM;
+    const int64_t n0 = (int64_t)tn * TN;
+    const int64_t g_begin = (int64_t)blockIdx.z * groups_per_slab;
+    const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
+    out += (int64_t)blockIdx.z * slab_stride;
+
+    f32x16 acc[AB][BB];
+#pragma unroll
+    for (int a = 0; a < AB; ++a)
+#pragma unroll
+        for (int b = 0; b < BB; ++b) acc_zero(acc[a][b]);
+
+    const int n_iters = (int)((g_end - g_begin + 1) / 2);      // stages of 2 token groups; the last may be ragged
+
+    // Raw buffer descriptors, re-based as the kernel advances: a load from past the end of the tensor (the token
+    // group a ragged last stage lacks) is dropped by the bounds check.
+    auto rsrc = [](const void *base, int64_t bytes) {
+        const uint32_t n = bytes <= 0 ? 0u : (bytes > 0xffffffffll ? 0xffffffffu : (uint32_t)bytes);
+        return __builtin_amdgcn_make_buffer_rsrc((void *)base, 0, (int)n, 0x00020000);
+    };
+    const int64_t T = n_groups * 32;
+
+    // per-lane source offsets (bytes, relative to the stage).  Rows >= O and columns >= I are clamped to the last
+    // valid ones: their products land in outputs that are never stored.
+    const int wgrp = wave / WPG, wsub = wave % WPG;
+    uint32_t a_src[A_DMA], m_src[M_DMA];
+#pragma unroll
+    for (int d = 0; d < A_DMA; ++d) {
+        // LDS slot q of a token group holds tile row slot_row(q): inside each wave-row block of AB*32 rows, the 32 rows
+        // that feed accumulator block a (rows a, AB+a, 2AB+a, ...) are stored next to each other
+        const int q = wsub * A_ROWS + 64 * d + (lane % A_LANES);
+        const int row = (q / (AB * 32)) * (AB * 32) + AB * (q % 32) + (q % (AB * 32)) / 32;
+        a_src[d] = (uint32_t)(wgrp * O + min(m0 + row, O - 1)) * 16u;
+        // index words stay in natural row order
+        m_src[d] = (uint32_t)(wgrp * O + min(m0 + wsub * A_ROWS + 64 * d + (lane % A_LANES), O - 1)) * 4u;
+    }
+    // h8: direct load d of this wave fills rows  wave*B_ROWS + d*ROWS_PER_DMA + lane/CPR  at chunk position
+    // lane%CPR, i.e. it must fetch global chunk  (lane%CPR) ^ 2*(row%8).
+    constexpr int PHASES = 8 / ROWS_PER_DMA;
+    static_assert(B_DMA % PHASES == 0, "a wave's rows cover whole swizzle periods");
+    uint32_t b_src[PHASES];
+    const int dma_row = lane / CPR, dma_pos = lane % CPR;
+#pragma unroll
+    for (int ph = 0; ph < PHASES; ++ph) {
+        const int row_mod8 = (ph * ROWS_PER_DMA + dma_row) & 7;
+        const int64_t col = min(n0 + 16 * (dma_pos ^ (2 * row_mod8)), I - 16);
+        b_src[ph] = (uint32_t)((int64_t)(wave * B_ROWS + dma_row) * ldh + col);
+    }
+    const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh);
+
+    __amdgpu_buffer_rsrc_t rh, rv, rm;
+    auto rebase = [&](int it) {
+        const int64_t Gs = g_begin + (int64_t)it * 2, t0 = Gs * 32;
+        rh = rsrc((const char *)h + t0 * ldh, (T - t0 - 1) * ldh + I);
+        rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
+        rm = rsrc((const char *)meta + Gs * O * 4, (n_groups - Gs) * O * 4);
+    };
+    const uint32_t h_stage = (uint32_t)(KT8 * ldh), v_stage = (uint32_t)(2 * O * 16), m_stage = (uint32_t)(2 * O * 4);
+    auto fetch_one = [&](auto u_c, auto k_c, char *stage) {
+        constexpr uint32_t U = decltype(u_c)::value;
+        constexpr int K = decltype(k_c)::value;
+        if constexpr (K < B_DMA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rh, (lptr_t)(stage + (wave * B_ROWS + K * ROWS_PER_DMA) * TN), 16,
+                                                     (int)(b_src[K % PHASES] + (uint32_t)K * b_row_step + U * h_stage), 0, 0, 0);
+        else if constexpr (K < B_DMA + A_DMA)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rv, (lptr_t)(stage + A_OFF + (wave * A_SLOTS + 64 * (K - B_DMA)) * 16), 16,
+                                                     (int)(a_src[K - B_DMA] + U * v_stage), 0, 0, 0);
+        else
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(rm, (lptr_t)(stage + M_OFF + (wave * M_SLOTS + 64 * (K - B_DMA - A_DMA)) * 4), 4,
+                                                     (int)(m_src[K - B_DMA - A_DMA] + U * m_stage), 0, 0, 0);
+    };
+    auto fetch = [&](auto u_c, char *stage) {
+        static_for<LOADS_PER_STAGE>([&](auto k_c) { fetch_one(u_c, k_c, stage); });
+    };
+    // first stage (relative to the slab) in which this wave's token group lies past the end of the tensor
+    const int first_missing = (int)min((int64_t)0x7fffffff, (n_groups - g_begin - wgrp + 1) / 2);
+    auto stage_ready = [&](auto in_flight_c, int it, char *stage) {
+        wait_vmcnt<decltype(in_flight_c)::value * LOADS_PER_STAGE>();
+        // a direct load whose source lies past the end of the tensor leaves its LDS bytes untouched: the wave
+        // clears what it would have brought
+        if (it >= first_missing) {
+            const uint4 z = make_uint4(0, 0, 0, 0);
+            for (int c = lane; c < B_ROWS * CPR; c += 64) *(uint4 *)(stage + wave * B_ROWS * TN + c * 16) = z;
+            for (int c = lane; c < A_SLOTS; c += 64) *(uint4 *)(stage + A_OFF + (wave * A_SLOTS + c) * 16) = z;
+            for (int c = lane; c < M_SLOTS / 4; c += 64) *(uint4 *)(stage + M_OFF + wave * M_SLOTS * 4 + c * 16) = z;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // lane's LDS read addresses inside a stage.  h8, read j (0..3) of a fragment covers the tokens
+    // 32*(j/2) + 16*(lane/32) + 8*(j%2) .. +7; the lane supplies token li/2 of them, half li%2 of its 16-column chunk.
+    const int li = lane & 15, grp = (lane >> 4) & 1, kg = lane >> 5;
+    const int rd_row = (16 * kg + (li >> 1)) * TN;
+    // The read addresses are registers that walk through the stages (advanced by an asm add after the reads of a
+    // stage: the compiler would otherwise keep one copy of every address per stage buffer).
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)S;
+    uint32_t cur_b[BB];
+#pragma unroll
+    for (int b = 0; b < BB; ++b)
+        cur_b[b] = lds0 + (uint32_t)(rd_row + ((2 * (wn * BB + b) + grp) ^ (2 * (li >> 1))) * 16 + (li & 1) * 8);
+    constexpr int A_BLOCK = (A_ROWS >= 64 ? 32 : 64) * 16;
+    static_assert(A_ROWS % 32 == 0 && (AB * 32) % A_ROWS == 0 || A_ROWS % (AB * 32) == 0, "shares and wave rows nest");
+    const int q0 = wm * (AB * 32), r0 = q0 + AB * (lane & 31);
+    uint32_t cur_a = lds0 + (uint32_t)(A_OFF + ((kg * WPG + q0 / A_ROWS) * A_SLOTS + q0 % A_ROWS + (lane & 31)) * 16);   // + a*A_BLOCK
+    uint32_t cur_m = lds0 + (uint32_t)(M_OFF + ((kg * WPG + r0 / A_ROWS) * M_SLOTS + r0 % A_ROWS) * 4);                   // AB consecutive words
+    static_assert(BB == 2, "advance() moves two column-fragment addresses");
+    auto advance = [&](int bytes) {
+        asm volatile("v_add_u32 %0, %4, %0\n\tv_add_u32 %1, %4, %1\n\tv_add_u32 %2, %4, %2\n\tv_add_u32 %3, %4, %3"
+                     : "+v"(cur_a), "+v"(cur_m), "+v"(cur_b[0]), "+v"(cur_b[1]) : "s"(bytes));
+    };
+
+    static_assert(AB == 2 || AB == 4, "AB is 2 or 4");
+    FragA8 af[2][AB];
+    u32x4 ix4[2]; u32x2 ix2[2];             // index words as read, AB consecutive 32-bit words
+    FragB8 bf[2][BB];
+    constexpr int NR = AB + 1 + 4 * BB;
+    constexpr int NM = AB * BB;
+    static_assert(NR <= 15, "lgkmcnt is a 4-bit counter");
+    // read number r of the stage the address registers point at
+    auto lds_read = [&](auto set_c, auto r_c) {
+        constexpr int set = decltype(set_c)::value, r = decltype(r_c)::value;
+        if constexpr (r < AB) af[set][r].u4 = lds_read_b128<r * A_BLOCK>(cur_a);
+        else if constexpr (r == AB) {
+            if constexpr (AB == 4) ix4[set] = lds_read_b128<0>(cur_m);
+            else                   ix2[set] = lds_read_b64<0>(cur_m);
+        } else {
+            constexpr int j = r - AB - 1, b = j / 4, qd = j % 4;
+            bf[set][b].q[qd] = lds_read_tr8<(32 * (qd >> 1) + 8 * (qd & 1)) * TN>(cur_b[b]);
+        }
+    };
+    // NEXT_STEP: what moves the address registers from the stage read here to the one after it
+    auto consume = [&](auto set_c, auto next_step_c, auto fu_c, char *far) {
+        constexpr int set = decltype(set_c)::value;
+        constexpr int NL = LOADS_PER_STAGE;
+        if constexpr (AB == 4) asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ix4[set]));
+        else                   asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(ix2[set]));
+        static_for<NM>([&](auto m_c) {
+            constexpr int m = decltype(m_c)::value, b = m / AB, a = m % AB;
+            uint32_t idx;
+            if constexpr (AB == 4) idx = ix4[set][a];
+            else                   idx = ix2[set][a];
+            smfmac_32x32x64_bf8_fp8(acc[a][b], af[set][a].v, bf[set][b].v, idx);
+            static_for<NR>([&](auto r_c) {
+                constexpr int r = decltype(r_c)::value;
+                if constexpr (r >= m * NR / NM && r < (m + 1) * NR / NM) lds_read(std::integral_constant<int, 1 - set>{}, r_c);
+            });
+            static_for<NL>([&](auto k_c) {
+                constexpr int k = decltype(k_c)::value;
+                if constexpr (k >= m * NL / NM && k < (m + 1) * NL / NM) fetch_one(fu_c, k_c, far);
+            });
+        });
+        advance(decltype(next_step_c)::value);
+    };
+
+    // Six LDS stages rotating, straight-line loop body of six stages per trip; stages past the end of the tensor
+    // hold zeros (dropped loads, cleared shares), so the stage count is padded to a multiple of six.
+    const int n_trips = (n_iters + NS8 - 1) / NS8;
+    if (n_trips > 0) {
+        rebase(0);
+        static_for<NS8 - 1>([&](auto u_c) { fetch(u_c, buf(u_c)); });
+        stage_ready(std::integral_constant<int, NS8 - 2>{}, 0, S);
+        static_for<NR>([&](auto r_c) { lds_read(std::integral_constant<int, 0>{}, r_c); });
+        advance(STAGE_BYTES);
+    }
+    for (int tr = 0; tr < n_trips; ++tr) {
+        const int it = NS8 * tr;
+        rebase(it);
+        static_for<NS8>([&](auto u_c) {
+            constexpr int u = decltype(u_c)::value;
+            stage_ready(std::integral_constant<int, NS8 - 3>{}, it + u + 1, buf(std::integral_constant<int, u + 1>{}));
+            // the reads issued during stage u are those of stage u+1; the ones after them belong to stage u+2
+            consume(std::integral_constant<int, u % 2>{},
+                    std::integral_constant<int, ((u + 2) % NS8 == 0) ? -(NS8 - 1) * STAGE_BYTES : STAGE_BYTES>{},
+                    std::integral_constant<int, u + NS8 - 1>{}, buf(std::integral_constant<int, u + NS8 - 1>{}));
+        });
+    }
+
+    // ---- epilogue: idle for longer than an 8-pass instruction before the first read of an accumulation register,
+    // and tie every such read behind that wait (the compiler cannot see MFMAs inside asm statements)
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+#pragma unroll
+    for (int a = 0; a < AB; ++a)
+#pragma unroll
+        for (int b = 0; b < BB; ++b) acc_settled(acc[a][b]);
+    __builtin_amdgcn_sched_barrier(0);
+    const int64_t o0 = m0 + wm * (AB * 32);
+#pragma unroll
+    for (int a = 0; a < AB; ++a)
+#pragma unroll
+        for (int b = 0; b < BB; ++b) {
+            const int64_t col = n0 + wn * (BB * 32) + b * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int64_t row = o0 + AB * (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) + a;   // block a holds rows a, AB+a, ...
+                if (row < O && col < I) {
+                    float *p = out + row * ldo + col;
+                    if (accumulate) *p = *p + acc[a][b][r] * alpha;
+                    else store_acc_scaled(p, acc[a][b][r], alpha);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        }
+}
+
+// ------------------------------------------------------------------------------------
+// host side: tile shape and split-K plan (pure function of the problem size)
+// ------------------------------------------------------------------------------------
+struct PlanQ8 { int shape; int tm; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; };
+
+static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
+{
+    PlanQ8 p;
+    const int64_t groups = T / 32;
+    const int CUS = 256;
+    // shape 0: 256x256 (8 waves), shape 1: 128x256, shape 2: 64x256 (4 waves)
+    if (O <= 64) { p.shape = 2; p.tm = 64; }
+    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) { p.shape = 0; p.tm = 256; }
+    else { p.shape = 1; p.tm = 128; }
+    p.tiles_m = (int)((O + p.tm - 1) / p.tm);
+    p.tiles_n = (int)((I + 255) / 256);
+    const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    int slabs = 1;
+    if (tiles < CUS && groups >= 32) {
+        slabs = (int)((2 * CUS + tiles - 1) / tiles);                 // about two workgroups per CU
+        const int64_t max_slabs = groups / 16;                         // at least 512 tokens per slab
+        if (slabs > max_slabs) slabs = (int)max_slabs;
+        if (slabs < 1) slabs = 1;
+    }
+    int64_t gps = (groups + slabs - 1) / slabs;
+    gps = (gps + 11) / 12 * 12;                                        // whole trips of six LDS stages
+    if (gps < 12) gps = 12;
+    p.groups_per_slab = gps;
+    p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
+    return p;
+}
+
+size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
+{
+    if (T <= 0 || O <= 0 || I <= 0) return 0;
+    const PlanQ8 p = make_plan_q8(T, O, I);
+    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+}
+
+hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
+                                 int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace,
+                                 hipStream_t st)
+{
+    if (O == 0 || I == 0) return hipSuccess;
+    const PlanQ8 p = make_plan_q8(T, O, I);
+    const int accumulate = beta != 0.f;
+    float *out = dW;
+    int64_t ldo = lddw, slab_stride = 0;
+    int acc_flag = accumulate;
+    float k_alpha = alpha;
+    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; k_alpha = 1.0f; }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
+#define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
+    hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, h8,    \
+                       ldh, out, ldo, slab_stride, T / 32, p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, k_alpha)
+    if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
+    else if (p.shape == 1) NM_LAUNCH(1, 4, 4, 2);
+    else NM_LAUNCH(1, 4, 2, 2);
+#undef NM_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, alpha, st);
+    return e;
+}
+
+}  // namespace nm

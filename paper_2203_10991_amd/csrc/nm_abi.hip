@@ -159,6 +159,69 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
                                                workspace_bytes, (hipStream_t)hip_stream));
 }
 
+int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                       int mode, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    const char *fn = "mvue_prune_2of4_q8";
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", fn, mode);
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32 (pad with zero rows)", fn, (long long)T);
+    if (!(scale > 0.0f) || !(scale < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: scale must be positive and finite", fn);
+    if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
+    if (!vals8 || !meta32) return fail(NM_ERR_NULL, "%s: vals8 and meta32 must not be NULL", fn);
+    if (!aligned16(vals8) || !aligned16(meta32)) return fail(NM_ERR_ALIGN, "%s: vals8 and meta32 need 16-byte aligned bases", fn);
+    Range rin = range_of(g, ((T - 1) * ldg + O) * esize(dtype), "g");
+    Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
+    if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm))
+        return fail(NM_ERR_ALIAS, "%s: g, vals8 and meta32 must not overlap", fn);
+    return launched(fn, nm::launch_prune_q8(dtype, mode, g, T, O, ldg, seed, stream_id, scale, vals8, meta32,
+                                            (hipStream_t)hip_stream));
+}
+
+size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
+{
+    if (T < 0 || O < 0 || I < 0) return 0;
+    return nm::update_gemm_q8_workspace(T, O, I);
+}
+
+int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW, int64_t lddw,
+                      int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace, size_t workspace_bytes,
+                      void *hip_stream)
+{
+    const char *fn = "nm_update_gemm_q8";
+    if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32", fn, (long long)T);
+    if (O % 8 || I % 16) return fail(NM_ERR_SHAPE, "%s: O=%lld must be a multiple of 8 and I=%lld of 16", fn, (long long)O, (long long)I);
+    if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
+    if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
+    if (!dW) return fail(NM_ERR_NULL, "%s: dW is NULL", fn);
+    if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
+    if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
+    Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    if (T > 0) {
+        if (!vals8 || !meta32 || !h8) return fail(NM_ERR_NULL, "%s: vals8, meta32 and h8 must not be NULL", fn);
+        if (ldh < I) return fail(NM_ERR_SHAPE, "%s: ldh=%lld is smaller than I=%lld", fn, (long long)ldh, (long long)I);
+        if (ldh > (1 << 21) || O > (1 << 21))
+            return fail(NM_ERR_UNSUPPORTED, "%s: O=%lld and ldh=%lld must not exceed 2^21", fn, (long long)O, (long long)ldh);
+        if (!aligned16(vals8) || !aligned16(meta32) || !aligned16(h8) || ldh % 16)
+            return fail(NM_ERR_ALIGN, "%s: vals8, meta32, h8 need 16-byte aligned bases (and h8 a 16-byte row stride)", fn);
+        Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
+        Range rh = range_of(h8, (T - 1) * ldh + I, "h8");
+        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rh)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+    }
+    const size_t need = nm::update_gemm_q8_workspace(T, O, I);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
+        Range rw = range_of(workspace, (int64_t)need, "workspace");
+        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+    }
+    return launched(fn, nm::launch_update_gemm_q8(vals8, meta32, h8, ldh, dW, lddw, T, O, I, alpha, beta, workspace,
+                                                  (hipStream_t)hip_stream));
+}
+
 const char *nm_last_error(void) { return g_err; }
 
 const char *nm_version(void) { return "nm_mvue 0.1 gfx950"; }

@@ -31,6 +31,15 @@ hipError_t launch_update_gemm_f32(const void *vals, const uint16_t *meta, const 
                                   hipStream_t st);
 size_t update_gemm_f32_workspace(int64_t T, int64_t O, int64_t I);
 hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
-                                int accumulate, hipStream_t st);
+                                int accumulate, float alpha, hipStream_t st);
+
+// 8-bit path: 2:4 prune with e5m2 output (stochastic rounding) in 32-token groups, and its update GEMM
+// dW = beta*dW + alpha * decompress(vals8, meta32)^T h8  (vals8 e5m2, h8 e4m3)
+hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+                           uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st);
+hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
+                                 int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace,
+                                 hipStream_t st);
+size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
 
 }  // namespace nm

@@ -11,6 +11,7 @@
 //   MVUE 1:2 ........ Sec. 4.1, eq. (6); threshold sampling as in App. B.1
 //   optimal 2:4 ..... Sec. 4.2 (eqs. (8), (12), (14)) and App. A.2 (cases 1-3)
 //   approx 2:4 ...... Sec. 4.4 (two magnitude-proportional draws, kept value a/p)
+//   8-bit output .... Sec. 5 (FP8 neural gradients on top of 2:4), stochastic rounding for the unbiasedness Sec. 3 asks for
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
@@ -387,6 +388,133 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
     void *__restrict__ vals, uint16_t *__restrict__ meta)
 {
     prune_compress_body<NM_DT_BF16, 4, 0, false>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
+}
+
+// ------------------------------------------------------------------------------------
+// 2:4 prune with 8-bit output (Sec. 5, 8-bit rows: FP8 neural gradients; Sec. 3: the quantiser of a neural
+// gradient has to be unbiased).  Selection and kept values as above, in binary32; each kept value is multiplied
+// by `scale` and rounded stochastically to e5m2 with 16 random bits: with lo <= |x| < hi neighbours on the e5m2
+// grid and f = (|x| - lo)/(hi - lo), the result is hi iff r16 + floor(f * 2^16) >= 2^16.
+//   normal range (|x| >= 2^-14): e5m2 is the top byte of a binary16, so the code is the binary32 exponent re-biased
+//     by 112 with the top two mantissa bits; the 21 discarded bits, cut to their top 16, are f: one add carries
+//     into the code.
+//   subnormal range: the grid step is 2^-16, so |x| * 2^32 truncated is the code in 16.16 fixed point.
+//   |x| >= 57344 (the largest finite e5m2) saturates; NaN stays NaN.
+// Rounding words: one Philox call per four blocks with last counter word 2, word blk%4; its low half rounds the
+// first kept value, its high half the second.
+// Output: 32-token groups, vals8[(G*O + o)*16 + 2i + s], meta32[G*O + o] (nibble i = quad i).
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t sr_e5m2(float x, uint32_t r16)
+{
+    const uint32_t b = __float_as_uint(x), a = b & 0x7fffffffu;
+    const uint32_t normal = (((a >> 5) + r16) >> 16) - 448u;
+    const uint32_t fixed = (uint32_t)(__uint_as_float(a) * 0x1p32f);          // truncates; only used below 2^-14
+    const uint32_t sub = (fixed + r16) >> 16;
+    uint32_t code = a < 0x38800000u ? sub : normal;
+    code = a >= 0x47600000u ? 0x7Bu : code;
+    code = a > 0x7f800000u ? 0x7Fu : code;
+    return ((b >> 24) & 0x80u) | code;
+}
+
+template <int DT, int EST>
+__global__ __launch_bounds__(256) void prune_compress_q8_kernel(
+    const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    float scale, uint8_t *__restrict__ vals8, uint32_t *__restrict__ meta32)
+{
+    constexpr int VEC = Row<DT>::VEC;
+    constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
+    const int64_t ncg = O / VEC;
+    const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
+    if (n >= n_groups * ncg) return;
+    const int64_t G = n / ncg;
+    const int64_t col0 = (n - G * ncg) * VEC;
+    const char *gp = (const char *)g_ + ((G * 32) * ldg + col0) * ESZ;
+
+    // rows live in two halves of 8 (two quad rows each); a half is refilled with the rows 16 further down as soon
+    // as its quads are decided, through an address the compiler cannot see through (keeps the loads where they are)
+    uint4 rows[16];
+#pragma unroll
+    for (int r = 0; r < 8; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
+
+    uint32_t kept[VEC][4];        // 16 e5m2 codes per column
+    uint32_t md[VEC];
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) { md[c] = 0; kept[c][0] = kept[c][1] = kept[c][2] = kept[c][3] = 0; }
+
+#pragma unroll
+    for (int b = 0; b < 8; ++b) {                       // quad row b: tensor rows 4b .. 4b+3, held in rows[(4b) % 16 ..]
+        if (b == 1 || b == 2 || b == 4) {
+            const int first = b == 1 ? 8 : b == 2 ? 16 : 24;
+            const char *gp2 = gp;
+            asm volatile("" : "+v"(gp2));
+#pragma unroll
+            for (int r = 0; r < 8; ++r) rows[(first + r) % 16] = *(const uint4 *)(gp2 + (int64_t)(first + r) * ldg * ESZ);
+        }
+        const uint64_t blk0 = (uint64_t)(G * 8 + b) * (uint64_t)O + (uint64_t)col0;
+        constexpr int WPB = EST == 1 ? 2 : 1;
+        uint32_t words[VEC * WPB], rnd[VEC];
+#pragma unroll
+        for (int q = 0; q < VEC * WPB / 4; ++q) {
+            const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
+            uint32_t w4[4];
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
+        }
+#pragma unroll
+        for (int q = 0; q < VEC / 4; ++q) {
+            const uint64_t ctr = (blk0 >> 2) + q;
+            uint32_t w4[4];
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 2u, key0, key1, w4);
+#pragma unroll
+            for (int j = 0; j < 4; ++j) rnd[4 * q + j] = w4[j];
+        }
+        const int R0 = (4 * b) % 16;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
+            float v0, v1; uint32_t nib;
+            if constexpr (EST == 1)
+                select_2of4_approx(Row<DT>::get(rows[R0], c), Row<DT>::get(rows[R0 + 1], c),
+                                   Row<DT>::get(rows[R0 + 2], c), Row<DT>::get(rows[R0 + 3], c),
+                                   words[2 * c], words[2 * c + 1], v0, v1, nib);
+            else
+                select_2of4<DT>(Key<DT>::make(rows[R0], c, 0), Key<DT>::make(rows[R0 + 1], c, 1),
+                                Key<DT>::make(rows[R0 + 2], c, 2), Key<DT>::make(rows[R0 + 3], c, 3),
+                                words[c], v0, v1, nib);
+            const uint32_t c0 = sr_e5m2(v0 * scale, rnd[c] & 0xffffu), c1 = sr_e5m2(v1 * scale, rnd[c] >> 16);
+            kept[c][b / 2] |= (c0 | (c1 << 8)) << (16 * (b & 1));
+            md[c] |= nib << (4 * b);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+    }
+
+    // 16 bytes per column, VEC columns contiguous; one index word per column
+    uint4 *vp = (uint4 *)(vals8 + (G * O + col0) * 16);
+#pragma unroll
+    for (int c = 0; c < VEC; ++c) vp[c] = make_uint4(kept[c][0], kept[c][1], kept[c][2], kept[c][3]);
+    uint4 *mp = (uint4 *)(meta32 + (G * O + col0));
+#pragma unroll
+    for (int c = 0; c < VEC / 4; ++c) mp[c] = make_uint4(md[4 * c], md[4 * c + 1], md[4 * c + 2], md[4 * c + 3]);
+}
+
+template <int DT, int EST>
+static hipError_t launch_prune_q8_t(const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed, uint32_t stream_id,
+                                    float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
+{
+    const int64_t groups = T / 32, threads = groups * (O / Row<DT>::VEC);
+    if (threads == 0) return hipSuccess;
+    hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, vals8, meta32);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
+                           uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
+{
+#define NM_PRUNE8(DT, EST) launch_prune_q8_t<DT, EST>(g, T, O, ldg, seed, stream_id, scale, vals8, meta32, st)
+    if (dt == NM_DT_F32) return est == 1 ? NM_PRUNE8(NM_DT_F32, 1) : NM_PRUNE8(NM_DT_F32, 0);
+    return est == 1 ? NM_PRUNE8(NM_DT_BF16, 1) : NM_PRUNE8(NM_DT_BF16, 0);
+#undef NM_PRUNE8
 }
 
 // ------------------------------------------------------------------------------------

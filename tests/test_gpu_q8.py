@@ -1,0 +1,146 @@
+"""GPU parity of the 8-bit path (e5m2 neural gradients by stochastic rounding on top of MVUE 2:4, e4m3
+activations, 8-bit sparse MFMA) against the CPU oracle, through the C ABI.
+
+  * mvue_prune_2of4_q8: vals8 / meta32 bit for bit, both estimators, bf16 and binary32 inputs, strided input.
+  * nm_update_gemm_q8: against the oracle's binary64 sums.  The 8-bit matrix instruction adds the 64 products of a
+    step in a fixed-point window below the largest of them before the binary32 accumulation, so small products
+    lose low bits next to large ones: tolerance 1e-3 of the sum of absolute products (observed up to 2e-4 on
+    lognormal gradients, printed; ten times tighter than the 16-bit path's 1e-2).
+"""
+import numpy as np
+import pytest
+import torch
+
+from paper_2203_10991_amd import synth
+from gpu_util import DEV, to_dev
+
+pytestmark = pytest.mark.gpu
+TOL = 1e-3
+
+
+@pytest.fixture(scope="module")
+def nm():
+    import paper_2203_10991_amd as p
+    p.load()
+    return p
+
+
+def fit_scale(g_f32: np.ndarray) -> float:
+    """power of two that keeps every kept value (at most the sum of a quad's magnitudes) below the largest e5m2"""
+    m = float(np.abs(g_f32).max())
+    return float(2.0 ** np.floor(np.log2(57344.0 / (4.0 * max(m, 1e-30)))))
+
+
+def as_f32(g: np.ndarray) -> np.ndarray:
+    return g if g.dtype == np.float32 else synth.bf16_to_f32(g)
+
+
+def h8_codes(T, I, seed, relu=False):
+    """e4m3 codes of a scaled normal (or half-normal with zeros) activation tensor: numpy draw, torch's nearest cast"""
+    rng = np.random.default_rng(seed)
+    x = rng.standard_normal((T, I)).astype(np.float32) * 8.0
+    if relu:
+        x = np.where(rng.random((T, I)) < 0.5, 0.0, np.abs(x)).astype(np.float32)
+    return torch.from_numpy(x).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("T,O", [(32, 8), (64, 64), (32 * 7, 8 * 13), (32 * 40, 8 * 67), (2048, 1024)])
+def test_prune_q8_bit_exact(nm, oracle, dtype, mode, T, O):
+    w = synth.Workload(f"q8_{T}x{O}", T, O, 16, dtype, "2:4", 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O + mode)
+    scale = fit_scale(as_f32(g))
+    ov, om = oracle.prune_2of4_q8(g, seed=77, stream_id=3, mode=mode, scale=scale)
+    v, m = nm.mvue_prune_2of4_q8(to_dev(g), seed=77, stream_id=3, mode=mode, scale=scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), om)
+    assert np.array_equal(v.cpu().numpy(), ov)
+
+
+def test_prune_q8_strided_input_small_and_large_scales(nm, oracle):
+    """row stride larger than O; scales that push kept values into the subnormal range and into saturation"""
+    T, O = 96, 40
+    w = synth.Workload("q8_strided", T, O, 16, "bf16", "2:4", 0.0, 3.0, 0.3)
+    g = synth.make_g(w, seed=4)
+    wide = torch.zeros((T, O + 24), dtype=torch.bfloat16, device=DEV)
+    wide[:, :O] = to_dev(g)
+    base = fit_scale(as_f32(g))
+    for scale in (base, base * 2.0 ** -22, base * 2.0 ** -30, base * 64.0, 1e30):
+        ov, om = oracle.prune_2of4_q8(g, seed=1, stream_id=0, mode=0, scale=scale)
+        v, m = nm.mvue_prune_2of4_q8(wide[:, :O], seed=1, stream_id=0, mode=0, scale=scale)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy().view(np.uint32), om), scale
+        assert np.array_equal(v.cpu().numpy(), ov), scale
+    sat = (ov & 0x7F) == 0x7B
+    assert sat.any()                                        # the last scale saturates
+
+
+def test_prune_q8_same_mask_as_the_16_bit_prune(nm):
+    """same seed, same stream: the 8-bit prune keeps the positions the 16-bit prune keeps"""
+    T, O = 256, 128
+    w = synth.Workload("q8_mask", T, O, 16, "bf16", "2:4", 0.0, 2.0, 0.2)
+    g = to_dev(synth.make_g(w, seed=8))
+    for mode in (0, 1):
+        _, m16, _ = nm.mvue_prune_2of4(g, seed=9, stream_id=1, mode=mode)
+        _, m32 = nm.mvue_prune_2of4_q8(g, seed=9, stream_id=1, mode=mode, scale=4.0)
+        torch.cuda.synchronize()
+        m16 = m16.cpu().numpy().view(np.uint16).astype(np.uint32)
+        assert np.array_equal(m32.cpu().numpy().view(np.uint32), m16[0::2] | (m16[1::2] << 16))
+
+
+def gemm_case(nm, oracle, T, O, I, seed, beta=0.0, sample=None, relu=False):
+    w = synth.Workload(f"q8_{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3)
+    g = synth.make_g(w, seed)
+    scale = fit_scale(as_f32(g))
+    ov, om = oracle.prune_2of4_q8(g, seed=seed, stream_id=0, mode=0, scale=scale)
+    h8 = h8_codes(T, I, seed + 1, relu)
+    alpha = 1.0 / (scale * 8.0)
+    v, m = nm.mvue_prune_2of4_q8(to_dev(g), seed=seed, stream_id=0, mode=0, scale=scale)
+    prior = np.random.default_rng(1).standard_normal((O, I)).astype(np.float32) if beta else None
+    dW = torch.from_numpy(prior).to(DEV) if beta else torch.full((O, I), float("nan"), device=DEV)
+    nm.nm_update_gemm_q8(v, m, torch.from_numpy(h8).to(DEV), dW=dW, alpha=alpha, beta=beta)
+    torch.cuda.synchronize()
+    assert np.array_equal(v.cpu().numpy(), ov) and np.array_equal(m.cpu().numpy().view(np.uint32), om)
+    got = dW.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    if sample is None:
+        want, wabs = oracle.update_gemm_q8(ov, om, h8, alpha=alpha)
+    else:                                   # whole rows and whole columns, chosen at random plus the edges
+        rng = np.random.default_rng(seed)
+        rows = np.unique(np.concatenate([rng.choice(O, sample, replace=False), [0, O - 1]]))
+        cols = np.unique(np.concatenate([rng.choice(I, sample, replace=False), [0, I - 1]]))
+        oi = np.concatenate([np.stack(np.meshgrid(rows, np.arange(I), indexing="ij"), -1).reshape(-1, 2),
+                             np.stack(np.meshgrid(np.arange(O), cols, indexing="ij"), -1).reshape(-1, 2)])
+        want, wabs = oracle.update_gemm_q8(ov, om, h8, alpha=alpha, oi=oi)
+        got = got[oi[:, 0], oi[:, 1]]
+        prior = prior[oi[:, 0], oi[:, 1]] if beta else None
+    if beta:
+        want = want + prior
+        wabs = wabs + np.abs(prior)
+    rel = float((np.abs(got - want) / np.maximum(wabs, 1e-300)).max())
+    fro = float(np.linalg.norm(got - want) / max(np.linalg.norm(want), 1e-300))
+    print(f"q8 T={T} O={O} I={I} beta={beta}: max |err|/sum|ab| = {rel:.3e}, frobenius = {fro:.3e}", flush=True)
+    assert rel <= TOL and fro <= TOL
+
+
+@pytest.mark.parametrize("T,O,I", [(64, 64, 64), (32, 8, 16), (32 * 11, 8 * 9, 16 * 7), (32 * 33, 64 * 3 + 8, 256 + 48),
+                                   (1024, 256, 320), (32 * 13, 128, 256), (2048, 1000, 528)])
+def test_update_gemm_q8_matches_fp64_oracle(nm, oracle, T, O, I):
+    gemm_case(nm, oracle, T, O, I, seed=T + I)
+
+
+def test_update_gemm_q8_beta_one_and_relu_activations(nm, oracle):
+    gemm_case(nm, oracle, 32 * 9, 200, 272, seed=5, beta=1.0, relu=True)
+    gemm_case(nm, oracle, 4096, 64, 576, seed=6, beta=1.0)             # few rows, split-K
+
+
+@pytest.mark.parametrize("T,O,I", [(160, 16 * 256, 16 * 256),            # 16 x 16 tiles of 256 x 256: the 2 x 4 XCD grid; odd group count
+                                   (96, 50 * 256 - 40, 8 * 256),         # banded map with a short last band, ragged rows
+                                   (32 * 14, 33 * 256, 8 * 256 - 16)])   # more than two trips of stages, ragged columns
+def test_update_gemm_q8_large_tile_kernel(nm, oracle, T, O, I):
+    gemm_case(nm, oracle, T, O, I, seed=T, sample=12)
+
+
+def test_update_gemm_q8_beta_one_large_tile(nm, oracle):
+    gemm_case(nm, oracle, 128, 16 * 256, 16 * 256, seed=3, beta=1.0, sample=8)
