@@ -25,6 +25,8 @@ sys.path.insert(0, ROOT)
 HBM_PEAK_GBPS = 8000.0            # MI355X HBM3E, published
 DENSE_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 SPARSE_PEAK_TFLOPS = 2.0 * DENSE_BF16_PEAK_TFLOPS   # 4:2 sparse MFMA skips half the products: dense-equivalent peak
+DENSE_FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA, published
+SPARSE_FP8_PEAK_TFLOPS = 2.0 * DENSE_FP8_PEAK_TFLOPS
 
 
 def read_traffic(workload: str, kernel: str):
@@ -62,6 +64,29 @@ def cpu_baseline(w, approx=False):
     }
 
 
+def cpu_baseline_q8(w, approx=False):
+    """The oracle's 8-bit path on a slice of the workload: first 8192 tokens x 2048 out x 1024 in."""
+    import numpy as np
+    import torch
+    from oracle import cwrap as oracle
+    from paper_2203_10991_amd import synth
+    s = synth.scaled(w, T=min(w.T, 8192), O=min(w.O, 2048), I=min(w.I, 1024), name=w.name + "_slice")
+    g, h = synth.make_g(s, 0), synth.make_h(s, 0)
+    h8 = torch.from_numpy(synth.bf16_to_f32(h)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    t0 = time.perf_counter()
+    v, m = oracle.prune_2of4_q8(g, 0, 0, 1 if approx else 0, 2.0 ** -9)
+    t1 = time.perf_counter()
+    oracle.update_gemm_q8(v, m, h8, alpha=2.0 ** 9)
+    t2 = time.perf_counter()
+    return {
+        "value": s.flops_dense_equiv / (t2 - t0) / 1e12, "unit": "TFLOP/s (dense-equivalent, prune+GEMM step)",
+        "cores": oracle.num_threads(), "kind": "oracle",
+        "sample": f"first {s.T} tokens x {s.O} out x {s.I} in of {w.name}, 8-bit path: prune {t1 - t0:.2f} s, "
+                  f"fp64 GEMM on decoded operands {t2 - t1:.2f} s "
+                  f"({s.flops_dense_equiv / (t2 - t1) / 1e9:.1f} GFLOP/s dense-equivalent)",
+    }
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -70,6 +95,9 @@ def main():
     ap.add_argument("--workload", default="c5_decoder_mlp_2of4")
     ap.add_argument("--estimator", default="optimal", choices=["optimal", "approx"],
                     help="2:4 workloads: the optimal MVUE (Sec. 4.2, default) or approx-MVUE (Sec. 4.4)")
+    ap.add_argument("--precision", default="bf16", choices=["bf16", "q8"],
+                    help="bf16: the workload's own dtype (default, the headline configuration); q8: e5m2 kept values by "
+                         "stochastic rounding + e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc byte counters")
@@ -97,16 +125,43 @@ def main():
         prune = nm.mvue_prune_1of2
     else:
         prune = lambda g_, **kw: nm.mvue_prune_2of4(g_, mode=1 if approx else 0, **kw)
-    vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, dev)
+    q8 = args.precision == "q8"
+    if q8 and w.nm != "2:4":
+        print("bench.py: --precision q8 needs a 2:4 workload", file=sys.stderr)
+        sys.exit(2)
     dW = torch.empty((w.O, w.I), dtype=torch.float32, device=dev)
-    need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
+    if q8:
+        # activations cast to e4m3 once, outside the timed region (they arrive in 8 bits from the forward pass);
+        # gradient scale: a power of two that keeps every kept value below the largest e5m2
+        h8 = torch.empty((w.T, w.I), dtype=torch.uint8, device=dev)
+        gmax = 0.0
+        for a in range(0, w.T, 4096):
+            h8[a:a + 4096] = h[a:a + 4096].float().to(torch.float8_e4m3fn).view(torch.uint8)
+            gmax = max(gmax, float(g[a:a + 4096].abs().max()))
+        import math
+        g_scale = 2.0 ** math.floor(math.log2(57344.0 / (4.0 * max(gmax, 1e-30))))
+        h = h8
+        vals, meta = nm.alloc_compressed_q8(w.T, w.O, dev)
+        need = nm.nm_update_gemm_q8_workspace(w.T, w.O, w.I)
+    else:
+        vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, dev)
+        need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
+
+    def gemm():
+        if q8:
+            nm.nm_update_gemm_q8(vals, meta, h, dW=dW, alpha=1.0 / g_scale, beta=0.0, workspace=ws)
+        else:
+            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
 
     def step(seed, evs=None):
         if evs: evs[0].record()
-        prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
+        if q8:
+            nm.mvue_prune_2of4_q8(g, seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=vals, meta32=meta)
+        else:
+            prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
         if evs: evs[1].record()
-        nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+        gemm()
         if evs: evs[2].record()
 
     for i in range(args.warmup):
@@ -123,7 +178,10 @@ def main():
     gemm_ms = sum(e[1].elapsed_time(e[2]) for e in events) / args.steps
 
     flops = w.flops_dense_equiv
-    prune_gbps = w.prune_bytes / (prune_ms * 1e-3) / 1e9
+    prune_bytes = w.T * w.O * 2 + w.T * w.O // 2 + w.T * w.O // 8 if q8 else w.prune_bytes
+    gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else SPARSE_PEAK_TFLOPS
+    tname = w.name + ("_q8" if q8 else "")
+    prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
         "metric": "MVUE prune GB/s (% HBM peak) + sparse dW GEMM TFLOP/s (% SMFMAC peak)",
@@ -131,22 +189,26 @@ def main():
         "unit": "TFLOP/s (dense-equivalent 2*T*O*I over the whole prune+GEMM step)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "bf16" if w.dtype == "bf16" else "f32", "data": "synthetic",
+        "dtype": "f8" if q8 else ("bf16" if w.dtype == "bf16" else "f32"), "data": "synthetic",
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
-                   "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0},
+                   "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0,
+                   "precision": "e5m2 kept values (stochastic rounding) x e4m3 activations" if q8 else w.dtype},
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
-        "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / SPARSE_PEAK_TFLOPS,
+        "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / gemm_peak,
         "gemm_ms": gemm_ms,
-        "roofline": {"kernel": "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
+        "roofline": {"kernel": "update_gemm_smfmac_q8_kernel" if q8 else
+                               "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
                                "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
-                     "peak": SPARSE_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": gemm_tflops / SPARSE_PEAK_TFLOPS,
-                     "traffic": read_traffic(w.name, "gemm"),
+                     "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,
+                     "traffic": read_traffic(tname, "gemm"),
                      "note": "dense-equivalent flops 2*T*O*I per call; time = HIP events around the call's kernels; "
-                             "peak = 2 x published dense bf16 MFMA peak (4:2 sparse MFMA executes half the products)"},
-        "roofline_prune": {"kernel": "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
+                             "peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
+                             " MFMA peak (4:2 sparse MFMA executes half the products)"},
+        "roofline_prune": {"kernel": "prune_compress_q8_kernel" if q8 else
+                           "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
-                           "traffic": read_traffic(w.name, "prune"),
-                           "note": f"algorithmic bytes {w.prune_bytes} per launch: read g, write T/2 values and T/16 index words per column"},
+                           "traffic": read_traffic(tname, "prune"),
+                           "note": f"algorithmic bytes {prune_bytes} per launch: read g, write T/2 values and T/16 index words per column"},
     }
     # Sustained shader clock and board power while the GEMM runs (best effort, driver's management interface):
     # a queue of back-to-back launches is sampled from the host.  MFMA-heavy kernels run below the 2.4 GHz the
@@ -154,7 +216,7 @@ def main():
     try:
         clocks, watts = [], []
         for _ in range(40):
-            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+            gemm()
         t_end = time.perf_counter() + 40 * gemm_ms * 1e-3 * 0.8
         time.sleep(5 * gemm_ms * 1e-3)
         while time.perf_counter() < t_end:
@@ -169,7 +231,7 @@ def main():
         sclk = clocks[len(clocks) // 2] if clocks else None
         if sclk and sclk > 200.0:
             out["gemm_sclk_MHz_sampled"] = sclk
-            out["roofline"]["frac_at_sustained_clock"] = gemm_tflops / (SPARSE_PEAK_TFLOPS * sclk / 2400.0)
+            out["roofline"]["frac_at_sustained_clock"] = gemm_tflops / (gemm_peak * sclk / 2400.0)
         if watts:
             watts.sort()
             out["gemm_board_power_W_sampled"] = watts[len(watts) // 2]
@@ -204,7 +266,7 @@ def main():
     if not args.no_cpu_baseline:
         del g, h, vals, meta, dW, ws
         torch.cuda.empty_cache()
-        out["cpu_baseline"] = cpu_baseline(w, approx)
+        out["cpu_baseline"] = cpu_baseline_q8(w, approx) if q8 else cpu_baseline(w, approx)
     print(json.dumps(out))
 
 

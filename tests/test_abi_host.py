@@ -29,7 +29,8 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version"}
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8",
+                          "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
         assert hasattr(lib, n), n
     assert b"gfx950" in lib.nm_version()
@@ -99,3 +100,47 @@ def test_gemm_argument_errors(lib):
     # binary32 problems with few output tiles split the reduction axis as well
     assert lib.nm_update_gemm_workspace(1024, 1024, 1024, 0) == 8 * 1024 * 1024 * 4
     assert gemm(T=1024, O=1024, I=1024, ldh=1024, lddw=1024, dt=0, dW=P + (1 << 40)) == NM_ERR_WORKSPACE
+
+
+def test_q8_argument_errors(lib):
+    f32, sz = C.c_float, C.c_size_t
+    lib.mvue_prune_2of4_q8.argtypes = [C.c_void_p, C.c_int64, C.c_int64, C.c_int64, C.c_int, C.c_uint64, C.c_uint32, C.c_int,
+                                       f32, C.c_void_p, C.c_void_p, C.c_void_p]
+
+    def prune8(g=P, T=64, O=16, ldg=16, dt=1, mode=0, scale=1.0, vals=P + 0x10000, meta=P + 0x20000):
+        return lib.mvue_prune_2of4_q8(g, T, O, ldg, dt, 0, 0, mode, scale, vals, meta, None)
+
+    assert prune8(T=48) == NM_ERR_SHAPE and b"multiple of 32" in lib.nm_last_error()
+    assert prune8(O=12) == NM_ERR_SHAPE
+    assert prune8(mode=2) == NM_ERR_UNSUPPORTED
+    assert prune8(scale=0.0) == NM_ERR_SHAPE and prune8(scale=float("inf")) == NM_ERR_SHAPE and prune8(scale=float("nan")) == NM_ERR_SHAPE
+    assert prune8(dt=3) == NM_ERR_DTYPE
+    assert prune8(vals=None) == NM_ERR_NULL and prune8(meta=None) == NM_ERR_NULL and prune8(g=None) == NM_ERR_NULL
+    assert prune8(vals=P + 8) == NM_ERR_ALIGN
+    assert prune8(vals=P) == NM_ERR_ALIAS and prune8(meta=P + 0x10000) == NM_ERR_ALIAS
+    assert prune8(T=0) == NM_OK and prune8(O=0, ldg=0) == NM_OK
+
+    lib.nm_update_gemm_q8.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_int64, C.c_void_p, C.c_int64, C.c_int64, C.c_int64,
+                                      C.c_int64, f32, f32, C.c_void_p, sz, C.c_void_p]
+    lib.nm_update_gemm_q8_workspace.argtypes = [C.c_int64] * 3
+    lib.nm_update_gemm_q8_workspace.restype = sz
+
+    def gemm8(vals=P, meta=P + 0x100000, h=P + 0x200000, ldh=64, dW=P + 0x300000, lddw=64, T=64, O=64, I=64, alpha=1.0, beta=0.0,
+              ws=None, wsb=0):
+        return lib.nm_update_gemm_q8(vals, meta, h, ldh, dW, lddw, T, O, I, alpha, beta, ws, wsb, None)
+
+    assert gemm8(T=48) == NM_ERR_SHAPE
+    assert gemm8(I=24, ldh=32) == NM_ERR_SHAPE and b"of 16" in lib.nm_last_error()
+    assert gemm8(O=12) == NM_ERR_SHAPE
+    assert gemm8(beta=0.5) == NM_ERR_UNSUPPORTED
+    assert gemm8(dW=None) == NM_ERR_NULL and gemm8(h=None) == NM_ERR_NULL
+    assert gemm8(ldh=48) == NM_ERR_SHAPE and gemm8(ldh=72) == NM_ERR_ALIGN
+    assert gemm8(lddw=32) == NM_ERR_SHAPE
+    assert gemm8(dW=P) == NM_ERR_ALIAS
+    assert gemm8(O=(1 << 21) + 8) == NM_ERR_UNSUPPORTED
+    # a problem with few tiles is split along T and needs the workspace it asks for
+    need = lib.nm_update_gemm_q8_workspace(4096, 64, 256)
+    assert need > 0 and need % (64 * 256 * 4) == 0
+    assert gemm8(T=4096, I=256, ldh=256, lddw=256) == NM_ERR_WORKSPACE
+    assert lib.nm_update_gemm_q8_workspace(32768, 28672, 8192) == 0
+    assert gemm8(O=0) == NM_OK

@@ -101,3 +101,45 @@ def test_freivalds_identity_over_every_entry(case, oracle):
         rel = np.abs(got - want) / np.maximum(scale, 1e-300)
         print(f"Freivalds trial {trial}: max |dW x - theta(g)^T h x| / sum|ab| = {rel.max():.3e}", flush=True)
         assert rel.max() <= 1e-2
+
+
+def test_full_size_q8_path(case, oracle):
+    """8-bit path at the benchmark's size: e5m2 codes and index words of the whole tensor bit for bit, dW on sampled
+    entries and one full output tile against the oracle's binary64 sums (tolerance as in test_gpu_q8.py)."""
+    import paper_2203_10991_amd as nm
+    w = case["w"]
+    g, h = synth.make_device(w, seed=0, device=DEV)
+    gmax = max(float(g[a:a + 4096].abs().max()) for a in range(0, w.T, 4096))
+    scale = float(2.0 ** np.floor(np.log2(57344.0 / (4.0 * gmax))))
+    h8 = torch.empty((w.T, w.I), dtype=torch.uint8, device=DEV)
+    for a in range(0, w.T, 4096):
+        h8[a:a + 4096] = h[a:a + 4096].float().to(torch.float8_e4m3fn).view(torch.uint8)
+    del h
+    v8, m32 = nm.alloc_compressed_q8(w.T, w.O, DEV)
+    nm.mvue_prune_2of4_q8(g, seed=3, stream_id=1, mode=0, scale=scale, vals8=v8, meta32=m32)
+    dW = torch.empty((w.O, w.I), dtype=torch.float32, device=DEV)
+    nm.nm_update_gemm_q8(v8, m32, h8, dW=dW, alpha=1.0 / scale, beta=0.0)
+    torch.cuda.synchronize()
+    g_host = to_host(g)
+    del g
+    print("oracle 8-bit prune of the full tensor ...", flush=True)
+    ov, om = oracle.prune_2of4_q8(g_host, 3, 1, 0, scale)
+    del g_host
+    assert np.array_equal(m32.cpu().numpy().view(np.uint32), om)
+    assert np.array_equal(v8.cpu().numpy(), ov)
+    h8_host = h8.cpu().numpy()
+    rng = np.random.default_rng(2)
+    oi = np.stack([rng.integers(0, w.O, size=2048), rng.integers(0, w.I, size=2048)], axis=1)
+    want, wabs = oracle.update_gemm_q8(ov, om, h8_host, alpha=1.0 / scale, oi=oi)
+    got = dW[torch.from_numpy(oi[:, 0]).to(DEV), torch.from_numpy(oi[:, 1]).to(DEV)].cpu().numpy().astype(np.float64)
+    rel = np.abs(got - want) / np.maximum(wabs, 1e-300)
+    print(f"q8, 2048 sampled entries: max |err|/sum|ab| = {rel.max():.3e}", flush=True)
+    assert rel.max() <= 1e-3
+    o0, i0 = w.O - 256, 512
+    want, wabs = oracle.update_gemm_q8(np.ascontiguousarray(ov[:, o0:o0 + 256]), np.ascontiguousarray(om[:, o0:o0 + 256]),
+                                       np.ascontiguousarray(h8_host[:, i0:i0 + 256]), alpha=1.0 / scale)
+    got = dW[o0:o0 + 256, i0:i0 + 256].cpu().numpy().astype(np.float64)
+    rel = np.abs(got - want) / np.maximum(wabs, 1e-300)
+    fro = np.linalg.norm(got - want) / np.linalg.norm(want)
+    print(f"q8, 256x256 tile: max |err|/sum|ab| = {rel.max():.3e}, frobenius = {fro:.3e}", flush=True)
+    assert rel.max() <= 1e-3 and fro <= 1e-3
