@@ -16,6 +16,7 @@
 #include <stdint.h>
 
 #include "nm_internal.h"
+#include "smfmac_common.h"       // static_for
 
 namespace nm {
 
@@ -441,9 +442,9 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
 #pragma unroll
     for (int c = 0; c < VEC; ++c) { md[c] = 0; kept[c][0] = kept[c][1] = kept[c][2] = kept[c][3] = 0; }
 
-#pragma unroll
-    for (int b = 0; b < 8; ++b) {                       // quad row b: tensor rows 4b .. 4b+3, held in rows[(4b) % 16 ..]
-        if (b == 1 || b == 2 || b == 4) {
+    static_for<8>([&](auto b_c) {                       // quad row b: tensor rows 4b .. 4b+3, held in rows[(4b) % 16 ..]
+        constexpr int b = decltype(b_c)::value;
+        if constexpr (b == 1 || b == 2 || b == 4) {
             const int first = b == 1 ? 8 : b == 2 ? 16 : 24;
             const char *gp2 = gp;
             asm volatile("" : "+v"(gp2));
@@ -469,7 +470,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) rnd[4 * q + j] = w4[j];
         }
-        const int R0 = (4 * b) % 16;
+        constexpr int R0 = (4 * b) % 16;
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             float v0, v1; uint32_t nib;
@@ -486,7 +487,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
             md[c] |= nib << (4 * b);
             __builtin_amdgcn_sched_barrier(0);
         }
-    }
+    });
 
     // 16 bytes per column, VEC columns contiguous; one index word per column
     uint4 *vp = (uint4 *)(vals8 + (G * O + col0) * 16);
