@@ -1,0 +1,130 @@
+"""Linear and Conv2d layers whose UPDATE phase runs through libnm_mvue.
+
+Only the weight-gradient GEMM dW = g^T h (eq. (3)) sees the pruned gradient; the forward GEMM (eq. (1)) and the
+backward GEMM that propagates g (eq. (2)) are torch's dense ones, as in the paper (Table 1: the neural-gradient
+column accelerates the update phase only).  The random source is a pure function of (seed, stream_id, block),
+so holding `seed` fixed for `reuse_every` iterations is the sample reuse of App. B.1 (up to 50 iterations
+without loss) at no extra cost.
+
+There is no fallback: tensors must live on the GPU and the HIP library must be built.
+"""
+from __future__ import annotations
+
+from dataclasses import dataclass
+from typing import Optional
+
+import torch
+import torch.nn.functional as F
+
+from . import api
+
+
+@dataclass
+class NMConfig:
+    """How a layer prunes its neural gradient in the update phase."""
+    nm: str = "2:4"            # "1:2" (Sec. 4.1) or "2:4"
+    mode: int = 0              # 2:4 only: 0 = optimal MVUE (Sec. 4.2), 1 = approx-MVUE (Sec. 4.4)
+    seed: int = 0              # base seed of the run
+    stream_id: int = 0         # one per layer: independent random streams
+    reuse_every: int = 1       # iterations that share one set of random samples (App. B.1)
+    step: int = 0              # iteration counter; advance() once per optimizer step
+
+    def current_seed(self) -> int:
+        return self.seed + self.step // max(1, self.reuse_every)
+
+    def advance(self) -> None:
+        self.step += 1
+
+
+def _update_gemm(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Tensor:
+    """dW[O x I] (binary32) = theta(g2)^T h2 for g2 [T x O], h2 [T x I]; T is padded with zero rows to a multiple of 16."""
+    if not (g2.is_cuda and h2.is_cuda):
+        raise RuntimeError("the N:M update phase runs on the GPU only (no CPU fallback)")
+    T, O = g2.shape
+    I = h2.shape[1]
+    if O % 8 or I % 8:
+        raise ValueError(f"out_features={O} and the reduction width {I} must be multiples of 8")
+    if g2.dtype != h2.dtype or g2.dtype not in (torch.float32, torch.bfloat16):
+        raise TypeError("g and h must both be float32 or both bfloat16")
+    pad = (-T) % 16
+    if pad:                                   # zero rows prune to zeros and add nothing to dW
+        g2 = F.pad(g2, (0, 0, 0, pad))
+        h2 = F.pad(h2, (0, 0, 0, pad))
+    g2, h2 = g2.contiguous(), h2.contiguous()
+    if cfg.nm == "1:2":
+        vals, meta, _ = api.mvue_prune_1of2(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id)
+    elif cfg.nm == "2:4":
+        vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
+    else:
+        raise ValueError(f"unknown N:M pattern {cfg.nm!r}")
+    return api.nm_update_gemm(vals, meta, h2)
+
+
+class _NMLinearFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, cfg):
+        ctx.save_for_backward(x, weight)
+        ctx.cfg, ctx.has_bias = cfg, bias is not None
+        return F.linear(x, weight, bias)
+
+    @staticmethod
+    def backward(ctx, gy):
+        x, weight = ctx.saved_tensors
+        dx = gy @ weight if ctx.needs_input_grad[0] else None                     # backward phase: dense (eq. (2))
+        dW = None
+        if ctx.needs_input_grad[1]:
+            dW = _update_gemm(gy.reshape(-1, gy.shape[-1]), x.reshape(-1, x.shape[-1]), ctx.cfg).to(weight.dtype)
+        db = gy.reshape(-1, gy.shape[-1]).sum(0) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        return dx, dW, db, None
+
+
+class NMLinear(torch.nn.Linear):
+    """torch.nn.Linear whose weight gradient is computed from the MVUE N:M pruned neural gradient."""
+
+    def __init__(self, in_features: int, out_features: int, bias: bool = True, cfg: Optional[NMConfig] = None, **kw):
+        super().__init__(in_features, out_features, bias=bias, **kw)
+        self.cfg = cfg or NMConfig()
+
+    def forward(self, x):
+        return _NMLinearFn.apply(x, self.weight, self.bias, self.cfg)
+
+
+class _NMConv2dFn(torch.autograd.Function):
+    @staticmethod
+    def forward(ctx, x, weight, bias, stride, padding, dilation, cfg):
+        ctx.save_for_backward(x, weight)
+        ctx.conv = (stride, padding, dilation)
+        ctx.cfg, ctx.has_bias = cfg, bias is not None
+        return F.conv2d(x, weight, bias, stride, padding, dilation)
+
+    @staticmethod
+    def backward(ctx, gy):
+        x, weight = ctx.saved_tensors
+        stride, padding, dilation = ctx.conv
+        dx = None
+        if ctx.needs_input_grad[0]:
+            dx = torch.nn.grad.conv2d_input(x.shape, weight, gy, stride, padding, dilation)
+        dW = None
+        if ctx.needs_input_grad[1]:
+            # im2col (App. B: the convolution's update GEMM reduces over batch x output positions):
+            # h [N*L, C*kh*kw], g [N*L, O]
+            O, C, kh, kw = weight.shape
+            cols = F.unfold(x, (kh, kw), dilation=dilation, padding=padding, stride=stride)      # [N, C*kh*kw, L]
+            h2 = cols.transpose(1, 2).reshape(-1, C * kh * kw)
+            g2 = gy.reshape(gy.shape[0], O, -1).transpose(1, 2).reshape(-1, O)
+            dW = _update_gemm(g2, h2, ctx.cfg).reshape(O, C, kh, kw).to(weight.dtype)
+        db = gy.sum((0, 2, 3)) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        return dx, dW, db, None, None, None, None
+
+
+class NMConv2d(torch.nn.Conv2d):
+    """torch.nn.Conv2d (groups = 1, zero padding) whose weight gradient comes from the pruned neural gradient."""
+
+    def __init__(self, *args, cfg: Optional[NMConfig] = None, **kw):
+        super().__init__(*args, **kw)
+        if self.groups != 1 or self.padding_mode != "zeros" or isinstance(self.padding, str):
+            raise ValueError("NMConv2d supports groups=1 with numeric zero padding")
+        self.cfg = cfg or NMConfig()
+
+    def forward(self, x):
+        return _NMConv2dFn.apply(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.cfg)

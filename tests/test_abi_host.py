@@ -144,3 +144,17 @@ def test_q8_argument_errors(lib):
     assert gemm8(T=4096, I=256, ldh=256, lddw=256) == NM_ERR_WORKSPACE
     assert lib.nm_update_gemm_q8_workspace(32768, 28672, 8192) == 0
     assert gemm8(O=0) == NM_OK
+
+
+def test_autograd_layers_have_no_cpu_fallback():
+    import torch
+    from paper_2203_10991_amd.autograd import NMConv2d, NMLinear
+    layer = NMLinear(16, 8)
+    x = torch.randn(16, 16, requires_grad=True)
+    with pytest.raises(RuntimeError, match="GPU only"):
+        layer(x).sum().backward()
+    conv = NMConv2d(8, 8, 3, padding=1)
+    with pytest.raises(RuntimeError, match="GPU only"):
+        conv(torch.randn(2, 8, 4, 4)).sum().backward()
+    with pytest.raises(ValueError):
+        NMConv2d(8, 8, 3, groups=2)

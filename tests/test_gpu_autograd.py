@@ -1,0 +1,85 @@
+"""GPU: the Linear / Conv2d layers whose update phase runs through the library (App. B: linear and im2col
+convolution shapes of the update GEMM).  dW is compared with the oracle's prune + binary64 GEMM on the same g and
+h; dx and db with torch's dense backward.  Holding the seed fixed reproduces the mask (App. B.1 sample reuse)."""
+import numpy as np
+import pytest
+import torch
+
+from gpu_util import DEV, to_host
+
+pytestmark = pytest.mark.gpu
+
+
+def bits(t):
+    return to_host(t.contiguous())
+
+
+@pytest.mark.parametrize("dtype,nmode,mode", [(torch.bfloat16, "2:4", 0), (torch.bfloat16, "2:4", 1),
+                                              (torch.float32, "1:2", 0), (torch.float32, "2:4", 0)])
+def test_linear_update_phase_matches_oracle(oracle, dtype, nmode, mode):
+    from paper_2203_10991_amd.autograd import NMConfig, NMLinear
+    torch.manual_seed(0)
+    B, S, I, O = 3, 37, 72, 40                      # T = 111: padded to 112 inside
+    cfg = NMConfig(nm=nmode, mode=mode, seed=5, stream_id=2)
+    layer = NMLinear(I, O, bias=True, cfg=cfg, device=DEV, dtype=dtype)
+    x = torch.randn(B, S, I, device=DEV, dtype=dtype, requires_grad=True)
+    gy = (torch.randn(B, S, O, device=DEV) * torch.exp(2 * torch.randn(B, S, O, device=DEV))).to(dtype)
+    layer(x).backward(gy)
+    # dense references for the phases the method leaves alone
+    ref = torch.nn.Linear(I, O, device=DEV, dtype=dtype)
+    ref.load_state_dict(layer.state_dict())
+    x2 = x.detach().clone().requires_grad_(True)
+    ref(x2).backward(gy)
+    assert torch.equal(x.grad, x2.grad) and torch.equal(layer.bias.grad, ref.bias.grad)
+    # update phase against the oracle
+    g2 = torch.nn.functional.pad(gy.reshape(-1, O), (0, 0, 0, 1))
+    h2 = torch.nn.functional.pad(x.detach().reshape(-1, I), (0, 0, 0, 1))
+    oprune = oracle.prune_1of2 if nmode == "1:2" else (oracle.prune_2of4_approx if mode else oracle.prune_2of4)
+    ov, om, _ = oprune(bits(g2), 5, 2)
+    want, wabs = oracle.update_gemm(ov, om, bits(h2))
+    got = layer.weight.grad.double().cpu().numpy()
+    tol = 1e-5 if dtype == torch.float32 else 1e-2          # (bf16: dW itself is rounded to bf16 by the layer)
+    assert (np.abs(got - want) <= tol * np.maximum(wabs, np.abs(want))).all()
+    # same seed -> same gradient; next seed (after reuse_every steps) -> another mask
+    w1 = layer.weight.grad.clone()
+    layer.weight.grad = None
+    layer(x).backward(gy)
+    assert torch.equal(w1, layer.weight.grad)
+    cfg.advance()
+    layer.weight.grad = None
+    layer(x).backward(gy)
+    assert not torch.equal(w1, layer.weight.grad)
+
+
+def test_conv2d_update_phase_matches_oracle(oracle):
+    from paper_2203_10991_amd.autograd import NMConfig, NMConv2d
+    torch.manual_seed(1)
+    N, C, H, W, O, k = 4, 8, 10, 10, 16, 3              # I = C*k*k = 72, T = N*H*W = 400
+    conv = NMConv2d(C, O, k, padding=1, bias=True, cfg=NMConfig(nm="2:4", seed=9, stream_id=1), device=DEV)
+    x = torch.relu(torch.randn(N, C, H, W, device=DEV)).requires_grad_(True)
+    gy = torch.randn(N, O, H, W, device=DEV) * torch.exp(2 * torch.randn(N, O, H, W, device=DEV))
+    conv(x).backward(gy)
+    ref = torch.nn.Conv2d(C, O, k, padding=1, device=DEV)
+    ref.load_state_dict(conv.state_dict())
+    x2 = x.detach().clone().requires_grad_(True)
+    ref(x2).backward(gy)
+    assert torch.allclose(x.grad, x2.grad, rtol=1e-4, atol=1e-4) and torch.allclose(conv.bias.grad, ref.bias.grad, rtol=1e-5, atol=1e-4)
+    cols = torch.nn.functional.unfold(x.detach(), (k, k), padding=1).transpose(1, 2).reshape(-1, C * k * k)
+    g2 = gy.reshape(N, O, -1).transpose(1, 2).reshape(-1, O)
+    ov, om, _ = oracle.prune_2of4(bits(g2), 9, 1)
+    want, wabs = oracle.update_gemm(ov, om, bits(cols))
+    got = conv.weight.grad.reshape(O, -1).double().cpu().numpy()
+    assert (np.abs(got - want) <= 1e-5 * wabs + 1e-30).all()
+    # the estimate is unbiased: the mean over seeds approaches the dense weight gradient
+    acc = torch.zeros_like(conv.weight)
+    n = 200
+    for s in range(n):
+        conv.cfg.seed = 100 + s
+        conv.weight.grad = None
+        conv(x).backward(gy)
+        acc += conv.weight.grad
+    dense = ref.weight.grad
+    err = (acc / n - dense).norm() / dense.norm()
+    one = (conv.weight.grad - dense).norm() / dense.norm()
+    print(f"conv dW: one draw off by {one:.3f}, mean of {n} draws off by {err:.3f}", flush=True)
+    assert err < 3.0 * one / np.sqrt(n) + 1e-3
