@@ -624,9 +624,9 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
     const int64_t groups = T / 16;
     const int CUS = 256;
     p.tall_rows = 0; p.tall_tiles_m = 0;
-    // shape 0: 256x256, shape 1: 128x128, shape 2: 64x256 (few rows)
-    if (O <= 64) { p.shape = 2; p.tm = 64; p.tn = 256; }
-    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
+    // shape 0: 256x256 (8 waves), shape 1: 128x128 (4 waves, two workgroups fit a CU)
+    bool small = false;
+    if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
         p.shape = 0; p.tm = 256; p.tn = 256;
         // Large problems: the 384 x 256 kernel moves 21 % fewer operand bytes per product and is ~10 % faster per
         // product, but a GPU-wide round of its tiles takes 1.34 times as long, and a partly filled last round costs
@@ -643,20 +643,33 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
         p.tall_tiles_m = (int)best_mt;
         p.tall_rows = std::min<int64_t>(O, best_mt * 384);
     }
-    else { p.shape = 1; p.tm = 128; p.tn = 128; }
+    else { p.shape = 1; p.tm = 128; p.tn = 128; small = true; }
     p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + p.tn - 1) / p.tn);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    // Smaller problems: the reduction axis is cut into slabs until the GPU is filled evenly -- one workgroup on every
+    // CU, or two on (nearly) every CU; anything between leaves some CUs with twice the work of the others.  Of the two
+    // the cheaper one by a measured cost model: microseconds per 32-token stage of a 128 x 128 tile (0.14 alone on
+    // its CU, rising to 0.18 with all CUs busy; 0.32 when two share a CU), never less than one pass over the operands
+    // at 4.5 TB/s, plus the second pass over the partial sums.
+    auto whole_trips = [](int64_t gps) { gps = (gps + 11) / 12 * 12; return gps < 12 ? (int64_t)12 : gps; };
     int slabs = 1;
-    if (p.tall_rows == 0 && tiles < CUS && groups >= 64) {
-        slabs = (int)((2 * CUS + tiles - 1) / tiles);                 // about two workgroups per CU
-        const int64_t max_slabs = groups / 32;                         // at least 512 tokens per slab
-        if (slabs > max_slabs) slabs = (int)max_slabs;
-        if (slabs < 1) slabs = 1;
+    if (small && groups >= 48) {
+        const int64_t max_s = std::max<int64_t>(1, groups / 24);               // at least 384 tokens per slab
+        auto cost = [&](int64_t sl) {
+            const int64_t wgs = tiles * sl, stages = whole_trips((groups + sl - 1) / sl) / 2;
+            const double t_stage = wgs <= CUS ? 0.14 + 0.04 * (double)wgs / CUS : 0.32;
+            const double rounds = wgs <= CUS ? 1.0 : (double)((wgs + 2 * CUS - 1) / (2 * CUS));
+            const double second_pass = sl > 1 ? 4.0 + (double)(sl + 1) * (double)O * (double)I * 4.0 / 3.5e6 : 0.0;
+            const double stream = (double)T * ((double)I * 2.0 + (double)O * 1.125) / 4.5e6;
+            return std::max(rounds * (double)stages * t_stage, stream) + second_pass;
+        };
+        const int64_t s_one = std::min(max_s, std::max<int64_t>(1, CUS / tiles));
+        const int64_t s_two = std::min(max_s, std::max<int64_t>(1, 2 * CUS / tiles));
+        slabs = (int)s_one;
+        if (tiles * s_two >= 3 * CUS / 2 && cost(s_two) < cost(s_one)) slabs = (int)s_two;
     }
-    int64_t gps = (groups + slabs - 1) / slabs;
-    gps = (gps + 11) / 12 * 12;                                        // whole trips of six LDS stages
-    if (gps < 12) gps = 12;
+    const int64_t gps = whole_trips((groups + slabs - 1) / slabs);           // whole trips of six LDS stages
     p.groups_per_slab = gps;
     p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
     return p;
@@ -694,8 +707,7 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
                        meta, (const uint16_t *)h, ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I,         \
                        p.tiles_m, p.tiles_n, acc_flag, p.tall_rows, O)
         if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
-        else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
-        else NM_LAUNCH(1, 4, 2, 2);
+        else NM_LAUNCH(2, 2, 2, 2);
 #undef NM_LAUNCH
     }
     hipError_t e = hipGetLastError();

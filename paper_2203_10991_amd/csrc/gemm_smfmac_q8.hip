@@ -322,10 +322,12 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
     p.tiles_m = (int)((O + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + 255) / 256);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
+    // few tiles: the reduction axis is cut into slabs until every CU has one workgroup (these kernels fit one per CU;
+    // more slabs than that only lengthen the second pass over the partial sums)
     int slabs = 1;
-    if (tiles < CUS && groups >= 32) {
-        slabs = (int)((2 * CUS + tiles - 1) / tiles);                 // about two workgroups per CU
-        const int64_t max_slabs = groups / 16;                         // at least 512 tokens per slab
+    if (tiles < CUS && groups >= 24) {
+        slabs = (int)(CUS / tiles);
+        const int64_t max_slabs = groups / 12;                         // at least 384 tokens per slab
         if (slabs > max_slabs) slabs = (int)max_slabs;
         if (slabs < 1) slabs = 1;
     }
