@@ -1,0 +1,58 @@
+"""GPU: the library's calls are capturable in a HIP graph (no allocation, no synchronisation, no memset inside):
+one prune + update-GEMM step of a ViT-sized layer, split-K path included, is captured once and replayed several
+times with eager work and synchronisations between the replays; every replay equals the eager result bit for bit."""
+import pytest
+import torch
+
+from paper_2203_10991_amd import synth
+from gpu_util import DEV
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("q8", [False, True])
+def test_step_replays_from_a_graph(q8):
+    import paper_2203_10991_amd as nm
+    nm.load()
+    w = synth.WORKLOADS["c4_vit_proj_2of4"]
+    T = w.T - w.T % 32
+    g, h = synth.make_device(w, seed=1, device=DEV)
+    g, h = g[:T].contiguous(), h[:T].contiguous()
+    dW = torch.zeros((w.O, w.I), dtype=torch.float32, device=DEV)
+    if q8:
+        h = h.float().to(torch.float8_e4m3fn).view(torch.uint8)
+        vals, meta = nm.alloc_compressed_q8(T, w.O, DEV)
+        need = nm.nm_update_gemm_q8_workspace(T, w.O, w.I)
+    else:
+        vals, meta = nm.alloc_compressed(T, w.O, g.dtype, DEV)
+        need = nm.nm_update_gemm_workspace(T, w.O, w.I, g.dtype)
+    assert need > 0                                    # this shape takes the split-K path
+    ws = torch.empty(need, dtype=torch.uint8, device=DEV)
+
+    def step():
+        if q8:
+            nm.mvue_prune_2of4_q8(g, seed=4, stream_id=0, mode=0, scale=0.25, vals8=vals, meta32=meta)
+            nm.nm_update_gemm_q8(vals, meta, h, dW=dW, alpha=4.0, beta=0.0, workspace=ws)
+        else:
+            nm.mvue_prune_2of4(g, seed=4, stream_id=0, vals=vals, meta=meta)
+            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+
+    step()
+    torch.cuda.synchronize()
+    want_dW, want_vals = dW.clone(), vals.clone()
+    side = torch.cuda.Stream()
+    with torch.cuda.stream(side):
+        step()                                          # warm-up on the capture stream
+        side.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=side):
+            step()
+    for i in range(4):
+        dW.fill_(float("nan"))                          # eager work between the replays
+        vals.zero_()
+        ws.zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(dW, want_dW), f"replay {i}"
+        assert torch.equal(vals.view(torch.uint8), want_vals.view(torch.uint8)), f"replay {i}"
