@@ -58,7 +58,11 @@ def lib():
         _lib.oracle_select_2of4_approx.restype = None
         _lib.oracle_enumerate_approx_draw.argtypes = [vp, i32, vp]
         _lib.oracle_enumerate_approx_draw.restype = None
-        for f in (_lib.oracle_prune_1of2, _lib.oracle_prune_2of4, _lib.oracle_prune_2of4_approx):
+        _lib.oracle_select_1of4.argtypes = [vp, C.c_float, vp, vp]
+        _lib.oracle_select_1of4.restype = None
+        _lib.oracle_enumerate_1of4.argtypes = [vp, vp, vp, vp]
+        _lib.oracle_enumerate_1of4.restype = None
+        for f in (_lib.oracle_prune_1of2, _lib.oracle_prune_2of4, _lib.oracle_prune_2of4_approx, _lib.oracle_prune_1of4):
             f.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64]
             f.restype = i32
         _lib.oracle_nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp]
@@ -201,6 +205,28 @@ def prune_2of4(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: boo
 
 def prune_2of4_approx(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
     return _prune(lib().oracle_prune_2of4_approx, g, seed, stream_id, want_dense)
+
+
+def select_1of4(x, eps: float) -> Tuple[int, float]:
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    k = C.c_int(0)
+    v = C.c_float(0)
+    lib().oracle_select_1of4(_p(xa), C.c_float(eps), C.byref(k), C.byref(v))
+    return int(k.value), float(v.value)
+
+
+def enumerate_1of4(x):
+    """Over all 2^24 uniforms: (counts[4], mean[4], second_moment[4]) of the kept position / emitted value."""
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    counts = np.zeros(4, dtype=np.uint64)
+    mean = np.zeros(4, dtype=np.float64)
+    second = np.zeros(4, dtype=np.float64)
+    lib().oracle_enumerate_1of4(_p(xa), _p(counts), _p(mean), _p(second))
+    return counts, mean, second
+
+
+def prune_1of4(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
+    return _prune(lib().oracle_prune_1of4, g, seed, stream_id, want_dense)
 
 
 def nm_compress(dense: np.ndarray, n: int, m: int):

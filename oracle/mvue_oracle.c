@@ -14,6 +14,8 @@
  *   - approx-MVUE 2:4 ............... Sec. 4.4: two draws without replacement, each proportional
  *                                      to magnitude; kept value a_i/p_i with the inclusion
  *                                      probability p_i of that section.
+ *   - MVUE 1:4 ...................... appendix ("Additional sparsity results"): eq. (6) on a block of
+ *                                      four, stored in the 2:4 container.
  *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T.
  *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
  *                                      fixes Philox4x32-10 (Salmon et al., SC'11) as a pure
@@ -370,6 +372,72 @@ int oracle_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
                     for (int k = 0; k < 4; ++k) store_elem(dense, dt, (t0 + k) * ldd + o, 0.0f);
                     store_elem(dense, dt, (t0 + pos[0]) * ldd + o, st0);
                     store_elem(dense, dt, (t0 + pos[1]) * ldd + o, st1);
+                }
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* MVUE 1:4 (appendix, additional sparsity results: "similar to MVUE 1:2, but  */
+/* for a bigger block").  The argument of Sec. 4.1 with one survivor out of    */
+/* four: unbiasedness forces the kept value a_i/p_i, and sum_i a_i^2/p_i under */
+/* sum_i p_i = 1 is smallest at p_i = |a_i|/sum|a|, which makes every kept     */
+/* value sign(a_i) * sum|a| (eq. (6) with four terms).                         */
+/* Var = sum_i |a_i| (sum|a| - |a_i|).                                          */
+/* Threshold walk in position order as for the draws above (a zero is never    */
+/* kept while a non-zero exists; an all-zero quad keeps position 0).           */
+/* Stored in the 2:4 group format: the second slot of the quad is a +0 at the  */
+/* lowest other position -- the padding nm_compress would choose.              */
+/* ------------------------------------------------------------------------- */
+void oracle_select_1of4(const float x[4], float eps, int *kept, float *value)
+{
+    float m[4];
+    for (int k = 0; k < 4; ++k) m[k] = fabsf(x[k]);
+    int k = approx_draw(m, eps, -1);
+    float total = ((m[0] + m[1]) + m[2]) + m[3];
+    *kept = k;
+    *value = copysignf(total, x[k]);
+}
+
+void oracle_enumerate_1of4(const float x[4], uint64_t counts[4], double mean[4], double second[4])
+{
+    for (int k = 0; k < 4; ++k) { counts[k] = 0; mean[k] = 0.0; second[k] = 0.0; }
+    for (uint32_t u = 0; u < (1u << 24); ++u) {
+        int k; float v;
+        oracle_select_1of4(x, u24_to_eps(u), &k, &v);
+        counts[k] += 1; mean[k] += (double)v; second[k] += (double)v * (double)v;
+    }
+    for (int k = 0; k < 4; ++k) { mean[k] /= 16777216.0; second[k] /= 16777216.0; }
+}
+
+int oracle_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                      uint64_t seed, uint32_t stream_id,
+                      void *vals, uint16_t *meta, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {
+                int64_t q = G * 4 + i, t0 = q * 4;
+                float x[4];
+                for (int k = 0; k < 4; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                uint32_t u = oracle_block_u24(seed, stream_id, (uint64_t)q * (uint64_t)O + (uint64_t)o);
+                int k; float v;
+                oracle_select_1of4(x, u24_to_eps(u), &k, &v);
+                int pad = (k == 0) ? 1 : 0;
+                int pos0 = k < pad ? k : pad, pos1 = k < pad ? pad : k;
+                float st0 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 0, pos0 == k ? v : 0.0f);
+                float st1 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 1, pos1 == k ? v : 0.0f);
+                md |= (uint16_t)((pos0 | (pos1 << 2)) << (4 * i));
+                if (dense) {
+                    for (int kk = 0; kk < 4; ++kk) store_elem(dense, dt, (t0 + kk) * ldd + o, 0.0f);
+                    store_elem(dense, dt, (t0 + pos0) * ldd + o, st0);
+                    store_elem(dense, dt, (t0 + pos1) * ldd + o, st1);
                 }
             }
             meta[G * O + o] = md;
