@@ -91,6 +91,18 @@ int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
 
 /*
+ * MVUE 1:4 prune + compress (appendix, "Additional sparsity results": MVUE 1:2 on a block of four).
+ * Of every quad one element survives: position k with probability |a_k|/sum|a|, emitting
+ * sign(a_k)*sum|a| (eq. (6) with four terms; variance sum_k |a_k|(sum|a| - |a_k|)).  One uniform per quad,
+ * the stream of mvue_prune_2of4 mode 0.  The output uses the 2:4 group format above -- gfx950's sparse
+ * matrix instructions are 4:2 only -- with a +0 in the quad's second slot (at the lowest other position,
+ * as nm_compress would pad), so nm_update_gemm consumes it unchanged.  Arguments as mvue_prune_1of2.
+ */
+int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                    uint64_t seed, uint32_t stream_id,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
+
+/*
  * Deterministic compression of a dense [T x O] tensor that already is n:m sparse along T
  * ((n,m) = (1,2) or (2,4)) into the group format: the "x2 footprint" of the abstract.
  * Kept positions are the non-zero positions, padded with the lowest-index zero positions of

@@ -36,6 +36,8 @@ def load():
     vp, i64, u64, u32, i32, f32, sz = C.c_void_p, C.c_int64, C.c_uint64, C.c_uint32, C.c_int, C.c_float, C.c_size_t
     lib.mvue_prune_1of2.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
     lib.mvue_prune_2of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, i64, vp]
+    lib.mvue_prune_1of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
+    lib.mvue_prune_1of4.restype = i32
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
@@ -97,7 +99,10 @@ def _prune(which: str, g, seed, stream_id, mode, vals, meta, dense_out, want_den
     if dense_out is None and want_dense:
         dense_out = torch.empty((T, O), dtype=g.dtype, device=g.device)
     ldd = _rowmajor(dense_out, "dense_out") if dense_out is not None else 0
-    if which == "1of2":
+    if which == "1of4":
+        rc = lib.mvue_prune_1of4(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, _ptr(vals), _ptr(meta),
+                                 _ptr(dense_out), ldd, _stream(g))
+    elif which == "1of2":
         rc = lib.mvue_prune_1of2(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, _ptr(vals), _ptr(meta),
                                  _ptr(dense_out), ldd, _stream(g))
     else:
@@ -111,6 +116,12 @@ def mvue_prune_1of2(g: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=Non
                     want_dense: bool = False):
     """MVUE 1:2 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
     return _prune("1of2", g, seed, stream_id, 0, vals, meta, dense_out, want_dense)
+
+
+def mvue_prune_1of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=None, meta=None, dense_out=None,
+                    want_dense: bool = False):
+    """MVUE 1:4 prune of g[T x O] along T, stored in the 2:4 group format.  Returns (vals, meta, dense_out or None)."""
+    return _prune("1of4", g, seed, stream_id, 0, vals, meta, dense_out, want_dense)
 
 
 def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, vals=None, meta=None,

@@ -102,6 +102,16 @@ int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                                          (hipStream_t)hip_stream));
 }
 
+int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream)
+{
+    const char *fn = "mvue_prune_1of4";
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
+    return launched(fn, nm::launch_prune(dtype, 4, 2, g, T, O, ldg, seed, stream_id, vals, meta, dense_out, ldd,
+                                         (hipStream_t)hip_stream));
+}
+
 int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, int n, int m, void *vals,
                 uint16_t *meta, int32_t *bad_blocks, void *hip_stream)
 {

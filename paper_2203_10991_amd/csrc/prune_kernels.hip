@@ -245,9 +245,33 @@ __device__ __forceinline__ void select_2of4_approx(float x0, float x1, float x2,
 }
 
 // ------------------------------------------------------------------------------------
+// MVUE 1:4 on one quad (appendix, additional sparsity results: MVUE 1:2 on a block of four): position k is kept
+// with probability a_k/sum and emits sign(x_k) * sum.  Same threshold walk and fallback as the draws above.
+// Stored in the 2:4 container: the quad's other slot is a +0 at the lowest other position.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void select_1of4(float x0, float x1, float x2, float x3, uint32_t word,
+                                            float &out0, float &out1, uint32_t &nib)
+{
+    const float m0 = fabsf(x0), m1 = fabsf(x1), m2 = fabsf(x2), m3 = fabsf(x3);
+    const float c1 = m0 + m1, c2 = c1 + m2, total = c2 + m3;
+    const float t = word_to_eps(word) * total;
+    const bool w0 = t < m0, w1 = t < c1, w2 = t < c2;
+    const bool n1 = m1 > 0.0f, n2 = m2 > 0.0f, n3 = m3 > 0.0f;
+    const bool i0 = w0 | (!w1 & !w2 & !n3 & !n2 & !n1);
+    const bool i1 = !w0 & (w1 | (!w2 & !n3 & !n2 & n1));
+    const bool i2 = !w0 & !w1 & (w2 | (!n3 & n2));
+    const float xi = i0 ? x0 : i1 ? x1 : i2 ? x2 : x3;
+    const float v = copysignf(total, xi);
+    const uint32_t k = i0 ? 0u : i1 ? 1u : i2 ? 2u : 3u;
+    out0 = i0 ? v : 0.0f;
+    out1 = i0 ? 0.0f : v;
+    nib = i0 ? 4u : (k << 2);                  // (0, 1) when position 0 is kept, else (0, k)
+}
+
+// ------------------------------------------------------------------------------------
 // the fused kernel
 // ------------------------------------------------------------------------------------
-// M = 2: MVUE 1:2; M = 4: MVUE 2:4, EST = 0 the optimal estimator, 1 approx-MVUE; DENSE: also write theta(g)
+// M = 2: MVUE 1:2; M = 4: EST = 0 the optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4; DENSE: also write theta(g)
 template <int DT, int M, int EST, bool DENSE>
 __device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
@@ -318,6 +342,9 @@ __device__ __forceinline__ void prune_compress_body(
                     select_2of4_approx(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
                                        Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c),
                                        words[2 * c], words[2 * c + 1], v0, v1, nib);
+                else if constexpr (EST == 2)
+                    select_1of4(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
+                                Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c), words[c], v0, v1, nib);
                 else
                     select_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
                                     Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3),
@@ -625,13 +652,14 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     return hipGetLastError();
 }
 
-// m = 2: MVUE 1:2;  m = 4: MVUE 2:4 with est = 0 (optimal) or 1 (approx-MVUE)
+// m = 2: MVUE 1:2;  m = 4: est = 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4
 hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
 {
 #define NM_PRUNE(DT, M, EST) launch_prune_t<DT, M, EST>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
-    if (dt == NM_DT_F32) return m == 2 ? NM_PRUNE(NM_DT_F32, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_F32, 4, 1) : NM_PRUNE(NM_DT_F32, 4, 0);
-    return m == 2 ? NM_PRUNE(NM_DT_BF16, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_BF16, 4, 1) : NM_PRUNE(NM_DT_BF16, 4, 0);
+    if (dt == NM_DT_F32)
+        return m == 2 ? NM_PRUNE(NM_DT_F32, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_F32, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_F32, 4, 2) : NM_PRUNE(NM_DT_F32, 4, 0);
+    return m == 2 ? NM_PRUNE(NM_DT_BF16, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_BF16, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_BF16, 4, 2) : NM_PRUNE(NM_DT_BF16, 4, 0);
 #undef NM_PRUNE
 }
 

@@ -95,3 +95,17 @@ def test_zero_operand_and_empty_reduction(nm):
                                         ("c4_vit_fc2_1of2", 1600, 256, 512), ("c5_decoder_mlp_2of4", 2048, 512, 512)])
 def test_config_recipes_reduced(nm, oracle, name, T, O, I):
     run_case(nm, oracle, synth.scaled(synth.WORKLOADS[name], T=T, O=O, I=I, name=name + "_reduced"))
+
+
+def test_update_gemm_consumes_the_1of4_container(nm, oracle):
+    """MVUE 1:4 output is stored in the 2:4 group format: the same GEMM multiplies it"""
+    w = synth.Workload("g14", 16 * 21, 200, 136, "bf16", "2:4", 0.0, 2.0, 0.3)
+    g, h = synth.make_g(w, 3), synth.make_h(w, 3)
+    ov, om, _ = oracle.prune_1of4(g, 3, 0)
+    want, wabs = oracle.update_gemm(ov, om, h)
+    v, m, _ = nm.mvue_prune_1of4(to_dev(g), seed=3, stream_id=0)
+    dW = nm.nm_update_gemm(v, m, to_dev(h))
+    torch.cuda.synchronize()
+    assert np.array_equal(to_host(m), om) and np.array_equal(to_host(v), ov)
+    rel = float((np.abs(dW.cpu().numpy().astype(np.float64) - want) / np.maximum(wabs, 1e-300)).max())
+    assert rel <= TOL["bf16"]

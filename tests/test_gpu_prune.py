@@ -22,6 +22,8 @@ def _prune_pair(nm, oracle, nmode):
     """(device entry point, oracle function) of an estimator: "1:2", "2:4" (optimal) or "2:4a" (approx-MVUE)."""
     if nmode == "1:2":
         return nm.mvue_prune_1of2, oracle.prune_1of2
+    if nmode == "1:4":
+        return nm.mvue_prune_1of4, oracle.prune_1of4
     if nmode == "2:4a":
         return (lambda g, *a, **kw: nm.mvue_prune_2of4(g, *a, mode=1, **kw)), oracle.prune_2of4_approx
     return nm.mvue_prune_2of4, oracle.prune_2of4
@@ -47,7 +49,7 @@ SHAPES = [(16, 8), (16 * 37, 8 * 29), (16 * 5, 8 * 64 + 8), (16 * 64, 1024)]
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a", "1:4"])
 @pytest.mark.parametrize("shape", SHAPES)
 def test_fused_prune_bit_exact(nm, oracle, dtype, nmode, shape):
     T, O = shape
@@ -74,7 +76,7 @@ def test_fused_prune_bit_exact(nm, oracle, dtype, nmode, shape):
         assert not torch.equal(m4, m)
 
 
-@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a", "1:4"])
 def test_row_stride_and_preallocated_outputs(nm, oracle, nmode):
     T, O = 16 * 9, 8 * 13
     w = synth.Workload("t", T, O, 8, "bf16", nmode, 0.0, 2.0, 0.2)
@@ -104,7 +106,7 @@ def _edge_tensor(dtype):
 
 
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
-@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a", "1:4"])
 def test_edge_values_bit_exact(nm, oracle, dtype, nmode):
     for seed in range(4):
         check_case(nm, oracle, _edge_tensor(dtype), nmode, seed, 0)
