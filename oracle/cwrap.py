@@ -88,6 +88,8 @@ def lib():
         _lib.oracle_nm_decompress_q8.restype = None
         _lib.oracle_update_gemm_q8.argtypes = [vp, vp, vp, i64, i64, i64, i64, dbl, vp, i64, vp, vp]
         _lib.oracle_update_gemm_q8.restype = None
+        _lib.oracle_update_gemm_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, i64, i32, vp, vp]
+        _lib.oracle_update_gemm_shifted.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -334,3 +336,20 @@ def update_gemm_q8(vals8: np.ndarray, meta32: np.ndarray, h8: np.ndarray, alpha:
     lib().oracle_update_gemm_q8(_p(np.ascontiguousarray(vals8)), _p(np.ascontiguousarray(meta32)), _p(h8), I, T, O, I,
                                 float(alpha), oip, n, _p(out), _p(out_abs))
     return out, out_abs
+
+
+def update_gemm_shifted(vals: np.ndarray, meta: np.ndarray, x_full: np.ndarray, margin: int, shifts):
+    """x_full: [margin + T + margin, C] (row 0 of the grid at index `margin`); shifts: one row shift per kernel tap.
+    Returns (dW, absdW) as float64 [O, len(shifts)*C]."""
+    G, O = meta.shape
+    T = G * 16
+    x_full = np.ascontiguousarray(x_full)
+    assert x_full.shape[0] == T + 2 * margin and max(abs(int(v)) for v in shifts) <= margin
+    Cc = x_full.shape[1]
+    sh = np.ascontiguousarray(shifts, dtype=np.int64)
+    dW = np.zeros((O, len(sh) * Cc), dtype=np.float64)
+    absdW = np.zeros_like(dW)
+    xp = C.c_void_p(x_full.ctypes.data + margin * Cc * x_full.itemsize)
+    lib().oracle_update_gemm_shifted(_p(np.ascontiguousarray(vals)), _p(np.ascontiguousarray(meta)), xp, Cc, Cc, _p(sh), len(sh),
+                                     T, O, _dt(x_full), _p(dW), _p(absdW))
+    return dW, absdW

@@ -778,6 +778,43 @@ void oracle_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const u
     }
 }
 
+/* ------------------------------------------------------------------------- */
+/* Update GEMM of a convolution without the im2col matrix (App. B.1, part 1:   */
+/* activation A [B x C_I x H x W], gradients G [B x C_O x H x W], update Delta  */
+/* [C_I x C_O x k x k]).  Stated on rows: x is a [rows x C] matrix (the zero-   */
+/* padded channels-last activation grid, flattened), gt the decompressed       */
+/* gradient on the same grid, and kernel tap j pairs output row t with input    */
+/* row t + shift[j]:                                                            */
+/*     dW[o][j*C + c] = sum_t gt[t][o] * x[(t + shift[j])*ldx + c]   (binary64)  */
+/* x points at row 0; rows -margin .. T+margin-1 must exist, margin >= |shift|. */
+/* ------------------------------------------------------------------------- */
+void oracle_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t C,
+                                const int64_t *shift, int n_shift, int64_t T, int64_t O, int dt,
+                                double *dW, double *absdW)
+{
+    const int64_t I = (int64_t)n_shift * C;
+    #pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t o = 0; o < O; ++o) {
+        double *row = dW + o * I, *arow = absdW ? absdW + o * I : NULL;
+        for (int64_t i = 0; i < I; ++i) { row[i] = 0.0; if (arow) arow[i] = 0.0; }
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t G = t / 16; int qi = (int)((t % 16) / 4), k = (int)(t % 4);
+            uint16_t md = meta[G * O + o];
+            double gv = 0.0;
+            for (int s = 0; s < 2; ++s)
+                if (((md >> (4 * qi + 2 * s)) & 3) == k)
+                    gv = (double)load_elem(vals, dt, (G * O + o) * 8 + 2 * qi + s);
+            if (gv == 0.0) continue;
+            for (int j = 0; j < n_shift; ++j)
+                for (int64_t c = 0; c < C; ++c) {
+                    double hv = (double)load_elem(x, dt, (t + shift[j]) * ldx + c);
+                    row[j * C + c] += gv * hv;
+                    if (arow) arow[j * C + c] += fabs(gv) * fabs(hv);
+                }
+        }
+    }
+}
+
 /* threads the parallel loops will use (for the benchmark's report) */
 #ifdef _OPENMP
 #include <omp.h>

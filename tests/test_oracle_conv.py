@@ -1,0 +1,77 @@
+"""Pins for the oracle's im2col-free update GEMM of a convolution (App. B.1, part 1: A [B x C_I x H x W],
+G [B x C_O x H x W], update [C_I x C_O x k x k]).
+
+Pinned by the oracle's plain update GEMM on a materialised im2col matrix built with numpy slicing, and by torch's
+own convolution weight gradient (a library routine) on the same pruned gradient."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2203_10991_amd import synth
+
+
+def padded_grid(a_nhwc: np.ndarray, pad: int) -> np.ndarray:
+    """[N, H, W, C] -> zero-padded [N*(H+2p)*(W+2p), C]"""
+    n, h, w, c = a_nhwc.shape
+    out = np.zeros((n, h + 2 * pad, w + 2 * pad, c), dtype=a_nhwc.dtype)
+    out[:, pad:pad + h, pad:pad + w] = a_nhwc
+    return out.reshape(-1, c)
+
+
+def tap_shifts(k: int, wp: int):
+    r = k // 2
+    return [(ky - r) * wp + (kx - r) for ky in range(k) for kx in range(k)]
+
+
+def with_margin(rows: np.ndarray, T: int, margin: int) -> np.ndarray:
+    full = np.zeros((T + 2 * margin, rows.shape[1]), dtype=rows.dtype)
+    full[margin:margin + rows.shape[0]] = rows
+    return full
+
+
+@pytest.mark.parametrize("k", [1, 3])
+def test_shifted_gemm_equals_plain_gemm_on_materialised_im2col(oracle, k):
+    rng = np.random.default_rng(k)
+    N, H, W, C, O = 2, 5, 6, 8, 16
+    pad = k // 2
+    Hp, Wp = H + 2 * pad, W + 2 * pad
+    rows = N * Hp * Wp
+    T = (rows + 15) // 16 * 16
+    x = padded_grid(rng.standard_normal((N, H, W, C)).astype(np.float32), pad)
+    g = np.zeros((T, O), dtype=np.float32)
+    g[:rows] = padded_grid((rng.standard_normal((N, H, W, O)) * np.exp(rng.standard_normal((N, H, W, O)))).astype(np.float32), pad)
+    vals, meta, _ = oracle.prune_2of4(g, seed=3, stream_id=0)
+    shifts = tap_shifts(k, Wp)
+    margin = max(abs(s) for s in shifts) if k > 1 else 0
+    xf = with_margin(x, T, margin)
+    dW, absdW = oracle.update_gemm_shifted(vals, meta, xf, margin, shifts)
+    h = np.concatenate([xf[margin + s: margin + s + T] for s in shifts], axis=1)        # the im2col matrix, materialised
+    want, wabs = oracle.update_gemm(vals, meta, np.ascontiguousarray(h))
+    assert dW.shape == (O, k * k * C)
+    assert np.allclose(dW, want, rtol=1e-13, atol=1e-13 * np.abs(want).max())
+    assert np.allclose(absdW, wabs, rtol=1e-13)
+
+
+def test_shifted_gemm_is_the_convolution_weight_gradient(oracle):
+    """against torch.nn.grad.conv2d_weight in float64 on the same pruned gradient (3x3, stride 1, zero padding 1)"""
+    rng = np.random.default_rng(7)
+    N, H, W, C, O, k = 3, 6, 7, 8, 8, 3
+    Hp, Wp = H + 2, W + 2
+    rows = N * Hp * Wp
+    T = (rows + 15) // 16 * 16
+    a = rng.standard_normal((N, H, W, C)).astype(np.float32)
+    gy = (rng.standard_normal((N, H, W, O)) * np.exp(rng.standard_normal((N, H, W, O)))).astype(np.float32)
+    g = np.zeros((T, O), dtype=np.float32)
+    g[:rows] = padded_grid(gy, 1)
+    vals, meta, dense = oracle.prune_2of4(g, seed=11, stream_id=2, want_dense=True)
+    shifts = tap_shifts(k, Wp)
+    margin = Wp + 1
+    dW, _ = oracle.update_gemm_shifted(vals, meta, with_margin(padded_grid(a, 1), T, margin), margin, shifts)
+    # the pruned gradient back on the unpadded grid, in torch's layout
+    theta = dense[:rows].reshape(N, Hp, Wp, O)
+    assert not theta[:, 0].any() and not theta[:, -1].any() and not theta[:, :, 0].any() and not theta[:, :, -1].any()
+    theta_nchw = torch.from_numpy(theta[:, 1:-1, 1:-1].transpose(0, 3, 1, 2).astype(np.float64).copy())
+    a_nchw = torch.from_numpy(a.transpose(0, 3, 1, 2).astype(np.float64).copy())
+    ref = torch.nn.grad.conv2d_weight(a_nchw, (O, C, k, k), theta_nchw, stride=1, padding=1).numpy()      # [O, C, ky, kx]
+    got = dW.reshape(O, k, k, C).transpose(0, 3, 1, 2)                                                      # [O, C, ky, kx]
+    assert np.allclose(got, ref, rtol=1e-12, atol=1e-12 * np.abs(ref).max())
