@@ -129,6 +129,24 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
                    float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, int dtype, float beta,
                    void *workspace, size_t workspace_bytes, void *hip_stream);
 
+/*
+ * Update GEMM of a convolution without the im2col matrix (App. B.1, part 1: activation A [B x C_I x H x W],
+ * gradients G [B x C_O x H x W], update [C_I x C_O x k x k]).  The dense operand is given as n_shift row-shifted
+ * views of ONE matrix x [rows x cb] (row stride ldx):
+ *     h[t][j*cb + c] = x[(t + row_shift[j])*ldx + c],   j = 0..n_shift-1,   I = n_shift*cb,
+ *     dW[O x I] = beta*dW + decompress(vals, meta)^T h.
+ * For a k x k, stride-1 convolution: x is the zero-padded channels-last activation grid [N][H+2p][W+2p][C]
+ * flattened to rows (cb = C), the gradient is pruned on the same padded grid (zeros on the border), and tap
+ * (ky, kx) has row_shift = (ky-p)*(W+2p) + (kx-p); dW comes out as [O][ky][kx][C].
+ *   x            device pointer to row 0.  Rows -m .. T+m-1, m = max|row_shift|, must be readable and hold finite
+ *                values (zeros): border rows of the gradient, whose kept values are zero, are multiplied with them.
+ *   row_shift    HOST array of n_shift (1..32) row shifts.
+ * NM_BF16 only (NM_ERR_UNSUPPORTED otherwise); cb % 8 == 0; workspace as nm_update_gemm for (T, O, I).
+ */
+int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
+                           const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                           int dtype, float beta, void *workspace, size_t workspace_bytes, void *hip_stream);
+
 /* Bytes of workspace nm_update_gemm needs for this problem (0 when it runs in one pass). */
 size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
 

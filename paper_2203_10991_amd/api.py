@@ -41,6 +41,8 @@ def load():
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
+    lib.nm_update_gemm_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, i32, f32, vp, sz, vp]
+    lib.nm_update_gemm_shifted.restype = i32
     lib.mvue_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp]
     lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
@@ -214,4 +216,36 @@ def nm_update_gemm_q8(vals8: torch.Tensor, meta32: torch.Tensor, h8: torch.Tenso
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     _check(lib.nm_update_gemm_q8(_ptr(vals8), _ptr(meta32), _ptr(h8), ldh, _ptr(dW), lddw, T, O, I, float(alpha),
                                  float(beta), _ptr(workspace), wbytes, _stream(h8)))
+    return dW
+
+
+def nm_update_gemm_shifted(vals: torch.Tensor, meta: torch.Tensor, x_full: torch.Tensor, margin: int, shifts,
+                           dW: Optional[torch.Tensor] = None, beta: float = 0.0,
+                           workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """dW[O x n*C] = beta*dW + decompress(vals, meta)^T [x shifted by shifts[0] | x shifted by shifts[1] | ...].
+
+    x_full is [margin + T + margin, C] (bf16): row 0 of the grid sits at index ``margin``; the margin rows hold zeros.
+    """
+    lib = load()
+    G, O, _ = vals.shape
+    T = G * 16
+    if x_full.dim() != 2 or x_full.shape[0] != T + 2 * margin:
+        raise ValueError(f"x_full must have {T + 2 * margin} rows (T = {T}, margin = {margin})")
+    if max(abs(int(v)) for v in shifts) > margin:
+        raise ValueError("a row shift exceeds the margin")
+    ldx = _rowmajor(x_full, "x_full")
+    Cb = x_full.shape[1]
+    n = len(shifts)
+    I = n * Cb
+    if dW is None:
+        dW = torch.empty((O, I), dtype=torch.float32, device=x_full.device)
+    lddw = _rowmajor(dW, "dW")
+    need = nm_update_gemm_workspace(T, O, I, x_full.dtype)
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x_full.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    sh = (C.c_int64 * n)(*[int(v) for v in shifts])
+    xp = x_full.data_ptr() + margin * ldx * x_full.element_size()
+    _check(lib.nm_update_gemm_shifted(_ptr(vals), _ptr(meta), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O,
+                                      _dtype_code(x_full), float(beta), _ptr(workspace), wbytes, _stream(x_full)))
     return dW

@@ -60,6 +60,35 @@ def _update_gemm(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Ten
     return api.nm_update_gemm(vals, meta, h2)
 
 
+def padded_rows(t_nchw: torch.Tensor, pad: int):
+    """[N, C, H, W] -> the zero-padded channels-last grid flattened to rows: ([N*(H+2p)*(W+2p), C], W+2p)"""
+    g = F.pad(t_nchw.permute(0, 2, 3, 1), (0, 0, pad, pad, pad, pad))
+    return g.reshape(-1, g.shape[-1]), g.shape[2]
+
+
+def _conv_update_shifted(gy: torch.Tensor, x: torch.Tensor, k: int, cfg: NMConfig) -> torch.Tensor:
+    """Weight gradient [O, C, k, k] (binary32) of a k x k, stride-1, 'same' convolution without an im2col matrix:
+    gradient and activation live on the zero-padded channels-last grid, kernel tap (ky, kx) is a row shift of the
+    activation rows (nm_update_gemm_shifted).  The N:M blocks run along the rows of that padded grid."""
+    if not (gy.is_cuda and x.is_cuda):
+        raise RuntimeError("the N:M update phase runs on the GPU only (no CPU fallback)")
+    pad = k // 2
+    xr, wp = padded_rows(x, pad)
+    gr, _ = padded_rows(gy, pad)
+    rows, C = xr.shape
+    O = gr.shape[1]
+    T = (rows + 15) // 16 * 16
+    margin = pad * wp + pad
+    x_full = torch.zeros((T + 2 * margin, C), dtype=x.dtype, device=x.device)
+    x_full[margin:margin + rows] = xr
+    g2 = torch.zeros((T, O), dtype=gy.dtype, device=gy.device)
+    g2[:rows] = gr
+    vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
+    shifts = [(ky - pad) * wp + (kx - pad) for ky in range(k) for kx in range(k)]
+    dW = api.nm_update_gemm_shifted(vals, meta, x_full, margin, shifts)              # [O, (ky, kx, c)]
+    return dW.reshape(O, k, k, C).permute(0, 3, 1, 2).contiguous()
+
+
 class _NMLinearFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, bias, cfg):
@@ -106,19 +135,27 @@ class _NMConv2dFn(torch.autograd.Function):
             dx = torch.nn.grad.conv2d_input(x.shape, weight, gy, stride, padding, dilation)
         dW = None
         if ctx.needs_input_grad[1]:
-            # im2col (App. B: the convolution's update GEMM reduces over batch x output positions):
-            # h [N*L, C*kh*kw], g [N*L, O]
             O, C, kh, kw = weight.shape
-            cols = F.unfold(x, (kh, kw), dilation=dilation, padding=padding, stride=stride)      # [N, C*kh*kw, L]
-            h2 = cols.transpose(1, 2).reshape(-1, C * kh * kw)
-            g2 = gy.reshape(gy.shape[0], O, -1).transpose(1, 2).reshape(-1, O)
-            dW = _update_gemm(g2, h2, ctx.cfg).reshape(O, C, kh, kw).to(weight.dtype)
+            same = (kh == kw and kh % 2 == 1 and tuple(stride) == (1, 1) and tuple(dilation) == (1, 1)
+                    and tuple(padding) == (kh // 2, kw // 2))
+            if same and x.dtype == torch.bfloat16 and ctx.cfg.nm == "2:4" and C % 8 == 0 and O % 8 == 0 and kh * kw <= 32:
+                dW = _conv_update_shifted(gy, x, kh, ctx.cfg).to(weight.dtype)
+            else:
+                # im2col (App. B: the convolution's update GEMM reduces over batch x output positions):
+                # h [N*L, C*kh*kw], g [N*L, O]
+                cols = F.unfold(x, (kh, kw), dilation=dilation, padding=padding, stride=stride)      # [N, C*kh*kw, L]
+                h2 = cols.transpose(1, 2).reshape(-1, C * kh * kw)
+                g2 = gy.reshape(gy.shape[0], O, -1).transpose(1, 2).reshape(-1, O)
+                dW = _update_gemm(g2, h2, ctx.cfg).reshape(O, C, kh, kw).to(weight.dtype)
         db = gy.sum((0, 2, 3)) if ctx.has_bias and ctx.needs_input_grad[2] else None
         return dx, dW, db, None, None, None, None
 
 
 class NMConv2d(torch.nn.Conv2d):
-    """torch.nn.Conv2d (groups = 1, zero padding) whose weight gradient comes from the pruned neural gradient."""
+    """torch.nn.Conv2d (groups = 1, zero padding) whose weight gradient comes from the pruned neural gradient.
+
+    bf16, odd square kernel, stride 1, 'same' padding, MVUE 2:4: no im2col matrix is built (row-shifted views of the
+    padded activation grid); anything else goes through an explicit im2col matrix."""
 
     def __init__(self, *args, cfg: Optional[NMConfig] = None, **kw):
         super().__init__(*args, **kw)

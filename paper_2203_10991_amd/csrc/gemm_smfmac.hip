@@ -45,12 +45,17 @@ constexpr int NS = 6;             // LDS stages: one being consumed, one landed,
 //   then                      vals fragments, [2 token groups][TM slots] x 16 bytes, one ds_read_b128 per fragment
 //   then                      meta words, [2 token groups][TM rows] x 2 bytes
 //                             (both as one share per wave, padded to a whole 64-lane load)
-template <int WM, int WN, int AB, int BB>
+// SHIFTED: the dense operand is a set of row-shifted views of one [rows x cb] matrix (a convolution's im2col matrix
+// that is never materialised): column block j of h is x read sh.rows[j] rows further down, h[t][j*cb + c] =
+// x[(t + rows[j])*ldh + c].  Only a lane's constant source offset and the descriptor's extent change.
+struct ShiftArg { int cb, n, margin; int rows[32]; };
+template <int WM, int WN, int AB, int BB, bool SHIFTED = false>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride,       // out + z*slab_stride
     int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate,
-    int64_t o_first, int64_t o_end)          // the launch computes rows [o_first, o_end) of dW; tiles_m counts its M-tiles
+    int64_t o_first, int64_t o_end,          // the launch computes rows [o_first, o_end) of dW; tiles_m counts its M-tiles
+    ShiftArg sh)                             // (SHIFTED only)
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
     constexpr int CPR = TN / 8;                           // 16-byte chunks per h row in LDS
@@ -147,6 +152,10 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     for (int ph = 0; ph < PHASES; ++ph) {
         const int row_mod4 = (ph * ROWS_PER_DMA + dma_row) & 3;
         const int64_t col = min(n0 + 8 * (dma_pos ^ (4 * row_mod4)), I - 8);
+        if constexpr (SHIFTED) {
+            const int j = (int)(col / sh.cb);             // (a 16-byte chunk never straddles two views: cb % 8 == 0)
+            b_src[ph] = (uint32_t)(((int64_t)(wave * B_ROWS + dma_row + sh.rows[j] + sh.margin) * ldh + (col - (int64_t)j * sh.cb)) * 2);
+        } else
         b_src[ph] = (uint32_t)(((int64_t)(wave * B_ROWS + dma_row) * ldh + col) * 2);
     }
     const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh * 2);
@@ -157,6 +166,9 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     __amdgpu_buffer_rsrc_t rh, rv, rm;
     auto rebase = [&](int it) {
         const int64_t Gs = g_begin + (int64_t)it * 2, t0 = Gs * 16;
+        if constexpr (SHIFTED)       // rows -margin .. T+margin-1 of x are readable; offsets are relative to row t0 - margin
+            rh = rsrc((const char *)h + (t0 - sh.margin) * ldh * 2, ((T - t0 - 1 + 2 * (int64_t)sh.margin) * ldh + sh.cb) * 2);
+        else
         rh = rsrc((const char *)h + t0 * ldh * 2, ((T - t0 - 1) * ldh + I) * 2);
         rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
         rm = rsrc((const char *)meta + Gs * O * 2, (n_groups - Gs) * O * 2);
@@ -618,7 +630,7 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
 struct Plan { int shape; int tm, tn; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
 static const bool g_allow_tall = getenv("NM_GEMM_NO_TALL") == nullptr;      // (switch for A/B measurements)
 
-static Plan make_plan(int64_t T, int64_t O, int64_t I)
+static Plan make_plan(int64_t T, int64_t O, int64_t I, bool allow_tall = true)
 {
     Plan p;
     const int64_t groups = T / 16;
@@ -635,7 +647,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I)
         const int64_t tn = (I + 255) / 256;
         double best = 1e300;
         int64_t best_mt = 0;
-        for (int64_t mt = 0; g_allow_tall && mt <= (O + 383) / 384; ++mt) {
+        for (int64_t mt = 0; g_allow_tall && allow_tall && mt <= (O + 383) / 384; ++mt) {
             const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
             const double cost = 1.34 * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
             if (cost < best - 1e-9) { best = cost; best_mt = mt; }
@@ -705,11 +717,45 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, (const uint16_t *)vals,   \
                        meta, (const uint16_t *)h, ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I,         \
-                       p.tiles_m, p.tiles_n, acc_flag, p.tall_rows, O)
+                       p.tiles_m, p.tiles_n, acc_flag, p.tall_rows, O, ShiftArg{})
         if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
         else NM_LAUNCH(2, 2, 2, 2);
 #undef NM_LAUNCH
     }
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, 1.0f, st);
+    return e;
+}
+
+// dW = beta*dW + decompress(vals, meta)^T [x shifted by rows[0] | x shifted by rows[1] | ...]  (I = n * cb columns).
+// Same plan as the plain GEMM of that size, on the kernels that take the shift table (no 384-row tiles).
+hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
+                                             const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,
+                                             float beta, void *workspace, hipStream_t st)
+{
+    const int64_t I = cb * n;
+    if (O == 0 || I == 0) return hipSuccess;
+    const Plan p = make_plan(T, O, I, false);
+    ShiftArg sh{};
+    sh.cb = (int)cb; sh.n = n; sh.margin = 0;
+    for (int j = 0; j < n; ++j) {
+        sh.rows[j] = (int)rows[j];
+        sh.margin = std::max(sh.margin, (int)(rows[j] < 0 ? -rows[j] : rows[j]));
+    }
+    const int accumulate = beta != 0.f;
+    float *out = dW;
+    int64_t ldo = lddw, slab_stride = 0;
+    int acc_flag = accumulate;
+    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
+#define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
+    hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB, true>), grid, dim3(WM * WN * 64), 0, st,              \
+                       (const uint16_t *)vals, meta, (const uint16_t *)x, ldx, out, ldo, slab_stride, T / 16,            \
+                       p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, (int64_t)0, O, sh)
+    if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
+    else NM_LAUNCH(2, 2, 2, 2);
+#undef NM_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
     if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, 1.0f, st);

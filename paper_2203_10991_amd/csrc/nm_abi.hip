@@ -169,6 +169,51 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
                                                workspace_bytes, (hipStream_t)hip_stream));
 }
 
+int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
+                           const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                           int dtype, float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const char *fn = "nm_update_gemm_shifted";
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (dtype != NM_BF16) return fail(NM_ERR_UNSUPPORTED, "%s: only NM_BF16 operands (the sparse-MFMA kernels) take shifted views", fn);
+    if (T < 0 || O < 0 || cb < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (n_shift < 1 || n_shift > 32) return fail(NM_ERR_SHAPE, "%s: n_shift=%d must be 1..32", fn, n_shift);
+    if (!row_shift) return fail(NM_ERR_NULL, "%s: row_shift is NULL", fn);
+    if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16", fn, (long long)T);
+    if (O % 8 || cb % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld and cb=%lld must be multiples of 8", fn, (long long)O, (long long)cb);
+    if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
+    const int64_t I = cb * n_shift;
+    if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
+    int64_t margin = 0;
+    for (int j = 0; j < n_shift; ++j) margin = row_shift[j] < -margin ? -row_shift[j] : row_shift[j] > margin ? row_shift[j] : margin;
+    if (margin > (1 << 20)) return fail(NM_ERR_UNSUPPORTED, "%s: row shifts must not exceed 2^20 rows", fn);
+    if (!dW) return fail(NM_ERR_NULL, "%s: dW is NULL", fn);
+    if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
+    if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
+    Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    if (T > 0) {
+        if (!vals || !meta || !x) return fail(NM_ERR_NULL, "%s: vals, meta and x must not be NULL", fn);
+        if (ldx < cb) return fail(NM_ERR_SHAPE, "%s: ldx=%lld is smaller than cb=%lld", fn, (long long)ldx, (long long)cb);
+        if (ldx > (1 << 21) || O > (1 << 21) || (margin + 512) * ldx > (1ll << 30))
+            return fail(NM_ERR_UNSUPPORTED, "%s: O, ldx and (shift x ldx) exceed what 32-bit byte offsets reach", fn);
+        if (!aligned16(vals) || !aligned16(meta) || !aligned16(x) || (ldx * 2) % 16)
+            return fail(NM_ERR_ALIGN, "%s: vals, meta, x need 16-byte aligned bases (and x a 16-byte row stride)", fn);
+        Range rv = range_of(vals, T / 2 * O * 2, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
+        Range rx = range_of((const char *)x - margin * ldx * 2, ((T + 2 * margin - 1) * ldx + cb) * 2, "x");
+        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rx)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+    }
+    const size_t need = nm::update_gemm_workspace(dtype, T, O, I);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
+        Range rw = range_of(workspace, (int64_t)need, "workspace");
+        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+    }
+    return launched(fn, nm::launch_update_gemm_smfmac_shifted(vals, meta, x, ldx, cb, row_shift, n_shift, dW, lddw, T, O, beta,
+                                                              workspace, (hipStream_t)hip_stream));
+}
+
 int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
                        int mode, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
 {

@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "nm_update_gemm_shifted",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
         assert hasattr(lib, n), n
@@ -158,3 +158,27 @@ def test_autograd_layers_have_no_cpu_fallback():
         conv(torch.randn(2, 8, 4, 4)).sum().backward()
     with pytest.raises(ValueError):
         NMConv2d(8, 8, 3, groups=2)
+
+
+def test_shifted_gemm_argument_errors(lib):
+    i64 = C.c_int64
+    lib.nm_update_gemm_shifted.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, i64, i64, C.c_void_p, C.c_int, C.c_void_p, i64, i64, i64,
+                                           C.c_int, C.c_float, C.c_void_p, C.c_size_t, C.c_void_p]
+    sh = (i64 * 9)(-11, -10, -9, -1, 0, 1, 9, 10, 11)
+
+    def call(vals=P, meta=P + 0x100000, x=P + 0x200000, ldx=16, cb=16, shifts=sh, n=9, dW=P + 0x400000, lddw=144, T=64, O=64, dt=1,
+             beta=0.0):
+        return lib.nm_update_gemm_shifted(vals, meta, x, ldx, cb, shifts, n, dW, lddw, T, O, dt, beta, None, 0, None)
+
+    assert call(dt=0) == NM_ERR_UNSUPPORTED and call(dt=5) == NM_ERR_DTYPE
+    assert call(n=0) == NM_ERR_SHAPE and call(n=33) == NM_ERR_SHAPE
+    assert call(shifts=None) == NM_ERR_NULL
+    assert call(cb=12) == NM_ERR_SHAPE and call(T=40) == NM_ERR_SHAPE and call(O=12) == NM_ERR_SHAPE
+    assert call(ldx=8) == NM_ERR_SHAPE and call(lddw=128) == NM_ERR_SHAPE
+    assert call(x=None) == NM_ERR_NULL and call(dW=None) == NM_ERR_NULL
+    assert call(ldx=20) == NM_ERR_ALIGN
+    assert call(beta=2.0) == NM_ERR_UNSUPPORTED
+    assert call(dW=P + 0x200000 - 64) == NM_ERR_ALIAS          # dW inside the margin rows of x
+    big = (i64 * 1)(1 << 21)
+    assert call(shifts=big, n=1, lddw=16) == NM_ERR_UNSUPPORTED
+    assert call(O=0) == NM_OK

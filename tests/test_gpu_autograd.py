@@ -83,3 +83,37 @@ def test_conv2d_update_phase_matches_oracle(oracle):
     one = (conv.weight.grad - dense).norm() / dense.norm()
     print(f"conv dW: one draw off by {one:.3f}, mean of {n} draws off by {err:.3f}", flush=True)
     assert err < 3.0 * one / np.sqrt(n) + 1e-3
+
+
+def test_conv2d_bf16_update_phase_without_im2col(oracle):
+    """bf16, 3x3, stride 1, padding 1: the layer prunes on the zero-padded channels-last grid and multiplies row-shifted
+    views of the activations; the oracle does the same from its own definitions"""
+    from paper_2203_10991_amd.autograd import NMConfig, NMConv2d, padded_rows
+    torch.manual_seed(2)
+    N, C, H, W, O, k = 3, 16, 9, 10, 24, 3
+    conv = NMConv2d(C, O, k, padding=1, bias=False, cfg=NMConfig(nm="2:4", seed=4, stream_id=3), device=DEV, dtype=torch.bfloat16)
+    x = torch.relu(torch.randn(N, C, H, W, device=DEV)).to(torch.bfloat16).requires_grad_(True)
+    gy = (torch.randn(N, O, H, W, device=DEV) * torch.exp(2 * torch.randn(N, O, H, W, device=DEV))).to(torch.bfloat16)
+    conv(x).backward(gy)
+    xr, wp = padded_rows(x.detach(), 1)
+    gr, _ = padded_rows(gy, 1)
+    rows = xr.shape[0]
+    T = (rows + 15) // 16 * 16
+    margin = wp + 1
+    x_full = np.zeros((T + 2 * margin, C), dtype=np.uint16)
+    x_full[margin:margin + rows] = bits(xr)
+    g2 = np.zeros((T, O), dtype=np.uint16)
+    g2[:rows] = bits(gr)
+    ov, om, _ = oracle.prune_2of4(g2, 4, 3)
+    shifts = [(ky - 1) * wp + (kx - 1) for ky in range(k) for kx in range(k)]
+    want, wabs = oracle.update_gemm_shifted(ov, om, x_full, margin, shifts)
+    want = want.reshape(O, k, k, C).transpose(0, 3, 1, 2)
+    wabs = wabs.reshape(O, k, k, C).transpose(0, 3, 1, 2)
+    got = conv.weight.grad.double().cpu().numpy()
+    assert (np.abs(got - want) <= 1e-2 * np.maximum(wabs, np.abs(want)) + 1e-30).all()
+    # dx is torch's dense backward
+    ref = torch.nn.Conv2d(C, O, k, padding=1, bias=False, device=DEV, dtype=torch.bfloat16)
+    ref.load_state_dict(conv.state_dict())
+    x2 = x.detach().clone().requires_grad_(True)
+    ref(x2).backward(gy)
+    assert torch.allclose(x.grad.float(), x2.grad.float(), rtol=2e-2, atol=2e-2 * float(x2.grad.float().abs().max()))
