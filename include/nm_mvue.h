@@ -141,11 +141,13 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
  *   x            device pointer to row 0.  Rows -m .. T+m-1, m = max|row_shift|, must be readable and hold finite
  *                values (zeros): border rows of the gradient, whose kept values are zero, are multiplied with them.
  *   row_shift    HOST array of n_shift (1..32) row shifts.
- * NM_BF16 only (NM_ERR_UNSUPPORTED otherwise); cb % 8 == 0; workspace as nm_update_gemm for (T, O, I).
+ * NM_BF16 only (NM_ERR_UNSUPPORTED otherwise); cb % 8 == 0; workspace of at least
+ * nm_update_gemm_shifted_workspace(T, O, cb, n_shift) bytes (its own plan: not the size nm_update_gemm asks for).
  */
 int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
                            const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
                            int dtype, float beta, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t nm_update_gemm_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift);
 
 /* Bytes of workspace nm_update_gemm needs for this problem (0 when it runs in one pass). */
 size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);

@@ -43,6 +43,8 @@ def load():
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
     lib.nm_update_gemm_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_shifted.restype = i32
+    lib.nm_update_gemm_shifted_workspace.argtypes = [i64, i64, i64, i32]
+    lib.nm_update_gemm_shifted_workspace.restype = sz
     lib.mvue_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp]
     lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
@@ -240,7 +242,7 @@ def nm_update_gemm_shifted(vals: torch.Tensor, meta: torch.Tensor, x_full: torch
     if dW is None:
         dW = torch.empty((O, I), dtype=torch.float32, device=x_full.device)
     lddw = _rowmajor(dW, "dW")
-    need = nm_update_gemm_workspace(T, O, I, x_full.dtype)
+    need = int(lib.nm_update_gemm_shifted_workspace(T, O, Cb, n))
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=x_full.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()

@@ -630,13 +630,16 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
 struct Plan { int shape; int tm, tn; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
 static const bool g_allow_tall = getenv("NM_GEMM_NO_TALL") == nullptr;      // (switch for A/B measurements)
 
-static Plan make_plan(int64_t T, int64_t O, int64_t I, bool allow_tall = true)
+// shifted: the dense operand is row-shifted views of one matrix (it stays in the caches: few-row problems are then
+// bound by the tile's own work, and the 64 x 256 tile wastes none of it; streamed from HBM, as a materialised
+// operand is, the 128 x 128 tile measures faster)
+static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
 {
     Plan p;
     const int64_t groups = T / 16;
     const int CUS = 256;
     p.tall_rows = 0; p.tall_tiles_m = 0;
-    // shape 0: 256x256 (8 waves), shape 1: 128x128 (4 waves, two workgroups fit a CU)
+    // shape 0: 256x256 (8 waves), shape 1: 128x128 (4 waves, two workgroups fit a CU), shape 2: 64x256 (4 waves, one per CU)
     bool small = false;
     if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
         p.shape = 0; p.tm = 256; p.tn = 256;
@@ -647,7 +650,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool allow_tall = true)
         const int64_t tn = (I + 255) / 256;
         double best = 1e300;
         int64_t best_mt = 0;
-        for (int64_t mt = 0; g_allow_tall && allow_tall && mt <= (O + 383) / 384; ++mt) {
+        for (int64_t mt = 0; g_allow_tall && !shifted && mt <= (O + 383) / 384; ++mt) {
             const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
             const double cost = 1.34 * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
             if (cost < best - 1e-9) { best = cost; best_mt = mt; }
@@ -655,6 +658,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool allow_tall = true)
         p.tall_tiles_m = (int)best_mt;
         p.tall_rows = std::min<int64_t>(O, best_mt * 384);
     }
+    else if (shifted && O <= 64 && I > 128) { p.shape = 2; p.tm = 64; p.tn = 256; small = true; }
     else { p.shape = 1; p.tm = 128; p.tn = 128; small = true; }
     p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + p.tn - 1) / p.tn);
@@ -679,7 +683,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool allow_tall = true)
         const int64_t s_one = std::min(max_s, std::max<int64_t>(1, CUS / tiles));
         const int64_t s_two = std::min(max_s, std::max<int64_t>(1, 2 * CUS / tiles));
         slabs = (int)s_one;
-        if (tiles * s_two >= 3 * CUS / 2 && cost(s_two) < cost(s_one)) slabs = (int)s_two;
+        if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two) < cost(s_one)) slabs = (int)s_two;
     }
     const int64_t gps = whole_trips((groups + slabs - 1) / slabs);           // whole trips of six LDS stages
     p.groups_per_slab = gps;
@@ -691,6 +695,13 @@ size_t update_gemm_smfmac_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
     const Plan p = make_plan(T, O, I);
+    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+}
+
+size_t update_gemm_smfmac_shifted_workspace(int64_t T, int64_t O, int64_t I)
+{
+    if (T <= 0 || O <= 0 || I <= 0) return 0;
+    const Plan p = make_plan(T, O, I, true);
     return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
 }
 
@@ -736,7 +747,7 @@ hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *m
 {
     const int64_t I = cb * n;
     if (O == 0 || I == 0) return hipSuccess;
-    const Plan p = make_plan(T, O, I, false);
+    const Plan p = make_plan(T, O, I, true);
     ShiftArg sh{};
     sh.cb = (int)cb; sh.n = n; sh.margin = 0;
     for (int j = 0; j < n; ++j) {
@@ -754,7 +765,8 @@ hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *m
                        (const uint16_t *)vals, meta, (const uint16_t *)x, ldx, out, ldo, slab_stride, T / 16,            \
                        p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, (int64_t)0, O, sh)
     if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
-    else NM_LAUNCH(2, 2, 2, 2);
+    else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
+    else NM_LAUNCH(1, 4, 2, 2);
 #undef NM_LAUNCH
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;

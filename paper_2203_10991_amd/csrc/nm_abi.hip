@@ -169,6 +169,12 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
                                                workspace_bytes, (hipStream_t)hip_stream));
 }
 
+size_t nm_update_gemm_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift)
+{
+    if (T < 0 || O < 0 || cb < 0 || n_shift < 1 || n_shift > 32) return 0;
+    return nm::update_gemm_smfmac_shifted_workspace(T, O, cb * n_shift);
+}
+
 int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
                            const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
                            int dtype, float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
@@ -202,7 +208,7 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
         Range rx = range_of((const char *)x - margin * ldx * 2, ((T + 2 * margin - 1) * ldx + cb) * 2, "x");
         if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rx)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    const size_t need = nm::update_gemm_workspace(dtype, T, O, I);
+    const size_t need = nm::update_gemm_smfmac_shifted_workspace(T, O, I);
     if (need) {
         if (!workspace || workspace_bytes < need)
             return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);

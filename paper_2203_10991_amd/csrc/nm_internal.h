@@ -26,6 +26,7 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
                                      int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
                                      hipStream_t st);
 size_t update_gemm_smfmac_workspace(int64_t T, int64_t O, int64_t I);
+size_t update_gemm_smfmac_shifted_workspace(int64_t T, int64_t O, int64_t I);
 // the same product with h given as n row-shifted views of one [rows x cb] matrix x (bf16): h[t][j*cb + c] = x[(t + rows[j])*ldx + c]
 hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *meta, const void *x, int64_t ldx, int64_t cb,
                                              const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,

@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "nm_update_gemm_shifted",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
         assert hasattr(lib, n), n
@@ -182,3 +182,9 @@ def test_shifted_gemm_argument_errors(lib):
     big = (i64 * 1)(1 << 21)
     assert call(shifts=big, n=1, lddw=16) == NM_ERR_UNSUPPORTED
     assert call(O=0) == NM_OK
+    # few rows, many tokens: split along T with its own plan, and the call insists on that much workspace
+    lib.nm_update_gemm_shifted_workspace.argtypes = [i64, i64, i64, C.c_int]
+    lib.nm_update_gemm_shifted_workspace.restype = C.c_size_t
+    need = lib.nm_update_gemm_shifted_workspace(65536, 64, 64, 9)
+    assert need > 0 and need % (64 * 576 * 4) == 0
+    assert call(T=65536, cb=64, ldx=64, lddw=576, meta=P + 0x10000000, x=P + 0x20000000, dW=P + 0x40000000) == NM_ERR_WORKSPACE
