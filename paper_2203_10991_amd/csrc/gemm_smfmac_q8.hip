@@ -92,17 +92,17 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     __shared__ __attribute__((aligned(1024))) char S[NS8 * STAGE_BYTES];
     auto buf = [&](auto u_c) -> char * { return S + (decltype(u_c)::value % NS8) * STAGE_BYTES; };
 
-    int tm, tn;
-    tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+    int tm, tn, slab;
+    tile_and_slab_of_workgroup(tiles_m, tiles_n, tm, tn, slab);
 
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
     const int64_t m0 = (int64_t)tm * TM;
     const int64_t n0 = (int64_t)tn * TN;
-    const int64_t g_begin = (int64_t)blockIdx.z * groups_per_slab;
+    const int64_t g_begin = (int64_t)slab * groups_per_slab;
     const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
-    out += (int64_t)blockIdx.z * slab_stride;
+    out += (int64_t)slab * slab_stride;
 
     f32x16 acc[AB][BB];
 #pragma unroll

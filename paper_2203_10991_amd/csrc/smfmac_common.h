@@ -183,4 +183,26 @@ __device__ __forceinline__ void tile_of_workgroup(int bid_, int tiles_m, int til
     }
 }
 
+// Split-K launches (gridDim.z slabs of the reduction axis, gridDim.x tiles): workgroups are dealt round-robin to the
+// XCDs in launch order (x fastest, then z).  With a tile count that is a multiple of 8 a tile stays on one XCD for
+// every slab and the single-pass tile map (compact tile sets per XCD) is still right.  Otherwise the tiles of one
+// slab would land on all eight XCDs, each pulling every slab's rows of both operands through the fabric; the
+// (slab, tile) pairs are then re-dealt: XCD x takes a contiguous run of the slab-major list, i.e. whole slabs (a
+// slab straddles at most two XCDs), whose tiles share the slab's rows through that XCD's L2.
+__device__ __forceinline__ void tile_and_slab_of_workgroup(int tiles_m, int tiles_n, int &tm, int &tn, int &slab)
+{
+    if (gridDim.z > 1 && gridDim.x % 8 != 0) {
+        const unsigned n = gridDim.x * gridDim.z;
+        const unsigned L = blockIdx.z * gridDim.x + blockIdx.x, xcd = L % 8, idx = L / 8;
+        const unsigned first = xcd * (n / 8) + min(xcd, n % 8);        // workgroups that XCDs 0 .. xcd-1 hold
+        const unsigned g = first + idx;
+        slab = (int)(g / gridDim.x);
+        const int t = (int)(g % gridDim.x);
+        tm = t / tiles_n; tn = t % tiles_n;
+    } else {
+        slab = (int)blockIdx.z;
+        tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+    }
+}
+
 }  // namespace nm
