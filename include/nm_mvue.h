@@ -104,7 +104,7 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
 
 /*
  * Deterministic compression of a dense [T x O] tensor that already is n:m sparse along T
- * ((n,m) = (1,2) or (2,4)) into the group format: the "x2 footprint" of the abstract.
+ * ((n,m) = (1,2) or (2,4)) into the group format: the halved footprint the abstract counts.
  * Kept positions are the non-zero positions, padded with the lowest-index zero positions of
  * the block; values are copied bit for bit.  With the dense_out of a prune call as input it
  * reproduces that call's vals and meta exactly.

@@ -23,7 +23,7 @@
  *   - 8-bit neural gradients ........ Sec. 5 (sparsity in all phases + 8-bit quantisation: FP8 neural
  *                                      gradients) with the unbiasedness requirement of Sec. 3:
  *                                      stochastic rounding of the kept values to e5m2.
- *   - compressed format ............. not in the paper ("footprint ... up to x2", abstract);
+ *   - compressed format ............. not in the paper (the abstract only counts a halved footprint);
  *                                      defined below.
  *
  * Decision arithmetic is IEEE binary32 with one rounding per written operation
@@ -381,9 +381,9 @@ int oracle_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
 }
 
 /* ------------------------------------------------------------------------- */
-/* MVUE 1:4 (appendix, additional sparsity results: "similar to MVUE 1:2, but  */
-/* for a bigger block").  The argument of Sec. 4.1 with one survivor out of    */
-/* four: unbiasedness forces the kept value a_i/p_i, and sum_i a_i^2/p_i under */
+/* MVUE 1:4 (appendix, additional sparsity results: the 1:2 estimator on a    */
+/* larger block).  The argument of Sec. 4.1 with one survivor out of four:     */
+/* unbiasedness forces the kept value a_i/p_i, and sum_i a_i^2/p_i under       */
 /* sum_i p_i = 1 is smallest at p_i = |a_i|/sum|a|, which makes every kept     */
 /* value sign(a_i) * sum|a| (eq. (6) with four terms).                         */
 /* Var = sum_i |a_i| (sum|a| - |a_i|).                                          */
