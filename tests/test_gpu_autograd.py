@@ -117,3 +117,48 @@ def test_conv2d_bf16_update_phase_without_im2col(oracle):
     x2 = x.detach().clone().requires_grad_(True)
     ref(x2).backward(gy)
     assert torch.allclose(x.grad.float(), x2.grad.float(), rtol=2e-2, atol=2e-2 * float(x2.grad.float().abs().max()))
+
+
+def test_training_with_pruned_update_phase_tracks_dense_training():
+    """A small teacher-student regression trained with SGD: with MVUE 2:4 in the update phase of every layer the loss
+    follows the dense run (the weight gradients differ from the dense ones at every step but are unbiased, Sec. 3)."""
+    from paper_2203_10991_amd.autograd import NMConfig, NMLinear
+    torch.manual_seed(0)
+    D, Hd, O, B = 64, 128, 32, 512
+    teacher = torch.nn.Sequential(torch.nn.Linear(D, Hd), torch.nn.Tanh(), torch.nn.Linear(Hd, O)).to(DEV)
+    for p in teacher.parameters():
+        p.requires_grad_(False)
+
+    def make(student_cls):
+        torch.manual_seed(1)
+        cfgs = [NMConfig(nm="2:4", seed=100, stream_id=i) for i in range(2)]
+        if student_cls is NMLinear:
+            net = torch.nn.Sequential(NMLinear(D, Hd, cfg=cfgs[0]), torch.nn.Tanh(), NMLinear(Hd, O, cfg=cfgs[1])).to(DEV)
+        else:
+            net = torch.nn.Sequential(torch.nn.Linear(D, Hd), torch.nn.Tanh(), torch.nn.Linear(Hd, O)).to(DEV)
+        return net, cfgs
+
+    def train(net, cfgs, steps=300):
+        opt = torch.optim.SGD(net.parameters(), lr=0.05)
+        gen = torch.Generator(device=DEV).manual_seed(7)
+        losses = []
+        for _ in range(steps):
+            x = torch.randn(B, D, device=DEV, generator=gen)
+            loss = torch.nn.functional.mse_loss(net(x), teacher(x))
+            opt.zero_grad()
+            loss.backward()
+            opt.step()
+            for c in cfgs:
+                c.advance()
+            losses.append(float(loss))
+        return losses
+
+    dense_net, _ = make(torch.nn.Linear)
+    nm_net, cfgs = make(NMLinear)
+    assert all(torch.equal(a, b) for a, b in zip(dense_net.state_dict().values(), nm_net.state_dict().values()))
+    ld = train(dense_net, [])
+    ln = train(nm_net, cfgs)
+    first, last_d, last_n = sum(ld[:10]) / 10, sum(ld[-20:]) / 20, sum(ln[-20:]) / 20
+    print(f"loss: start {first:.4f}, dense end {last_d:.4f}, MVUE 2:4 end {last_n:.4f}", flush=True)
+    assert last_d < 0.5 * first                       # the task is learnable
+    assert last_n < 0.5 * first and last_n < 1.5 * last_d + 1e-3
