@@ -590,20 +590,31 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
     });
 }
 
-// out[o][i] = (accumulate ? out : 0) + alpha * sum_z part[z][o][i], z ascending
+// out[o][i] = (accumulate ? out : 0) + alpha * sum_z part[z][o][i].  R threads share one float4 of the output
+// (R = 1 for a few slabs, 8 for many): thread r sums the slabs z = r, r+R, ... in ascending order, then the R partial
+// sums are combined in a fixed tree (neighbours at distance 1, 2, 4): the order of the additions depends on the slab
+// count only, never on timing.
+template <int R>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int slabs, int64_t slab_stride,
                                                            float *__restrict__ out, int64_t ldo, int64_t O, int64_t I, int accumulate,
                                                            float alpha)
 {
     const int64_t n4 = O * (I / 4);
-    const int64_t idx = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (idx >= n4) return;
-    const int64_t o = idx / (I / 4), i = (idx % (I / 4)) * 4;
+    const int r = threadIdx.x % R;
+    const int64_t idx = (int64_t)blockIdx.x * (256 / R) + threadIdx.x / R;
+    const bool valid = idx < n4;
+    const int64_t o = valid ? idx / (I / 4) : 0, i = valid ? (idx % (I / 4)) * 4 : 0;
     float4 s = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int z = 0; z < slabs; ++z) {
-        const float4 v = *(const float4 *)(part + (int64_t)z * slab_stride + o * I + i);
-        s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+    if (valid)
+        for (int z = r; z < slabs; z += R) {
+            const float4 v = *(const float4 *)(part + (int64_t)z * slab_stride + o * I + i);
+            s.x += v.x; s.y += v.y; s.z += v.z; s.w += v.w;
+        }
+#pragma unroll
+    for (int d = 1; d < R; d <<= 1) {
+        s.x += __shfl_xor(s.x, d); s.y += __shfl_xor(s.y, d); s.z += __shfl_xor(s.z, d); s.w += __shfl_xor(s.w, d);
     }
+    if (!valid || r != 0) return;
     s.x *= alpha; s.y *= alpha; s.z *= alpha; s.w *= alpha;
     if (accumulate) {
         const float4 d = *(const float4 *)(out + o * ldo + i);
@@ -617,8 +628,12 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
                                 int accumulate, float alpha, hipStream_t st)
 {
     const int64_t n4 = O * (I / 4);
-    hipLaunchKernelGGL(splitk_reduce_kernel, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, slabs, O * I,
-                       dW, lddw, O, I, accumulate, alpha);
+    if (slabs >= 12)
+        hipLaunchKernelGGL(splitk_reduce_kernel<8>, dim3((unsigned)((n4 + 31) / 32)), dim3(256), 0, st, part, slabs, O * I,
+                           dW, lddw, O, I, accumulate, alpha);
+    else
+        hipLaunchKernelGGL(splitk_reduce_kernel<1>, dim3((unsigned)((n4 + 255) / 256)), dim3(256), 0, st, part, slabs, O * I,
+                           dW, lddw, O, I, accumulate, alpha);
     return hipGetLastError();
 }
 
