@@ -16,7 +16,8 @@
  *                                      probability p_i of that section.
  *   - MVUE 1:4 ...................... appendix ("Additional sparsity results"): eq. (6) on a block of
  *                                      four, stored in the 2:4 container.
- *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T.
+ *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T; for a convolution (App. B.1, part 1)
+ *                                      also without the im2col matrix.
  *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
  *                                      fixes Philox4x32-10 (Salmon et al., SC'11) as a pure
  *                                      function of (seed, stream, block index).
@@ -41,7 +42,8 @@
  * Parity pins: every function here is pinned by tests/test_oracle_*.py (published
  * Philox known answers, closed-form probabilities/variances, exhaustive enumeration of
  * all 2^24 thresholds, brute-force minimum variance, library GEMM; the 8-bit path by a library's
- * float8 decoder and nearest cast, exact rational counts over all 2^16 rounding words, library GEMM).
+ * float8 decoder and nearest cast, exact rational counts over all 2^16 rounding words, library GEMM;
+ * the convolution's update GEMM by a library's convolution weight gradient).
  */
 #include <math.h>
 #include <stdint.h>
