@@ -10,6 +10,7 @@ There is no fallback: tensors must live on the GPU and the HIP library must be b
 """
 from __future__ import annotations
 
+import math
 from dataclasses import dataclass
 from typing import Optional
 
@@ -27,6 +28,8 @@ class NMConfig:
     seed: int = 0              # base seed of the run
     stream_id: int = 0         # one per layer: independent random streams
     reuse_every: int = 1       # iterations that share one set of random samples (App. B.1)
+    precision: str = "native"  # "native": the tensors' own dtype; "q8": 2:4 with e5m2 kept values (stochastic rounding)
+                               # and e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows)
     step: int = 0              # iteration counter; advance() once per optimizer step
 
     def current_seed(self) -> int:
@@ -51,6 +54,8 @@ def _update_gemm(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Ten
         g2 = F.pad(g2, (0, 0, 0, pad))
         h2 = F.pad(h2, (0, 0, 0, pad))
     g2, h2 = g2.contiguous(), h2.contiguous()
+    if cfg.precision == "q8":
+        return _update_gemm_q8(g2, h2, cfg)
     if cfg.nm == "1:2":
         vals, meta, _ = api.mvue_prune_1of2(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id)
     elif cfg.nm == "2:4":
@@ -87,6 +92,32 @@ def _conv_update_shifted(gy: torch.Tensor, x: torch.Tensor, k: int, cfg: NMConfi
     shifts = [(ky - pad) * wp + (kx - pad) for ky in range(k) for kx in range(k)]
     dW = api.nm_update_gemm_shifted(vals, meta, x_full, margin, shifts)              # [O, (ky, kx, c)]
     return dW.reshape(O, k, k, C).permute(0, 3, 1, 2).contiguous()
+
+
+def pow2_scale(t: torch.Tensor, top: float) -> float:
+    """largest power of two s with s * max|t| <= top (1.0 for an all-zero tensor); reads the maximum back to the host"""
+    m = float(t.abs().max())
+    return 1.0 if m == 0.0 or not math.isfinite(m) else 2.0 ** math.floor(math.log2(top / m))
+
+
+def _update_gemm_q8(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Tensor:
+    """The 8-bit update phase: per-tensor power-of-two scales from the current maxima (a kept value is at most the
+    sum of its quad's magnitudes, hence the factor 4), activations cast to e4m3 by torch, everything else in the library."""
+    if cfg.nm != "2:4":
+        raise ValueError("the 8-bit update phase exists for 2:4 only")
+    T, O = g2.shape
+    I = h2.shape[1]
+    if I % 16:
+        raise ValueError(f"the 8-bit update GEMM needs a reduction width that is a multiple of 16, got {I}")
+    pad = (-T) % 32
+    if pad:
+        g2 = F.pad(g2, (0, 0, 0, pad))
+        h2 = F.pad(h2, (0, 0, 0, pad))
+    sg = pow2_scale(g2, 57344.0 / 4.0)
+    sh = pow2_scale(h2, 448.0)
+    h8 = (h2.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8)
+    v8, m32 = api.mvue_prune_2of4_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
+    return api.nm_update_gemm_q8(v8, m32, h8, alpha=1.0 / (sg * sh))
 
 
 class _NMLinearFn(torch.autograd.Function):

@@ -162,3 +162,25 @@ def test_training_with_pruned_update_phase_tracks_dense_training():
     print(f"loss: start {first:.4f}, dense end {last_d:.4f}, MVUE 2:4 end {last_n:.4f}", flush=True)
     assert last_d < 0.5 * first                       # the task is learnable
     assert last_n < 0.5 * first and last_n < 1.5 * last_d + 1e-3
+
+
+def test_linear_q8_update_phase_matches_oracle(oracle):
+    """precision="q8": the layer's scales, torch's e4m3 cast of the activations, then the oracle's 8-bit path"""
+    from paper_2203_10991_amd.autograd import NMConfig, NMLinear, pow2_scale
+    torch.manual_seed(3)
+    T, I, O = 160, 48, 40
+    layer = NMLinear(I, O, bias=False, cfg=NMConfig(nm="2:4", seed=6, stream_id=1, precision="q8"), device=DEV, dtype=torch.bfloat16)
+    x = torch.randn(T, I, device=DEV).to(torch.bfloat16).requires_grad_(True)
+    gy = (torch.randn(T, O, device=DEV) * torch.exp(2 * torch.randn(T, O, device=DEV))).to(torch.bfloat16)
+    layer(x).backward(gy)
+    sg, sh = pow2_scale(gy, 57344.0 / 4.0), pow2_scale(x.detach(), 448.0)
+    h8 = (x.detach().float() * sh).to(torch.float8_e4m3fn).view(torch.uint8).cpu().numpy()
+    ov, om = oracle.prune_2of4_q8(bits(gy), 6, 1, 0, sg)
+    want, wabs = oracle.update_gemm_q8(ov, om, h8, alpha=1.0 / (sg * sh))
+    got = layer.weight.grad.double().cpu().numpy()
+    assert (np.abs(got - want) <= 1e-2 * np.maximum(wabs, np.abs(want)) + 1e-30).all()      # (dW is rounded to bf16 by the layer)
+    # and it estimates the dense weight gradient: relative error of one draw well below 1
+    dense = gy.float().t() @ x.detach().float()
+    rel = float((layer.weight.grad.float() - dense).norm() / dense.norm())
+    print(f"q8 update phase: one draw off the dense gradient by {rel:.3f}", flush=True)
+    assert rel < 0.8
