@@ -229,7 +229,8 @@ def main():
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
         "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / gemm_peak,
         "gemm_ms": gemm_ms,
-        "roofline": {"kernel": "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else "update_gemm_smfmac_q8_kernel" if q8 else
+        "roofline": {"kernel": "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
+                               "update_gemm_smfmac_q8_tall_kernel + update_gemm_smfmac_q8_kernel (rows split as in the 16-bit path)" if q8 else
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
                                "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
                      "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,

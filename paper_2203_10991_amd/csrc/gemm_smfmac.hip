@@ -452,15 +452,17 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
         constexpr int BUF = decltype(buf_c)::value % TNS;
         wait_vmcnt<decltype(in_flight_c)::value * LPS>();
         if (it >= first_missing) {
-            // zero kept values make the group's products zero whatever the h rows and index words left in the buffer are
-            // (finite operands of an earlier stage).  Everything the branch needs is made inside it: nothing of it
-            // occupies a register on the common path.
+            // zero kept values make the group's products zero whatever the index words left in the buffer are; the h
+            // rows are cleared too (a buffer no load has reached yet may hold NaN patterns).  Everything the branch
+            // needs is made inside it: nothing of it occupies a register on the common path.
             char *stage = S + BUF * STAGE;
             uint32_t zero, ln;
             asm volatile("v_mov_b32 %0, 0\n\tv_mbcnt_lo_u32_b32 %1, -1, 0\n\tv_mbcnt_hi_u32_b32 %1, -1, %1" : "=v"(zero), "=v"(ln));
             const uint4 z = make_uint4(zero, zero, zero, zero);
             *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + ln) * 16) = z;
             if (ln < 32) *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + 64 + ln) * 16) = z;
+            *(uint4 *)(stage + wave * 4 * (TN * 2) + ln * 16) = z;
+            *(uint4 *)(stage + wave * 4 * (TN * 2) + 1024 + ln * 16) = z;
             asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
         }
         __builtin_amdgcn_s_barrier();

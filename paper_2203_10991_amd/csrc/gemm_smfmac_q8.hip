@@ -38,9 +38,20 @@ constexpr int NS8 = 6;            // LDS stages
 union FragB8 { i32x8 v; u32x2 q[4]; };
 union FragA8 { i32x4 v; u32x4 u4; };
 
+// IN_VGPR: the accumulator block lives in ordinary registers (see acc_zero)
+template <bool IN_VGPR = false>
 __device__ __forceinline__ void smfmac_32x32x64_bf8_fp8(f32x16 &acc, const i32x4 &a, const i32x8 &b, uint32_t idx)
 {
-    asm volatile("v_smfmac_f32_32x32x64_bf8_fp8 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+    if constexpr (IN_VGPR) asm volatile("v_smfmac_f32_32x32x64_bf8_fp8 %0, %1, %2, %3" : "+v"(acc) : "v"(a), "v"(b), "v"(idx));
+    else                   asm volatile("v_smfmac_f32_32x32x64_bf8_fp8 %0, %1, %2, %3" : "+a"(acc) : "v"(a), "v"(b), "v"(idx));
+}
+template <int OFFSET> __device__ __forceinline__ void lds_refill_tr8(u32x2 &r, uint32_t addr)
+{
+    asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
+}
+template <int OFFSET> __device__ __forceinline__ void lds_refill_b64(u32x2 &r, uint32_t addr)
+{
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "+v"(r) : "v"(addr), "n"(OFFSET) : "memory");
 }
 // alpha * (one accumulator element) to global memory: the element is copied out of its accumulation register, scaled
 // and stored inside one statement, so that the compiler never holds whole blocks in ordinary registers
@@ -67,7 +78,8 @@ template <int WM, int WN, int AB, int BB>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     const uint8_t *__restrict__ vals, const uint32_t *__restrict__ meta, const uint8_t *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride,
-    int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate, float alpha)
+    int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate, float alpha,
+    int64_t o_first)                         // the launch computes rows [o_first, O) of dW; tiles_m counts its M-tiles
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
     static_assert(TN == 256, "the h8 swizzle is written for 16 chunks per row");
@@ -98,7 +110,7 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     const int tid = threadIdx.x, lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int wm = wave / WN, wn = wave % WN;
-    const int64_t m0 = (int64_t)tm * TM;
+    const int64_t m0 = o_first + (int64_t)tm * TM;
     const int64_t n0 = (int64_t)tn * TN;
     const int64_t g_begin = (int64_t)slab * groups_per_slab;
     const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
@@ -306,9 +318,255 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
 }
 
 // ------------------------------------------------------------------------------------
+// 384 x 256 tile for large problems (the 8-bit kernels are bound by the path from the L2s to the CUs; a tile that is
+// 1.5 times taller needs 21 % fewer operand bytes per product).  Same construction as the 16-bit 384 x 256 kernel:
+// 8 waves as 2 x 4, wave tile 192 x 64 = 6 x 2 accumulator blocks, four of the six row blocks in accumulation
+// registers and two in ordinary ones, single operand registers refilled in place right after the last MFMA that
+// reads them, five stages of 31 KB, rows of a wave's block interleaved by six (block a holds rows 6m + a) so that a
+// lane's six index words are adjacent.  Differences: a stage is 64 one-byte tokens; the index words are 32-bit
+// (three ds_read_b64 per lane and stage); h8 goes through ds_read_b64_tr_b8 with the swizzle c ^ 2(k%8), under
+// which the wave's second column block (8 chunks further) sits at the first one's address with bit 7 flipped.
+// No split-K: this kernel only serves problems with at least a GPU-wide round of its tiles.
+// ------------------------------------------------------------------------------------
+__global__ __launch_bounds__(512) void update_gemm_smfmac_q8_tall_kernel(
+    const uint8_t *__restrict__ vals, const uint32_t *__restrict__ meta, const uint8_t *__restrict__ h, int64_t ldh,
+    float *__restrict__ out, int64_t ldo, int64_t n_groups, int64_t O, int64_t I, int tiles_m, int tiles_n,
+    int accumulate, float alpha, int64_t o_end)          // rows [0, o_end) of dW
+{
+    constexpr int WN = 4, AB = 6, BB = 2, TM = 384, TN = 256, TNS = 5;
+    constexpr int A_OFF = KT8 * TN, M_OFF = A_OFF + 2 * TM * 16, STAGE = (M_OFF + 2 * TM * 4 + 1023) / 1024 * 1024;
+    constexpr int LPS = 6;                                   // direct loads per wave and stage: 2 h8, 2 vals8, 2 meta32
+    static_assert(TNS * STAGE <= 160 * 1024 && STAGE % 256 == 0, "LDS");
+    __shared__ __attribute__((aligned(1024))) char S[TNS * STAGE];
+
+    int tm, tn;
+    tile_of_workgroup((int)blockIdx.x, tiles_m, tiles_n, tm, tn);
+    const int tid = threadIdx.x, lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wm = wave / WN, wn = wave % WN;
+    const int64_t m0 = (int64_t)tm * TM, n0 = (int64_t)tn * TN;
+
+    f32x16 acc[AB][BB];
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
+        static_for<BB>([&](auto b_c) { acc_zero<(a >= 4)>(acc[a][decltype(b_c)::value]); });
+    });
+
+    const int n_iters = (int)((n_groups + 1) / 2);           // stages of 2 token groups; the last may be ragged
+    const int n_trips = (n_iters + TNS - 1) / TNS;
+
+    auto slot_row = [](int q) {                               // tile row held by slot q of a token group
+        const int blk = q / 192, r = q % 192, a = r / 32, m = r % 32;
+        return blk * 192 + 6 * m + a;
+    };
+    // ---- direct loads.  Wave w brings, of token group w/4 of the stage: 8 rows of h8 (2 loads), vals8 slots and
+    // meta32 rows [96*(w%4), +96) as one 64-lane and one 32-lane load each.  Per-lane byte offsets inside a stage;
+    // the stage is reached through the scalar offset, which the bounds check does not cover: a load for a token
+    // group past the end of the tensor is switched off through the descriptor's size instead.
+    const int wgrp = wave / 4, ws = wave % 4;
+    uint32_t b_src[2], a_src[2], m_src[2];
+    {
+        constexpr int CPR = TN / 16;                         // 16 chunks of 16 bytes per h8 row
+        const int dma_row = lane / CPR, dma_pos = lane % CPR;
+#pragma unroll
+        for (int ph = 0; ph < 2; ++ph) {                     // load ph covers rows 8*wave + 4*ph + dma_row
+            const int row_mod8 = (4 * ph + dma_row) & 7;
+            const int64_t col = min(n0 + 16 * (dma_pos ^ (2 * row_mod8)), I - 16);
+            b_src[ph] = (uint32_t)((int64_t)(wave * 8 + 4 * ph + dma_row) * ldh + col);
+        }
+#pragma unroll
+        for (int d = 0; d < 2; ++d) {
+            const int q = 96 * ws + 64 * d + (d ? (lane & 31) : lane);
+            a_src[d] = (uint32_t)(wgrp * O + min(m0 + slot_row(q), O - 1)) * 16u;
+            m_src[d] = (uint32_t)(wgrp * O + min(m0 + q, O - 1)) * 4u;
+        }
+    }
+    const bool lane_lt32 = lane < 32;
+    const uint32_t h_stage = (uint32_t)(KT8 * ldh), v_stage = (uint32_t)(2 * O * 16), m_stage = (uint32_t)(2 * O * 4);
+    const int first_missing = (int)min((int64_t)0x7fffffff, (n_groups - wgrp + 1) / 2);
+    const char *hp = nullptr, *vp = nullptr, *mp = nullptr;   // the tensors at the first stage of the current trip
+    int trip_first = 0;
+    auto rebase = [&](int it) {
+        const int64_t Gs = (int64_t)it * 2;
+        hp = (const char *)h + Gs * 32 * ldh;
+        vp = (const char *)vals + Gs * O * 16;
+        mp = (const char *)meta + Gs * O * 4;
+        trip_first = it;
+    };
+    auto fetch_one = [&](auto u_c, auto k_c, auto buf_c) {
+        constexpr uint32_t U = decltype(u_c)::value;
+        constexpr int K = decltype(k_c)::value, BUF = decltype(buf_c)::value % TNS;
+        const int size = trip_first + (int)U < first_missing ? 0x7fffffff : 0;        // 0: nothing is loaded
+        char *stage = S + BUF * STAGE;
+        if constexpr (K < 2)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)hp, 0, size, 0x00020000),
+                                                     (lptr_t)(stage + (wave * 8 + 4 * K) * TN), 16, (int)b_src[K],
+                                                     (int)(U * h_stage), 0, 0);
+        else if constexpr (K == 2)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)vp, 0, size, 0x00020000),
+                                                     (lptr_t)(stage + A_OFF + (wgrp * TM + 96 * ws) * 16), 16,
+                                                     (int)a_src[0], (int)(U * v_stage), 0, 0);
+        else if constexpr (K == 3) {
+            if (lane_lt32)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)vp, 0, size, 0x00020000),
+                                                         (lptr_t)(stage + A_OFF + (wgrp * TM + 96 * ws + 64) * 16), 16,
+                                                         (int)a_src[1], (int)(U * v_stage), 0, 0);
+        } else if constexpr (K == 4)
+            __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)mp, 0, size, 0x00020000),
+                                                     (lptr_t)(stage + M_OFF + (wgrp * TM + 96 * ws) * 4), 4, (int)m_src[0],
+                                                     (int)(U * m_stage), 0, 0);
+        else {
+            if (lane_lt32)
+                __builtin_amdgcn_raw_ptr_buffer_load_lds(__builtin_amdgcn_make_buffer_rsrc((void *)mp, 0, size, 0x00020000),
+                                                         (lptr_t)(stage + M_OFF + (wgrp * TM + 96 * ws + 64) * 4), 4,
+                                                         (int)m_src[1], (int)(U * m_stage), 0, 0);
+        }
+    };
+    // "stage `it` has landed"; a wave whose token group lies past the end of the tensor clears the kept values and
+    // the h8 rows it would have brought (its loads were switched off; index words may hold anything)
+    auto stage_ready = [&](auto in_flight_c, int it, auto buf_c) {
+        constexpr int BUF = decltype(buf_c)::value % TNS;
+        wait_vmcnt<decltype(in_flight_c)::value * LPS>();
+        if (it >= first_missing) {
+            char *stage = S + BUF * STAGE;
+            uint32_t zero, ln;
+            asm volatile("v_mov_b32 %0, 0\n\tv_mbcnt_lo_u32_b32 %1, -1, 0\n\tv_mbcnt_hi_u32_b32 %1, -1, %1" : "=v"(zero), "=v"(ln));
+            const uint4 z = make_uint4(zero, zero, zero, zero);
+            *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + ln) * 16) = z;
+            if (ln < 32) *(uint4 *)(stage + A_OFF + (wgrp * TM + 96 * ws + 64 + ln) * 16) = z;
+            *(uint4 *)(stage + wave * 8 * TN + ln * 16) = z;
+            *(uint4 *)(stage + wave * 8 * TN + 1024 + ln * 16) = z;
+            asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+        }
+        __builtin_amdgcn_s_barrier();
+        __builtin_amdgcn_sched_barrier(0);
+    };
+
+    // ---- LDS read addresses of the stage being read; they advance by one stage per slot
+    const int li = lane & 15, grp = (lane >> 4) & 1, kg = lane >> 5, m = lane & 31;
+    const uint32_t lds0 = (uint32_t)(uintptr_t)(lptr_t)S;
+    uint32_t cur_a = lds0 + (uint32_t)(A_OFF + (kg * TM + wm * 192 + m) * 16);                 // + 32*a*16
+    uint32_t cur_m = lds0 + (uint32_t)(M_OFF + (kg * TM + wm * 192 + 6 * m) * 4);              // 6 consecutive words (three reads)
+    // column block b of wave wn is block b*4 + wn of the tile, chunks 8b + 2wn + {0,1}: block 1 = block 0 with bit 7
+    // of the address flipped (every stage starts on a multiple of 256 bytes)
+    uint32_t cur_b = lds0 + (uint32_t)((16 * kg + (li >> 1)) * TN + ((2 * wn + grp) ^ (2 * (li >> 1))) * 16 + (li & 1) * 8);
+    auto advance = [&](int bytes) {
+        asm volatile("v_add_u32 %0, %3, %0\n\tv_add_u32 %1, %3, %1\n\tv_add_u32 %2, %3, %2" : "+v"(cur_a), "+v"(cur_m), "+v"(cur_b) : "s"(bytes));
+    };
+
+    FragA8 af[AB];
+    FragB8 bf[BB];
+    u32x2 ix[3] = {u32x2{0, 0}, u32x2{0, 0}, u32x2{0, 0}};   // index words of blocks (0,1), (2,3), (4,5)
+#pragma unroll
+    for (int a = 0; a < AB; ++a) af[a].u4 = u32x4{0, 0, 0, 0};
+#pragma unroll
+    for (int b = 0; b < BB; ++b)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) bf[b].q[j] = u32x2{0, 0};
+    auto read_a = [&](auto a_c) { constexpr int a = decltype(a_c)::value; lds_refill_b128<32 * a * 16>(af[a].u4, cur_a); };
+    auto read_ix = [&](auto j_c) { constexpr int j = decltype(j_c)::value; lds_refill_b64<8 * j>(ix[j], cur_m); };
+    auto read_b = [&](auto b_c) {
+        constexpr int b = decltype(b_c)::value;
+        uint32_t addr = cur_b;
+        if constexpr (b == 1) asm volatile("v_xor_b32 %0, 0x80, %1" : "=v"(addr) : "v"(cur_b));
+        lds_refill_tr8<0 * TN>(bf[b].q[0], addr);
+        lds_refill_tr8<8 * TN>(bf[b].q[1], addr);
+        lds_refill_tr8<32 * TN>(bf[b].q[2], addr);
+        lds_refill_tr8<40 * TN>(bf[b].q[3], addr);
+    };
+    // LDS reads of one stage, in issue order (the waits below count on it):
+    //   B0 (4 reads) | A0 | A1, ix0 | A2 | A3, ix1 | A4 | A5, ix2, B1 (4)
+    auto mfma = [&](auto a_c, auto b_c) {
+        constexpr int a = decltype(a_c)::value, b = decltype(b_c)::value;
+        smfmac_32x32x64_bf8_fp8<(a >= 4)>(acc[a][b], af[a].v, bf[b].v, ix[a / 2][a & 1]);
+    };
+    auto lgkm_wait = [&](auto n_c) { asm volatile("s_waitcnt lgkmcnt(%0)" : : "n"(decltype(n_c)::value)); };
+    using I0 = std::integral_constant<int, 0>; using I1 = std::integral_constant<int, 1>; using I2 = std::integral_constant<int, 2>;
+    using I3 = std::integral_constant<int, 3>; using I4 = std::integral_constant<int, 4>; using I5 = std::integral_constant<int, 5>;
+    auto consume = [&](auto fu_c, auto fbuf_c) {
+        lgkm_wait(std::integral_constant<int, 10>{}); mfma(I0{}, I0{});
+        fetch_one(fu_c, I0{}, fbuf_c);
+        mfma(I1{}, I0{});
+        lgkm_wait(std::integral_constant<int, 7>{});  mfma(I2{}, I0{});
+        fetch_one(fu_c, I1{}, fbuf_c);
+        mfma(I3{}, I0{});
+        lgkm_wait(std::integral_constant<int, 4>{});  mfma(I4{}, I0{});           // (ix2 is the last read before B1)
+        fetch_one(fu_c, I2{}, fbuf_c);
+        mfma(I5{}, I0{});
+        read_b(I0{});
+        asm volatile("s_waitcnt lgkmcnt(4)");
+        mfma(I0{}, I1{}); read_a(I0{});
+        fetch_one(fu_c, I3{}, fbuf_c);
+        mfma(I1{}, I1{}); read_a(I1{}); read_ix(I0{});
+        mfma(I2{}, I1{}); read_a(I2{});
+        fetch_one(fu_c, I4{}, fbuf_c);
+        mfma(I3{}, I1{}); read_a(I3{}); read_ix(I1{});
+        mfma(I4{}, I1{}); read_a(I4{});
+        fetch_one(fu_c, I5{}, fbuf_c);
+        mfma(I5{}, I1{}); read_a(I5{}); read_ix(I2{}); read_b(I1{});
+    };
+    auto read_all = [&]() {
+        read_b(I0{}); read_a(I0{}); read_a(I1{}); read_ix(I0{}); read_a(I2{}); read_a(I3{}); read_ix(I1{}); read_a(I4{});
+        read_a(I5{}); read_ix(I2{}); read_b(I1{});
+    };
+
+    // Five LDS stages.  Slot j: stage j's operands are in (or on their way into) registers, read during slot j-1;
+    // stage j+1 has landed (the barrier that opens the slot) and is read during the slot; the loads of stages j+2 and
+    // j+3 are in flight, those of stage j+4 are issued into the buffer stage j-1 occupied.  Stages past the end of
+    // the tensor hold zeros, so the stage count is padded to a multiple of five.
+    if (n_trips > 0) {
+        rebase(0);
+        static_for<TNS - 1>([&](auto u_c) { static_for<LPS>([&](auto k_c) { fetch_one(u_c, k_c, u_c); }); });
+        stage_ready(std::integral_constant<int, TNS - 2>{}, 0, I0{});
+        read_all();
+        advance(STAGE);
+    }
+    for (int tr = 0; tr < n_trips; ++tr) {
+        const int it = TNS * tr;
+        rebase(it);
+        static_for<TNS>([&](auto u_c) {
+            constexpr int u = decltype(u_c)::value;
+            stage_ready(std::integral_constant<int, TNS - 3>{}, it + u + 1, std::integral_constant<int, u + 1>{});
+            consume(std::integral_constant<int, u + TNS - 1>{}, std::integral_constant<int, u + TNS - 1>{});
+            advance(u == TNS - 2 ? -(TNS - 1) * STAGE : STAGE);
+        });
+    }
+
+    __builtin_amdgcn_sched_barrier(0);
+    asm volatile("s_waitcnt lgkmcnt(0)\n\ts_nop 15\n\ts_nop 15\n\ts_nop 15" ::: "memory");
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
+#pragma unroll
+        for (int b = 0; b < BB; ++b) acc_settled<(a >= 4)>(acc[a][b]);
+    });
+    __builtin_amdgcn_sched_barrier(0);
+    static_for<AB>([&](auto a_c) {
+        constexpr int a = decltype(a_c)::value;
+#pragma unroll
+        for (int b = 0; b < BB; ++b) {
+            const int64_t col = n0 + (b * 4 + wn) * 32 + (lane & 31);
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int mr = 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);               // row inside the accumulator block
+                const int64_t row = m0 + wm * 192 + 6 * mr + a;
+                if (row < o_end && col < I) {
+                    float *p = out + row * ldo + col;
+                    if (accumulate) *p = *p + acc[a][b][r] * alpha;
+                    else if constexpr (a >= 4) *p = acc[a][b][r] * alpha;
+                    else store_acc_scaled(p, acc[a][b][r], alpha);
+                }
+            }
+            __builtin_amdgcn_sched_barrier(0);       // one block at a time
+        }
+    });
+}
+
+// ------------------------------------------------------------------------------------
 // host side: tile shape and split-K plan (pure function of the problem size)
 // ------------------------------------------------------------------------------------
-struct PlanQ8 { int shape; int tm; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; };
+// tall_rows: rows [0, tall_rows) of dW are computed by the 384 x 256 kernel (tall_tiles_m tile rows), the rest by the
+// kernel of `shape`
+struct PlanQ8 { int shape; int tm; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
 
 static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
 {
@@ -316,16 +574,33 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
     const int64_t groups = T / 32;
     const int CUS = 256;
     // shape 0: 256x256 (8 waves), shape 1: 128x256, shape 2: 64x256 (4 waves)
+    p.tall_rows = 0; p.tall_tiles_m = 0;
     if (O <= 64) { p.shape = 2; p.tm = 64; }
-    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) { p.shape = 0; p.tm = 256; }
+    else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
+        p.shape = 0; p.tm = 256;
+        // rows split between the 384 x 256 and the 256 x 256 kernel as in the 16-bit path: fewer operand bytes per
+        // product on the taller tile, but a GPU-wide round of it takes TALL_ROUND times as long and a partly
+        // filled last round costs a full one; the split minimises the summed cost of whole rounds
+        constexpr double TALL_ROUND = 1.36;       // measured: 412 us against 302 us per round
+        const int64_t tn = (I + 255) / 256;
+        double best = 1e300;
+        int64_t best_mt = 0;
+        for (int64_t mt = 0; mt <= (O + 383) / 384; ++mt) {
+            const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
+            const double cost = TALL_ROUND * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
+            if (cost < best - 1e-9) { best = cost; best_mt = mt; }
+        }
+        p.tall_tiles_m = (int)best_mt;
+        p.tall_rows = std::min<int64_t>(O, best_mt * 384);
+    }
     else { p.shape = 1; p.tm = 128; }
-    p.tiles_m = (int)((O + p.tm - 1) / p.tm);
+    p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + 255) / 256);
     const int64_t tiles = (int64_t)p.tiles_m * p.tiles_n;
     // few tiles: the reduction axis is cut into slabs until every CU has one workgroup (these kernels fit one per CU;
     // more slabs than that only lengthen the second pass over the partial sums)
     int slabs = 1;
-    if (tiles < CUS && groups >= 24) {
+    if (p.tall_rows == 0 && tiles < CUS && groups >= 24) {
         slabs = (int)(CUS / tiles);
         const int64_t max_slabs = groups / 12;                         // at least 384 tokens per slab
         if (slabs > max_slabs) slabs = (int)max_slabs;
@@ -358,10 +633,18 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
     int acc_flag = accumulate;
     float k_alpha = alpha;
     if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; k_alpha = 1.0f; }
+    if (p.tall_rows > 0) {
+        hipLaunchKernelGGL(update_gemm_smfmac_q8_tall_kernel, dim3((unsigned)(p.tall_tiles_m * p.tiles_n)), dim3(512), 0, st,
+                           vals8, meta32, h8, ldh, out, ldo, T / 32, O, I, p.tall_tiles_m, p.tiles_n, acc_flag, k_alpha, p.tall_rows);
+        hipError_t e0 = hipGetLastError();
+        if (e0 != hipSuccess) return e0;
+        if (p.tiles_m == 0) return hipSuccess;
+    }
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, h8,    \
-                       ldh, out, ldo, slab_stride, T / 32, p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, k_alpha)
+                       ldh, out, ldo, slab_stride, T / 32, p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, k_alpha,  \
+                       p.tall_rows)
     if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
     else if (p.shape == 1) NM_LAUNCH(1, 4, 4, 2);
     else NM_LAUNCH(1, 4, 2, 2);
