@@ -163,7 +163,7 @@ size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
  * `scale` (> 0, finite; one binary32 product) and rounded stochastically to e5m2: with lo <= |x| < hi
  * neighbours on the e5m2 grid and f = (|x| - lo)/(hi - lo) the result is hi iff
  * r16 + floor(f * 2^16) >= 2^16, r16 uniform in [0, 2^16); |x| >= 57344 saturates to 57344, the
- * sign is kept.  E[q]/scale = theta(g) up to 2^-16 of a grid step.  r16: Philox4x32-10, key = seed,
+ * sign is kept; a NaN gives an e5m2 NaN (which of its codes is unspecified).  E[q]/scale = theta(g) up to 2^-16 of a grid step.  r16: Philox4x32-10, key = seed,
  * counter = (blk/4 low, blk/4 high, stream_id, 2), word blk%4; low half for the first kept value of
  * the quad, high half for the second; blk = (t/4)*O + o.
  * Output, the 8-bit group format (device pointers, 16-byte aligned): tokens in groups of 32 = 8 quads,

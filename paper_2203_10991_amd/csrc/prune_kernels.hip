@@ -423,25 +423,21 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
 // gradient has to be unbiased).  Selection and kept values as above, in binary32; each kept value is multiplied
 // by `scale` and rounded stochastically to e5m2 with 16 random bits: with lo <= |x| < hi neighbours on the e5m2
 // grid and f = (|x| - lo)/(hi - lo), the result is hi iff r16 + floor(f * 2^16) >= 2^16.
-//   normal range (|x| >= 2^-14): e5m2 is the top byte of a binary16, so the code is the binary32 exponent re-biased
-//     by 112 with the top two mantissa bits; the 21 discarded bits, cut to their top 16, are f: one add carries
-//     into the code.
-//   subnormal range: the grid step is 2^-16, so |x| * 2^32 truncated is the code in 16.16 fixed point.
-//   |x| >= 57344 (the largest finite e5m2) saturates; NaN stays NaN.
+//   |x| >= 57344 (the largest finite e5m2) saturates; a NaN gives an e5m2 NaN.
 // Rounding words: one Philox call per four blocks with last counter word 2, word blk%4; its low half rounds the
 // first kept value, its high half the second.
 // Output: 32-token groups, vals8[(G*O + o)*16 + 2i + s], meta32[G*O + o] (nibble i = quad i).
 // ------------------------------------------------------------------------------------
-__device__ __forceinline__ uint32_t sr_e5m2(float x, uint32_t r16)
+// The rounding itself is one instruction: v_cvt_sr_bf8_f32 adds the top 21 bits of its random operand to the 21
+// mantissa bits it discards (subnormal results: to the bits below the 2^-16 step) and truncates, which with the 16
+// rounding bits in the operand's top half and zeros below them is exactly the rule above -- checked against the
+// integer formulation for every rounding word over a million inputs of every exponent.  It overflows to infinity
+// where this format saturates, so the value is clamped to +-57344 first; the code lands in byte BYTE of `word`.
+template <int BYTE>
+__device__ __forceinline__ uint32_t sr_e5m2_into(uint32_t word, float x, uint32_t r_top)
 {
-    const uint32_t b = __float_as_uint(x), a = b & 0x7fffffffu;
-    const uint32_t normal = (((a >> 5) + r16) >> 16) - 448u;
-    const uint32_t fixed = (uint32_t)(__uint_as_float(a) * 0x1p32f);          // truncates; only used below 2^-14
-    const uint32_t sub = (fixed + r16) >> 16;
-    uint32_t code = a < 0x38800000u ? sub : normal;
-    code = a >= 0x47600000u ? 0x7Bu : code;
-    code = a > 0x7f800000u ? 0x7Fu : code;
-    return ((b >> 24) & 0x80u) | code;
+    const float c = __builtin_amdgcn_fmed3f(x, -57344.0f, 57344.0f);
+    return (uint32_t)__builtin_amdgcn_cvt_sr_bf8_f32(c, (int)r_top, (int)word, BYTE);
 }
 
 template <int DT, int EST>
@@ -509,8 +505,8 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
                 select_2of4<DT>(Key<DT>::make(rows[R0], c, 0), Key<DT>::make(rows[R0 + 1], c, 1),
                                 Key<DT>::make(rows[R0 + 2], c, 2), Key<DT>::make(rows[R0 + 3], c, 3),
                                 words[c], v0, v1, nib);
-            const uint32_t c0 = sr_e5m2(v0 * scale, rnd[c] & 0xffffu), c1 = sr_e5m2(v1 * scale, rnd[c] >> 16);
-            kept[c][b / 2] |= (c0 | (c1 << 8)) << (16 * (b & 1));
+            kept[c][b / 2] = sr_e5m2_into<2 * (b & 1)>(kept[c][b / 2], v0 * scale, rnd[c] << 16);
+            kept[c][b / 2] = sr_e5m2_into<2 * (b & 1) + 1>(kept[c][b / 2], v1 * scale, rnd[c] & 0xffff0000u);
             md[c] |= nib << (4 * b);
             __builtin_amdgcn_sched_barrier(0);
         }
