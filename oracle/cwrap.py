@@ -90,6 +90,8 @@ def lib():
         _lib.oracle_update_gemm_q8.restype = None
         _lib.oracle_update_gemm_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, i64, i32, vp, vp]
         _lib.oracle_update_gemm_shifted.restype = None
+        _lib.oracle_update_gemm_q8_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, i64, dbl, vp, vp]
+        _lib.oracle_update_gemm_q8_shifted.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -352,4 +354,20 @@ def update_gemm_shifted(vals: np.ndarray, meta: np.ndarray, x_full: np.ndarray, 
     xp = C.c_void_p(x_full.ctypes.data + margin * Cc * x_full.itemsize)
     lib().oracle_update_gemm_shifted(_p(np.ascontiguousarray(vals)), _p(np.ascontiguousarray(meta)), xp, Cc, Cc, _p(sh), len(sh),
                                      T, O, _dt(x_full), _p(dW), _p(absdW))
+    return dW, absdW
+
+
+def update_gemm_q8_shifted(vals8: np.ndarray, meta32: np.ndarray, x8_full: np.ndarray, margin: int, shifts, alpha: float = 1.0):
+    """x8_full: [margin + T + margin, C] uint8 e4m3 codes (row 0 of the grid at index `margin`).  Returns (dW, absdW) float64."""
+    G, O = meta32.shape
+    T = G * 32
+    x8_full = np.ascontiguousarray(x8_full)
+    assert x8_full.dtype == np.uint8 and x8_full.shape[0] == T + 2 * margin and max(abs(int(v)) for v in shifts) <= margin
+    Cc = x8_full.shape[1]
+    sh = np.ascontiguousarray(shifts, dtype=np.int64)
+    dW = np.zeros((O, len(sh) * Cc), dtype=np.float64)
+    absdW = np.zeros_like(dW)
+    xp = C.c_void_p(x8_full.ctypes.data + margin * Cc)
+    lib().oracle_update_gemm_q8_shifted(_p(np.ascontiguousarray(vals8)), _p(np.ascontiguousarray(meta32)), xp, Cc, Cc, _p(sh), len(sh),
+                                        T, O, float(alpha), _p(dW), _p(absdW))
     return dW, absdW

@@ -817,6 +817,35 @@ void oracle_update_gemm_shifted(const void *vals, const uint16_t *meta, const vo
     }
 }
 
+/* the 8-bit form of the same product: dW[o][j*C + c] = alpha * sum_t e5m2(gt[t][o]) * e4m3(x8[(t + shift[j])*ldx + c]) */
+void oracle_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t C,
+                                   const int64_t *shift, int n_shift, int64_t T, int64_t O, double alpha,
+                                   double *dW, double *absdW)
+{
+    const int64_t I = (int64_t)n_shift * C;
+    #pragma omp parallel for schedule(dynamic, 4)
+    for (int64_t o = 0; o < O; ++o) {
+        double *row = dW + o * I, *arow = absdW ? absdW + o * I : NULL;
+        for (int64_t i = 0; i < I; ++i) { row[i] = 0.0; if (arow) arow[i] = 0.0; }
+        for (int64_t t = 0; t < T; ++t) {
+            int64_t G = t / 32; int qi = (int)((t % 32) / 4), k = (int)(t % 4);
+            uint32_t md = meta32[G * O + o];
+            double gv = 0.0;
+            for (int s = 0; s < 2; ++s)
+                if ((int)((md >> (4 * qi + 2 * s)) & 3u) == k)
+                    gv = oracle_e5m2_value(vals8[(G * O + o) * 16 + 2 * qi + s]);
+            if (gv == 0.0) continue;
+            for (int j = 0; j < n_shift; ++j)
+                for (int64_t c = 0; c < C; ++c) {
+                    double hv = oracle_e4m3_value(x8[(t + shift[j]) * ldx + c]);
+                    row[j * C + c] += gv * hv;
+                    if (arow) arow[j * C + c] += fabs(gv) * fabs(hv);
+                }
+        }
+        for (int64_t i = 0; i < I; ++i) { row[i] *= alpha; if (arow) arow[i] *= fabs(alpha); }
+    }
+}
+
 /* threads the parallel loops will use (for the benchmark's report) */
 #ifdef _OPENMP
 #include <omp.h>

@@ -75,3 +75,22 @@ def test_shifted_gemm_is_the_convolution_weight_gradient(oracle):
     ref = torch.nn.grad.conv2d_weight(a_nchw, (O, C, k, k), theta_nchw, stride=1, padding=1).numpy()      # [O, C, ky, kx]
     got = dW.reshape(O, k, k, C).transpose(0, 3, 1, 2)                                                      # [O, C, ky, kx]
     assert np.allclose(got, ref, rtol=1e-12, atol=1e-12 * np.abs(ref).max())
+
+
+def test_q8_shifted_gemm_equals_q8_gemm_on_materialised_im2col(oracle):
+    rng = np.random.default_rng(4)
+    N, H, W, C, O, k = 2, 5, 6, 16, 16, 3
+    Hp, Wp = H + 2, W + 2
+    rows = N * Hp * Wp
+    T = (rows + 31) // 32 * 32
+    x = padded_grid(rng.standard_normal((N, H, W, C)).astype(np.float32) * 4, 1)
+    g = np.zeros((T, O), dtype=np.float32)
+    g[:rows] = padded_grid((rng.standard_normal((N, H, W, O)) * np.exp(rng.standard_normal((N, H, W, O)))).astype(np.float32), 1)
+    vals8, meta32 = oracle.prune_2of4_q8(g, seed=3, stream_id=0, mode=0, scale=16.0)
+    shifts = tap_shifts(k, Wp)
+    margin = Wp + 1
+    x8 = torch.from_numpy(with_margin(x, T, margin)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    dW, absdW = oracle.update_gemm_q8_shifted(vals8, meta32, x8, margin, shifts, alpha=0.125)
+    h8 = np.concatenate([x8[margin + s: margin + s + T] for s in shifts], axis=1)
+    want, wabs = oracle.update_gemm_q8(vals8, meta32, np.ascontiguousarray(h8), alpha=0.125)
+    assert np.allclose(dW, want, rtol=1e-13, atol=1e-13 * np.abs(want).max()) and np.allclose(absdW, wabs, rtol=1e-13)
