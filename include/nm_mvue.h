@@ -187,6 +187,17 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
                       void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
 
+/*
+ * The 8-bit update GEMM with the dense operand as row-shifted views (nm_update_gemm_shifted for the operands of
+ * nm_update_gemm_q8: the paper's 8-bit rows are convolutional networks):
+ *     dW[O x n_shift*cb] = beta*dW + alpha * decompress(vals8, meta32)^T h8,   h8[t][j*cb + c] = x8[(t + row_shift[j])*ldx + c].
+ * x8: e4m3 codes; rows -m .. T+m-1 (m = max|row_shift|) readable and finite (zero codes).  cb % 16 == 0, T % 32 == 0.
+ */
+int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                              const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                              float alpha, float beta, void *workspace, size_t workspace_bytes, void *hip_stream);
+size_t nm_update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift);
+
 /* Message of the last error on this thread ("" if none).  Static storage; do not free. */
 const char *nm_last_error(void);
 

@@ -45,6 +45,10 @@ def load():
     lib.nm_update_gemm_shifted.restype = i32
     lib.nm_update_gemm_shifted_workspace.argtypes = [i64, i64, i64, i32]
     lib.nm_update_gemm_shifted_workspace.restype = sz
+    lib.nm_update_gemm_q8_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, f32, f32, vp, sz, vp]
+    lib.nm_update_gemm_q8_shifted.restype = i32
+    lib.nm_update_gemm_q8_shifted_workspace.argtypes = [i64, i64, i64, i32]
+    lib.nm_update_gemm_q8_shifted_workspace.restype = sz
     lib.mvue_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp]
     lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
@@ -250,4 +254,32 @@ def nm_update_gemm_shifted(vals: torch.Tensor, meta: torch.Tensor, x_full: torch
     xp = x_full.data_ptr() + margin * ldx * x_full.element_size()
     _check(lib.nm_update_gemm_shifted(_ptr(vals), _ptr(meta), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O,
                                       _dtype_code(x_full), float(beta), _ptr(workspace), wbytes, _stream(x_full)))
+    return dW
+
+
+def nm_update_gemm_q8_shifted(vals8: torch.Tensor, meta32: torch.Tensor, x8_full: torch.Tensor, margin: int, shifts,
+                              dW: Optional[torch.Tensor] = None, alpha: float = 1.0, beta: float = 0.0,
+                              workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """8-bit form of nm_update_gemm_shifted: x8_full is [margin + T + margin, C] e4m3 codes, margin rows zero."""
+    lib = load()
+    G, O, _ = vals8.shape
+    T = G * 32
+    if x8_full.dim() != 2 or x8_full.shape[0] != T + 2 * margin or x8_full.element_size() != 1:
+        raise ValueError(f"x8_full must be an 8-bit tensor with {T + 2 * margin} rows (T = {T}, margin = {margin})")
+    if max(abs(int(v)) for v in shifts) > margin:
+        raise ValueError("a row shift exceeds the margin")
+    ldx = _rowmajor(x8_full, "x8_full")
+    Cb = x8_full.shape[1]
+    n = len(shifts)
+    if dW is None:
+        dW = torch.empty((O, n * Cb), dtype=torch.float32, device=x8_full.device)
+    lddw = _rowmajor(dW, "dW")
+    need = int(lib.nm_update_gemm_q8_shifted_workspace(T, O, Cb, n))
+    if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
+        workspace = torch.empty(need, dtype=torch.uint8, device=x8_full.device)
+    wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
+    sh = (C.c_int64 * n)(*[int(v) for v in shifts])
+    xp = x8_full.data_ptr() + margin * ldx
+    _check(lib.nm_update_gemm_q8_shifted(_ptr(vals8), _ptr(meta32), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O, float(alpha),
+                                         float(beta), _ptr(workspace), wbytes, _stream(x8_full)))
     return dW

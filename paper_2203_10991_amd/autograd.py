@@ -82,15 +82,22 @@ def _conv_update_shifted(gy: torch.Tensor, x: torch.Tensor, k: int, cfg: NMConfi
     gr, _ = padded_rows(gy, pad)
     rows, C = xr.shape
     O = gr.shape[1]
-    T = (rows + 15) // 16 * 16
+    q8 = cfg.precision == "q8"
+    T = (rows + 31) // 32 * 32 if q8 else (rows + 15) // 16 * 16
     margin = pad * wp + pad
     x_full = torch.zeros((T + 2 * margin, C), dtype=x.dtype, device=x.device)
     x_full[margin:margin + rows] = xr
     g2 = torch.zeros((T, O), dtype=gy.dtype, device=gy.device)
     g2[:rows] = gr
-    vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
     shifts = [(ky - pad) * wp + (kx - pad) for ky in range(k) for kx in range(k)]
-    dW = api.nm_update_gemm_shifted(vals, meta, x_full, margin, shifts)              # [O, (ky, kx, c)]
+    if q8:
+        sg, sh = pow2_scale(g2, 57344.0 / 4.0), pow2_scale(x_full, 448.0)
+        x8 = (x_full.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8)
+        v8, m32 = api.mvue_prune_2of4_q8(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
+        dW = api.nm_update_gemm_q8_shifted(v8, m32, x8, margin, shifts, alpha=1.0 / (sg * sh))
+    else:
+        vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
+        dW = api.nm_update_gemm_shifted(vals, meta, x_full, margin, shifts)          # [O, (ky, kx, c)]
     return dW.reshape(O, k, k, C).permute(0, 3, 1, 2).contiguous()
 
 
@@ -169,7 +176,8 @@ class _NMConv2dFn(torch.autograd.Function):
             O, C, kh, kw = weight.shape
             same = (kh == kw and kh % 2 == 1 and tuple(stride) == (1, 1) and tuple(dilation) == (1, 1)
                     and tuple(padding) == (kh // 2, kw // 2))
-            if same and x.dtype == torch.bfloat16 and ctx.cfg.nm == "2:4" and C % 8 == 0 and O % 8 == 0 and kh * kw <= 32:
+            cmul = 16 if ctx.cfg.precision == "q8" else 8
+            if same and x.dtype == torch.bfloat16 and ctx.cfg.nm == "2:4" and C % cmul == 0 and O % 8 == 0 and kh * kw <= 32:
                 dW = _conv_update_shifted(gy, x, kh, ctx.cfg).to(weight.dtype)
             else:
                 # im2col (App. B: the convolution's update GEMM reduces over batch x output positions):

@@ -48,7 +48,6 @@ constexpr int NS = 6;             // LDS stages: one being consumed, one landed,
 // SHIFTED: the dense operand is a set of row-shifted views of one [rows x cb] matrix (a convolution's im2col matrix
 // that is never materialised): column block j of h is x read sh.rows[j] rows further down, h[t][j*cb + c] =
 // x[(t + rows[j])*ldh + c].  Only a lane's constant source offset and the descriptor's extent change.
-struct ShiftArg { int cb, n, margin; int rows[32]; };
 template <int WM, int WN, int AB, int BB, bool SHIFTED = false>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
     const uint16_t *__restrict__ vals, const uint16_t *__restrict__ meta, const uint16_t *__restrict__ h, int64_t ldh,

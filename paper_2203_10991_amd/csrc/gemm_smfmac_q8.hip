@@ -74,12 +74,14 @@ template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t add
 //   then           vals8 fragments, [2 token groups][TM slots] x 16 bytes
 //   then           meta32 words,   [2 token groups][TM rows]  x 4 bytes
 //                  (both as one share per wave, padded to a whole 64-lane load)
-template <int WM, int WN, int AB, int BB>
+// SHIFTED: h8 as row-shifted views of one matrix (see ShiftArg); only a lane's source offset and the descriptor change.
+template <int WM, int WN, int AB, int BB, bool SHIFTED = false>
 __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     const uint8_t *__restrict__ vals, const uint32_t *__restrict__ meta, const uint8_t *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride,
     int64_t n_groups, int64_t groups_per_slab, int64_t O, int64_t I, int tiles_m, int tiles_n, int accumulate, float alpha,
-    int64_t o_first)                         // the launch computes rows [o_first, O) of dW; tiles_m counts its M-tiles
+    int64_t o_first,                         // the launch computes rows [o_first, O) of dW; tiles_m counts its M-tiles
+    ShiftArg sh)                             // (SHIFTED only)
 {
     constexpr int TM = WM * AB * 32, TN = WN * BB * 32;
     static_assert(TN == 256, "the h8 swizzle is written for 16 chunks per row");
@@ -156,6 +158,10 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     for (int ph = 0; ph < PHASES; ++ph) {
         const int row_mod8 = (ph * ROWS_PER_DMA + dma_row) & 7;
         const int64_t col = min(n0 + 16 * (dma_pos ^ (2 * row_mod8)), I - 16);
+        if constexpr (SHIFTED) {
+            const int j = (int)(col / sh.cb);             // (a 16-byte chunk never straddles two views: cb % 16 == 0)
+            b_src[ph] = (uint32_t)((int64_t)(wave * B_ROWS + dma_row + sh.rows[j] + sh.margin) * ldh + (col - (int64_t)j * sh.cb));
+        } else
         b_src[ph] = (uint32_t)((int64_t)(wave * B_ROWS + dma_row) * ldh + col);
     }
     const uint32_t b_row_step = (uint32_t)(ROWS_PER_DMA * ldh);
@@ -163,6 +169,9 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
     __amdgpu_buffer_rsrc_t rh, rv, rm;
     auto rebase = [&](int it) {
         const int64_t Gs = g_begin + (int64_t)it * 2, t0 = Gs * 32;
+        if constexpr (SHIFTED)       // offsets are relative to row t0 - margin
+            rh = rsrc((const char *)h + (t0 - sh.margin) * ldh, (T - t0 - 1 + 2 * (int64_t)sh.margin) * ldh + sh.cb);
+        else
         rh = rsrc((const char *)h + t0 * ldh, (T - t0 - 1) * ldh + I);
         rv = rsrc((const char *)vals + Gs * O * 16, (n_groups - Gs) * O * 16);
         rm = rsrc((const char *)meta + Gs * O * 4, (n_groups - Gs) * O * 4);
@@ -568,7 +577,7 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_q8_tall_kernel(
 // kernel of `shape`
 struct PlanQ8 { int shape; int tm; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
 
-static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
+static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I, bool shifted = false)
 {
     PlanQ8 p;
     const int64_t groups = T / 32;
@@ -585,7 +594,7 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I)
         const int64_t tn = (I + 255) / 256;
         double best = 1e300;
         int64_t best_mt = 0;
-        for (int64_t mt = 0; mt <= (O + 383) / 384; ++mt) {
+        for (int64_t mt = 0; !shifted && mt <= (O + 383) / 384; ++mt) {
             const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
             const double cost = TALL_ROUND * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
             if (cost < best - 1e-9) { best = cost; best_mt = mt; }
@@ -644,7 +653,49 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, h8,    \
                        ldh, out, ldo, slab_stride, T / 32, p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, k_alpha,  \
-                       p.tall_rows)
+                       p.tall_rows, ShiftArg{})
+    if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
+    else if (p.shape == 1) NM_LAUNCH(1, 4, 4, 2);
+    else NM_LAUNCH(1, 4, 2, 2);
+#undef NM_LAUNCH
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess) return e;
+    if (p.slabs > 1) e = launch_splitk_reduce((const float *)workspace, p.slabs, dW, lddw, O, I, accumulate, alpha, st);
+    return e;
+}
+
+size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I)
+{
+    if (T <= 0 || O <= 0 || I <= 0) return 0;
+    const PlanQ8 p = make_plan_q8(T, O, I, true);
+    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+}
+
+// dW = beta*dW + alpha * decompress(vals8, meta32)^T [x8 shifted by rows[0] | x8 shifted by rows[1] | ...]
+hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                                         const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,
+                                         float alpha, float beta, void *workspace, hipStream_t st)
+{
+    const int64_t I = cb * n;
+    if (O == 0 || I == 0) return hipSuccess;
+    const PlanQ8 p = make_plan_q8(T, O, I, true);
+    ShiftArg sh{};
+    sh.cb = (int)cb; sh.n = n; sh.margin = 0;
+    for (int j = 0; j < n; ++j) {
+        sh.rows[j] = (int)rows[j];
+        sh.margin = std::max(sh.margin, (int)(rows[j] < 0 ? -rows[j] : rows[j]));
+    }
+    const int accumulate = beta != 0.f;
+    float *out = dW;
+    int64_t ldo = lddw, slab_stride = 0;
+    int acc_flag = accumulate;
+    float k_alpha = alpha;
+    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; k_alpha = 1.0f; }
+    dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
+#define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
+    hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB, true>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, x8, \
+                       ldx, out, ldo, slab_stride, T / 32, p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, k_alpha,   \
+                       (int64_t)0, sh)
     if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
     else if (p.shape == 1) NM_LAUNCH(1, 4, 4, 2);
     else NM_LAUNCH(1, 4, 2, 2);

@@ -283,6 +283,55 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
                                                   (hipStream_t)hip_stream));
 }
 
+size_t nm_update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift)
+{
+    if (T < 0 || O < 0 || cb < 0 || n_shift < 1 || n_shift > 32) return 0;
+    return nm::update_gemm_q8_shifted_workspace(T, O, cb * n_shift);
+}
+
+int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                              const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                              float alpha, float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    const char *fn = "nm_update_gemm_q8_shifted";
+    if (T < 0 || O < 0 || cb < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (n_shift < 1 || n_shift > 32) return fail(NM_ERR_SHAPE, "%s: n_shift=%d must be 1..32", fn, n_shift);
+    if (!row_shift) return fail(NM_ERR_NULL, "%s: row_shift is NULL", fn);
+    if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32", fn, (long long)T);
+    if (O % 8 || cb % 16) return fail(NM_ERR_SHAPE, "%s: O=%lld must be a multiple of 8 and cb=%lld of 16", fn, (long long)O, (long long)cb);
+    if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
+    const int64_t I = cb * n_shift;
+    if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
+    int64_t margin = 0;
+    for (int j = 0; j < n_shift; ++j) margin = row_shift[j] < -margin ? -row_shift[j] : row_shift[j] > margin ? row_shift[j] : margin;
+    if (margin > (1 << 20)) return fail(NM_ERR_UNSUPPORTED, "%s: row shifts must not exceed 2^20 rows", fn);
+    if (!dW) return fail(NM_ERR_NULL, "%s: dW is NULL", fn);
+    if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
+    if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
+    Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    if (T > 0) {
+        if (!vals8 || !meta32 || !x8) return fail(NM_ERR_NULL, "%s: vals8, meta32 and x8 must not be NULL", fn);
+        if (ldx < cb) return fail(NM_ERR_SHAPE, "%s: ldx=%lld is smaller than cb=%lld", fn, (long long)ldx, (long long)cb);
+        if (ldx > (1 << 21) || O > (1 << 21) || (margin + 1024) * ldx > (1ll << 30))
+            return fail(NM_ERR_UNSUPPORTED, "%s: O, ldx and (shift x ldx) exceed what 32-bit byte offsets reach", fn);
+        if (!aligned16(vals8) || !aligned16(meta32) || !aligned16(x8) || ldx % 16)
+            return fail(NM_ERR_ALIGN, "%s: vals8, meta32, x8 need 16-byte aligned bases (and x8 a 16-byte row stride)", fn);
+        Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
+        Range rx = range_of((const char *)x8 - margin * ldx, (T + 2 * margin - 1) * ldx + cb, "x8");
+        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rx)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+    }
+    const size_t need = nm::update_gemm_q8_shifted_workspace(T, O, I);
+    if (need) {
+        if (!workspace || workspace_bytes < need)
+            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
+        Range rw = range_of(workspace, (int64_t)need, "workspace");
+        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+    }
+    return launched(fn, nm::launch_update_gemm_q8_shifted(vals8, meta32, x8, ldx, cb, row_shift, n_shift, dW, lddw, T, O, alpha,
+                                                          beta, workspace, (hipStream_t)hip_stream));
+}
+
 const char *nm_last_error(void) { return g_err; }
 
 const char *nm_version(void) { return "nm_mvue 0.1 gfx950"; }

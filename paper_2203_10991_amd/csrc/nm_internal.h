@@ -46,5 +46,10 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
                                  int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace,
                                  hipStream_t st);
 size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
+// ... with h8 given as n row-shifted views of one [rows x cb] matrix x8
+hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                                         const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,
+                                         float alpha, float beta, void *workspace, hipStream_t st);
+size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I);
 
 }  // namespace nm

@@ -183,6 +183,11 @@ __device__ __forceinline__ void tile_of_workgroup(int bid_, int tiles_m, int til
     }
 }
 
+// The dense operand as row-shifted views of one [rows x cb] matrix (a convolution's im2col matrix that is never
+// materialised): column block j of h is x read rows[j] rows further down, h[t][j*cb + c] = x[(t + rows[j])*ldh + c];
+// rows -margin .. T+margin-1 of x are readable.
+struct ShiftArg { int cb, n, margin; int rows[32]; };
+
 // Split-K launches (gridDim.z slabs of the reduction axis, gridDim.x tiles): workgroups are dealt round-robin to the
 // XCDs in launch order (x fastest, then z).  With a tile count that is a multiple of 8 a tile stays on one XCD for
 // every slab and the single-pass tile map (compact tile sets per XCD) is still right.  Otherwise the tiles of one

@@ -184,3 +184,33 @@ def test_linear_q8_update_phase_matches_oracle(oracle):
     rel = float((layer.weight.grad.float() - dense).norm() / dense.norm())
     print(f"q8 update phase: one draw off the dense gradient by {rel:.3f}", flush=True)
     assert rel < 0.8
+
+
+def test_conv2d_q8_update_phase_without_im2col(oracle):
+    """precision="q8" on a 3x3 'same' convolution: the layer's padded grids and scales, then the oracle's 8-bit shifted GEMM"""
+    from paper_2203_10991_amd.autograd import NMConfig, NMConv2d, padded_rows, pow2_scale
+    torch.manual_seed(5)
+    N, C, H, W, O, k = 2, 16, 8, 9, 24, 3
+    conv = NMConv2d(C, O, k, padding=1, bias=False, cfg=NMConfig(nm="2:4", seed=8, stream_id=2, precision="q8"), device=DEV,
+                    dtype=torch.bfloat16)
+    x = torch.relu(torch.randn(N, C, H, W, device=DEV)).to(torch.bfloat16).requires_grad_(True)
+    gy = (torch.randn(N, O, H, W, device=DEV) * torch.exp(2 * torch.randn(N, O, H, W, device=DEV))).to(torch.bfloat16)
+    conv(x).backward(gy)
+    xr, wp = padded_rows(x.detach(), 1)
+    gr, _ = padded_rows(gy, 1)
+    rows = xr.shape[0]
+    T = (rows + 31) // 32 * 32
+    margin = wp + 1
+    x_full = torch.zeros((T + 2 * margin, C), dtype=torch.bfloat16, device=DEV)
+    x_full[margin:margin + rows] = xr
+    g2 = torch.zeros((T, O), dtype=torch.bfloat16, device=DEV)
+    g2[:rows] = gr
+    sg, sh = pow2_scale(g2, 57344.0 / 4.0), pow2_scale(x_full, 448.0)
+    x8 = (x_full.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8).cpu().numpy()
+    ov, om = oracle.prune_2of4_q8(bits(g2), 8, 2, 0, sg)
+    shifts = [(ky - 1) * wp + (kx - 1) for ky in range(k) for kx in range(k)]
+    want, wabs = oracle.update_gemm_q8_shifted(ov, om, x8, margin, shifts, alpha=1.0 / (sg * sh))
+    want = want.reshape(O, k, k, C).transpose(0, 3, 1, 2)
+    wabs = wabs.reshape(O, k, k, C).transpose(0, 3, 1, 2)
+    got = conv.weight.grad.double().cpu().numpy()
+    assert (np.abs(got - want) <= 1e-2 * np.maximum(wabs, np.abs(want)) + 1e-30).all()

@@ -83,3 +83,33 @@ def test_shifted_gemm_large_tiles(nm, oracle):
     rel = float((np.abs(got - want) / np.maximum(wabs, 1e-300)).max())
     print(f"conv large tiles: T={T} O=2048 I={9 * 256} max |err|/sum|ab| = {rel:.3e}", flush=True)
     assert rel <= 1e-2
+
+
+@pytest.mark.parametrize("N,H,W,C,O,k", [(2, 6, 6, 16, 8, 3), (3, 14, 14, 64, 64, 3), (2, 9, 11, 32, 200, 3), (1, 12, 12, 256, 2048, 3)])
+def test_q8_shifted_gemm_matches_oracle(nm, oracle, N, H, W, C, O, k):
+    """the 8-bit form: e5m2 kept values pruned on the padded grid, e4m3 activations as shifted views"""
+    x_full, g, T, margin, shifts = make_case(N, H, W, C, O, k, seed=H + C)
+    T32 = (T + 31) // 32 * 32                                    # 32-token groups
+    g32 = np.zeros((T32, O), dtype=np.uint16); g32[:T] = g
+    xf = np.zeros((T32 + 2 * margin, C), dtype=np.uint16); xf[:T + 2 * margin] = x_full
+    gmax = float(np.abs(synth.bf16_to_f32(g32)).max())
+    scale = float(2.0 ** np.floor(np.log2(57344.0 / (4.0 * gmax))))
+    x8 = torch.from_numpy(synth.bf16_to_f32(xf) * 16.0).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    ov, om = oracle.prune_2of4_q8(g32, 5, 1, 0, scale)
+    alpha = 1.0 / (16.0 * scale)
+    if O * C * k * k <= 1 << 20:
+        want, wabs = oracle.update_gemm_q8_shifted(ov, om, x8, margin, shifts, alpha=alpha)
+        pick = None
+    else:                                                        # large case: a band of rows is enough for the oracle
+        pick = np.r_[0:8, O // 2:O // 2 + 8, O - 8:O]
+        want, wabs = oracle.update_gemm_q8_shifted(np.ascontiguousarray(ov[:, pick]), np.ascontiguousarray(om[:, pick]), x8, margin, shifts, alpha=alpha)
+    v, m = nm.mvue_prune_2of4_q8(to_dev(g32), seed=5, stream_id=1, mode=0, scale=scale)
+    dW = nm.nm_update_gemm_q8_shifted(v, m, torch.from_numpy(x8).to(DEV), margin, shifts, alpha=alpha)
+    torch.cuda.synchronize()
+    assert np.array_equal(v.cpu().numpy(), ov) and np.array_equal(m.cpu().numpy().view(np.uint32), om)
+    got = dW.cpu().numpy().astype(np.float64)
+    if pick is not None:
+        got = got[pick]
+    rel = float((np.abs(got - want) / np.maximum(wabs, 1e-300)).max())
+    print(f"q8 conv N={N} {H}x{W} C={C} O={O}: max |err|/sum|ab| = {rel:.3e}", flush=True)
+    assert np.isfinite(got).all() and rel <= 1e-3
