@@ -109,3 +109,21 @@ def test_update_gemm_consumes_the_1of4_container(nm, oracle):
     assert np.array_equal(to_host(m), om) and np.array_equal(to_host(v), ov)
     rel = float((np.abs(dW.cpu().numpy().astype(np.float64) - want) / np.maximum(wabs, 1e-300)).max())
     assert rel <= TOL["bf16"]
+
+
+def _random_shapes(n, seed, t_mult, i_mult):
+    rng = np.random.default_rng(seed)
+    out = []
+    for _ in range(n):
+        T = int(rng.integers(1, 300)) * t_mult
+        O = int(rng.integers(1, 80)) * 8
+        I = int(rng.integers(1, 60)) * i_mult
+        out.append((T, O, I))
+    return out
+
+
+@pytest.mark.parametrize("T,O,I", _random_shapes(14, 2024, 16, 8))
+def test_update_gemm_random_shapes(nm, oracle, T, O, I):
+    """seeded random problem sizes: every branch of the split-K plan (slab counts, tile counts that are and are not
+    multiples of 8, ragged tiles, ragged last stages) against the oracle"""
+    run_case(nm, oracle, synth.Workload(f"r{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T + O + I)

@@ -144,3 +144,14 @@ def test_update_gemm_q8_large_tile_kernel(nm, oracle, T, O, I):
 
 def test_update_gemm_q8_beta_one_large_tile(nm, oracle):
     gemm_case(nm, oracle, 128, 16 * 256, 16 * 256, seed=3, beta=1.0, sample=8)
+
+
+def _random_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(1, 150)) * 32, int(rng.integers(1, 80)) * 8, int(rng.integers(1, 40)) * 16) for _ in range(n)]
+
+
+@pytest.mark.parametrize("T,O,I", _random_shapes(12, 77))
+def test_update_gemm_q8_random_shapes(nm, oracle, T, O, I):
+    """seeded random problem sizes through every branch of the 8-bit split-K plan"""
+    gemm_case(nm, oracle, T, O, I, seed=T + O)
