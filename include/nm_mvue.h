@@ -91,6 +91,15 @@ int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
 
 /*
+ * mvue_prune_2of4 for a gradient that is stored transposed: gT is [O x T] with the tokens contiguous (row stride ldt
+ * elements), as a producer that writes g^T leaves it; N:M blocks are then four adjacent elements of a row (the
+ * "contiguous elements" of Sec. 1).  Same estimators (mode 0 / 1), random stream and block index as mvue_prune_2of4:
+ * vals and meta equal what mvue_prune_2of4 writes for the transposed tensor, bit for bit.  No dense output.
+ */
+int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype,
+                      uint64_t seed, uint32_t stream_id, int mode, void *vals, uint16_t *meta, void *hip_stream);
+
+/*
  * MVUE 1:4 prune + compress (appendix, "Additional sparsity results": MVUE 1:2 on a block of four).
  * Of every quad one element survives: position k with probability |a_k|/sum|a|, emitting
  * sign(a_k)*sum|a| (eq. (6) with four terms; variance sum_k |a_k|(sum|a| - |a_k|)).  One uniform per quad,

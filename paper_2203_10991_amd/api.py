@@ -38,6 +38,8 @@ def load():
     lib.mvue_prune_2of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.restype = i32
+    lib.mvue_prune_2of4_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp]
+    lib.mvue_prune_2of4_t.restype = i32
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
@@ -136,6 +138,19 @@ def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: in
                     dense_out=None, want_dense: bool = False):
     """Optimal MVUE 2:4 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
     return _prune("2of4", g, seed, stream_id, mode, vals, meta, dense_out, want_dense)
+
+
+def mvue_prune_2of4_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, vals=None, meta=None):
+    """MVUE 2:4 prune + compress of a gradient stored transposed, gT[O x T] (tokens contiguous).  Returns (vals, meta)."""
+    lib = load()
+    if not gT.is_cuda:
+        raise ValueError("gT must live on the GPU")
+    O, T = gT.shape
+    ldt = _rowmajor(gT, "gT")
+    if vals is None or meta is None:
+        vals, meta = alloc_compressed(T - T % 16, O, gT.dtype, gT.device)
+    _check(lib.mvue_prune_2of4_t(_ptr(gT), T, O, ldt, _dtype_code(gT), seed, stream_id, mode, _ptr(vals), _ptr(meta), _stream(gT)))
+    return vals, meta
 
 
 def nm_compress(dense: torch.Tensor, n: int, m: int, vals=None, meta=None, bad_blocks: Optional[torch.Tensor] = None):

@@ -112,6 +112,28 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                                          (hipStream_t)hip_stream));
 }
 
+int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id,
+                      int mode, void *vals, uint16_t *meta, void *hip_stream)
+{
+    const char *fn = "mvue_prune_2of4_t";
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", fn, mode);
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
+    if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16 (pad with zero tokens)", fn, (long long)T);
+    if (O % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld is not a multiple of 8 (pad with zero rows)", fn, (long long)O);
+    if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
+    if (!gT || !vals || !meta) return fail(NM_ERR_NULL, "%s: gT, vals and meta must not be NULL", fn);
+    if (ldt < T) return fail(NM_ERR_SHAPE, "%s: row stride %lld of gT is smaller than T=%lld", fn, (long long)ldt, (long long)T);
+    const int64_t es = esize(dtype);
+    if (!aligned16(gT) || (ldt * es) % 16 || !aligned16(vals) || !aligned16(meta))
+        return fail(NM_ERR_ALIGN, "%s: gT (base and row stride), vals and meta need 16-byte alignment", fn);
+    Range rin = range_of(gT, ((O - 1) * ldt + T) * es, "gT");
+    Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
+    if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm)) return fail(NM_ERR_ALIAS, "%s: gT, vals and meta must not overlap", fn);
+    return launched(fn, nm::launch_prune_transposed(dtype, mode, gT, T, O, ldt, seed, stream_id, vals, meta, (hipStream_t)hip_stream));
+}
+
 int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, int n, int m, void *vals,
                 uint16_t *meta, int32_t *bad_blocks, void *hip_stream)
 {

@@ -542,6 +542,125 @@ hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O,
 }
 
 // ------------------------------------------------------------------------------------
+// MVUE 2:4 prune + compress of a gradient stored TRANSPOSED: gT is [O x T], tokens contiguous, so a quad is four
+// adjacent elements of a row.  Same estimators, same random stream and block index (blk = (t/4)*O + o) as the
+// kernels above: the output equals theirs on the transposed tensor, bit for bit.
+// Workgroup = 16 columns o x 16 token groups; a thread owns one (o, group): it loads the group's 16 tokens as one
+// contiguous piece (16 threads of a column read 512 or 1024 consecutive bytes), decides its four quads, and the
+// kept values and index words go through LDS so that the stores run along o (16 x 16 or 32 bytes contiguous per
+// token group), which is how the group format is laid out.
+// ------------------------------------------------------------------------------------
+template <int DT, int EST>
+__global__ __launch_bounds__(256) void prune_compress_t_kernel(
+    const void *__restrict__ gT_, int64_t n_groups, int64_t O, int64_t ldt, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals_, uint16_t *__restrict__ meta_)
+{
+    constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
+    constexpr int VW = 16 * ESZ / 4;                       // 32-bit words of a group's 16 tokens: 8 (bf16) or 16 (fp32)
+    constexpr int KW = 8 * ESZ / 4;                        // words of its 8 kept values: 4 or 8
+    __shared__ uint32_t kept_s[16][16][KW + 1];            // [group][column][word] (+1: no bank conflicts on the way in)
+    __shared__ uint16_t meta_s[16][16];
+    const int tid = threadIdx.x, oi = tid >> 4, gi = tid & 15;
+    const int64_t o = (int64_t)blockIdx.y * 16 + oi, G = (int64_t)blockIdx.x * 16 + gi;
+    const bool live = o < O && G < n_groups;
+
+    uint32_t w[VW];
+#pragma unroll
+    for (int j = 0; j < VW; ++j) w[j] = 0;
+    if (live) {
+        const uint4 *src = (const uint4 *)((const char *)gT_ + (o * ldt + G * 16) * ESZ);
+#pragma unroll
+        for (int j = 0; j < VW / 4; ++j) { const uint4 v = src[j]; w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w; }
+    }
+    auto elem_bits = [&](int t) -> uint32_t {             // token t of the group as binary32 bits
+        if constexpr (DT == NM_DT_F32) return w[t];
+        else return (t & 1) ? (w[t >> 1] & 0xffff0000u) : (w[t >> 1] << 16);
+    };
+    // Random words.  A wave holds 4 columns (a multiple of 4 onwards) x 16 groups, and the blocks of those 4 columns
+    // in one quad row share their Philox calls (one call for the optimal estimator, two for approx-MVUE), as in the
+    // token-major kernels.  Lane (a, gi) makes the calls of quad row a of group gi for the wave's columns and leaves
+    // the words in LDS; lane (j, gi) then picks, for each quad row, the words of its own column j.
+    constexpr int WPC = EST == 1 ? 8 : 4;                  // words per (group, quad row) of a wave's four columns
+    __shared__ __attribute__((aligned(16))) uint32_t rnd_s[4][4][16][WPC];       // [wave][quad row][group][word]
+    {
+        const int wave = tid >> 6, a = oi & 3;
+        const uint64_t blk0 = (uint64_t)(G * 4 + a) * (uint64_t)O + (uint64_t)(o - a);
+#pragma unroll
+        for (int c = 0; c < WPC / 4; ++c) {
+            uint32_t r4[4];
+            const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + c;
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, r4);
+            *(uint4 *)&rnd_s[wave][a][gi][4 * c] = make_uint4(r4[0], r4[1], r4[2], r4[3]);
+        }
+    }
+    __syncthreads();
+    uint32_t md = 0;
+    uint32_t kept[KW];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+        float v0, v1; uint32_t nib;
+        const uint32_t *rw = rnd_s[tid >> 6][i][gi];
+        if constexpr (EST == 1) {
+            const uint2 wab = *(const uint2 *)&rw[2 * (oi & 3)];
+            select_2of4_approx(__uint_as_float(elem_bits(4 * i)), __uint_as_float(elem_bits(4 * i + 1)),
+                               __uint_as_float(elem_bits(4 * i + 2)), __uint_as_float(elem_bits(4 * i + 3)), wab.x, wab.y, v0, v1, nib);
+        } else {
+            const uint32_t word = rw[oi & 3];
+            // (the ranking keys are built from one-element "rows": the element sits where column 0 of a row would)
+            uint4 e[4];
+#pragma unroll
+            for (int p = 0; p < 4; ++p) {
+                const uint32_t b = elem_bits(4 * i + p);
+                e[p] = make_uint4(DT == NM_DT_F32 ? b : (b >> 16), 0u, 0u, 0u);
+            }
+            select_2of4<DT>(Key<DT>::make(e[0], 0, 0), Key<DT>::make(e[1], 0, 1), Key<DT>::make(e[2], 0, 2), Key<DT>::make(e[3], 0, 3),
+                            word, v0, v1, nib);
+        }
+        if constexpr (DT == NM_DT_F32) { kept[2 * i] = __float_as_uint(v0); kept[2 * i + 1] = __float_as_uint(v1); }
+        else kept[i] = pack_bf16_rne(v0, v1);
+        md |= nib << (4 * i);
+    }
+#pragma unroll
+    for (int j = 0; j < KW; ++j) kept_s[gi][oi][j] = kept[j];
+    meta_s[gi][oi] = (uint16_t)md;
+    __syncthreads();
+    // second half: thread (group gj, column oj) stores what thread (oj, gj) computed: 16 threads write one token group's run along o
+    const int gj = tid >> 4, oj = tid & 15;
+    const int64_t o2 = (int64_t)blockIdx.y * 16 + oj, G2 = (int64_t)blockIdx.x * 16 + gj;
+    if (o2 < O && G2 < n_groups) {
+        uint32_t *dst = (uint32_t *)((char *)vals_ + ((G2 * O + o2) * 8) * ESZ);
+        if constexpr (KW == 4) *(uint4 *)dst = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
+        else {
+            ((uint4 *)dst)[0] = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
+            ((uint4 *)dst)[1] = make_uint4(kept_s[gj][oj][4], kept_s[gj][oj][5], kept_s[gj][oj][6], kept_s[gj][oj][7]);
+        }
+        meta_[G2 * O + o2] = meta_s[gj][oj];
+    }
+}
+
+template <int DT, int EST>
+static hipError_t launch_prune_t_t(const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed, uint32_t stream_id,
+                                   void *vals, uint16_t *meta, hipStream_t st)
+{
+    const int64_t groups = T / 16;
+    if (groups == 0 || O == 0) return hipSuccess;
+    dim3 grid((unsigned)((groups + 15) / 16), (unsigned)((O + 15) / 16));
+    hipLaunchKernelGGL((prune_compress_t_kernel<DT, EST>), grid, dim3(256), 0, st, gT, groups, O, ldt, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), stream_id, vals, meta);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
+                                   uint32_t stream_id, void *vals, uint16_t *meta, hipStream_t st)
+{
+    if (dt == NM_DT_F32)
+        return est == 1 ? launch_prune_t_t<NM_DT_F32, 1>(gT, T, O, ldt, seed, stream_id, vals, meta, st)
+                        : launch_prune_t_t<NM_DT_F32, 0>(gT, T, O, ldt, seed, stream_id, vals, meta, st);
+    return est == 1 ? launch_prune_t_t<NM_DT_BF16, 1>(gT, T, O, ldt, seed, stream_id, vals, meta, st)
+                    : launch_prune_t_t<NM_DT_BF16, 0>(gT, T, O, ldt, seed, stream_id, vals, meta, st);
+}
+
+// ------------------------------------------------------------------------------------
 // nm_compress: dense n:m tensor -> group format.  Same thread tiling as above.
 // ------------------------------------------------------------------------------------
 template <int DT, int M>

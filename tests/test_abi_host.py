@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
                           "nm_update_gemm_q8_shifted_workspace",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
@@ -70,6 +70,21 @@ def test_prune_2of4_modes(lib):
     assert call(7) == NM_ERR_UNSUPPORTED and call(-1) == NM_ERR_UNSUPPORTED
     assert call(1, T=24) == NM_ERR_SHAPE
     assert call(0, T=24) == NM_ERR_SHAPE
+
+
+def test_transposed_prune_argument_errors(lib):
+    def call(gT=P, T=32, O=16, ldt=32, dt=1, mode=0, vals=P + 0x10000, meta=P + 0x20000):
+        return lib.mvue_prune_2of4_t(gT, T, O, ldt, dt, 0, 0, mode, vals, meta, None)
+    assert call(T=24) == NM_ERR_SHAPE and b"multiple of 16" in lib.nm_last_error()
+    assert call(O=12) == NM_ERR_SHAPE
+    assert call(ldt=16) == NM_ERR_SHAPE
+    assert call(dt=3) == NM_ERR_DTYPE
+    assert call(mode=2) == NM_ERR_UNSUPPORTED
+    assert call(gT=None) == NM_ERR_NULL and call(vals=None) == NM_ERR_NULL and call(meta=None) == NM_ERR_NULL
+    assert call(gT=P + 4) == NM_ERR_ALIGN
+    assert call(ldt=36) == NM_ERR_ALIGN                           # 72-byte bf16 rows
+    assert call(vals=P) == NM_ERR_ALIAS and call(meta=P + 0x10000) == NM_ERR_ALIAS
+    assert call(T=0) == NM_OK and call(O=0) == NM_OK
 
 
 def test_compress_argument_errors(lib):
