@@ -561,7 +561,10 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
     __shared__ uint32_t kept_s[16][16][KW + 1];            // [group][column][word] (+1: no bank conflicts on the way in)
     __shared__ uint16_t meta_s[16][16];
     const int tid = threadIdx.x, oi = tid >> 4, gi = tid & 15;
-    const int64_t o = (int64_t)blockIdx.y * 16 + oi, G = (int64_t)blockIdx.x * 16 + gi;
+    // consecutive workgroups walk along the tokens of the same 16 columns
+    const int64_t gblocks = (n_groups + 15) / 16;
+    const int64_t ob = (int64_t)blockIdx.x / gblocks, gb = (int64_t)blockIdx.x % gblocks;
+    const int64_t o = ob * 16 + oi, G = gb * 16 + gi;
     const bool live = o < O && G < n_groups;
 
     uint32_t w[VW];
@@ -626,7 +629,7 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
     __syncthreads();
     // second half: thread (group gj, column oj) stores what thread (oj, gj) computed: 16 threads write one token group's run along o
     const int gj = tid >> 4, oj = tid & 15;
-    const int64_t o2 = (int64_t)blockIdx.y * 16 + oj, G2 = (int64_t)blockIdx.x * 16 + gj;
+    const int64_t o2 = ob * 16 + oj, G2 = gb * 16 + gj;
     if (o2 < O && G2 < n_groups) {
         uint32_t *dst = (uint32_t *)((char *)vals_ + ((G2 * O + o2) * 8) * ESZ);
         if constexpr (KW == 4) *(uint4 *)dst = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
@@ -644,8 +647,9 @@ static hipError_t launch_prune_t_t(const void *gT, int64_t T, int64_t O, int64_t
 {
     const int64_t groups = T / 16;
     if (groups == 0 || O == 0) return hipSuccess;
-    dim3 grid((unsigned)((groups + 15) / 16), (unsigned)((O + 15) / 16));
-    hipLaunchKernelGGL((prune_compress_t_kernel<DT, EST>), grid, dim3(256), 0, st, gT, groups, O, ldt, (uint32_t)seed,
+    const int64_t blocks = ((groups + 15) / 16) * ((O + 15) / 16);
+    if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((prune_compress_t_kernel<DT, EST>), dim3((unsigned)blocks), dim3(256), 0, st, gT, groups, O, ldt, (uint32_t)seed,
                        (uint32_t)(seed >> 32), stream_id, vals, meta);
     return hipGetLastError();
 }
