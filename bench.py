@@ -334,10 +334,13 @@ def main():
     # published peak assumes, so the roofline is also stated against the peak at the clock that was actually held.
     try:
         clocks, watts = [], []
-        for _ in range(40):
+        n_queue = max(40, int(1000.0 / max(gemm_ms, 0.05)))       # about a second of launches: the interface's
+        n_queue = min(n_queue, 2000)                               # readings lag the hardware by tens of milliseconds
+        t_begin = time.perf_counter()
+        for _ in range(n_queue):
             gemm()
-        t_end = time.perf_counter() + 40 * gemm_ms * 1e-3 * 0.8
-        time.sleep(5 * gemm_ms * 1e-3)
+        t_end = t_begin + n_queue * gemm_ms * 1e-3 * 0.9
+        time.sleep(max(0.0, t_begin + n_queue * gemm_ms * 1e-3 * 0.4 - time.perf_counter()))
         while time.perf_counter() < t_end:
             clocks.append(float(torch.cuda.clock_rate()))
             try:
@@ -348,12 +351,20 @@ def main():
         torch.cuda.synchronize()
         clocks.sort()
         sclk = clocks[len(clocks) // 2] if clocks else None
-        if sclk and sclk > 200.0:
+        frac_at = gemm_tflops / (gemm_peak * sclk / 2400.0) if sclk else None
+        watts.sort()
+        power = watts[len(watts) // 2] if watts else None
+        # A reading is used only if it can be one of a loaded device: a plausible clock, and a board power far above
+        # idle (a GEMM queue holds this part near its limit, well above a kilowatt; some boxes' interfaces return
+        # idle or averaged figures instead).
+        if sclk and 500.0 <= sclk <= 2400.0 and frac_at <= 1.0 and power is not None and power >= 600.0:
             out["gemm_sclk_MHz_sampled"] = sclk
-            out["roofline"]["frac_at_sustained_clock"] = gemm_tflops / (gemm_peak * sclk / 2400.0)
-        if watts:
-            watts.sort()
-            out["gemm_board_power_W_sampled"] = watts[len(watts) // 2]
+            out["gemm_board_power_W_sampled"] = power
+            out["roofline"]["frac_at_sustained_clock"] = frac_at
+        else:
+            out["gemm_sclk_MHz_sampled"] = None
+            out["gemm_sclk_note"] = (f"management interface returned {sclk} MHz / {power} W while the GEMM queue ran: "
+                                     "not the readings of a loaded device, not used")
     except Exception as e:                       # no management interface: the published-peak roofline stands alone
         out["gemm_sclk_MHz_sampled"] = None
         out["gemm_sclk_note"] = repr(e)[:200]
