@@ -127,3 +127,29 @@ def test_update_gemm_random_shapes(nm, oracle, T, O, I):
     """seeded random problem sizes: every branch of the split-K plan (slab counts, tile counts that are and are not
     multiples of 8, ragged tiles, ragged last stages) against the oracle"""
     run_case(nm, oracle, synth.Workload(f"r{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T + O + I)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32", "q8"])
+@pytest.mark.parametrize("T,O,I", [(4096, 64, 576), (12608 - 12608 % 32, 768, 768), (2048, 1000, 528), (32 * 300, 256, 2304)])
+def test_update_gemm_is_bitwise_reproducible(nm, dtype, T, O, I):
+    """The reduction over the token slabs of a split-K plan has a fixed order: the same call gives the same bits,
+    whatever ran on the device in between."""
+    gen = torch.Generator(device=DEV)
+    gen.manual_seed(T + O)
+    if dtype == "q8":
+        g = torch.empty((T, O), dtype=torch.bfloat16, device=DEV).normal_(generator=gen)
+        v, m = nm.mvue_prune_2of4_q8(g, seed=3, stream_id=0, mode=0, scale=64.0)
+        h = (torch.empty((T, I), device=DEV).normal_(generator=gen) * 4.0).to(torch.float8_e4m3fn).view(torch.uint8)
+        call = lambda: nm.nm_update_gemm_q8(v, m, h, alpha=1.0 / 64.0)
+    else:
+        td = torch.bfloat16 if dtype == "bf16" else torch.float32
+        g = torch.empty((T, O), dtype=td, device=DEV).normal_(generator=gen)
+        h = torch.empty((T, I), dtype=td, device=DEV).normal_(generator=gen)
+        v, m, _ = nm.mvue_prune_2of4(g, seed=3, stream_id=0)
+        call = lambda: nm.nm_update_gemm(v, m, h)
+    first = call().clone()
+    for k in range(3):
+        torch.mm(torch.empty((1024, 1024), device=DEV).normal_(generator=gen), torch.ones((1024, 1024), device=DEV))
+        again = call()
+        torch.cuda.synchronize()
+        assert torch.equal(again.view(torch.int32), first.view(torch.int32)), (dtype, T, O, I, k)
