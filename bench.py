@@ -183,6 +183,9 @@ def main():
     ap.add_argument("--conv-implicit", action="store_true",
                     help="c3_conv_2of4 only: the layer's update GEMM without the im2col matrix (gradient and activations on "
                          "the zero-padded channels-last grid, nm_update_gemm_shifted) instead of the materialised one")
+    ap.add_argument("--g-layout", default="token-major", choices=["token-major", "transposed"],
+                    help="transposed: the gradient arrives as g^T [O x T] (tokens contiguous) and is pruned by "
+                         "mvue_prune_2of4_t; 2:4 workloads in their own dtype only")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--pmc-calibration", action="store_true",
                     help="also run one plain 1 GiB device copy, the known-size reference for rocprofv3 --pmc byte counters")
@@ -215,6 +218,15 @@ def main():
         prune = lambda g_, **kw: nm.mvue_prune_2of4(g_, mode=1 if approx else 0, **kw)
     q8 = args.precision == "q8"
     conv = None
+    transposed = args.g_layout == "transposed"
+    if transposed:
+        if w.nm != "2:4" or q8 or args.conv_implicit:
+            print("bench.py: --g-layout transposed runs 2:4 workloads in their own dtype, materialised operands", file=sys.stderr)
+            sys.exit(2)
+        gT = g.t().contiguous()                 # outside the timed region: a producer would have written g^T
+        del g
+        g = gT
+        prune = lambda g_, **kw: nm.mvue_prune_2of4_t(g_, mode=1 if approx else 0, **kw)
     if args.conv_implicit:
         if w.name != "c3_conv_2of4" or q8:
             print("bench.py: --conv-implicit runs the bf16 c3_conv_2of4 layer only", file=sys.stderr)
@@ -296,7 +308,7 @@ def main():
     if conv:
         prune_bytes = conv["T"] * w.O * 25 // 8          # the padded grid's rows
     gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else SPARSE_PEAK_TFLOPS
-    tname = w.name + ("_q8" if q8 else "_shifted" if conv else "")
+    tname = w.name + ("_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -309,6 +321,7 @@ def main():
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
                    "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0,
                    "precision": "e5m2 kept values (stochastic rounding) x e4m3 activations" if q8 else w.dtype,
+                   "g_layout": args.g_layout,
                    **({"conv": "3x3 stride 1, batch 256, 56x56x64 -> 64, no im2col matrix: 9 row-shifted views of the padded "
                                "activation grid; flops counted on the layer's own T = 802816"} if conv else {})},
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
@@ -319,11 +332,11 @@ def main():
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
                                "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
                      "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,
-                     "traffic": read_traffic(tname, "gemm"),
+                     "traffic": read_traffic(w.name if transposed else tname, "gemm"),
                      "note": "dense-equivalent flops 2*T*O*I per call; time = HIP events around the call's kernels; "
                              "peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
                              " MFMA peak (4:2 sparse MFMA executes half the products)"},
-        "roofline_prune": {"kernel": "prune_compress_q8_kernel" if q8 else
+        "roofline_prune": {"kernel": "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
                            "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(tname, "prune"),
