@@ -99,6 +99,10 @@ int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
 int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype,
                       uint64_t seed, uint32_t stream_id, int mode, void *vals, uint16_t *meta, void *hip_stream);
 
+/* The same for MVUE 1:2 (eq. (6)): equals mvue_prune_1of2 on the transposed tensor, bit for bit. */
+int mvue_prune_1of2_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype,
+                      uint64_t seed, uint32_t stream_id, void *vals, uint16_t *meta, void *hip_stream);
+
 /*
  * MVUE 1:4 prune + compress (appendix, "Additional sparsity results": MVUE 1:2 on a block of four).
  * Of every quad one element survives: position k with probability |a_k|/sum|a|, emitting

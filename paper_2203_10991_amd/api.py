@@ -40,6 +40,8 @@ def load():
     lib.mvue_prune_1of4.restype = i32
     lib.mvue_prune_2of4_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp]
     lib.mvue_prune_2of4_t.restype = i32
+    lib.mvue_prune_1of2_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp]
+    lib.mvue_prune_1of2_t.restype = i32
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
@@ -140,16 +142,29 @@ def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: in
     return _prune("2of4", g, seed, stream_id, mode, vals, meta, dense_out, want_dense)
 
 
-def mvue_prune_2of4_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, vals=None, meta=None):
-    """MVUE 2:4 prune + compress of a gradient stored transposed, gT[O x T] (tokens contiguous).  Returns (vals, meta)."""
-    lib = load()
+def _prune_transposed(gT: torch.Tensor, vals, meta):
     if not gT.is_cuda:
         raise ValueError("gT must live on the GPU")
     O, T = gT.shape
     ldt = _rowmajor(gT, "gT")
     if vals is None or meta is None:
         vals, meta = alloc_compressed(T - T % 16, O, gT.dtype, gT.device)
+    return T, O, ldt, vals, meta
+
+
+def mvue_prune_2of4_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, vals=None, meta=None):
+    """MVUE 2:4 prune + compress of a gradient stored transposed, gT[O x T] (tokens contiguous).  Returns (vals, meta)."""
+    lib = load()
+    T, O, ldt, vals, meta = _prune_transposed(gT, vals, meta)
     _check(lib.mvue_prune_2of4_t(_ptr(gT), T, O, ldt, _dtype_code(gT), seed, stream_id, mode, _ptr(vals), _ptr(meta), _stream(gT)))
+    return vals, meta
+
+
+def mvue_prune_1of2_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=None, meta=None):
+    """MVUE 1:2 prune + compress of a gradient stored transposed, gT[O x T] (tokens contiguous).  Returns (vals, meta)."""
+    lib = load()
+    T, O, ldt, vals, meta = _prune_transposed(gT, vals, meta)
+    _check(lib.mvue_prune_1of2_t(_ptr(gT), T, O, ldt, _dtype_code(gT), seed, stream_id, _ptr(vals), _ptr(meta), _stream(gT)))
     return vals, meta
 
 

@@ -112,12 +112,9 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                                          (hipStream_t)hip_stream));
 }
 
-int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id,
-                      int mode, void *vals, uint16_t *meta, void *hip_stream)
+static int prune_transposed(const char *fn, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed,
+                            uint32_t stream_id, void *vals, uint16_t *meta, void *hip_stream)
 {
-    const char *fn = "mvue_prune_2of4_t";
-    if (mode != 0 && mode != 1)
-        return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", fn, mode);
     if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
     if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16 (pad with zero tokens)", fn, (long long)T);
@@ -131,7 +128,21 @@ int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dty
     Range rin = range_of(gT, ((O - 1) * ldt + T) * es, "gT");
     Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
     if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm)) return fail(NM_ERR_ALIAS, "%s: gT, vals and meta must not overlap", fn);
-    return launched(fn, nm::launch_prune_transposed(dtype, mode, gT, T, O, ldt, seed, stream_id, vals, meta, (hipStream_t)hip_stream));
+    return launched(fn, nm::launch_prune_transposed(dtype, est, gT, T, O, ldt, seed, stream_id, vals, meta, (hipStream_t)hip_stream));
+}
+
+int mvue_prune_2of4_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id,
+                      int mode, void *vals, uint16_t *meta, void *hip_stream)
+{
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_t: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
+    return prune_transposed("mvue_prune_2of4_t", mode, gT, T, O, ldt, dtype, seed, stream_id, vals, meta, hip_stream);
+}
+
+int mvue_prune_1of2_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id,
+                      void *vals, uint16_t *meta, void *hip_stream)
+{
+    return prune_transposed("mvue_prune_1of2_t", 3, gT, T, O, ldt, dtype, seed, stream_id, vals, meta, hip_stream);
 }
 
 int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, int n, int m, void *vals,

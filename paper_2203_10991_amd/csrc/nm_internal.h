@@ -11,7 +11,7 @@ namespace nm {
 hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st);
 
-// the same 2:4 prune for a gradient stored transposed: gT [O x T], row stride ldt (est 0 optimal, 1 approx-MVUE)
+// the same prunes for a gradient stored transposed: gT [O x T], row stride ldt (est 0 optimal 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2)
 hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
                                    uint32_t stream_id, void *vals, uint16_t *meta, hipStream_t st);
 

@@ -542,8 +542,8 @@ hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O,
 }
 
 // ------------------------------------------------------------------------------------
-// MVUE 2:4 prune + compress of a gradient stored TRANSPOSED: gT is [O x T], tokens contiguous, so a quad is four
-// adjacent elements of a row.  Same estimators, same random stream and block index (blk = (t/4)*O + o) as the
+// MVUE 2:4 (or 1:2) prune + compress of a gradient stored TRANSPOSED: gT is [O x T], tokens contiguous, so a quad
+// (a pair) is four (two) adjacent elements of a row.  Same estimators, same random stream and block index (blk = (t/4)*O + o) as the
 // kernels above: the output equals theirs on the transposed tensor, bit for bit.
 // Workgroup = 16 columns o x 16 token groups; a thread owns one (o, group): it loads the group's 16 tokens as one
 // contiguous piece (16 threads of a column read 512 or 1024 consecutive bytes), decides its four quads, and the
@@ -583,17 +583,22 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
     // in one quad row share their Philox calls (one call for the optimal estimator, two for approx-MVUE), as in the
     // token-major kernels.  Lane (a, gi) makes the calls of quad row a of group gi for the wave's columns and leaves
     // the words in LDS; lane (j, gi) then picks, for each quad row, the words of its own column j.
-    constexpr int WPC = EST == 1 ? 8 : 4;                  // words per (group, quad row) of a wave's four columns
-    __shared__ __attribute__((aligned(16))) uint32_t rnd_s[4][4][16][WPC];       // [wave][quad row][group][word]
+    constexpr int WPC = EST == 1 ? 8 : 4;                  // words per (group, block row) of a wave's four columns
+    constexpr int RB = EST == 3 ? 8 : 4;                   // block rows of a group: 8 pair rows (1:2) or 4 quad rows
+    __shared__ __attribute__((aligned(16))) uint32_t rnd_s[4][RB][16][WPC];      // [wave][block row][group][word]
     {
         const int wave = tid >> 6, a = oi & 3;
-        const uint64_t blk0 = (uint64_t)(G * 4 + a) * (uint64_t)O + (uint64_t)(o - a);
 #pragma unroll
-        for (int c = 0; c < WPC / 4; ++c) {
-            uint32_t r4[4];
-            const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + c;
-            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, r4);
-            *(uint4 *)&rnd_s[wave][a][gi][4 * c] = make_uint4(r4[0], r4[1], r4[2], r4[3]);
+        for (int rb = 0; rb < RB / 4; ++rb) {
+            const int b = a + 4 * rb;
+            const uint64_t blk0 = (uint64_t)(G * RB + b) * (uint64_t)O + (uint64_t)(o - a);
+#pragma unroll
+            for (int c = 0; c < WPC / 4; ++c) {
+                uint32_t r4[4];
+                const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + c;
+                philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, r4);
+                *(uint4 *)&rnd_s[wave][b][gi][4 * c] = make_uint4(r4[0], r4[1], r4[2], r4[3]);
+            }
         }
     }
     __syncthreads();
@@ -602,6 +607,15 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
         float v0, v1; uint32_t nib;
+        if constexpr (EST == 3) {
+            // two pairs fill the two slots of quad i: the first keeps position 0 or 1, the second 2 or 3
+            uint32_t k0, k1;
+            select_1of2(__uint_as_float(elem_bits(4 * i)), __uint_as_float(elem_bits(4 * i + 1)),
+                        rnd_s[tid >> 6][2 * i][gi][oi & 3], k0, v0);
+            select_1of2(__uint_as_float(elem_bits(4 * i + 2)), __uint_as_float(elem_bits(4 * i + 3)),
+                        rnd_s[tid >> 6][2 * i + 1][gi][oi & 3], k1, v1);
+            nib = k0 | ((2u | k1) << 2);
+        } else {
         const uint32_t *rw = rnd_s[tid >> 6][i][gi];
         if constexpr (EST == 1) {
             const uint2 wab = *(const uint2 *)&rw[2 * (oi & 3)];
@@ -618,6 +632,7 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
             }
             select_2of4<DT>(Key<DT>::make(e[0], 0, 0), Key<DT>::make(e[1], 0, 1), Key<DT>::make(e[2], 0, 2), Key<DT>::make(e[3], 0, 3),
                             word, v0, v1, nib);
+        }
         }
         if constexpr (DT == NM_DT_F32) { kept[2 * i] = __float_as_uint(v0); kept[2 * i + 1] = __float_as_uint(v1); }
         else kept[i] = pack_bf16_rne(v0, v1);
@@ -657,11 +672,13 @@ static hipError_t launch_prune_t_t(const void *gT, int64_t T, int64_t O, int64_t
 hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
                                    uint32_t stream_id, void *vals, uint16_t *meta, hipStream_t st)
 {
-    if (dt == NM_DT_F32)
-        return est == 1 ? launch_prune_t_t<NM_DT_F32, 1>(gT, T, O, ldt, seed, stream_id, vals, meta, st)
-                        : launch_prune_t_t<NM_DT_F32, 0>(gT, T, O, ldt, seed, stream_id, vals, meta, st);
-    return est == 1 ? launch_prune_t_t<NM_DT_BF16, 1>(gT, T, O, ldt, seed, stream_id, vals, meta, st)
-                    : launch_prune_t_t<NM_DT_BF16, 0>(gT, T, O, ldt, seed, stream_id, vals, meta, st);
+    // est: 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2
+#define NM_T_CASE(DT_, EST_) \
+    if (dt == DT_ && est == EST_) return launch_prune_t_t<DT_, EST_>(gT, T, O, ldt, seed, stream_id, vals, meta, st)
+    NM_T_CASE(NM_DT_F32, 0); NM_T_CASE(NM_DT_F32, 1); NM_T_CASE(NM_DT_F32, 3);
+    NM_T_CASE(NM_DT_BF16, 0); NM_T_CASE(NM_DT_BF16, 1); NM_T_CASE(NM_DT_BF16, 3);
+#undef NM_T_CASE
+    return hipErrorInvalidValue;
 }
 
 // ------------------------------------------------------------------------------------

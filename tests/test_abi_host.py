@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "mvue_prune_1of2_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
                           "nm_update_gemm_q8_shifted_workspace",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
@@ -85,6 +85,10 @@ def test_transposed_prune_argument_errors(lib):
     assert call(ldt=36) == NM_ERR_ALIGN                           # 72-byte bf16 rows
     assert call(vals=P) == NM_ERR_ALIAS and call(meta=P + 0x10000) == NM_ERR_ALIAS
     assert call(T=0) == NM_OK and call(O=0) == NM_OK
+    call12 = lambda T=32, O=16, ldt=32, vals=P + 0x10000: lib.mvue_prune_1of2_t(P, T, O, ldt, 1, 0, 0, vals, P + 0x20000, None)
+    assert call12(T=8) == NM_ERR_SHAPE and b"mvue_prune_1of2_t" in lib.nm_last_error()
+    assert call12(O=4) == NM_ERR_SHAPE and call12(ldt=24) == NM_ERR_SHAPE and call12(vals=None) == NM_ERR_NULL
+    assert call12(T=0) == NM_OK
 
 
 def test_compress_argument_errors(lib):

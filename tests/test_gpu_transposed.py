@@ -1,4 +1,4 @@
-"""GPU parity of mvue_prune_2of4_t (gradient stored transposed, tokens contiguous) through the C ABI:
+"""GPU parity of mvue_prune_2of4_t and mvue_prune_1of2_t (gradient stored transposed, tokens contiguous) through the C ABI:
 vals and meta equal the CPU oracle's prune of the transposed tensor bit for bit, and so equal what
 mvue_prune_2of4 writes for it; the compressed operand then feeds the same update GEMM."""
 import numpy as np
@@ -48,6 +48,25 @@ def test_transposed_prune_bit_exact(nm, oracle, dtype, mode, shape):
     assert torch.equal(m2, m) and torch.equal(v2.view(it), v.view(it))
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", SHAPES)
+def test_transposed_prune_1of2_bit_exact(nm, oracle, dtype, shape):
+    T, O = shape
+    print(f"case 1:2 dtype={dtype} T={T} O={O}", flush=True)
+    w = synth.Workload("t", T, O, 8, dtype, "1:2", 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O + 2)
+    seed, stream = 0x77 + (5 << 40), 2
+    ov, om, _ = oracle.prune_1of2(g, seed, stream, want_dense=False)
+    v, m = nm.mvue_prune_1of2_t(to_dev(np.ascontiguousarray(g.T)), seed=seed, stream_id=stream)
+    torch.cuda.synchronize()
+    hv, hm = to_host(v), to_host(m)
+    assert first_mismatch(hm, om) is None, ("meta", first_mismatch(hm, om))
+    assert first_mismatch(_bits(hv), _bits(ov)) is None, ("vals", first_mismatch(_bits(hv), _bits(ov)))
+    v2, m2, _ = nm.mvue_prune_1of2(to_dev(g), seed=seed, stream_id=stream)
+    it = torch.int16 if dtype == "bf16" else torch.int32
+    assert torch.equal(m2, m) and torch.equal(v2.view(it), v.view(it))
+
+
 def test_transposed_prune_row_stride_and_edge_values(nm, oracle):
     """row stride larger than T; zeros, ties, infinities and subnormals in the quads"""
     T, O = 16 * 6, 24
@@ -65,6 +84,11 @@ def test_transposed_prune_row_stride_and_edge_values(nm, oracle):
         torch.cuda.synchronize()
         assert first_mismatch(to_host(m), om) is None
         assert first_mismatch(to_host(v), ov) is None
+    ov, om, _ = oracle.prune_1of2(g, 9, 1, want_dense=False)
+    v, m = nm.mvue_prune_1of2_t(wide[:, :T], seed=9, stream_id=1)
+    torch.cuda.synchronize()
+    assert first_mismatch(to_host(m), om) is None
+    assert first_mismatch(to_host(v), ov) is None
 
 
 def test_transposed_prune_feeds_the_update_gemm(nm, oracle):
