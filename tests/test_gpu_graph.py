@@ -56,3 +56,54 @@ def test_step_replays_from_a_graph(q8):
         torch.cuda.synchronize()
         assert torch.equal(dW, want_dW), f"replay {i}"
         assert torch.equal(vals.view(torch.uint8), want_vals.view(torch.uint8)), f"replay {i}"
+
+
+def test_two_host_threads_on_two_streams():
+    """The library keeps no state between calls (its error text is per thread): two host threads, each with its own
+    stream, buffers and workspace, run different layers at the same time and get what a lone run gets, bit for bit."""
+    import threading
+    import paper_2203_10991_amd as nm
+    nm.load()
+    jobs = []
+    for k, name in enumerate(["c4_vit_proj_2of4", "c4_vit_fc2_2of4"]):
+        w = synth.WORKLOADS[name]
+        T = w.T - w.T % 16
+        g, h = synth.make_device(w, seed=3 + k, device=DEV)
+        g, h = g[:T].contiguous(), h[:T].contiguous()
+        vals, meta = nm.alloc_compressed(T, w.O, g.dtype, DEV)
+        ws = torch.empty(max(16, nm.nm_update_gemm_workspace(T, w.O, w.I, g.dtype)), dtype=torch.uint8, device=DEV)
+        dW = torch.empty((w.O, w.I), dtype=torch.float32, device=DEV)
+        jobs.append(dict(g=g, h=h, vals=vals, meta=meta, ws=ws, dW=dW, seed=10 + k))
+
+    def step(j):
+        nm.mvue_prune_2of4(j["g"], seed=j["seed"], stream_id=1, vals=j["vals"], meta=j["meta"])
+        nm.nm_update_gemm(j["vals"], j["meta"], j["h"], dW=j["dW"], beta=0.0, workspace=j["ws"])
+
+    for j in jobs:                                      # lone runs
+        step(j)
+        torch.cuda.synchronize()
+        j["want"] = j["dW"].clone()
+    errors = []
+
+    def worker(j):
+        try:
+            s = torch.cuda.Stream()
+            with torch.cuda.stream(s):
+                for _ in range(20):
+                    j["dW"].fill_(float("nan"))
+                    step(j)
+                    s.synchronize()
+                    if not torch.equal(j["dW"], j["want"]):
+                        errors.append("dW differs")
+                        return
+        except Exception as e:                          # surfaces in the main thread
+            errors.append(repr(e))
+
+    threads = [threading.Thread(target=worker, args=(j,)) for j in jobs]
+    for t in threads:
+        t.start()
+    for t in threads:
+        t.join(timeout=100)
+    torch.cuda.synchronize()
+    assert not errors, errors
+    assert not any(t.is_alive() for t in threads)
