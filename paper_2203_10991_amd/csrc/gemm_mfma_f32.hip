@@ -9,11 +9,17 @@
 // Lane layouts of v_mfma_f32_32x32x2_f32 (l = lane): A value of row l%32 for reduction index l/32,
 // B value of column l%32 for reduction index l/32, D reg r = row 8*(r/4) + 4*(l/32) + r%4, column l%32.
 //
-// Workgroup = 4 waves (2 x 2), output tile 128 x 128, wave tile 64 x 64 (2 x 2 accumulator blocks).
-// The reduction axis advances one 16-token group per stage; the next stage's global loads are issued
-// into registers before the current stage's MFMAs.  Split-K over blockIdx.z as in the bf16 kernel.
+// Workgroup = 4 waves (2 x 2), output tile 128 (rows of dW) x 256 (columns), wave tile 64 x 128 (2 x 4 accumulator
+// blocks = 128 accumulator registers).  The tile is wide in the direction of h because expanding the sparse
+// operand is vector-ALU work that delays the matrix pipeline of the same SIMD: one expanded row now feeds 256 columns.
+// The reduction axis advances one 16-token group per stage through two LDS buffers (one barrier per stage); the
+// global loads of the stage after next and the register -> LDS traffic of the next stage are spread between the
+// current stage's MFMAs, and the LDS reads of step kk+1 are issued before the MFMAs of step kk.  Every thread expands half a row of the
+// sparse operand (two quads) and brings four 16-byte pieces of h.  Split-K over blockIdx.z as in the bf16 kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
+
+#include <type_traits>
 
 #include "nm_internal.h"
 
@@ -21,16 +27,18 @@ namespace nm {
 
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
-constexpr int F32_TM = 128, F32_TN = 128;
-constexpr int F32_LD = 128 + 32;      // LDS row stride in floats: the two half-waves of a fragment read hit disjoint banks
+constexpr int F32_TM = 128, F32_TN = 256;
+// LDS row strides in floats: the two half-waves of a fragment read (rows 2kk and 2kk+1) hit disjoint banks
+constexpr int F32_LDA = F32_TM + 32, F32_LDB = F32_TN + 32;
 
-__global__ __launch_bounds__(256) void update_gemm_f32_mfma_kernel(
+// (two workgroups per CU: 128 accumulator registers + at most 128 others per lane)
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(2, 2))) void update_gemm_f32_mfma_kernel(
     const float *__restrict__ vals, const uint16_t *__restrict__ meta, const float *__restrict__ h, int64_t ldh,
     float *__restrict__ out, int64_t ldo, int64_t slab_stride, int64_t n_groups, int64_t groups_per_slab,
     int64_t O, int64_t I, int accumulate)
 {
-    __shared__ __attribute__((aligned(16))) float As[16 * F32_LD];      // expanded sparse operand: [token in group][o]
-    __shared__ __attribute__((aligned(16))) float Bs[16 * F32_LD];      // h rows: [token in group][i]
+    __shared__ __attribute__((aligned(16))) float As2[2][16 * F32_LDA];  // expanded sparse operand: [token in group][o]
+    __shared__ __attribute__((aligned(16))) float Bs2[2][16 * F32_LDB];  // h rows: [token in group][i]
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int wm = wave >> 1, wn = wave & 1;
     const int64_t o0 = (int64_t)blockIdx.y * F32_TM, i0 = (int64_t)blockIdx.x * F32_TN;
@@ -38,83 +46,130 @@ __global__ __launch_bounds__(256) void update_gemm_f32_mfma_kernel(
     const int64_t g_end = min(n_groups, g_begin + groups_per_slab);
     out += (int64_t)blockIdx.z * slab_stride;
 
-    f32x16 acc[2][2];
+    f32x16 acc[2][4];
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b)
+        for (int b = 0; b < 4; ++b)
 #pragma unroll
             for (int r = 0; r < 16; ++r) acc[a][b][r] = 0.f;
 
-    // Threads 0..127 bring the sparse operand (one row of the tile each: 8 kept values + the index word of
-    // the group), threads 128..255 bring h (16 rows x 128 columns = 512 float4, four per thread).
-    const bool is_a = tid < 128;
-    const int64_t o = o0 + tid;                              // (threads of the first half only)
-    const bool o_ok = is_a && o < O;
-    const int hb = tid - 128;                                // (threads of the second half only)
-    float4 pre[4];                                           // A: kept values in pre[0], pre[1]; B: four float4 of h
-    uint32_t pre_meta = 0;
-    auto prefetch = [&](int64_t G) {
-        if (is_a) {
-            if (o_ok) {
-                const float4 *vp = (const float4 *)(vals + (G * O + o) * 8);
-                pre[0] = vp[0]; pre[1] = vp[1];
-                pre_meta = meta[G * O + o];
-            } else { pre[0] = pre[1] = make_float4(0.f, 0.f, 0.f, 0.f); pre_meta = 0x4444u; }   // positions (0,1) of every quad: zeros
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int idx = hb + 128 * e, r = idx >> 5, c4 = idx & 31;
-                const int64_t i = i0 + 4 * c4;
-                pre[e] = i < I ? *(const float4 *)(h + (G * 16 + r) * ldh + i) : make_float4(0.f, 0.f, 0.f, 0.f);
-            }
-        }
+    // sparse operand: thread = row ar of the tile, half ah of the group (quads 2ah, 2ah+1: kept values 4ah..4ah+3,
+    // index bits 8ah..8ah+7).  h: 16 rows x 256 columns = 1024 pieces of 16 bytes, four per thread.
+    const int ar = tid & 127, ah = tid >> 7;
+    // Rows >= O and columns >= I are clamped to the last valid ones (no branch in the loop): what they
+    // contribute lands in outputs that are never stored.
+    const int64_t o = min(o0 + ar, O - 1);
+    const float *a_src = vals + o * 8 + 4 * ah;
+    const uint16_t *m_src = meta + o;
+    auto b_ptr = [&](int e) {
+        const int idx = tid + 256 * e, r = idx >> 6, c4 = idx & 63;
+        return h + (int64_t)r * ldh + min(i0 + 4 * c4, I - 4);
     };
-    auto to_lds = [&]() {
-        if (is_a) {
-            const float v[8] = {pre[0].x, pre[0].y, pre[0].z, pre[0].w, pre[1].x, pre[1].y, pre[1].z, pre[1].w};
+    const float *b_src0 = b_ptr(0), *b_src1 = b_ptr(1), *b_src2 = b_ptr(2), *b_src3 = b_ptr(3);
+    // One stage's share of this thread on its way from global memory to LDS.  Two of them alternate, so a load has a
+    // whole stage (about two microseconds) to arrive.  (Separate members, no arrays: arrays here end up in LDS.)
+    struct Pre { float4 a, b0, b1, b2, b3; uint32_t meta; };
+    Pre pre_x, pre_y;
+    auto prefetch = [&](int64_t G, Pre &pre) {
+        pre.a = *(const float4 *)(a_src + G * O * 8);
+        pre.meta = (uint32_t)m_src[G * O] >> (8 * ah);
+        const int64_t step = G * 16 * ldh;
+        pre.b0 = *(const float4 *)(b_src0 + step);
+        pre.b1 = *(const float4 *)(b_src1 + step);
+        pre.b2 = *(const float4 *)(b_src2 + step);
+        pre.b3 = *(const float4 *)(b_src3 + step);
+    };
+    const int b_dst = (tid >> 6) * F32_LDB + 4 * (tid & 63);            // piece e lands 4 rows further down per e
+    // registers -> LDS in four pieces, so that the loop can spread them between its MFMAs:
+    // piece c = quad c of this thread's half row (c < 2) and h piece c
+    auto lds_piece = [&](int c, int buf, const Pre &pre) {
+        float *As = As2[buf], *Bs = Bs2[buf];
+        if (c < 2) {
+            // quad c of the half row: zeros to its four tokens, then the two kept values on top at the positions the
+            // index bits name (LDS executes a wave's writes in order); far fewer vector-ALU instructions than
+            // selecting each of the four values
+            const float v0 = c == 0 ? pre.a.x : pre.a.z, v1 = c == 0 ? pre.a.y : pre.a.w;
+            const uint32_t p0 = (pre.meta >> (4 * c)) & 3u, p1 = (pre.meta >> (4 * c + 2)) & 3u;
+            float *q = As + (8 * ah + 4 * c) * F32_LDA + ar;
 #pragma unroll
-            for (int q = 0; q < 4; ++q) {
-                const uint32_t nib = (pre_meta >> (4 * q)) & 0xfu, p0 = nib & 3u, p1 = nib >> 2;
-#pragma unroll
-                for (int p = 0; p < 4; ++p)
-                    As[(4 * q + p) * F32_LD + tid] = p0 == (uint32_t)p ? v[2 * q] : (p1 == (uint32_t)p ? v[2 * q + 1] : 0.f);
-            }
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const int idx = hb + 128 * e, r = idx >> 5, c4 = idx & 31;
-                *(float4 *)(Bs + r * F32_LD + 4 * c4) = pre[e];
-            }
+            for (int p = 0; p < 4; ++p) q[p * F32_LDA] = 0.f;
+            q[p0 * F32_LDA] = v0;
+            q[p1 * F32_LDA] = v1;
         }
+        const float4 piece = c == 0 ? pre.b0 : c == 1 ? pre.b1 : c == 2 ? pre.b2 : pre.b3;
+        *(float4 *)(Bs + b_dst + 4 * c * F32_LDB) = piece;
     };
 
-    const int rd = (lane >> 5) * F32_LD + (lane & 31);       // + 2*kk*F32_LD + block offset
-    if (g_begin < g_end) prefetch(g_begin);
-    for (int64_t G = g_begin; G < g_end; ++G) {
-        to_lds();
-        __syncthreads();
-        if (G + 1 < g_end) prefetch(G + 1);
+    const int rd_a = (lane >> 5) * F32_LDA + (lane & 31) + wm * 64;      // + 2*kk*F32_LDA + 32*a
+    const int rd_b = (lane >> 5) * F32_LDB + (lane & 31) + wn * 128;     // + 2*kk*F32_LDB + 32*b
+    float af[2][2], bf[2][4];                            // operand registers in two sets
+    auto read_step = [&](int buf, int kk, int set) {
+        const float *As = As2[buf], *Bs = Bs2[buf];
+#pragma unroll
+        for (int a = 0; a < 2; ++a) af[set][a] = As[2 * kk * F32_LDA + rd_a + a * 32];
+#pragma unroll
+        for (int b = 0; b < 4; ++b) bf[set][b] = Bs[2 * kk * F32_LDB + rd_b + b * 32];
+    };
+    // One stage: multiplies the group in LDS buffer `cur`; `next` holds the following group (loaded a stage ago) and
+    // goes to the other buffer; `after` receives the loads of the group after that.
+    // Step kk: the LDS reads of step kk+1 first (in step 7: those of the next stage's step 0), then the eight MFMAs.
+    // Behind the first two MFMAs of step 0 go the global loads, behind those of steps 1..4 one piece each of the next
+    // stage: vector-ALU and memory instructions issue while the matrix pipeline works on the MFMAs already issued.
+    // The stage's one barrier sits after step 6: by then this wave has written its pieces of the next stage and holds
+    // the operands of step 7 in registers, so past the barrier the next stage may be read and -- from its step 1
+    // on -- the buffer of this stage overwritten.
+    auto stage = [&](int64_t G, auto cur_c, const Pre &next, Pre &after) {
+        constexpr int cur = decltype(cur_c)::value;
+        // No branches in here: a branch makes the compiler merge its counts of outstanding LDS operations at the join,
+        // and the merged count makes the MFMAs behind it wait for the reads and writes just issued.  At the end of
+        // the slab the pieces, the reads of "the next stage" and the loads (of the last group again) are done all
+        // the same and nobody uses them.
 #pragma unroll
         for (int kk = 0; kk < 8; ++kk) {
-            float af[2], bf[2];
+            if (kk + 1 < 8) read_step(cur, kk + 1, (kk + 1) & 1);
+            else read_step(cur ^ 1, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);           // (keeps the reads ahead of the MFMAs: the scheduler would sink them)
 #pragma unroll
-            for (int a = 0; a < 2; ++a) af[a] = As[2 * kk * F32_LD + rd + wm * 64 + a * 32];
+            for (int b = 0; b < 2; ++b)
+                acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kk & 1][0], bf[kk & 1][b], acc[0][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk == 0) prefetch(min(G + 2, g_end - 1), after);
+            if (kk >= 1 && kk <= 4) lds_piece(kk - 1, cur ^ 1, next);
+            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-            for (int b = 0; b < 2; ++b) bf[b] = Bs[2 * kk * F32_LD + rd + wn * 64 + b * 32];
+            for (int b = 2; b < 4; ++b)
+                acc[0][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kk & 1][0], bf[kk & 1][b], acc[0][b], 0, 0, 0);
 #pragma unroll
-            for (int a = 0; a < 2; ++a)
-#pragma unroll
-                for (int b = 0; b < 2; ++b) acc[a][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[a], bf[b], acc[a][b], 0, 0, 0);
+            for (int b = 0; b < 4; ++b)
+                acc[1][b] = __builtin_amdgcn_mfma_f32_32x32x2f32(af[kk & 1][1], bf[kk & 1][b], acc[1][b], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if (kk == 6) {
+                // orders LDS traffic only: the global loads in flight stay in flight (__syncthreads() would wait for them)
+                asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
+                __builtin_amdgcn_s_barrier();
+                __builtin_amdgcn_sched_barrier(0);
+            }
         }
+    };
+    if (g_begin < g_end) {
+        prefetch(g_begin, pre_x);
+#pragma unroll
+        for (int c = 0; c < 4; ++c) lds_piece(c, 0, pre_x);
+        if (g_begin + 1 < g_end) prefetch(g_begin + 1, pre_y);
         __syncthreads();
+        read_step(0, 0, 0);
+    }
+    for (int64_t G = g_begin; G < g_end; G += 2) {
+        stage(G, std::integral_constant<int, 0>{}, pre_y, pre_x);
+        if (G + 1 < g_end) stage(G + 1, std::integral_constant<int, 1>{}, pre_x, pre_y);
     }
 
 #pragma unroll
     for (int a = 0; a < 2; ++a)
 #pragma unroll
-        for (int b = 0; b < 2; ++b) {
-            const int64_t col = i0 + wn * 64 + b * 32 + (lane & 31);
+        for (int b = 0; b < 4; ++b) {
+            const int64_t col = i0 + wn * 128 + b * 32 + (lane & 31);
 #pragma unroll
             for (int r = 0; r < 16; ++r) {
                 const int64_t row = o0 + wm * 64 + a * 32 + 8 * (r >> 2) + 4 * (lane >> 5) + (r & 3);
