@@ -27,6 +27,7 @@ DENSE_BF16_PEAK_TFLOPS = 2500.0   # MI355X dense bf16 MFMA, published
 SPARSE_PEAK_TFLOPS = 2.0 * DENSE_BF16_PEAK_TFLOPS   # 4:2 sparse MFMA skips half the products: dense-equivalent peak
 DENSE_FP8_PEAK_TFLOPS = 5000.0    # MI355X dense fp8 MFMA, published
 SPARSE_FP8_PEAK_TFLOPS = 2.0 * DENSE_FP8_PEAK_TFLOPS
+DENSE_FP32_PEAK_TFLOPS = 157.3    # MI355X dense fp32 MFMA, published
 
 
 def read_traffic(workload: str, kernel: str):
@@ -307,7 +308,9 @@ def main():
     prune_bytes = w.T * w.O * 2 + w.T * w.O // 2 + w.T * w.O // 8 if q8 else w.prune_bytes
     if conv:
         prune_bytes = conv["T"] * w.O * 25 // 8          # the padded grid's rows
-    gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else SPARSE_PEAK_TFLOPS
+    f32 = w.dtype == "f32" and not q8
+    # binary32 operands: dense fp32 MFMA (no sparse fp32 instruction exists; every product is executed)
+    gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else DENSE_FP32_PEAK_TFLOPS if f32 else SPARSE_PEAK_TFLOPS
     tname = w.name + ("_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
@@ -325,17 +328,19 @@ def main():
                    **({"conv": "3x3 stride 1, batch 256, 56x56x64 -> 64, no im2col matrix: 9 row-shifted views of the padded "
                                "activation grid; flops counted on the layer's own T = 802816"} if conv else {})},
         "prune_GBps": prune_gbps, "prune_pct_hbm_peak": 100.0 * prune_gbps / HBM_PEAK_GBPS, "prune_ms": prune_ms,
-        "gemm_TFLOPs_dense_equiv": gemm_tflops, "gemm_pct_smfmac_peak": 100.0 * gemm_tflops / gemm_peak,
+        "gemm_TFLOPs_dense_equiv": gemm_tflops, ("gemm_pct_fp32_mfma_peak" if f32 else "gemm_pct_smfmac_peak"): 100.0 * gemm_tflops / gemm_peak,
         "gemm_ms": gemm_ms,
-        "roofline": {"kernel": "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
+        "roofline": {"kernel": "update_gemm_f32_mfma_kernel (+ splitk_reduce_kernel when the plan splits the token axis)" if f32 else
+                               "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
                                "update_gemm_smfmac_q8_tall_kernel + update_gemm_smfmac_q8_kernel (rows split as in the 16-bit path)" if q8 else
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
                                "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
                      "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,
                      "traffic": read_traffic(w.name if transposed else tname, "gemm"),
-                     "note": "dense-equivalent flops 2*T*O*I per call; time = HIP events around the call's kernels; "
-                             "peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
-                             " MFMA peak (4:2 sparse MFMA executes half the products)"},
+                     "note": "flops 2*T*O*I per call; time = HIP events around the call's kernels; " +
+                             ("peak = published dense fp32 MFMA peak (binary32 operands are expanded and multiplied densely)" if f32 else
+                              "dense-equivalent; peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
+                              " MFMA peak (4:2 sparse MFMA executes half the products)")},
         "roofline_prune": {"kernel": "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
                            "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,

@@ -75,6 +75,9 @@ WORKLOADS: Dict[str, Workload] = {w.name: w for w in [
     _w("c4_vit_fc2_2of4", 12608, 768, 3072, "bf16", "2:4", 0.0, 2.0, 0.20),
     _w("c5_decoder_mlp_2of4", 32768, 28672, 8192, "bf16", "2:4", 0.0, 2.5, 0.10,
        note="large decoder MLP, hidden 8192, FFN 28672, 32768 tokens"),
+    # not one of the five: the binary32 path at a size that is not launch-bound (c1 is 2 GFLOP)
+    _w("x_fp32_mlp_2of4", 16384, 8192, 8192, "f32", "2:4", 0.0, 2.5, 0.10,
+       note="binary32 operands, 16384 tokens, 8192 x 8192"),
 ]}
 
 
