@@ -178,9 +178,10 @@ def main():
     ap.add_argument("--workload", default="c5_decoder_mlp_2of4")
     ap.add_argument("--estimator", default="optimal", choices=["optimal", "approx"],
                     help="2:4 workloads: the optimal MVUE (Sec. 4.2, default) or approx-MVUE (Sec. 4.4)")
-    ap.add_argument("--precision", default="bf16", choices=["bf16", "q8"],
+    ap.add_argument("--precision", default="bf16", choices=["bf16", "q8", "bf16x3"],
                     help="bf16: the workload's own dtype (default, the headline configuration); q8: e5m2 kept values by "
-                         "stochastic rounding + e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows)")
+                         "stochastic rounding + e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows); bf16x3: "
+                         "binary32 workloads only, the update GEMM through three bf16 terms per value on the sparse 16-bit path")
     ap.add_argument("--conv-implicit", action="store_true",
                     help="c3_conv_2of4 only: the layer's update GEMM without the im2col matrix (gradient and activations on "
                          "the zero-padded channels-last grid, nm_update_gemm_shifted) instead of the materialised one")
@@ -218,6 +219,10 @@ def main():
     else:
         prune = lambda g_, **kw: nm.mvue_prune_2of4(g_, mode=1 if approx else 0, **kw)
     q8 = args.precision == "q8"
+    x3 = args.precision == "bf16x3"
+    if x3 and (w.dtype != "f32" or args.conv_implicit):
+        print("bench.py: --precision bf16x3 is a mode of the binary32 update GEMM: pick a binary32 workload", file=sys.stderr)
+        sys.exit(2)
     conv = None
     transposed = args.g_layout == "transposed"
     if transposed:
@@ -270,7 +275,7 @@ def main():
         need = int(nm.load().nm_update_gemm_shifted_workspace(conv["T"], w.O, 64, len(conv["shifts"])))
     else:
         vals, meta = nm.alloc_compressed(w.T, w.O, g.dtype, dev)
-        need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype)
+        need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype, x3)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
     def gemm():
@@ -279,7 +284,7 @@ def main():
         elif q8:
             nm.nm_update_gemm_q8(vals, meta, h, dW=dW, alpha=1.0 / g_scale, beta=0.0, workspace=ws)
         else:
-            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws)
+            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws, f32_as_bf16x3=x3)
 
     def step(seed, evs=None):
         if evs: evs[0].record()
@@ -308,10 +313,10 @@ def main():
     prune_bytes = w.T * w.O * 2 + w.T * w.O // 2 + w.T * w.O // 8 if q8 else w.prune_bytes
     if conv:
         prune_bytes = conv["T"] * w.O * 25 // 8          # the padded grid's rows
-    f32 = w.dtype == "f32" and not q8
+    f32 = w.dtype == "f32" and not q8 and not x3
     # binary32 operands: dense fp32 MFMA (no sparse fp32 instruction exists; every product is executed)
     gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else DENSE_FP32_PEAK_TFLOPS if f32 else SPARSE_PEAK_TFLOPS
-    tname = w.name + ("_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
+    tname = w.name + ("_bf16x3" if x3 else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -320,10 +325,11 @@ def main():
         "unit": "TFLOP/s (dense-equivalent 2*T*O*I over the whole prune+GEMM step)",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
-        "dtype": "f8" if q8 else ("bf16" if w.dtype == "bf16" else "f32"), "data": "synthetic",
+        "dtype": "f8" if q8 else "bf16x3" if x3 else ("bf16" if w.dtype == "bf16" else "f32"), "data": "synthetic",
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
                    "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0,
-                   "precision": "e5m2 kept values (stochastic rounding) x e4m3 activations" if q8 else w.dtype,
+                   "precision": "e5m2 kept values (stochastic rounding) x e4m3 activations" if q8 else
+                                "binary32 tensors, three bf16 terms per value, six partial products on the sparse 16-bit path" if x3 else w.dtype,
                    "g_layout": args.g_layout,
                    **({"conv": "3x3 stride 1, batch 256, 56x56x64 -> 64, no im2col matrix: 9 row-shifted views of the padded "
                                "activation grid; flops counted on the layer's own T = 802816"} if conv else {})},
@@ -334,10 +340,13 @@ def main():
                                "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
                                "update_gemm_smfmac_q8_tall_kernel + update_gemm_smfmac_q8_kernel (rows split as in the 16-bit path)" if q8 else
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
-                               "between the 384x256 and the 256x256 tile kernel)", "bound": "mfma", "achieved": gemm_tflops,
-                     "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops / gemm_peak,
+                               "between the 384x256 and the 256x256 tile kernel)" + (" x 6 partial products, + split3_bf16_kernel" if x3 else ""),
+                     "bound": "mfma", "achieved": gemm_tflops * (6.0 if x3 else 1.0),
+                     "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops * (6.0 if x3 else 1.0) / gemm_peak,
                      "traffic": read_traffic(w.name if transposed else tname, "gemm"),
-                     "note": "flops 2*T*O*I per call; time = HIP events around the call's kernels; " +
+                     "note": ("six partial products: achieved = 6 x 2*T*O*I / time of the whole call (splits included), against the "
+                              "sparse bf16 peak; gemm_TFLOPs_dense_equiv counts 2*T*O*I once (binary32-equivalent); " if x3 else "") +
+                             "flops 2*T*O*I per call; time = HIP events around the call's kernels; " +
                              ("peak = published dense fp32 MFMA peak (binary32 operands are expanded and multiplied densely)" if f32 else
                               "dense-equivalent; peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
                               " MFMA peak (4:2 sparse MFMA executes half the products)")},

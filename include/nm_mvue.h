@@ -57,7 +57,9 @@ typedef enum {
     NM_ERR_LAUNCH = 8       /* the HIP runtime refused the launch (message has the HIP error) */
 } nm_status;
 
-typedef enum { NM_F32 = 0, NM_BF16 = 1 } nm_dtype;
+/* NM_F32_BF16X3 is an arithmetic mode of nm_update_gemm for binary32 operands (see there); the prune and compress
+ * entry points take NM_F32 or NM_BF16 only. */
+typedef enum { NM_F32 = 0, NM_BF16 = 1, NM_F32_BF16X3 = 2 } nm_dtype;
 
 /*
  * MVUE 1:2 prune + compress (Sec. 4.1, eq. (6); threshold sampling of App. B.1).
@@ -132,7 +134,12 @@ int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, 
  * Update GEMM (eq. (3)):  dW[O x I] = beta*dW + decompress(vals, meta)^T h,  beta in {0, 1},
  * accumulation in binary32.  NM_BF16 runs on sparse MFMA (4:2 along the reduction axis) and
  * skips the pruned half of the products; NM_F32 has no sparse matrix instruction on gfx950
- * and expands the operand on the fly for dense fp32 MFMA.
+ * and expands the operand on the fly for dense fp32 MFMA (every product is executed).
+ * NM_F32_BF16X3: the same binary32 tensors, but each value is split into three bf16 terms (24 significant bits)
+ * and the six partial products of first and second order run on the sparse 16-bit path, accumulated in binary32:
+ * |error| below 2^-22 of the sum of absolute products plus the accumulation's own rounding, at less than half the
+ * time of NM_F32.  It needs a larger workspace (the six bf16 planes live there).  A non-finite operand value makes the
+ * results it touches non-finite, but an infinity may come out as a NaN.
  *   workspace    device scratch of at least nm_update_gemm_workspace(T,O,I,dtype) bytes
  *                (split-K partial sums); may be NULL when that size is 0.
  * O and ldh may not exceed 2^21 (NM_ERR_UNSUPPORTED): the kernels reach a few hundred rows of h

@@ -15,7 +15,7 @@ import torch
 _HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(_HERE, "libnm_mvue.so")
 
-NM_F32, NM_BF16 = 0, 1
+NM_F32, NM_BF16, NM_F32_BF16X3 = 0, 1, 2
 _lib = None
 
 
@@ -180,13 +180,21 @@ def nm_compress(dense: torch.Tensor, n: int, m: int, vals=None, meta=None, bad_b
     return vals, meta
 
 
-def nm_update_gemm_workspace(T: int, O: int, I: int, dtype: torch.dtype) -> int:
-    return int(load().nm_update_gemm_workspace(T, O, I, NM_F32 if dtype == torch.float32 else NM_BF16))
+def _gemm_mode(dtype: torch.dtype, f32_as_bf16x3: bool) -> int:
+    if dtype == torch.float32:
+        return NM_F32_BF16X3 if f32_as_bf16x3 else NM_F32
+    return NM_BF16
+
+
+def nm_update_gemm_workspace(T: int, O: int, I: int, dtype: torch.dtype, f32_as_bf16x3: bool = False) -> int:
+    return int(load().nm_update_gemm_workspace(T, O, I, _gemm_mode(dtype, f32_as_bf16x3)))
 
 
 def nm_update_gemm(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: Optional[torch.Tensor] = None,
-                   beta: float = 0.0, workspace: Optional[torch.Tensor] = None) -> torch.Tensor:
-    """dW[O x I] = beta*dW + decompress(vals, meta)^T h  (binary32 output)."""
+                   beta: float = 0.0, workspace: Optional[torch.Tensor] = None, f32_as_bf16x3: bool = False) -> torch.Tensor:
+    """dW[O x I] = beta*dW + decompress(vals, meta)^T h  (binary32 output).
+
+    f32_as_bf16x3 (binary32 tensors only): multiply through three bf16 terms per value on the sparse 16-bit path."""
     lib = load()
     G, O, _ = vals.shape
     T, I = h.shape
@@ -196,11 +204,13 @@ def nm_update_gemm(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: 
     if dW is None:
         dW = torch.empty((O, I), dtype=torch.float32, device=h.device)
     lddw = _rowmajor(dW, "dW")
-    need = nm_update_gemm_workspace(T, O, I, h.dtype)
+    if vals.dtype != h.dtype:
+        raise TypeError("vals and h must have the same dtype")
+    need = nm_update_gemm_workspace(T, O, I, h.dtype, f32_as_bf16x3)
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=h.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.nm_update_gemm(_ptr(vals), _ptr(meta), _ptr(h), ldh, _ptr(dW), lddw, T, O, I, _dtype_code(h),
+    _check(lib.nm_update_gemm(_ptr(vals), _ptr(meta), _ptr(h), ldh, _ptr(dW), lddw, T, O, I, _gemm_mode(h.dtype, f32_as_bf16x3),
                               float(beta), _ptr(workspace), wbytes, _stream(h)))
     return dW
 

@@ -21,7 +21,7 @@ int fail(int code, const char *fmt, ...)
     return code;
 }
 
-inline int64_t esize(int dt) { return dt == NM_F32 ? 4 : 2; }
+inline int64_t esize(int dt) { return dt == NM_BF16 ? 2 : 4; }
 inline bool aligned16(const void *p) { return ((uintptr_t)p & 15u) == 0; }
 
 struct Range { uintptr_t lo, hi; const char *name; };
@@ -158,7 +158,7 @@ int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, 
 
 size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype)
 {
-    if (T < 0 || O < 0 || I < 0 || (dtype != NM_F32 && dtype != NM_BF16)) return 0;
+    if (T < 0 || O < 0 || I < 0 || (dtype != NM_F32 && dtype != NM_BF16 && dtype != NM_F32_BF16X3)) return 0;
     return nm::update_gemm_workspace(dtype, T, O, I);
 }
 
@@ -167,7 +167,8 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
                    void *hip_stream)
 {
     const char *fn = "nm_update_gemm";
-    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (dtype != NM_F32 && dtype != NM_BF16 && dtype != NM_F32_BF16X3)
+        return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0), NM_BF16 (1) or NM_F32_BF16X3 (2)", fn, dtype);
     if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16", fn, (long long)T);
     if (O % 8 || I % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld and I=%lld must be multiples of 8", fn, (long long)O, (long long)I);
@@ -197,6 +198,12 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
         if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
         Range rw = range_of(workspace, (int64_t)need, "workspace");
         if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+        if (T > 0) {
+            const int64_t es = esize(dtype);
+            if (overlap(rw, range_of(vals, T / 2 * O * es, "vals")) || overlap(rw, range_of(meta, T / 16 * O * 2, "meta")) ||
+                overlap(rw, range_of(h, ((T - 1) * ldh + I) * es, "h")))
+                return fail(NM_ERR_ALIAS, "%s: workspace must not overlap an input", fn);
+        }
     }
     return launched(fn, nm::launch_update_gemm(dtype, vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace,
                                                workspace_bytes, (hipStream_t)hip_stream));

@@ -5,6 +5,7 @@
 
 #define NM_DT_F32 0
 #define NM_DT_BF16 1
+#define NM_DT_F32_BF16X3 2   // update GEMM only: binary32 operands, multiplied as three bf16 terms each
 
 namespace nm {
 
@@ -39,6 +40,12 @@ hipError_t launch_update_gemm_f32(const void *vals, const uint16_t *meta, const 
                                   int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
                                   hipStream_t st);
 size_t update_gemm_f32_workspace(int64_t T, int64_t O, int64_t I);
+
+// binary32 operands split into three bf16 terms each, six runs of the 16-bit sparse GEMM (gemm_f32_split.hip)
+hipError_t launch_update_gemm_f32_split(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
+                                        int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
+                                        hipStream_t st);
+size_t update_gemm_f32_split_workspace(int64_t T, int64_t O, int64_t I);
 hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
                                 int accumulate, float alpha, hipStream_t st);
 

@@ -153,3 +153,58 @@ def test_update_gemm_is_bitwise_reproducible(nm, dtype, T, O, I):
         again = call()
         torch.cuda.synchronize()
         assert torch.equal(again.view(torch.int32), first.view(torch.int32)), (dtype, T, O, I, k)
+
+
+def split_case(nm, oracle, T, O, I, seed, beta=0.0, sigma=2.5, sample=None):
+    """binary32 tensors through the three-bf16-term mode of nm_update_gemm, against the oracle's binary64 sums at the
+    binary32 tolerance (the dropped third-order products are below 2^-24 of a product)"""
+    w = synth.Workload(f"x3_{T}x{O}x{I}", T, O, I, "f32", "2:4", 0.0, sigma, 0.3)
+    g, h = synth.make_g(w, seed), synth.make_h(w, seed)
+    ov, om, _ = oracle.prune_2of4(g, seed, 0)
+    prior = np.random.default_rng(1).standard_normal((O, I)).astype(np.float32) if beta else None
+    v, m, _ = nm.mvue_prune_2of4(to_dev(g), seed=seed, stream_id=0)
+    dW = to_dev(prior) if beta else torch.full((O, I), float("nan"), device=DEV)
+    nm.nm_update_gemm(v, m, to_dev(h), dW=dW, beta=beta, f32_as_bf16x3=True)
+    torch.cuda.synchronize()
+    got = dW.cpu().numpy().astype(np.float64)
+    assert np.isfinite(got).all()
+    if sample is None:
+        want, wabs = oracle.update_gemm(ov, om, h, beta=beta, dW_in=prior)
+        if beta:
+            wabs = wabs + np.abs(prior)
+    else:
+        rng = np.random.default_rng(seed)
+        oi = np.stack([rng.integers(0, O, sample), rng.integers(0, I, sample)], axis=1)
+        want, wabs = oracle.update_gemm_entries(ov, om, h, oi)
+        got = got[oi[:, 0], oi[:, 1]]
+    rel = float((np.abs(got - want) / np.maximum(wabs, 1e-300)).max())
+    print(f"bf16x3 T={T} O={O} I={I} beta={beta}: max |err|/sum|ab| = {rel:.3e}", flush=True)
+    assert rel <= TOL["f32"]
+
+
+@pytest.mark.parametrize("T,O,I", [(64, 64, 64), (16, 8, 8), (16 * 11, 8 * 9, 8 * 7), (16 * 33, 64 * 3 + 8, 64 * 2 + 24),
+                                   (1024, 256, 320), (4096, 64, 576)])
+def test_update_gemm_f32_as_three_bf16_terms(nm, oracle, T, O, I):
+    split_case(nm, oracle, T, O, I, seed=T + I)
+
+
+def test_update_gemm_f32_as_three_bf16_terms_beta_one_and_wide_range(nm, oracle):
+    split_case(nm, oracle, 16 * 20, 136, 96, seed=2, beta=1.0)
+    split_case(nm, oracle, 512, 128, 128, seed=3, sigma=6.0)           # magnitudes over many binades
+    split_case(nm, oracle, 2048, 16 * 256, 8 * 256, seed=4, sample=2000)  # large-tile kernels
+
+
+def test_update_gemm_f32_split_special_values(nm):
+    """an infinity in the compressed operand makes its row of dW non-finite (infinity times a zero low-order term of h
+    is a NaN, so it need not stay an infinity); the other rows are untouched"""
+    T, O, I = 64, 16, 16
+    g = torch.randn((T, O), device=DEV)
+    h = torch.rand((T, I), device=DEV) + 0.5
+    v, m, _ = nm.mvue_prune_2of4(g, seed=1, stream_id=0)
+    v[0, 3, 0] = float("inf")
+    dW = nm.nm_update_gemm(v, m, h, f32_as_bf16x3=True)
+    ref = nm.nm_update_gemm(v, m, h)
+    torch.cuda.synchronize()
+    assert not torch.isfinite(dW[3]).any()
+    keep = [r for r in range(O) if r != 3]
+    assert torch.allclose(dW[keep], ref[keep], rtol=1e-5, atol=1e-5)
