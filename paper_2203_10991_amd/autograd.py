@@ -28,7 +28,9 @@ class NMConfig:
     seed: int = 0              # base seed of the run
     stream_id: int = 0         # one per layer: independent random streams
     reuse_every: int = 1       # iterations that share one set of random samples (App. B.1)
-    precision: str = "native"  # "native": the tensors' own dtype; "q8": 2:4 with e5m2 kept values (stochastic rounding)
+    # "native": the tensors' own dtype; "q8": 2:4 with e5m2 kept values (stochastic rounding) and e4m3 activations;
+    # "bf16x3": float32 tensors, the update GEMM through three bf16 terms per value on the sparse 16-bit path
+    precision: str = "native"
                                # and e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows)
     step: int = 0              # iteration counter; advance() once per optimizer step
 
@@ -62,7 +64,9 @@ def _update_gemm(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Ten
         vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
     else:
         raise ValueError(f"unknown N:M pattern {cfg.nm!r}")
-    return api.nm_update_gemm(vals, meta, h2)
+    if cfg.precision == "bf16x3" and g2.dtype != torch.float32:
+        raise TypeError('precision="bf16x3" is a mode for float32 tensors')
+    return api.nm_update_gemm(vals, meta, h2, f32_as_bf16x3=cfg.precision == "bf16x3")
 
 
 def padded_rows(t_nchw: torch.Tensor, pad: int):

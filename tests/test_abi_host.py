@@ -120,6 +120,12 @@ def test_gemm_argument_errors(lib):
     # binary32 problems with few output tiles split the reduction axis as well
     assert lib.nm_update_gemm_workspace(1024, 1024, 1024, 0) == 8 * 1024 * 1024 * 4
     assert gemm(T=1024, O=1024, I=1024, ldh=1024, lddw=1024, dt=0, dW=P + (1 << 40)) == NM_ERR_WORKSPACE
+    # mode 2 (binary32 tensors as three bf16 terms): six bf16 planes live in the workspace, so it is never optional
+    need = lib.nm_update_gemm_workspace(64, 32, 64, 2)
+    assert need >= 3 * (32 * 32 * 2) + 3 * (64 * 64 * 2)
+    assert gemm(dt=2, ldh=64, dW=P + (1 << 40)) == NM_ERR_WORKSPACE
+    assert lib.nm_update_gemm(P, P + 0x10000, P + 0x20000, 64, P + (1 << 40), 64, 64, 32, 64, 2, 0.0, P + 0x10000, need, None) == NM_ERR_ALIAS
+    assert lib.nm_update_gemm_workspace(64, 32, 64, 3) == 0
 
 
 def test_q8_argument_errors(lib):

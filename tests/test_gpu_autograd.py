@@ -14,13 +14,14 @@ def bits(t):
     return to_host(t.contiguous())
 
 
-@pytest.mark.parametrize("dtype,nmode,mode", [(torch.bfloat16, "2:4", 0), (torch.bfloat16, "2:4", 1),
-                                              (torch.float32, "1:2", 0), (torch.float32, "2:4", 0)])
-def test_linear_update_phase_matches_oracle(oracle, dtype, nmode, mode):
+@pytest.mark.parametrize("dtype,nmode,mode,precision", [(torch.bfloat16, "2:4", 0, "native"), (torch.bfloat16, "2:4", 1, "native"),
+                                                        (torch.float32, "1:2", 0, "native"), (torch.float32, "2:4", 0, "native"),
+                                                        (torch.float32, "2:4", 0, "bf16x3"), (torch.float32, "1:2", 0, "bf16x3")])
+def test_linear_update_phase_matches_oracle(oracle, dtype, nmode, mode, precision):
     from paper_2203_10991_amd.autograd import NMConfig, NMLinear
     torch.manual_seed(0)
     B, S, I, O = 3, 37, 72, 40                      # T = 111: padded to 112 inside
-    cfg = NMConfig(nm=nmode, mode=mode, seed=5, stream_id=2)
+    cfg = NMConfig(nm=nmode, mode=mode, seed=5, stream_id=2, precision=precision)
     layer = NMLinear(I, O, bias=True, cfg=cfg, device=DEV, dtype=dtype)
     x = torch.randn(B, S, I, device=DEV, dtype=dtype, requires_grad=True)
     gy = (torch.randn(B, S, O, device=DEV) * torch.exp(2 * torch.randn(B, S, O, device=DEV))).to(dtype)
