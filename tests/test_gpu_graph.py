@@ -107,3 +107,52 @@ def test_two_host_threads_on_two_streams():
     torch.cuda.synchronize()
     assert not errors, errors
     assert not any(t.is_alive() for t in threads)
+
+
+def test_independent_layers_replay_from_a_branched_graph():
+    """Two layers captured as parallel branches of one graph (a second stream forks from and joins the capture
+    stream): every replay, with eager work and synchronisations in between, equals the eager results bit for bit."""
+    import paper_2203_10991_amd as nm
+    nm.load()
+    jobs = []
+    for k, name in enumerate(["c4_vit_qkv_2of4", "c4_vit_fc2_1of2"]):
+        w = synth.WORKLOADS[name]
+        T = w.T - w.T % 16
+        g, h = synth.make_device(w, seed=7 + k, device=DEV)
+        g, h = g[:T].contiguous(), h[:T].contiguous()
+        vals, meta = nm.alloc_compressed(T, w.O, g.dtype, DEV)
+        ws = torch.empty(max(16, nm.nm_update_gemm_workspace(T, w.O, w.I, g.dtype)), dtype=torch.uint8, device=DEV)
+        dW = torch.empty((w.O, w.I), dtype=torch.float32, device=DEV)
+        prune = nm.mvue_prune_1of2 if w.nm == "1:2" else nm.mvue_prune_2of4
+        jobs.append(dict(g=g, h=h, vals=vals, meta=meta, ws=ws, dW=dW, prune=prune))
+
+    def layer(j):
+        j["prune"](j["g"], seed=21, stream_id=3, vals=j["vals"], meta=j["meta"])
+        nm.nm_update_gemm(j["vals"], j["meta"], j["h"], dW=j["dW"], beta=0.0, workspace=j["ws"])
+
+    for j in jobs:
+        layer(j)
+    torch.cuda.synchronize()
+    want = [j["dW"].clone() for j in jobs]
+    main, branch = torch.cuda.Stream(), torch.cuda.Stream()
+    with torch.cuda.stream(main):
+        for j in jobs:
+            layer(j)                                    # warm-up on the capture stream
+        main.synchronize()
+        graph = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(graph, stream=main):
+            branch.wait_stream(main)
+            layer(jobs[0])
+            with torch.cuda.stream(branch):
+                layer(jobs[1])
+            main.wait_stream(branch)
+    for i in range(4):
+        for j in jobs:
+            j["dW"].fill_(float("nan"))
+            j["vals"].zero_()
+            j["ws"].zero_()
+        torch.cuda.synchronize()
+        graph.replay()
+        torch.cuda.synchronize()
+        for j, x in zip(jobs, want):
+            assert torch.equal(j["dW"], x), f"replay {i}"
