@@ -460,6 +460,28 @@ def main():
         del src, dst
     except Exception as e:
         out["roofline_prune"]["device_copy_GBps_measured"] = None
+    # Context, not the product path: the vendor library's DENSE update GEMM g^T h on the unpruned gradient, same
+    # tensors and dtype (what the update phase costs without the method).  Not run under a profiler's counters.
+    if not (conv or q8 or transposed or args.pmc_calibration) and g is not None and h is not None:
+        try:
+            dense_out = torch.empty((w.O, w.I), dtype=g.dtype, device=dev)
+            gt = g.t()
+            for _ in range(2):
+                torch.mm(gt, h, out=dense_out)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(5):
+                torch.mm(gt, h, out=dense_out)
+            e1.record()
+            torch.cuda.synchronize()
+            dense_ms = e0.elapsed_time(e1) / 5
+            out["dense_update_gemm_context"] = {
+                "what": "torch.mm(g.t(), h) on the unpruned gradient (vendor dense GEMM, output in the tensors' dtype)",
+                "ms": dense_ms, "TFLOPs": flops / (dense_ms * 1e-3) / 1e12,
+                "step_speedup_over_dense": dense_ms / ms_step}
+            del dense_out
+        except Exception as e:
+            out["dense_update_gemm_context"] = {"error": repr(e)[:200]}
     if args.pmc_calibration:
         src = torch.ones(1 << 28, dtype=torch.float32, device=dev)
         dst = torch.empty_like(src)
