@@ -214,3 +214,28 @@ def test_shifted_gemm_argument_errors(lib):
     need = lib.nm_update_gemm_shifted_workspace(65536, 64, 64, 9)
     assert need > 0 and need % (64 * 576 * 4) == 0
     assert call(T=65536, cb=64, ldx=64, lddw=576, meta=P + 0x10000000, x=P + 0x20000000, dW=P + 0x40000000) == NM_ERR_WORKSPACE
+
+
+def test_workspace_queries_over_random_shapes(lib):
+    """The workspace a plan asks for is a whole number of partial dW slabs (or nothing), for every kernel family;
+    a plan never asks for more slabs than there are token groups."""
+    import random
+    rnd = random.Random(5)
+    for _ in range(400):
+        T = 32 * rnd.randint(1, 4000)
+        O = 8 * rnd.randint(1, 600)
+        I = 16 * rnd.randint(1, 300)
+        slab = O * I * 4
+        for need, groups in ((lib.nm_update_gemm_workspace(T, O, I, 1), T // 16),
+                             (lib.nm_update_gemm_workspace(T, O, I, 0), T // 16),
+                             (lib.nm_update_gemm_q8_workspace(T, O, I), T // 32)):
+            assert need % slab == 0, (T, O, I, need)
+            assert need // slab <= groups, (T, O, I, need)
+            assert need // slab != 1                      # one slab needs no second pass
+        cb = 8 * rnd.randint(1, 64)
+        n = rnd.choice([1, 9, 25])
+        need = lib.nm_update_gemm_shifted_workspace(T, O, cb, n)
+        assert need % (O * cb * n * 4) == 0 and need // (O * cb * n * 4) <= T // 16
+        # the three-term mode holds six bf16 planes besides the 16-bit kernel's own workspace
+        need3 = lib.nm_update_gemm_workspace(T, O, I, 2)
+        assert need3 >= 3 * (T // 2 * O * 2) + 3 * (T * I * 2) + lib.nm_update_gemm_workspace(T, O, I, 1)
