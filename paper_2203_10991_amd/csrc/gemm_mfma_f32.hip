@@ -14,8 +14,9 @@
 // operand is vector-ALU work that delays the matrix pipeline of the same SIMD: one expanded row now feeds 256 columns.
 // The reduction axis advances one 16-token group per stage through two LDS buffers (one barrier per stage); the
 // global loads of the stage after next and the register -> LDS traffic of the next stage are spread between the
-// current stage's MFMAs, and the LDS reads of step kk+1 are issued before the MFMAs of step kk.  Every thread expands half a row of the
-// sparse operand (two quads) and brings four 16-byte pieces of h.  Split-K over blockIdx.z as in the bf16 kernel.
+// current stage's MFMAs, and the LDS reads of step kk+1 are issued before the MFMAs of step kk.  Every thread
+// expands half a row of the sparse operand (two quads) and brings four 16-byte pieces of h.  Split-K over
+// blockIdx.z as in the bf16 kernel.
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
