@@ -84,6 +84,8 @@ def lib():
         _lib.oracle_block_r16_pair.restype = None
         _lib.oracle_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, flt, vp, vp]
         _lib.oracle_prune_2of4_q8.restype = i32
+        _lib.oracle_prune_1of2_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, flt, vp, vp]
+        _lib.oracle_prune_1of2_q8.restype = i32
         _lib.oracle_nm_decompress_q8.argtypes = [vp, vp, i64, i64, vp]
         _lib.oracle_nm_decompress_q8.restype = None
         _lib.oracle_update_gemm_q8.argtypes = [vp, vp, vp, i64, i64, i64, i64, dbl, vp, i64, vp, vp]
@@ -311,6 +313,19 @@ def prune_2of4_q8(g: np.ndarray, seed: int = 0, stream_id: int = 0, mode: int = 
                                     C.c_float(float(scale)), _p(vals8), _p(meta32))
     if rc != 0:
         raise ValueError("oracle_prune_2of4_q8: bad shape or mode")
+    return vals8, meta32
+
+
+def prune_1of2_q8(g: np.ndarray, seed: int = 0, stream_id: int = 0, scale: float = 1.0):
+    """MVUE 1:2 with e5m2 output.  g: [T, O] float32 or uint16 (bf16 bits), T % 32 == 0.  Returns (vals8, meta32)."""
+    g = np.ascontiguousarray(g)
+    T, O = g.shape
+    vals8 = np.zeros((T // 32, O, 16), dtype=np.uint8)
+    meta32 = np.zeros((T // 32, O), dtype=np.uint32)
+    rc = lib().oracle_prune_1of2_q8(_p(g), T, O, O, _dt(g), int(seed), int(stream_id), C.c_float(float(scale)),
+                                    _p(vals8), _p(meta32))
+    if rc != 0:
+        raise ValueError("oracle_prune_1of2_q8: bad shape")
     return vals8, meta32
 
 

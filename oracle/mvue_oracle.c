@@ -736,6 +736,39 @@ int oracle_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int d
     return 0;
 }
 
+/*
+ * MVUE 1:2 prune (Sec. 4.1, eq. (6)) with 8-bit output, in the same 8-bit group format: quad i of a group holds
+ * the pairs 2i and 2i+1; the kept value of the first pair (position 0 or 1) is slot 2i, that of the second
+ * (position 2 or 3) slot 2i+1.  Selection and value are those of oracle_prune_1of2 (same random stream, block
+ * index = pair row * O + column), taken in binary32 before any storage rounding; the value is multiplied by
+ * `scale` and rounded stochastically to e5m2 with the LOW half of the pair block's rounding word
+ * (oracle_block_r16_pair with the pair's block index).
+ */
+int oracle_prune_1of2_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                         uint64_t seed, uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32)
+{
+    if (T % 32 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 32; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint32_t md = 0;
+            for (int p = 0; p < 16; ++p) {                 /* pair p of the group: tokens 32G + 2p, 32G + 2p + 1 */
+                int64_t pr = G * 16 + p, t0 = pr * 2;
+                uint64_t blk = (uint64_t)pr * (uint64_t)O + (uint64_t)o;
+                float x[2] = { load_elem(g, dt, t0 * ldg + o), load_elem(g, dt, (t0 + 1) * ldg + o) };
+                int k; float v;
+                oracle_select_1of2(x, u24_to_eps(oracle_block_u24(seed, stream_id, blk)), &k, &v);
+                uint32_t r[2];
+                oracle_block_r16_pair(seed, stream_id, blk, r);
+                vals8[(G * O + o) * 16 + p] = oracle_sr_e5m2(v * scale, r[0]);
+                md |= (uint32_t)(((p & 1) << 1) | k) << (2 * p);
+            }
+            meta32[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
 /* expand the 8-bit group format to a dense binary64 [T x O] tensor (decoded e5m2 values, pruned positions 0) */
 void oracle_nm_decompress_q8(const uint8_t *vals8, const uint32_t *meta32, int64_t T, int64_t O, double *dense)
 {

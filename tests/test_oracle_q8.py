@@ -204,3 +204,58 @@ def test_q8_prune_rejects_bad_shapes(oracle):
         oracle.prune_2of4_q8(g, mode=0)          # 48 is not a multiple of 32
     with pytest.raises(ValueError):
         oracle.prune_2of4_q8(_inputs(32, 8), mode=2)
+
+
+def test_q8_prune_1of2_selects_like_the_16_bit_path_and_rounds_to_a_neighbour(oracle):
+    """MVUE 1:2 with e5m2 output: the positions are those of the pinned 16-bit 1:2 prune for the same seed, every
+    code is a neighbour of scale * (|a1| + |a2|) with the kept element's sign, and the layout is the 2:4 container."""
+    T, O, scale = 64, 24, 8.0
+    g = _inputs(T, O)
+    vals8, meta32 = oracle.prune_1of2_q8(g, seed=11, stream_id=2, scale=scale)
+    g32 = (g.astype(np.uint32) << 16).view(np.float32)
+    vals, meta = oracle.prune_1of2(g32, seed=11, stream_id=2)[:2]
+    lo16, hi16 = meta[0::2].astype(np.uint32), meta[1::2].astype(np.uint32)
+    assert np.array_equal(meta32, lo16 | (hi16 << 16))
+    kept = np.concatenate([vals[0::2], vals[1::2]], axis=2)
+    dec = _torch_decode(torch.float8_e5m2)[vals8]
+    scaled = (kept * np.float32(scale)).astype(np.float32).astype(np.float64)
+    for q, x in zip(dec.ravel(), scaled.ravel()):
+        if abs(x) >= 57344.0:
+            assert abs(q) == 57344.0
+            continue
+        lo, hi, _ = _neighbours(abs(x))
+        assert abs(q) in (lo, hi) and (q == 0 or np.sign(q) == np.sign(x))
+    # every quad keeps one element of its first pair and one of its second
+    for i in range(8):
+        nib = (meta32 >> np.uint32(4 * i)) & np.uint32(15)
+        assert np.all((nib & 3) <= 1) and np.all((nib >> 2) >= 2)
+    # the rounding word is the LOW half of the pair block's word in the rounding domain
+    G, o, p = 1, 5, 7
+    blk = (G * 16 + p) * O + o
+    r_lo, _ = oracle.block_r16_pair(11, 2, blk)
+    x = np.float32(kept[G, o, p]) * np.float32(scale)
+    assert int(vals8[G, o, p]) == oracle.sr_e5m2(float(x), r_lo)
+
+
+def test_q8_prune_1of2_is_unbiased_over_seeds(oracle):
+    T, O = 32, 16
+    g = _inputs(T, O, seed=4)
+    g64 = (g.astype(np.uint32) << 16).view(np.float32).astype(np.float64)
+    scale = 2.0 ** np.floor(np.log2(57344.0 / (2.0 * np.abs(g64).max())))
+    n = 3000
+    acc = np.zeros((T, O))
+    for s in range(n):
+        d = oracle.nm_decompress_q8(*oracle.prune_1of2_q8(g, seed=s, stream_id=0, scale=scale)) / scale
+        acc += d
+    mean = acc / n
+    # 5-sigma band from the ANALYTIC variance of the selection, |a||b| per element of a pair (Sec. 4.1) -- an element
+    # that is kept with probability 1e-6 never shows up in 3000 draws, so a sampled variance would be zero -- plus
+    # the rounding step's own variance, at most (an e5m2 step = a quarter of the value)^2 / 4
+    a = np.abs(g64)
+    partner = a.reshape(T // 2, 2, O)[:, ::-1, :].reshape(T, O)
+    s2 = (a + partner) ** 2
+    var = a * partner + np.where(a > 0, a / np.maximum(a + partner, 1e-300), 0.0) * s2 / 64.0
+    tol = 5.0 * np.sqrt(var / n) + 1e-4 * a + 1e-12
+    assert np.all(np.abs(mean - g64) <= tol)
+    big = a * partner > 0
+    assert np.abs(mean - g64)[big].max() > 0              # (and it is a random estimate, not a copy)
