@@ -196,6 +196,16 @@ int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dty
                        uint8_t *vals8, uint32_t *meta32, void *hip_stream);
 
 /*
+ * The same for MVUE 1:2 (eq. (6)): quad i of a group holds the pairs 2i and 2i+1, the kept value of the first is
+ * slot 2i (position 0 or 1), that of the second slot 2i+1 (position 2 or 3).  Selection as in mvue_prune_1of2 (same
+ * stream, block index = pair row * O + o); the value, times scale, is rounded with the LOW half of the pair block's
+ * rounding word (same counter layout as above, last counter word 2).  Consumed by nm_update_gemm_q8.
+ */
+int mvue_prune_1of2_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                       uint64_t seed, uint32_t stream_id, float scale,
+                       uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+
+/*
  * Update GEMM (eq. (3)) on the 8-bit operands:
  *     dW[O x I] = beta*dW + alpha * decompress(vals8, meta32)^T h8,   beta in {0, 1},
  * h8 [T x I] e4m3 with row stride ldh (bytes = elements), products exact and accumulation in binary32

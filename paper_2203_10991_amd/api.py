@@ -54,6 +54,8 @@ def load():
     lib.nm_update_gemm_q8_shifted_workspace.argtypes = [i64, i64, i64, i32]
     lib.nm_update_gemm_q8_shifted_workspace.restype = sz
     lib.mvue_prune_2of4_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp]
+    lib.mvue_prune_1of2_q8.argtypes = [vp, i64, i64, i64, i32, u64, u32, f32, vp, vp, vp]
+    lib.mvue_prune_1of2_q8.restype = i32
     lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
     for f in (lib.mvue_prune_1of2, lib.mvue_prune_2of4, lib.nm_compress, lib.nm_update_gemm, lib.mvue_prune_2of4_q8,
@@ -234,6 +236,20 @@ def mvue_prune_2of4_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode:
     if vals8 is None or meta32 is None:
         vals8, meta32 = alloc_compressed_q8(T - T % 32, O, g.device)
     _check(lib.mvue_prune_2of4_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, float(scale),
+                                  _ptr(vals8), _ptr(meta32), _stream(g)))
+    return vals8, meta32
+
+
+def mvue_prune_1of2_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, scale: float = 1.0, vals8=None, meta32=None):
+    """MVUE 1:2 prune of g[T x O] along T with kept values scaled and rounded stochastically to e5m2.  Returns (vals8, meta32)."""
+    lib = load()
+    if not g.is_cuda:
+        raise ValueError("g must live on the GPU")
+    T, O = g.shape
+    ldg = _rowmajor(g, "g")
+    if vals8 is None or meta32 is None:
+        vals8, meta32 = alloc_compressed_q8(T - T % 32, O, g.device)
+    _check(lib.mvue_prune_1of2_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, float(scale),
                                   _ptr(vals8), _ptr(meta32), _stream(g)))
     return vals8, meta32
 

@@ -28,10 +28,10 @@ class NMConfig:
     seed: int = 0              # base seed of the run
     stream_id: int = 0         # one per layer: independent random streams
     reuse_every: int = 1       # iterations that share one set of random samples (App. B.1)
-    # "native": the tensors' own dtype; "q8": 2:4 with e5m2 kept values (stochastic rounding) and e4m3 activations;
-    # "bf16x3": float32 tensors, the update GEMM through three bf16 terms per value on the sparse 16-bit path
+    # "native": the tensors' own dtype; "q8": e5m2 kept values (stochastic rounding) and e4m3 activations on the 8-bit
+    # sparse MFMA (Sec. 5, 8-bit rows); "bf16x3": float32 tensors, the update GEMM through three bf16 terms per value
+    # on the sparse 16-bit path
     precision: str = "native"
-                               # and e4m3 activations on the 8-bit sparse MFMA (Sec. 5, 8-bit rows)
     step: int = 0              # iteration counter; advance() once per optimizer step
 
     def current_seed(self) -> int:
@@ -113,9 +113,9 @@ def pow2_scale(t: torch.Tensor, top: float) -> float:
 
 def _update_gemm_q8(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Tensor:
     """The 8-bit update phase: per-tensor power-of-two scales from the current maxima (a kept value is at most the
-    sum of its quad's magnitudes, hence the factor 4), activations cast to e4m3 by torch, everything else in the library."""
-    if cfg.nm != "2:4":
-        raise ValueError("the 8-bit update phase exists for 2:4 only")
+    sum of its block's magnitudes, hence the factor 4 or 2), activations cast to e4m3 by torch, everything else in the library."""
+    if cfg.nm not in ("2:4", "1:2"):
+        raise ValueError(f"unknown N:M pattern {cfg.nm!r}")
     T, O = g2.shape
     I = h2.shape[1]
     if I % 16:
@@ -124,10 +124,13 @@ def _update_gemm_q8(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.
     if pad:
         g2 = F.pad(g2, (0, 0, 0, pad))
         h2 = F.pad(h2, (0, 0, 0, pad))
-    sg = pow2_scale(g2, 57344.0 / 4.0)
+    sg = pow2_scale(g2, 57344.0 / (4.0 if cfg.nm == "2:4" else 2.0))    # (1:2: the sum of a pair's magnitudes)
     sh = pow2_scale(h2, 448.0)
     h8 = (h2.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8)
-    v8, m32 = api.mvue_prune_2of4_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
+    if cfg.nm == "1:2":
+        v8, m32 = api.mvue_prune_1of2_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, scale=sg)
+    else:
+        v8, m32 = api.mvue_prune_2of4_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
     return api.nm_update_gemm_q8(v8, m32, h8, alpha=1.0 / (sg * sh))
 
 

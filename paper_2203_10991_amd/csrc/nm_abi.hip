@@ -260,12 +260,9 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
                                                               workspace, (hipStream_t)hip_stream));
 }
 
-int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
-                       int mode, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+static int prune_q8(const char *fn, int est, const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed,
+                    uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
 {
-    const char *fn = "mvue_prune_2of4_q8";
-    if (mode != 0 && mode != 1)
-        return fail(NM_ERR_UNSUPPORTED, "%s: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", fn, mode);
     if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
     if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32 (pad with zero rows)", fn, (long long)T);
     if (!(scale > 0.0f) || !(scale < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: scale must be positive and finite", fn);
@@ -276,8 +273,22 @@ int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dty
     Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
     if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm))
         return fail(NM_ERR_ALIAS, "%s: g, vals8 and meta32 must not overlap", fn);
-    return launched(fn, nm::launch_prune_q8(dtype, mode, g, T, O, ldg, seed, stream_id, scale, vals8, meta32,
+    return launched(fn, nm::launch_prune_q8(dtype, est, g, T, O, ldg, seed, stream_id, scale, vals8, meta32,
                                             (hipStream_t)hip_stream));
+}
+
+int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                       int mode, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_q8: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
+    return prune_q8("mvue_prune_2of4_q8", mode, g, T, O, ldg, dtype, seed, stream_id, scale, vals8, meta32, hip_stream);
+}
+
+int mvue_prune_1of2_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                       float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    return prune_q8("mvue_prune_1of2_q8", 3, g, T, O, ldg, dtype, seed, stream_id, scale, vals8, meta32, hip_stream);
 }
 
 size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)

@@ -474,6 +474,36 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
 #pragma unroll
             for (int r = 0; r < 8; ++r) rows[(first + r) % 16] = *(const uint4 *)(gp2 + (int64_t)(first + r) * ldg * ESZ);
         }
+        constexpr int R0 = (4 * b) % 16;
+        if constexpr (EST == 3) {
+            // MVUE 1:2: the quad row holds two pair rows; the kept value of pair row 2b+pr is slot pr of quad b, rounded
+            // with the low half of the pair block's rounding word
+            static_for<2>([&](auto pr_c) {
+                constexpr int pr = decltype(pr_c)::value;
+                const uint64_t pblk0 = (uint64_t)(G * 16 + 2 * b + pr) * (uint64_t)O + (uint64_t)col0;
+                uint32_t sel[VEC], rnd1[VEC];
+#pragma unroll
+                for (int q = 0; q < VEC / 4; ++q) {
+                    const uint64_t ctr = (pblk0 >> 2) + q;
+                    uint32_t w4[4];
+                    philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 0u, key0, key1, w4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) sel[4 * q + j] = w4[j];
+                    philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 2u, key0, key1, w4);
+#pragma unroll
+                    for (int j = 0; j < 4; ++j) rnd1[4 * q + j] = w4[j];
+                }
+#pragma unroll
+                for (int c = 0; c < VEC; ++c) {
+                    uint32_t k; float v;
+                    select_1of2(Row<DT>::get(rows[R0 + 2 * pr], c), Row<DT>::get(rows[R0 + 2 * pr + 1], c), sel[c], k, v);
+                    kept[c][b / 2] = sr_e5m2_into<2 * (b & 1) + pr>(kept[c][b / 2], v * scale, rnd1[c] << 16);
+                    md[c] |= ((uint32_t)(pr << 1) | k) << (4 * b + 2 * pr);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            });
+            return;
+        }
         const uint64_t blk0 = (uint64_t)(G * 8 + b) * (uint64_t)O + (uint64_t)col0;
         constexpr int WPB = EST == 1 ? 2 : 1;
         uint32_t words[VEC * WPB], rnd[VEC];
@@ -493,7 +523,6 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
 #pragma unroll
             for (int j = 0; j < 4; ++j) rnd[4 * q + j] = w4[j];
         }
-        constexpr int R0 = (4 * b) % 16;
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             float v0, v1; uint32_t nib;
@@ -536,8 +565,9 @@ hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O,
                            uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
 {
 #define NM_PRUNE8(DT, EST) launch_prune_q8_t<DT, EST>(g, T, O, ldg, seed, stream_id, scale, vals8, meta32, st)
-    if (dt == NM_DT_F32) return est == 1 ? NM_PRUNE8(NM_DT_F32, 1) : NM_PRUNE8(NM_DT_F32, 0);
-    return est == 1 ? NM_PRUNE8(NM_DT_BF16, 1) : NM_PRUNE8(NM_DT_BF16, 0);
+    // est: 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2
+    if (dt == NM_DT_F32) return est == 3 ? NM_PRUNE8(NM_DT_F32, 3) : est == 1 ? NM_PRUNE8(NM_DT_F32, 1) : NM_PRUNE8(NM_DT_F32, 0);
+    return est == 3 ? NM_PRUNE8(NM_DT_BF16, 3) : est == 1 ? NM_PRUNE8(NM_DT_BF16, 1) : NM_PRUNE8(NM_DT_BF16, 0);
 #undef NM_PRUNE8
 }
 

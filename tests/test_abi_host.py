@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "mvue_prune_1of2_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of2_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "mvue_prune_1of2_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
                           "nm_update_gemm_q8_shifted_workspace",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:
@@ -137,6 +137,9 @@ def test_q8_argument_errors(lib):
         return lib.mvue_prune_2of4_q8(g, T, O, ldg, dt, 0, 0, mode, scale, vals, meta, None)
 
     assert prune8(T=48) == NM_ERR_SHAPE and b"multiple of 32" in lib.nm_last_error()
+    p12 = lambda T=64, O=16, scale=1.0, vals=P + 0x10000: lib.mvue_prune_1of2_q8(P, T, O, 16, 1, 0, 0, f32(scale), vals, P + 0x20000, None)
+    assert p12(T=48) == NM_ERR_SHAPE and b"mvue_prune_1of2_q8" in lib.nm_last_error()
+    assert p12(scale=-1.0) == NM_ERR_SHAPE and p12(vals=None) == NM_ERR_NULL and p12(vals=P) == NM_ERR_ALIAS and p12(T=0) == NM_OK
     assert prune8(O=12) == NM_ERR_SHAPE
     assert prune8(mode=2) == NM_ERR_UNSUPPORTED
     assert prune8(scale=0.0) == NM_ERR_SHAPE and prune8(scale=float("inf")) == NM_ERR_SHAPE and prune8(scale=float("nan")) == NM_ERR_SHAPE

@@ -165,18 +165,19 @@ def test_training_with_pruned_update_phase_tracks_dense_training():
     assert last_n < 0.5 * first and last_n < 1.5 * last_d + 1e-3
 
 
-def test_linear_q8_update_phase_matches_oracle(oracle):
+@pytest.mark.parametrize("nmode", ["2:4", "1:2"])
+def test_linear_q8_update_phase_matches_oracle(oracle, nmode):
     """precision="q8": the layer's scales, torch's e4m3 cast of the activations, then the oracle's 8-bit path"""
     from paper_2203_10991_amd.autograd import NMConfig, NMLinear, pow2_scale
     torch.manual_seed(3)
     T, I, O = 160, 48, 40
-    layer = NMLinear(I, O, bias=False, cfg=NMConfig(nm="2:4", seed=6, stream_id=1, precision="q8"), device=DEV, dtype=torch.bfloat16)
+    layer = NMLinear(I, O, bias=False, cfg=NMConfig(nm=nmode, seed=6, stream_id=1, precision="q8"), device=DEV, dtype=torch.bfloat16)
     x = torch.randn(T, I, device=DEV).to(torch.bfloat16).requires_grad_(True)
     gy = (torch.randn(T, O, device=DEV) * torch.exp(2 * torch.randn(T, O, device=DEV))).to(torch.bfloat16)
     layer(x).backward(gy)
-    sg, sh = pow2_scale(gy, 57344.0 / 4.0), pow2_scale(x.detach(), 448.0)
+    sg, sh = pow2_scale(gy, 57344.0 / (4.0 if nmode == "2:4" else 2.0)), pow2_scale(x.detach(), 448.0)
     h8 = (x.detach().float() * sh).to(torch.float8_e4m3fn).view(torch.uint8).cpu().numpy()
-    ov, om = oracle.prune_2of4_q8(bits(gy), 6, 1, 0, sg)
+    ov, om = oracle.prune_2of4_q8(bits(gy), 6, 1, 0, sg) if nmode == "2:4" else oracle.prune_1of2_q8(bits(gy), 6, 1, sg)
     want, wabs = oracle.update_gemm_q8(ov, om, h8, alpha=1.0 / (sg * sh))
     got = layer.weight.grad.double().cpu().numpy()
     assert (np.abs(got - want) <= 1e-2 * np.maximum(wabs, np.abs(want)) + 1e-30).all()      # (dW is rounded to bf16 by the layer)

@@ -155,3 +155,34 @@ def _random_shapes(n, seed):
 def test_update_gemm_q8_random_shapes(nm, oracle, T, O, I):
     """seeded random problem sizes through every branch of the 8-bit split-K plan"""
     gemm_case(nm, oracle, T, O, I, seed=T + O)
+
+
+@pytest.mark.parametrize("dtype", ["bf16", "f32"])
+@pytest.mark.parametrize("T,O", [(32, 8), (64, 64), (32 * 7, 8 * 13), (32 * 40, 8 * 67), (2048, 1024)])
+def test_prune_1of2_q8_bit_exact(nm, oracle, dtype, T, O):
+    w = synth.Workload(f"q8_12_{T}x{O}", T, O, 16, dtype, "1:2", 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O + 3)
+    scale = fit_scale(as_f32(g)) * 2.0                    # a kept value is at most the sum of TWO magnitudes
+    ov, om = oracle.prune_1of2_q8(g, seed=78, stream_id=4, scale=scale)
+    v, m = nm.mvue_prune_1of2_q8(to_dev(g), seed=78, stream_id=4, scale=scale)
+    torch.cuda.synchronize()
+    assert np.array_equal(m.cpu().numpy().view(np.uint32), om)
+    assert np.array_equal(v.cpu().numpy(), ov)
+
+
+def test_prune_1of2_q8_feeds_the_8_bit_gemm(nm, oracle):
+    T, O, I = 32 * 12, 136, 144
+    w = synth.Workload("q8_12_gemm", T, O, I, "bf16", "1:2", 0.0, 2.0, 0.3)
+    g = synth.make_g(w, 5)
+    scale = fit_scale(as_f32(g)) * 2.0
+    ov, om = oracle.prune_1of2_q8(g, seed=5, stream_id=0, scale=scale)
+    h8 = h8_codes(T, I, 6)
+    alpha = 1.0 / (scale * 8.0)
+    v, m = nm.mvue_prune_1of2_q8(to_dev(g), seed=5, stream_id=0, scale=scale)
+    dW = nm.nm_update_gemm_q8(v, m, torch.from_numpy(h8).to(DEV), alpha=alpha)
+    torch.cuda.synchronize()
+    want, wabs = oracle.update_gemm_q8(ov, om, h8, alpha=alpha)
+    got = dW.cpu().numpy().astype(np.float64)
+    rel = float((np.abs(got - want) / np.maximum(wabs, 1e-300)).max())
+    print(f"1:2 q8 gemm: max |err|/sum|ab| = {rel:.3e}", flush=True)
+    assert rel <= TOL
