@@ -75,7 +75,7 @@ def cpu_baseline_q8(w, approx=False):
     g, h = synth.make_g(s, 0), synth.make_h(s, 0)
     h8 = torch.from_numpy(synth.bf16_to_f32(h)).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
     t0 = time.perf_counter()
-    v, m = oracle.prune_2of4_q8(g, 0, 0, 1 if approx else 0, 2.0 ** -9)
+    v, m = oracle.prune_1of2_q8(g, 0, 0, 2.0 ** -9) if w.nm == "1:2" else oracle.prune_2of4_q8(g, 0, 0, 1 if approx else 0, 2.0 ** -9)
     t1 = time.perf_counter()
     oracle.update_gemm_q8(v, m, h8, alpha=2.0 ** 9)
     t2 = time.perf_counter()
@@ -299,8 +299,8 @@ def main():
         conv = dict(x_full=x_full, margin=margin, shifts=shifts, T=Tp)
         del h
         g, h = g_pad, None
-    if q8 and w.nm != "2:4":
-        print("bench.py: --precision q8 needs a 2:4 workload", file=sys.stderr)
+    if q8 and (w.dtype != "bf16" or w.T % 32):
+        print("bench.py: --precision q8 runs the bf16 workloads whose token count is a multiple of 32", file=sys.stderr)
         sys.exit(2)
     dW = torch.empty((w.O, w.I), dtype=torch.float32, device=dev)
     if q8:
@@ -312,7 +312,7 @@ def main():
             h8[a:a + 4096] = h[a:a + 4096].float().to(torch.float8_e4m3fn).view(torch.uint8)
             gmax = max(gmax, float(g[a:a + 4096].abs().max()))
         import math
-        g_scale = 2.0 ** math.floor(math.log2(57344.0 / (4.0 * max(gmax, 1e-30))))
+        g_scale = 2.0 ** math.floor(math.log2(57344.0 / ((2.0 if w.nm == "1:2" else 4.0) * max(gmax, 1e-30))))
         h = h8
         vals, meta = nm.alloc_compressed_q8(w.T, w.O, dev)
         need = nm.nm_update_gemm_q8_workspace(w.T, w.O, w.I)
@@ -335,7 +335,10 @@ def main():
     def step(seed, evs=None):
         if evs: evs[0].record()
         if q8:
-            nm.mvue_prune_2of4_q8(g, seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=vals, meta32=meta)
+            if w.nm == "1:2":
+                nm.mvue_prune_1of2_q8(g, seed=seed, stream_id=0, scale=g_scale, vals8=vals, meta32=meta)
+            else:
+                nm.mvue_prune_2of4_q8(g, seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=vals, meta32=meta)
         else:
             prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
         if evs: evs[1].record()
