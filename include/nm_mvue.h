@@ -27,8 +27,11 @@
  * null stream) and returns.  Outputs must not overlap inputs.
  *
  * Errors: every entry point returns an nm_status (0 = ok).  Validation happens before any
- * device work, so a non-zero return means nothing was enqueued.  nm_last_error() gives a
- * thread-local message for the last failing call on the calling thread.
+ * device work: a validation error (codes 1-7) means nothing was enqueued and no output was
+ * touched.  NM_ERR_LAUNCH means the HIP runtime refused one of the call's launches; a call may
+ * consist of several kernels, earlier ones may already be queued, and the call's outputs (and
+ * workspace) are then undefined.  nm_last_error() gives a thread-local message for the last
+ * failing call on the calling thread.
  *
  * Shape rules (ragged sizes are rejected; zero-padding by the caller is exact because an
  * all-zero block stays zero):  T % 16 == 0, O % 8 == 0, I % 8 == 0 (GEMM), ldg/ldd/ldh/lddw
@@ -54,7 +57,7 @@ typedef enum {
     NM_ERR_ALIAS = 5,       /* an output range overlaps an input range */
     NM_ERR_WORKSPACE = 6,   /* workspace missing or smaller than nm_update_gemm_workspace() */
     NM_ERR_UNSUPPORTED = 7, /* valid request this build does not implement */
-    NM_ERR_LAUNCH = 8       /* the HIP runtime refused the launch (message has the HIP error) */
+    NM_ERR_LAUNCH = 8       /* the HIP runtime refused a launch (message has the HIP error); outputs undefined */
 } nm_status;
 
 /* NM_F32_BF16X3 is an arithmetic mode of nm_update_gemm for binary32 operands (see there); the prune and compress

@@ -23,7 +23,6 @@
 // fixed order (deterministic; no atomics).
 #include <hip/hip_runtime.h>
 #include <stdint.h>
-#include <stdlib.h>
 
 #include <algorithm>
 #include <type_traits>
@@ -385,11 +384,13 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
         const int blk = q / 192, r = q % 192, a = r / 32, m = r % 32;
         return blk * 192 + 6 * m + a;
     };
-    // ---- direct loads.  Wave w brings, of token group w/4 of the stage: 4 rows of h (2 loads), vals slots
-    // [64c, 64c+64) for c = w%4 and c = (w%4 + 4) % 6 (2 loads; chunks 0 and 1 come twice, same bytes to the same
-    // place), meta rows [128c, 128c+128) for c = (w%4) % 3 (1 load).  Per-lane byte offsets inside a stage; the
-    // stage itself is reached through the scalar offset, which the bounds check does not cover: a load for a
-    // token group past the end of the tensor is switched off through the descriptor's size instead.
+    // ---- direct loads.  Wave w brings, of token group w/4 of the stage and with ws = w%4: 4 rows of h (2 loads of
+    // 64 lanes), vals slots [96 ws, 96 ws + 96) (one load of 64 lanes and one of the low 32 lanes), meta rows
+    // [96 ws, 96 ws + 96) (one load of the low 48 lanes, two words each): every slot and row of the tile once.  The
+    // lane-masked loads still count for every wave: vmcnt advances by LPS = 5 per stage whatever the mask, which is
+    // what the waits in stage_ready assume.  Per-lane byte offsets inside a stage; the stage itself is reached through
+    // the scalar offset, which the bounds check does not cover: a load for a token group past the end of the tensor is
+    // switched off through the descriptor's size instead.
     const int wgrp = wave / 4, ws = wave % 4;
     uint32_t b_src[2], a_src[2], m_src;
     {
@@ -644,7 +645,6 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
 // tall_rows: rows [0, tall_rows) of dW are computed by the 384 x 256 kernel (tall_tiles_m tile rows), the rest by the
 // kernel of `shape` (tiles_m tile rows); 0 = that kernel alone.
 struct Plan { int shape; int tm, tn; int tiles_m, tiles_n; int slabs; int64_t groups_per_slab; int64_t tall_rows; int tall_tiles_m; };
-static const bool g_allow_tall = getenv("NM_GEMM_NO_TALL") == nullptr;      // (switch for A/B measurements)
 
 // shifted: the dense operand is row-shifted views of one matrix (it stays in the caches: few-row problems are then
 // bound by the tile's own work, and the 64 x 256 tile wastes none of it; streamed from HBM, as a materialised
@@ -666,7 +666,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
         const int64_t tn = (I + 255) / 256;
         double best = 1e300;
         int64_t best_mt = 0;
-        for (int64_t mt = 0; g_allow_tall && !shifted && mt <= (O + 383) / 384; ++mt) {
+        for (int64_t mt = 0; !shifted && mt <= (O + 383) / 384; ++mt) {
             const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
             const double cost = 1.34 * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
             if (cost < best - 1e-9) { best = cost; best_mt = mt; }

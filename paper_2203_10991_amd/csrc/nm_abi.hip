@@ -69,6 +69,21 @@ int check_outputs(const char *fn, const void *in, int64_t T, int64_t O, int64_t 
     return NM_OK;
 }
 
+// workspace of `need` bytes: present, large enough, aligned, and clear of dW and of every input range
+int check_workspace(const char *fn, size_t need, const void *workspace, size_t workspace_bytes, const Range &rd,
+                    const Range *inputs, int n_inputs)
+{
+    if (!need) return NM_OK;
+    if (!workspace || workspace_bytes < need)
+        return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
+    if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
+    const Range rw = range_of(workspace, (int64_t)need, "workspace");
+    if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
+    for (int i = 0; i < n_inputs; ++i)
+        if (overlap(rw, inputs[i])) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap %s", fn, inputs[i].name);
+    return NM_OK;
+}
+
 int launched(const char *fn, hipError_t e)
 {
     if (e != hipSuccess) return fail(NM_ERR_LAUNCH, "%s: HIP launch failed: %s", fn, hipGetErrorString(e));
@@ -179,6 +194,8 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
     if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
     if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
     Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    Range rin[3];
+    int n_in = 0;
     if (T > 0) {
         if (!vals || !meta || !h) return fail(NM_ERR_NULL, "%s: vals, meta and h must not be NULL", fn);
         if (ldh < I) return fail(NM_ERR_SHAPE, "%s: ldh=%lld is smaller than I=%lld", fn, (long long)ldh, (long long)I);
@@ -187,24 +204,12 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
             return fail(NM_ERR_UNSUPPORTED, "%s: O=%lld and ldh=%lld must not exceed 2^21", fn, (long long)O, (long long)ldh);
         if (!aligned16(vals) || !aligned16(meta) || !aligned16(h) || (ldh * es) % 16)
             return fail(NM_ERR_ALIGN, "%s: vals, meta, h need 16-byte aligned bases (and h a 16-byte row stride)", fn);
-        Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
-        Range rh = range_of(h, ((T - 1) * ldh + I) * es, "h");
-        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rh)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+        rin[0] = range_of(vals, T / 2 * O * es, "vals"); rin[1] = range_of(meta, T / 16 * O * 2, "meta");
+        rin[2] = range_of(h, ((T - 1) * ldh + I) * es, "h");
+        n_in = 3;
+        if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    const size_t need = nm::update_gemm_workspace(dtype, T, O, I);
-    if (need) {
-        if (!workspace || workspace_bytes < need)
-            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
-        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
-        Range rw = range_of(workspace, (int64_t)need, "workspace");
-        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
-        if (T > 0) {
-            const int64_t es = esize(dtype);
-            if (overlap(rw, range_of(vals, T / 2 * O * es, "vals")) || overlap(rw, range_of(meta, T / 16 * O * 2, "meta")) ||
-                overlap(rw, range_of(h, ((T - 1) * ldh + I) * es, "h")))
-                return fail(NM_ERR_ALIAS, "%s: workspace must not overlap an input", fn);
-        }
-    }
+    if (int rc = check_workspace(fn, nm::update_gemm_workspace(dtype, T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
     return launched(fn, nm::launch_update_gemm(dtype, vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace,
                                                workspace_bytes, (hipStream_t)hip_stream));
 }
@@ -237,6 +242,8 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
     if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
     if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
     Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    Range rin[3];
+    int n_in = 0;
     if (T > 0) {
         if (!vals || !meta || !x) return fail(NM_ERR_NULL, "%s: vals, meta and x must not be NULL", fn);
         if (ldx < cb) return fail(NM_ERR_SHAPE, "%s: ldx=%lld is smaller than cb=%lld", fn, (long long)ldx, (long long)cb);
@@ -244,18 +251,12 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
             return fail(NM_ERR_UNSUPPORTED, "%s: O, ldx and (shift x ldx) exceed what 32-bit byte offsets reach", fn);
         if (!aligned16(vals) || !aligned16(meta) || !aligned16(x) || (ldx * 2) % 16)
             return fail(NM_ERR_ALIGN, "%s: vals, meta, x need 16-byte aligned bases (and x a 16-byte row stride)", fn);
-        Range rv = range_of(vals, T / 2 * O * 2, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
-        Range rx = range_of((const char *)x - margin * ldx * 2, ((T + 2 * margin - 1) * ldx + cb) * 2, "x");
-        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rx)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+        rin[0] = range_of(vals, T / 2 * O * 2, "vals"); rin[1] = range_of(meta, T / 16 * O * 2, "meta");
+        rin[2] = range_of((const char *)x - margin * ldx * 2, ((T + 2 * margin - 1) * ldx + cb) * 2, "x");
+        n_in = 3;
+        if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    const size_t need = nm::update_gemm_smfmac_shifted_workspace(T, O, I);
-    if (need) {
-        if (!workspace || workspace_bytes < need)
-            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
-        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
-        Range rw = range_of(workspace, (int64_t)need, "workspace");
-        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
-    }
+    if (int rc = check_workspace(fn, nm::update_gemm_smfmac_shifted_workspace(T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
     return launched(fn, nm::launch_update_gemm_smfmac_shifted(vals, meta, x, ldx, cb, row_shift, n_shift, dW, lddw, T, O, beta,
                                                               workspace, (hipStream_t)hip_stream));
 }
@@ -311,6 +312,8 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
     if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
     if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
     Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    Range rin[3];
+    int n_in = 0;
     if (T > 0) {
         if (!vals8 || !meta32 || !h8) return fail(NM_ERR_NULL, "%s: vals8, meta32 and h8 must not be NULL", fn);
         if (ldh < I) return fail(NM_ERR_SHAPE, "%s: ldh=%lld is smaller than I=%lld", fn, (long long)ldh, (long long)I);
@@ -318,18 +321,12 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
             return fail(NM_ERR_UNSUPPORTED, "%s: O=%lld and ldh=%lld must not exceed 2^21", fn, (long long)O, (long long)ldh);
         if (!aligned16(vals8) || !aligned16(meta32) || !aligned16(h8) || ldh % 16)
             return fail(NM_ERR_ALIGN, "%s: vals8, meta32, h8 need 16-byte aligned bases (and h8 a 16-byte row stride)", fn);
-        Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
-        Range rh = range_of(h8, (T - 1) * ldh + I, "h8");
-        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rh)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+        rin[0] = range_of(vals8, T / 2 * O, "vals8"); rin[1] = range_of(meta32, T / 32 * O * 4, "meta32");
+        rin[2] = range_of(h8, (T - 1) * ldh + I, "h8");
+        n_in = 3;
+        if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    const size_t need = nm::update_gemm_q8_workspace(T, O, I);
-    if (need) {
-        if (!workspace || workspace_bytes < need)
-            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
-        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
-        Range rw = range_of(workspace, (int64_t)need, "workspace");
-        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
-    }
+    if (int rc = check_workspace(fn, nm::update_gemm_q8_workspace(T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
     return launched(fn, nm::launch_update_gemm_q8(vals8, meta32, h8, ldh, dW, lddw, T, O, I, alpha, beta, workspace,
                                                   (hipStream_t)hip_stream));
 }
@@ -360,6 +357,8 @@ int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, cons
     if (lddw < I) return fail(NM_ERR_SHAPE, "%s: lddw=%lld is smaller than I=%lld", fn, (long long)lddw, (long long)I);
     if (!aligned16(dW) || (lddw * 4) % 16) return fail(NM_ERR_ALIGN, "%s: dW needs a 16-byte aligned base and row stride", fn);
     Range rd = range_of(dW, ((O - 1) * lddw + I) * 4, "dW");
+    Range rin[3];
+    int n_in = 0;
     if (T > 0) {
         if (!vals8 || !meta32 || !x8) return fail(NM_ERR_NULL, "%s: vals8, meta32 and x8 must not be NULL", fn);
         if (ldx < cb) return fail(NM_ERR_SHAPE, "%s: ldx=%lld is smaller than cb=%lld", fn, (long long)ldx, (long long)cb);
@@ -367,18 +366,12 @@ int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, cons
             return fail(NM_ERR_UNSUPPORTED, "%s: O, ldx and (shift x ldx) exceed what 32-bit byte offsets reach", fn);
         if (!aligned16(vals8) || !aligned16(meta32) || !aligned16(x8) || ldx % 16)
             return fail(NM_ERR_ALIGN, "%s: vals8, meta32, x8 need 16-byte aligned bases (and x8 a 16-byte row stride)", fn);
-        Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
-        Range rx = range_of((const char *)x8 - margin * ldx, (T + 2 * margin - 1) * ldx + cb, "x8");
-        if (overlap(rd, rv) || overlap(rd, rm) || overlap(rd, rx)) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
+        rin[0] = range_of(vals8, T / 2 * O, "vals8"); rin[1] = range_of(meta32, T / 32 * O * 4, "meta32");
+        rin[2] = range_of((const char *)x8 - margin * ldx, (T + 2 * margin - 1) * ldx + cb, "x8");
+        n_in = 3;
+        if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    const size_t need = nm::update_gemm_q8_shifted_workspace(T, O, I);
-    if (need) {
-        if (!workspace || workspace_bytes < need)
-            return fail(NM_ERR_WORKSPACE, "%s: workspace of %zu bytes required, %zu given", fn, need, workspace ? workspace_bytes : (size_t)0);
-        if (!aligned16(workspace)) return fail(NM_ERR_ALIGN, "%s: workspace needs a 16-byte aligned base", fn);
-        Range rw = range_of(workspace, (int64_t)need, "workspace");
-        if (overlap(rw, rd)) return fail(NM_ERR_ALIAS, "%s: workspace must not overlap dW", fn);
-    }
+    if (int rc = check_workspace(fn, nm::update_gemm_q8_shifted_workspace(T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
     return launched(fn, nm::launch_update_gemm_q8_shifted(vals8, meta32, x8, ldx, cb, row_shift, n_shift, dW, lddw, T, O, alpha,
                                                           beta, workspace, (hipStream_t)hip_stream));
 }

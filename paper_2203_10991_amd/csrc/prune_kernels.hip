@@ -556,6 +556,7 @@ static hipError_t launch_prune_q8_t(const void *g, int64_t T, int64_t O, int64_t
 {
     const int64_t groups = T / 32, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
+    if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                        g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, vals8, meta32);
     return hipGetLastError();
@@ -806,6 +807,7 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
     if (dense)
         hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
@@ -835,6 +837,7 @@ static hipError_t launch_compress_t(const void *d, int64_t T, int64_t O, int64_t
 {
     const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
+    if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((compress_kernel<DT, M>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
                        d, groups, O, ld, vals, meta, bad);
     return hipGetLastError();
