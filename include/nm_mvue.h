@@ -176,6 +176,22 @@ size_t nm_update_gemm_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_
 size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
 
 /*
+ * nm_update_gemm for callers that cannot allocate device memory or carry a workspace: code under HIP graph
+ * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and results as
+ * nm_update_gemm, without the workspace pair: the split-K partial sums go to a static device array inside the
+ * library (nm_update_gemm_static_max() bytes, 32 MiB, held by every GPU the library runs on until the process
+ * ends).  The call allocates and frees nothing.  A problem whose nm_update_gemm_workspace() exceeds that size
+ * returns NM_ERR_WORKSPACE (nothing is enqueued); problems that need no workspace are unlimited.
+ * All calls on one GPU share the array: two calls that may run at the same time on one GPU (different streams,
+ * different threads) race on it.  Calls on one stream, or otherwise ordered, are safe; the array keeps the last
+ * call's partial sums and every call overwrites what it reads.
+ */
+int nm_update_gemm_static(const void *vals, const uint16_t *meta, const void *h, int64_t ldh,
+                          float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, int dtype, float beta,
+                          void *hip_stream);
+size_t nm_update_gemm_static_max(void);
+
+/*
  * 8-bit neural gradients on top of 2:4 sparsity (Sec. 5: the rows that combine N:M sparsity in all
  * phases with 8-bit quantisation use FP8 neural gradients; Sec. 3: the quantiser of a neural gradient
  * has to be unbiased).  The paper fixes neither bit layout nor scale; this library takes OCP e5m2

@@ -45,6 +45,10 @@ def load():
     lib.nm_compress.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, vp]
     lib.nm_update_gemm.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_workspace.argtypes = [i64, i64, i64, i32]
+    lib.nm_update_gemm_static.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, i32, f32, vp]
+    lib.nm_update_gemm_static.restype = i32
+    lib.nm_update_gemm_static_max.argtypes = []
+    lib.nm_update_gemm_static_max.restype = sz
     lib.nm_update_gemm_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, i32, f32, vp, sz, vp]
     lib.nm_update_gemm_shifted.restype = i32
     lib.nm_update_gemm_shifted_workspace.argtypes = [i64, i64, i64, i32]
@@ -215,6 +219,26 @@ def nm_update_gemm(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: 
     _check(lib.nm_update_gemm(_ptr(vals), _ptr(meta), _ptr(h), ldh, _ptr(dW), lddw, T, O, I, _gemm_mode(h.dtype, f32_as_bf16x3),
                               float(beta), _ptr(workspace), wbytes, _stream(h)))
     return dW
+
+
+def nm_update_gemm_static(vals: torch.Tensor, meta: torch.Tensor, h: torch.Tensor, dW: torch.Tensor, beta: float = 0.0,
+                          f32_as_bf16x3: bool = False) -> torch.Tensor:
+    """nm_update_gemm without a workspace: split-K partial sums go to the library's static device array.  The caller
+    passes dW; nothing is allocated."""
+    lib = load()
+    G, O, _ = vals.shape
+    T, I = h.shape
+    if T != G * 16:
+        raise ValueError(f"h has {T} rows, the compressed operand covers {G * 16}")
+    if vals.dtype != h.dtype:
+        raise TypeError("vals and h must have the same dtype")
+    _check(lib.nm_update_gemm_static(_ptr(vals), _ptr(meta), _ptr(h), _rowmajor(h, "h"), _ptr(dW), _rowmajor(dW, "dW"), T, O, I,
+                                     _gemm_mode(h.dtype, f32_as_bf16x3), float(beta), _stream(h)))
+    return dW
+
+
+def nm_update_gemm_static_max() -> int:
+    return int(load().nm_update_gemm_static_max())
 
 
 # ---- 8-bit neural gradients (e5m2, stochastic rounding) on top of 2:4 sparsity

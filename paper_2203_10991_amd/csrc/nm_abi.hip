@@ -177,11 +177,12 @@ size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype)
     return nm::update_gemm_workspace(dtype, T, O, I);
 }
 
-int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW, int64_t lddw,
-                   int64_t T, int64_t O, int64_t I, int dtype, float beta, void *workspace, size_t workspace_bytes,
-                   void *hip_stream)
+// nm_update_gemm and nm_update_gemm_static: the same checks and kernels; the second takes its split-K workspace from
+// the library's static device array instead of the caller
+static int update_gemm_checked(const char *fn, bool static_scratch, const void *vals, const uint16_t *meta, const void *h,
+                               int64_t ldh, float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, int dtype, float beta,
+                               void *workspace, size_t workspace_bytes, void *hip_stream)
 {
-    const char *fn = "nm_update_gemm";
     if (dtype != NM_F32 && dtype != NM_BF16 && dtype != NM_F32_BF16X3)
         return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0), NM_BF16 (1) or NM_F32_BF16X3 (2)", fn, dtype);
     if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
@@ -209,10 +210,39 @@ int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_
         n_in = 3;
         if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
-    if (int rc = check_workspace(fn, nm::update_gemm_workspace(dtype, T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
+    const size_t need = nm::update_gemm_workspace(dtype, T, O, I);
+    if (static_scratch) {
+        workspace = nullptr;
+        workspace_bytes = 0;
+        if (need > nm::static_scratch_bytes())
+            return fail(NM_ERR_WORKSPACE, "%s: this problem needs %zu bytes of split-K scratch, the static array holds %zu; "
+                        "use nm_update_gemm with a workspace", fn, need, nm::static_scratch_bytes());
+        if (need) {
+            const hipError_t e = nm::static_scratch(&workspace);
+            if (e != hipSuccess) return fail(NM_ERR_LAUNCH, "%s: address of the static scratch array: %s", fn, hipGetErrorString(e));
+            workspace_bytes = nm::static_scratch_bytes();
+        }
+    } else if (int rc = check_workspace(fn, need, workspace, workspace_bytes, rd, rin, n_in)) return rc;
     return launched(fn, nm::launch_update_gemm(dtype, vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace,
                                                workspace_bytes, (hipStream_t)hip_stream));
 }
+
+int nm_update_gemm(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW, int64_t lddw,
+                   int64_t T, int64_t O, int64_t I, int dtype, float beta, void *workspace, size_t workspace_bytes,
+                   void *hip_stream)
+{
+    return update_gemm_checked("nm_update_gemm", false, vals, meta, h, ldh, dW, lddw, T, O, I, dtype, beta, workspace,
+                               workspace_bytes, hip_stream);
+}
+
+int nm_update_gemm_static(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW, int64_t lddw,
+                          int64_t T, int64_t O, int64_t I, int dtype, float beta, void *hip_stream)
+{
+    return update_gemm_checked("nm_update_gemm_static", true, vals, meta, h, ldh, dW, lddw, T, O, I, dtype, beta, nullptr, 0,
+                               hip_stream);
+}
+
+size_t nm_update_gemm_static_max(void) { return nm::static_scratch_bytes(); }
 
 size_t nm_update_gemm_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift)
 {

@@ -63,4 +63,9 @@ hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *m
                                          float alpha, float beta, void *workspace, hipStream_t st);
 size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I);
 
+// The library's static device scratch array (nm_static.hip): its size, and its address on the current device
+// (looked up once per device; no allocation).
+size_t static_scratch_bytes();
+hipError_t static_scratch(void **ptr);
+
 }  // namespace nm
