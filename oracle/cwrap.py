@@ -94,6 +94,24 @@ def lib():
         _lib.oracle_update_gemm_shifted.restype = None
         _lib.oracle_update_gemm_q8_shifted.argtypes = [vp, vp, vp, i64, i64, vp, i32, i64, i64, dbl, vp, vp]
         _lib.oracle_update_gemm_q8_shifted.restype = None
+        _lib.oracle_select_greedy.argtypes = [vp, i32, i32, vp]
+        _lib.oracle_select_greedy.restype = None
+        _lib.oracle_prune_greedy.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, i64]
+        _lib.oracle_prune_greedy.restype = i32
+        _lib.oracle_block_u24_quad.argtypes = [u64, u32, u64, vp]
+        _lib.oracle_block_u24_quad.restype = None
+        _lib.oracle_draw8.argtypes = [vp, flt, u32]
+        _lib.oracle_draw8.restype = i32
+        _lib.oracle_inclusion_4of8.argtypes = [vp, vp]
+        _lib.oracle_inclusion_4of8.restype = None
+        _lib.oracle_select_4of8_approx.argtypes = [vp, vp, vp, vp]
+        _lib.oracle_select_4of8_approx.restype = None
+        _lib.oracle_enumerate_draw8.argtypes = [vp, u32, vp]
+        _lib.oracle_enumerate_draw8.restype = None
+        _lib.oracle_prune_4of8_approx.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64]
+        _lib.oracle_prune_4of8_approx.restype = i32
+        _lib.oracle_nm_decompress_4of8.argtypes = [vp, vp, i64, i64, i32, vp, i64]
+        _lib.oracle_nm_decompress_4of8.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -386,3 +404,79 @@ def update_gemm_q8_shifted(vals8: np.ndarray, meta32: np.ndarray, x8_full: np.nd
     lib().oracle_update_gemm_q8_shifted(_p(np.ascontiguousarray(vals8)), _p(np.ascontiguousarray(meta32)), xp, Cc, Cc, _p(sh), len(sh),
                                         T, O, float(alpha), _p(dW), _p(absdW))
     return dW, absdW
+
+
+# ---- Greedy N:M (the comparison method of the paper's tables): keep the n largest magnitudes, unchanged
+
+def select_greedy(x, n: int):
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    pos = np.zeros(n, dtype=np.int32)
+    lib().oracle_select_greedy(_p(xa), len(xa), n, _p(pos))
+    return [int(v) for v in pos]
+
+
+def prune_greedy(g: np.ndarray, n: int, m: int, want_dense: bool = False):
+    T, O = g.shape
+    ld = g.strides[0] // g.itemsize
+    vals = np.zeros((T // 16, O, 8), dtype=g.dtype)
+    meta = np.zeros((T // 16, O), dtype=np.uint16)
+    dense = np.zeros((T, O), dtype=g.dtype) if want_dense else None
+    if lib().oracle_prune_greedy(_p(g), T, O, ld, _dt(g), n, m, _p(vals), _p(meta), _p(dense), O) != 0:
+        raise ValueError("oracle: bad shape or (n, m)")
+    return vals, meta, dense
+
+
+# ---- approx-MVUE 4:8: four magnitude-proportional draws out of eight; vals[T/16, O, 8] + meta32[T/16, O] (uint32:
+# octet b of the group in bits [16b, 16b+12), 3 bits per kept position)
+
+def block_u24_quad(seed: int, stream_id: int, blk: int):
+    u = np.zeros(4, dtype=np.uint32)
+    lib().oracle_block_u24_quad(seed, stream_id, blk, _p(u))
+    return [int(v) for v in u]
+
+
+def draw8(m, eps: float, taken: int = 0) -> int:
+    ma = np.ascontiguousarray(m, dtype=np.float32)
+    return int(lib().oracle_draw8(_p(ma), C.c_float(eps), taken))
+
+
+def inclusion_4of8(m) -> np.ndarray:
+    ma = np.ascontiguousarray(m, dtype=np.float32)
+    p = np.zeros(8, dtype=np.float32)
+    lib().oracle_inclusion_4of8(_p(ma), _p(p))
+    return p
+
+
+def select_4of8_approx(x, eps):
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    ea = np.ascontiguousarray(eps, dtype=np.float32)
+    pos = np.zeros(4, dtype=np.int32)
+    val = np.zeros(4, dtype=np.float32)
+    lib().oracle_select_4of8_approx(_p(xa), _p(ea), _p(pos), _p(val))
+    return [int(v) for v in pos], val
+
+
+def enumerate_draw8(x, taken: int = 0) -> np.ndarray:
+    """How often each position is drawn over all 2^24 uniforms, given the bit mask of positions already drawn."""
+    xa = np.ascontiguousarray(x, dtype=np.float32)
+    counts = np.zeros(8, dtype=np.uint64)
+    lib().oracle_enumerate_draw8(_p(xa), taken, _p(counts))
+    return counts
+
+
+def prune_4of8_approx(g: np.ndarray, seed: int = 0, stream_id: int = 0, want_dense: bool = False):
+    T, O = g.shape
+    ld = g.strides[0] // g.itemsize
+    vals = np.zeros((T // 16, O, 8), dtype=g.dtype)
+    meta32 = np.zeros((T // 16, O), dtype=np.uint32)
+    dense = np.zeros((T, O), dtype=g.dtype) if want_dense else None
+    if lib().oracle_prune_4of8_approx(_p(g), T, O, ld, _dt(g), seed, stream_id, _p(vals), _p(meta32), _p(dense), O) != 0:
+        raise ValueError("oracle: shape not representable (T must be a multiple of 16)")
+    return vals, meta32, dense
+
+
+def nm_decompress_4of8(vals: np.ndarray, meta32: np.ndarray) -> np.ndarray:
+    G, O, _ = vals.shape
+    dense = np.zeros((G * 16, O), dtype=vals.dtype)
+    lib().oracle_nm_decompress_4of8(_p(vals), _p(meta32), G * 16, O, _dt(vals), _p(dense), O)
+    return dense

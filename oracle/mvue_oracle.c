@@ -16,6 +16,11 @@
  *                                      probability p_i of that section.
  *   - MVUE 1:4 ...................... appendix ("Additional sparsity results"): eq. (6) on a block of
  *                                      four, stored in the 2:4 container.
+ *   - Greedy N:M .................... the comparison method of the paper's tables (keep the n largest,
+ *                                      unchanged): deterministic, biased.
+ *   - approx-MVUE 4:8 ............... appendix ("Additional sparsity results"): four magnitude-proportional
+ *                                      draws out of eight, kept value a_k/p_k with the exact inclusion
+ *                                      probability of the four draws.
  *   - update GEMM ................... eq. (3):  dC/dW_l = g_l h_{l-1}^T; for a convolution (App. B.1, part 1)
  *                                      also without the im2col matrix.
  *   - random source ................. the paper only asks for eps ~ U[0,1) per block; this build
@@ -877,6 +882,270 @@ void oracle_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32,
         }
         for (int64_t i = 0; i < I; ++i) { row[i] *= alpha; if (arow) arow[i] *= fabs(alpha); }
     }
+}
+
+/* ------------------------------------------------------------------------- */
+/* Greedy N:M (the "Greedy" rows of the 1:2 ablation table in Sec. 4.1 and of   */
+/* the result tables in Sec. 5): keep the n largest magnitudes of the block,    */
+/* values unchanged.  Deterministic and biased -- the comparison method, not    */
+/* an estimator of this paper.  Among equal magnitudes the lower position is    */
+/* kept (the ranking of the optimal 2:4 estimator above: of equal magnitudes    */
+/* the element at the higher position ranks lower).                             */
+/* pos[] comes back in ascending order.                                         */
+/* ------------------------------------------------------------------------- */
+void oracle_select_greedy(const float *x, int m, int n, int *pos)
+{
+    int taken[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    for (int s = 0; s < n; ++s) {
+        int best = -1;
+        for (int k = 0; k < m; ++k)
+            if (!taken[k] && (best < 0 || fabsf(x[k]) > fabsf(x[best]))) best = k;     /* strict: the first (lowest) wins a tie */
+        taken[best] = 1;
+    }
+    int c = 0;
+    for (int k = 0; k < m; ++k) if (taken[k]) pos[c++] = k;
+}
+
+/* tensor level, group format; (n, m) = (1, 2) or (2, 4).  Values are copied bit for bit. */
+int oracle_prune_greedy(const void *g, int64_t T, int64_t O, int64_t ldg, int dt, int n, int m,
+                        void *vals, uint16_t *meta, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0 || !((n == 1 && m == 2) || (n == 2 && m == 4))) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint16_t md = 0;
+            for (int i = 0; i < 4; ++i) {
+                int64_t t0 = (G * 4 + i) * 4;
+                float x[4];
+                for (int k = 0; k < 4; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                int pos[2];
+                if (m == 4) oracle_select_greedy(x, 4, 2, pos);
+                else {                                   /* the quad holds two pairs */
+                    oracle_select_greedy(x, 2, 1, &pos[0]);
+                    oracle_select_greedy(x + 2, 2, 1, &pos[1]);
+                    pos[1] += 2;
+                }
+                float st0 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 0, x[pos[0]]);
+                float st1 = store_elem(vals, dt, (G * O + o) * 8 + 2 * i + 1, x[pos[1]]);
+                md |= (uint16_t)((pos[0] | (pos[1] << 2)) << (4 * i));
+                if (dense) {
+                    for (int k = 0; k < 4; ++k) store_elem(dense, dt, (t0 + k) * ldd + o, 0.0f);
+                    store_elem(dense, dt, (t0 + pos[0]) * ldd + o, st0);
+                    store_elem(dense, dt, (t0 + pos[1]) * ldd + o, st1);
+                }
+            }
+            meta[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+/* ------------------------------------------------------------------------- */
+/* approx-MVUE 4:8 (appendix, "Additional sparsity results": the approximate    */
+/* 2:4 method of Sec. 4.4 carried over to more elements).  Four elements of a   */
+/* block of eight are drawn one after the other without replacement, each with  */
+/* probability a_j / (sum of the magnitudes not yet drawn); every drawn element */
+/* is kept with the value a_k / p_k, p_k = the probability that k is among the  */
+/* four (the unbiasedness argument of Sec. 4.2, eq. (8)).                        */
+/*                                                                             */
+/* p_k has no short closed form for four draws.  It is computed from the        */
+/* definition, organised by the SET of elements drawn so far (the next draw     */
+/* depends on that set only): with f(U) the probability that the first |U|      */
+/* draws are exactly the set U,                                                 */
+/*     f({}) = 1,   f(U) = sum_{k in U} f(U \ k) * a_k / rest(U \ k),            */
+/*     rest(V) = sum of the magnitudes outside V,   p_k = sum_{|U|=4, k in U} f(U). */
+/* Pinned arithmetic (binary32, one rounding per operation):                    */
+/*     rest(V) = lo(V) + hi(V), lo / hi = the sums of the magnitudes outside V   */
+/*               among positions 0-3 / 4-7, each added in ascending position     */
+/*               (never by subtraction: no cancellation when one element carries */
+/*               the sum);                                                       */
+/*     g(V) = f(V) / rest(V)   (IEEE division);                                  */
+/*     f(U) = sum over k in U, ascending position, of g(U \ k) * a_k;            */
+/*     p_k  = sum over the 4-sets U containing k in ascending order of their     */
+/*            bit mask (bit j = position j).                                     */
+/* A block with at most four non-zero magnitudes keeps all of them unchanged    */
+/* (p = 1) and pads with its lowest-index zeros.  Otherwise every draw finds a  */
+/* non-zero element, rest() is positive wherever it is used, and the value is   */
+/* min(a_k / p_k, sum): in exact arithmetic a_k / p_k <= sum (the first draw     */
+/* alone gives p_k >= a_k / sum), so the bound only acts on rounding.            */
+/*                                                                             */
+/* Draw: the threshold walk of the 2:4 method over eight positions (t = eps *   */
+/* remaining total; first position whose running sum exceeds t; else the last   */
+/* position with a non-zero magnitude left; else the lowest position not taken).*/
+/* Four uniforms per block: one Philox call, counter = (blk low, blk high,      */
+/* stream, 3), blk = (t / 8) * O + o, draw d takes the top 24 bits of word d.   */
+/*                                                                             */
+/* Compressed form (gfx950's sparse matrix instructions are 4:2 only, so this   */
+/* is a storage format, not a GEMM operand): per 16-token group and column,     */
+/*     vals[(G*O + o)*8 + 4*b + s]   s-th kept value (ascending position) of     */
+/*                                   octet b = 0, 1 of the group                 */
+/*     meta32[G*O + o]  (uint32)     bits [16b + 3s + 2 : 16b + 3s] = position    */
+/*                                   (0..7) of kept value s of octet b            */
+/* ------------------------------------------------------------------------- */
+void oracle_block_u24_quad(uint64_t seed, uint32_t stream_id, uint64_t blk, uint32_t u[4])
+{
+    uint32_t ctr[4] = { (uint32_t)blk, (uint32_t)(blk >> 32), stream_id, 3u };
+    uint32_t key[2] = { (uint32_t)seed, (uint32_t)(seed >> 32) };
+    uint32_t out[4];
+    oracle_philox4x32_10(ctr, key, out);
+    for (int d = 0; d < 4; ++d) u[d] = out[d] >> 8;
+}
+
+/* one draw among eight positions; m[] holds 0 at the positions already drawn, `taken` is their bit mask */
+int oracle_draw8(const float m[8], float eps, unsigned taken)
+{
+    float run[8];
+    run[0] = m[0];
+    for (int k = 1; k < 8; ++k) run[k] = run[k - 1] + m[k];
+    const float t = eps * run[7];
+    for (int k = 0; k < 8; ++k) if (t < run[k]) return k;
+    for (int k = 7; k >= 0; --k) if (m[k] > 0.0f) return k;
+    for (int k = 0; k < 8; ++k) if (!((taken >> k) & 1u)) return k;
+    return 0;
+}
+
+static int popcount8(unsigned v) { int c = 0; for (int k = 0; k < 8; ++k) c += (int)((v >> k) & 1u); return c; }
+
+/* inclusion probabilities of four successive magnitude-proportional draws out of eight (needs >= 5 non-zeros) */
+void oracle_inclusion_4of8(const float m[8], float p[8])
+{
+    static float f[256], g[256];
+    #pragma omp threadprivate(f, g)
+    for (int size = 0; size <= 4; ++size) {
+        for (unsigned U = 0; U < 256; ++U) {
+            if (popcount8(U) != size) continue;
+            if (size == 0) f[U] = 1.0f;
+            else {
+                float acc = 0.0f;
+                int first = 1;
+                for (int k = 0; k < 8; ++k) {
+                    if (!((U >> k) & 1u)) continue;
+                    const float term = g[U & ~(1u << k)] * m[k];
+                    acc = first ? term : acc + term;
+                    first = 0;
+                }
+                f[U] = acc;
+            }
+            if (size < 4) {
+                float lo = 0.0f, hi = 0.0f;
+                int flo = 1, fhi = 1;
+                for (int k = 0; k < 4; ++k) if (!((U >> k) & 1u)) { lo = flo ? m[k] : lo + m[k]; flo = 0; }
+                for (int k = 4; k < 8; ++k) if (!((U >> k) & 1u)) { hi = fhi ? m[k] : hi + m[k]; fhi = 0; }
+                g[U] = f[U] / (lo + hi);
+            }
+        }
+    }
+    for (int k = 0; k < 8; ++k) {
+        float acc = 0.0f;
+        int first = 1;
+        for (unsigned U = 0; U < 256; ++U) {
+            if (popcount8(U) != 4 || !((U >> k) & 1u)) continue;
+            acc = first ? f[U] : acc + f[U];
+            first = 0;
+        }
+        p[k] = acc;
+    }
+}
+
+/* pos[] ascending, value[] in the same order */
+void oracle_select_4of8_approx(const float x[8], const float eps[4], int pos[4], float value[4])
+{
+    float m[8], r[8];
+    int nz = 0;
+    for (int k = 0; k < 8; ++k) { m[k] = fabsf(x[k]); r[k] = m[k]; nz += m[k] > 0.0f; }
+    unsigned taken = 0;
+    for (int d = 0; d < 4; ++d) {
+        const int k = oracle_draw8(r, eps[d], taken);
+        taken |= 1u << k;
+        r[k] = 0.0f;
+    }
+    float p[8];
+    float total = 0.0f;
+    if (nz > 4) {
+        oracle_inclusion_4of8(m, p);
+        const float lo = ((m[0] + m[1]) + m[2]) + m[3], hi = ((m[4] + m[5]) + m[6]) + m[7];
+        total = lo + hi;
+    }
+    int c = 0;
+    for (int k = 0; k < 8; ++k) {
+        if (!((taken >> k) & 1u)) continue;
+        pos[c] = k;
+        if (nz > 4) value[c] = copysignf(fminf(m[k] / p[k], total), x[k]);
+        else        value[c] = x[k];
+        ++c;
+    }
+}
+
+/* test support: how often each position is drawn over all 2^24 uniforms, given the set already drawn */
+void oracle_enumerate_draw8(const float x[8], unsigned taken, uint64_t counts[8])
+{
+    float m[8];
+    for (int k = 0; k < 8; ++k) { m[k] = ((taken >> k) & 1u) ? 0.0f : fabsf(x[k]); counts[k] = 0; }
+    uint64_t c[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+    #pragma omp parallel
+    {
+        uint64_t loc[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+        #pragma omp for schedule(static)
+        for (uint32_t u = 0; u < (1u << 24); ++u) loc[oracle_draw8(m, u24_to_eps(u), taken)] += 1;
+        #pragma omp critical
+        for (int k = 0; k < 8; ++k) c[k] += loc[k];
+    }
+    for (int k = 0; k < 8; ++k) counts[k] = c[k];
+}
+
+int oracle_prune_4of8_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int dt,
+                             uint64_t seed, uint32_t stream_id,
+                             void *vals, uint32_t *meta32, void *dense, int64_t ldd)
+{
+    if (T % 16 || T < 0 || O < 0) return -1;
+    #pragma omp parallel for schedule(static)
+    for (int64_t G = 0; G < T / 16; ++G) {
+        for (int64_t o = 0; o < O; ++o) {
+            uint32_t md = 0;
+            for (int b = 0; b < 2; ++b) {
+                int64_t oc = G * 2 + b, t0 = oc * 8;
+                float x[8];
+                for (int k = 0; k < 8; ++k) x[k] = load_elem(g, dt, (t0 + k) * ldg + o);
+                uint32_t u[4];
+                oracle_block_u24_quad(seed, stream_id, (uint64_t)oc * (uint64_t)O + (uint64_t)o, u);
+                float eps[4];
+                for (int d = 0; d < 4; ++d) eps[d] = u24_to_eps(u[d]);
+                int pos[4]; float v[4];
+                oracle_select_4of8_approx(x, eps, pos, v);
+                if (dense) for (int k = 0; k < 8; ++k) store_elem(dense, dt, (t0 + k) * ldd + o, 0.0f);
+                for (int s = 0; s < 4; ++s) {
+                    float st = store_elem(vals, dt, (G * O + o) * 8 + 4 * b + s, v[s]);
+                    md |= (uint32_t)pos[s] << (16 * b + 3 * s);
+                    if (dense) store_elem(dense, dt, (t0 + pos[s]) * ldd + o, st);
+                }
+            }
+            meta32[G * O + o] = md;
+        }
+    }
+    return 0;
+}
+
+void oracle_nm_decompress_4of8(const void *vals, const uint32_t *meta32, int64_t T, int64_t O, int dt,
+                               void *dense, int64_t ldd)
+{
+    for (int64_t G = 0; G < T / 16; ++G)
+        for (int64_t o = 0; o < O; ++o) {
+            uint32_t md = meta32[G * O + o];
+            for (int b = 0; b < 2; ++b) {
+                int64_t t0 = (G * 2 + b) * 8;
+                for (int k = 0; k < 8; ++k) {
+                    int64_t dst = (t0 + k) * ldd + o;
+                    if (dt == DT_F32) ((float *)dense)[dst] = 0.0f; else ((uint16_t *)dense)[dst] = 0;
+                }
+                for (int s = 0; s < 4; ++s) {
+                    int k = (int)((md >> (16 * b + 3 * s)) & 7u);
+                    int64_t src = (G * O + o) * 8 + 4 * b + s, dst = (t0 + k) * ldd + o;
+                    if (dt == DT_F32) ((float *)dense)[dst] = ((const float *)vals)[src];
+                    else ((uint16_t *)dense)[dst] = ((const uint16_t *)vals)[src];
+                }
+            }
+        }
 }
 
 /* threads the parallel loops will use (for the benchmark's report) */
