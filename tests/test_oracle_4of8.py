@@ -186,7 +186,8 @@ def test_tensor_prune_is_unbiased_over_seeds(oracle):
     z = (mean - g)[live] / np.sqrt(var[live] / n)
     assert np.abs(z).max() < 4.8
     assert abs((z ** 2).sum() - live.sum()) < 5 * np.sqrt(2 * live.sum())
-    # the rest was kept in every sample (a zero, a block with at most four non-zeros, or an element that carries
-    # its block: inclusion probability within 1e-4 of one): reproduced up to that probability
-    assert (np.abs(mean - g)[~live] <= 2e-4 * np.abs(g)[~live]).all()
+    # the rest was kept in every sample (a zero, a block with at most four non-zeros, or an element whose inclusion
+    # probability p is so close to one that n samples never dropped it, so 1 - p is a few times 1/n at most): the mean
+    # is a/p, off by no more than that
+    assert (np.abs(mean - g)[~live] <= (8.0 / n) * np.abs(g)[~live]).all()
     assert np.array_equal(mean[g == 0], g[g == 0].astype(np.float64))
