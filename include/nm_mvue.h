@@ -121,6 +121,36 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
 
 /*
+ * approx-MVUE 4:8 prune + compress (appendix, "Additional sparsity results": the approximate 2:4 method of Sec. 4.4
+ * carried over to more elements).  Of every block of eight consecutive tokens of a column four elements are drawn one
+ * after the other without replacement, each with probability |a_j| / (sum of the magnitudes not yet drawn), and kept
+ * with the value a_k / p_k (eq. (8)), p_k = the probability that k is among the four, computed exactly from its
+ * definition (by the set of elements drawn so far; binary32, fixed operation order).  A block with at most four
+ * non-zeros keeps them unchanged and pads with its lowest-index zeros; a zero is never drawn while a non-zero
+ * remains.  Four uniforms per block: Philox4x32-10, key = seed, counter = (blk low, blk high, stream_id, 3),
+ * blk = (t/8)*O + o, draw d uses the top 24 bits of word d.  Pure function of (g, T, O, dtype, seed, stream_id).
+ * gfx950's sparse matrix instructions are 4:2 only, so the output is a storage format, not an operand of
+ * nm_update_gemm (the appendix itself remarks that other ratios need other hardware):
+ *     vals[(G*O + o)*8 + 4*b + s]   s-th kept value (ascending position) of octet b = 0, 1 of 16-token group G = t/16
+ *     meta32[G*O + o]  (uint32)     bits [16b + 3s + 2 : 16b + 3s] = position (0..7) of that value inside the octet
+ *     dense_out                     optional (NULL = skip): theta(g) as a dense [T x O] tensor, pruned positions +0
+ * T % 16 == 0, O % 8 == 0; vals holds T/2 * O elements of the dtype, meta32 T/16 * O words.
+ */
+int mvue_prune_4of8_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                           uint64_t seed, uint32_t stream_id,
+                           void *vals, uint32_t *meta32, void *dense_out, int64_t ldd, void *hip_stream);
+
+/*
+ * Greedy N:M prune + compress: the comparison method of the paper's tables (Sec. 4.1, 1:2 ablation table: the
+ * traditional minimum-MSE method; Sec. 5: "keeping the N largest elements in each block").  (n,m) = (1,2) or (2,4):
+ * of every block along T the n largest magnitudes are kept, values unchanged (bit for bit); among equal
+ * magnitudes the lower position is kept.  Deterministic and BIASED: it exists to reproduce the paper's baseline,
+ * not to train with.  Outputs as mvue_prune_1of2 (group format; optional dense_out).
+ */
+int nm_prune_greedy(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, int n, int m,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
+
+/*
  * Deterministic compression of a dense [T x O] tensor that already is n:m sparse along T
  * ((n,m) = (1,2) or (2,4)) into the group format: the halved footprint the abstract counts.
  * Kept positions are the non-zero positions, padded with the lowest-index zero positions of

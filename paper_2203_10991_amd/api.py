@@ -38,6 +38,10 @@ def load():
     lib.mvue_prune_2of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.restype = i32
+    lib.mvue_prune_4of8_approx.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
+    lib.mvue_prune_4of8_approx.restype = i32
+    lib.nm_prune_greedy.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, i64, vp]
+    lib.nm_prune_greedy.restype = i32
     lib.mvue_prune_2of4_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp]
     lib.mvue_prune_2of4_t.restype = i32
     lib.mvue_prune_1of2_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp]
@@ -146,6 +150,42 @@ def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: in
                     dense_out=None, want_dense: bool = False):
     """Optimal MVUE 2:4 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
     return _prune("2of4", g, seed, stream_id, mode, vals, meta, dense_out, want_dense)
+
+
+def mvue_prune_4of8_approx(g: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=None, meta32=None, dense_out=None,
+                           want_dense: bool = False):
+    """approx-MVUE 4:8 prune + compress of g[T x O] along T.  Returns (vals[T/16, O, 8], meta32[T/16, O] int32, dense_out or None)."""
+    lib = load()
+    if not g.is_cuda:
+        raise ValueError("g must live on the GPU")
+    T, O = g.shape
+    ldg = _rowmajor(g, "g")
+    if vals is None or meta32 is None:
+        vals = torch.empty(((T - T % 16) // 16, O, 8), dtype=g.dtype, device=g.device)
+        meta32 = torch.empty(((T - T % 16) // 16, O), dtype=torch.int32, device=g.device)
+    if dense_out is None and want_dense:
+        dense_out = torch.empty((T, O), dtype=g.dtype, device=g.device)
+    ldd = _rowmajor(dense_out, "dense_out") if dense_out is not None else 0
+    _check(lib.mvue_prune_4of8_approx(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, _ptr(vals), _ptr(meta32),
+                                      _ptr(dense_out), ldd, _stream(g)))
+    return vals, meta32, dense_out
+
+
+def nm_prune_greedy(g: torch.Tensor, n: int, m: int, vals=None, meta=None, dense_out=None, want_dense: bool = False):
+    """Greedy n:m prune + compress (keep the n largest magnitudes of every block along T, unchanged): the paper's
+    biased baseline.  Returns (vals, meta, dense_out or None)."""
+    lib = load()
+    if not g.is_cuda:
+        raise ValueError("g must live on the GPU")
+    T, O = g.shape
+    ldg = _rowmajor(g, "g")
+    if vals is None or meta is None:
+        vals, meta = alloc_compressed(T - T % 16, O, g.dtype, g.device)
+    if dense_out is None and want_dense:
+        dense_out = torch.empty((T, O), dtype=g.dtype, device=g.device)
+    ldd = _rowmajor(dense_out, "dense_out") if dense_out is not None else 0
+    _check(lib.nm_prune_greedy(_ptr(g), T, O, ldg, _dtype_code(g), n, m, _ptr(vals), _ptr(meta), _ptr(dense_out), ldd, _stream(g)))
+    return vals, meta, dense_out
 
 
 def _prune_transposed(gT: torch.Tensor, vals, meta):

@@ -127,6 +127,39 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                                          (hipStream_t)hip_stream));
 }
 
+int nm_prune_greedy(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, int n, int m,
+                    void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream)
+{
+    const char *fn = "nm_prune_greedy";
+    if (!((n == 1 && m == 2) || (n == 2 && m == 4)))
+        return fail(NM_ERR_UNSUPPORTED, "%s: (n,m)=(%d,%d); only 1:2 and 2:4 exist in the group format", fn, n, m);
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (int rc = check_outputs(fn, g, T, O, ldg, dtype, vals, meta, dense_out, ldd)) return rc;
+    return launched(fn, nm::launch_prune(dtype, m, 4, g, T, O, ldg, 0, 0, vals, meta, dense_out, ldd, (hipStream_t)hip_stream));
+}
+
+int mvue_prune_4of8_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                           void *vals, uint32_t *meta32, void *dense_out, int64_t ldd, void *hip_stream)
+{
+    const char *fn = "mvue_prune_4of8_approx";
+    if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
+    if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
+    if (!vals || !meta32) return fail(NM_ERR_NULL, "%s: vals and meta32 must not be NULL", fn);
+    if (!aligned16(vals) || !aligned16(meta32)) return fail(NM_ERR_ALIGN, "%s: vals and meta32 need 16-byte aligned bases", fn);
+    const int64_t es = esize(dtype);
+    Range rin = range_of(g, ((T - 1) * ldg + O) * es, "g");
+    Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta32, T / 16 * O * 4, "meta32");
+    if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm)) return fail(NM_ERR_ALIAS, "%s: g, vals and meta32 must not overlap", fn);
+    if (dense_out) {
+        if (ldd < O) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld", fn, (long long)ldd, (long long)O);
+        if (!aligned16(dense_out) || (ldd * es) % 16) return fail(NM_ERR_ALIGN, "%s: dense_out needs a 16-byte aligned base and row stride", fn);
+        Range rd = range_of(dense_out, ((T - 1) * ldd + O) * es, "dense_out");
+        if (overlap(rd, rin) || overlap(rd, rv) || overlap(rd, rm)) return fail(NM_ERR_ALIAS, "%s: dense_out must not overlap g, vals or meta32", fn);
+    }
+    return launched(fn, nm::launch_prune_4of8_approx(dtype, g, T, O, ldg, seed, stream_id, vals, meta32, dense_out, ldd,
+                                                     (hipStream_t)hip_stream));
+}
+
 static int prune_transposed(const char *fn, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed,
                             uint32_t stream_id, void *vals, uint16_t *meta, void *hip_stream)
 {

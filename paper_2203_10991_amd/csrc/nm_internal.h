@@ -16,6 +16,10 @@ hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_
 hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
                                    uint32_t stream_id, void *vals, uint16_t *meta, hipStream_t st);
 
+// approx-MVUE 4:8 (four magnitude-proportional draws out of eight): vals [T/2 x O] in octet order, meta32 [T/16 x O]
+hipError_t launch_prune_4of8_approx(int dt, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed, uint32_t stream_id,
+                                    void *vals, uint32_t *meta32, void *dense, int64_t ldd, hipStream_t st);
+
 hipError_t launch_compress(int dt, int m, const void *d, int64_t T, int64_t O, int64_t ld, void *vals,
                            uint16_t *meta, int32_t *bad, hipStream_t st);
 

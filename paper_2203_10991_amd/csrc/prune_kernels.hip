@@ -17,74 +17,9 @@
 
 #include "nm_internal.h"
 #include "smfmac_common.h"       // static_for
+#include "prune_common.h"
 
 namespace nm {
-
-// ------------------------------------------------------------------------------------
-// Philox4x32-10 (Salmon et al., SC'11).  Key words are wave-uniform (scalar registers).
-// ------------------------------------------------------------------------------------
-__device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
-                                              uint32_t k0, uint32_t k1, uint32_t (&out)[4])
-{
-#pragma unroll
-    for (int r = 0; r < 10; ++r) {
-        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
-        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
-        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
-        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
-        c1 = (uint32_t)p1;
-        c3 = (uint32_t)p0;
-        c0 = n0;
-        c2 = n2;
-        k0 += 0x9E3779B9u;
-        k1 += 0xBB67AE85u;
-    }
-    out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
-}
-
-__device__ __forceinline__ float word_to_eps(uint32_t word)
-{
-    return (float)(word >> 8) * 0x1p-24f;      // 24-bit uniform in [0,1), exact
-}
-
-// ------------------------------------------------------------------------------------
-// element access inside a 16-byte row vector
-// ------------------------------------------------------------------------------------
-template <int DT> struct Row;
-template <> struct Row<NM_DT_F32> {
-    static constexpr int VEC = 4;
-    static __device__ __forceinline__ float get(const uint4 &v, int c)
-    {
-        const uint32_t w = c == 0 ? v.x : c == 1 ? v.y : c == 2 ? v.z : v.w;
-        return __uint_as_float(w);
-    }
-};
-template <> struct Row<NM_DT_BF16> {
-    static constexpr int VEC = 8;
-    static __device__ __forceinline__ float get(const uint4 &v, int c)
-    {
-        const uint32_t w = (c >> 1) == 0 ? v.x : (c >> 1) == 1 ? v.y : (c >> 1) == 2 ? v.z : v.w;
-        return __uint_as_float((c & 1) ? (w & 0xffff0000u) : (w << 16));
-    }
-};
-
-// binary32 -> bf16 bits, round to nearest even (finite inputs)
-__device__ __forceinline__ uint32_t bf16_bits_rne(float f)
-{
-    const uint32_t b = __float_as_uint(f);
-    return (b + 0x7fffu + ((b >> 16) & 1u)) >> 16;
-}
-// two binary32 -> packed bf16 (lo, hi), round to nearest even: one v_cvt_pk_bf16_f32
-typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
-typedef float f32x2_t __attribute__((ext_vector_type(2)));
-__device__ __forceinline__ uint32_t pack_bf16_rne(float lo, float hi)
-{
-    const f32x2_t v = {lo, hi};
-    const bf16x2_t b = __builtin_convertvector(v, bf16x2_t);
-    uint32_t u;
-    __builtin_memcpy(&u, &b, 4);
-    return u;
-}
 
 // ------------------------------------------------------------------------------------
 // MVUE 1:2 on one pair: returns kept position (0/1) and the kept value (unrounded).
@@ -269,9 +204,35 @@ __device__ __forceinline__ void select_1of4(float x0, float x1, float x2, float 
 }
 
 // ------------------------------------------------------------------------------------
+// Greedy N:M (the comparison method of the paper's tables, Sec. 4.1 ablation and Sec. 5: keep the n largest
+// magnitudes of the block, values unchanged).  Deterministic: no random words.  Among equal magnitudes the lower
+// position is kept -- the order of the ranking keys above.
+// ------------------------------------------------------------------------------------
+__device__ __forceinline__ void select_greedy_1of2(float x0, float x1, uint32_t &kept, float &value)
+{
+    const bool keep1 = fabsf(x1) > fabsf(x0);
+    kept = keep1 ? 1u : 0u;
+    value = keep1 ? x1 : x0;
+}
+template <int DT>
+__device__ __forceinline__ void select_greedy_2of4(typename Key<DT>::type k1, typename Key<DT>::type k2, typename Key<DT>::type k3,
+                                                   typename Key<DT>::type k4, float &out0, float &out1, uint32_t &nib)
+{
+    typedef Key<DT> KT;
+    order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
+    const float va = KT::with_sign(KT::mag(k3), k3), vb = KT::with_sign(KT::mag(k4), k4);
+    const uint32_t pa = KT::pos(k3), pb = KT::pos(k4);
+    const bool swap = pa > pb;
+    out0 = swap ? vb : va;
+    out1 = swap ? va : vb;
+    nib = swap ? (pb | (pa << 2)) : (pa | (pb << 2));
+}
+
+// ------------------------------------------------------------------------------------
 // the fused kernel
 // ------------------------------------------------------------------------------------
-// M = 2: MVUE 1:2; M = 4: EST = 0 the optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4; DENSE: also write theta(g)
+// M = 2: MVUE 1:2; M = 4: EST = 0 the optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4; EST = 4 (either M): Greedy;
+// DENSE: also write theta(g)
 template <int DT, int M, int EST, bool DENSE>
 __device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
@@ -321,18 +282,22 @@ __device__ __forceinline__ void prune_compress_body(
         // approx-MVUE draws twice: two blocks share a call (counter blk/2, last counter word 1)
         constexpr int WPB = EST == 1 ? 2 : 1;            // words per block
         uint32_t words[VEC * WPB];
+        if constexpr (EST != 4) {
 #pragma unroll
-        for (int q = 0; q < VEC * WPB / 4; ++q) {
-            const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
-            uint32_t w4[4];
-            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
+            for (int q = 0; q < VEC * WPB / 4; ++q) {
+                const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
+                uint32_t w4[4];
+                philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
+                for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
+            }
         }
 #pragma unroll
         for (int c = 0; c < VEC; ++c) {
             if (M == 2) {
                 uint32_t k; float v;
+                if constexpr (EST == 4) select_greedy_1of2(Row<DT>::get(rows[2 * b], c), Row<DT>::get(rows[2 * b + 1], c), k, v);
+                else
                 select_1of2(Row<DT>::get(rows[2 * b], c), Row<DT>::get(rows[2 * b + 1], c), words[c], k, v);
                 if (b & 1) put2(c, b >> 1, held[c], v); else held[c] = v;
                 md[c] |= ((uint32_t)((b & 1) << 1) | k) << (2 * b);
@@ -345,6 +310,9 @@ __device__ __forceinline__ void prune_compress_body(
                 else if constexpr (EST == 2)
                     select_1of4(Row<DT>::get(rows[4 * b], c), Row<DT>::get(rows[4 * b + 1], c),
                                 Row<DT>::get(rows[4 * b + 2], c), Row<DT>::get(rows[4 * b + 3], c), words[c], v0, v1, nib);
+                else if constexpr (EST == 4)
+                    select_greedy_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
+                                           Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3), v0, v1, nib);
                 else
                     select_2of4<DT>(Key<DT>::make(rows[4 * b], c, 0), Key<DT>::make(rows[4 * b + 1], c, 1),
                                     Key<DT>::make(rows[4 * b + 2], c, 2), Key<DT>::make(rows[4 * b + 3], c, 3),
@@ -820,14 +788,17 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     return hipGetLastError();
 }
 
-// m = 2: MVUE 1:2;  m = 4: est = 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4
+// m = 2: est = 0 MVUE 1:2, 4 Greedy 1:2;  m = 4: est = 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4, 4 Greedy 2:4
 hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st)
 {
 #define NM_PRUNE(DT, M, EST) launch_prune_t<DT, M, EST>(g, T, O, ldg, seed, stream_id, vals, meta, dense, ldd, st)
-    if (dt == NM_DT_F32)
-        return m == 2 ? NM_PRUNE(NM_DT_F32, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_F32, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_F32, 4, 2) : NM_PRUNE(NM_DT_F32, 4, 0);
-    return m == 2 ? NM_PRUNE(NM_DT_BF16, 2, 0) : est == 1 ? NM_PRUNE(NM_DT_BF16, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_BF16, 4, 2) : NM_PRUNE(NM_DT_BF16, 4, 0);
+    if (dt == NM_DT_F32) {
+        if (m == 2) return est == 4 ? NM_PRUNE(NM_DT_F32, 2, 4) : NM_PRUNE(NM_DT_F32, 2, 0);
+        return est == 1 ? NM_PRUNE(NM_DT_F32, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_F32, 4, 2) : est == 4 ? NM_PRUNE(NM_DT_F32, 4, 4) : NM_PRUNE(NM_DT_F32, 4, 0);
+    }
+    if (m == 2) return est == 4 ? NM_PRUNE(NM_DT_BF16, 2, 4) : NM_PRUNE(NM_DT_BF16, 2, 0);
+    return est == 1 ? NM_PRUNE(NM_DT_BF16, 4, 1) : est == 2 ? NM_PRUNE(NM_DT_BF16, 4, 2) : est == 4 ? NM_PRUNE(NM_DT_BF16, 4, 4) : NM_PRUNE(NM_DT_BF16, 4, 0);
 #undef NM_PRUNE
 }
 
