@@ -29,6 +29,12 @@ inline Range range_of(const void *p, int64_t bytes, const char *name)
 {
     return Range{(uintptr_t)p, (uintptr_t)p + (bytes > 0 ? (uintptr_t)bytes : 0), name};
 }
+// rows x stride elements must stay far below 2^63 bytes: every byte range below is formed without overflow
+inline bool too_big(int64_t rows, int64_t stride)
+{
+    const int64_t lim = (int64_t)1 << 58;
+    return rows > lim || stride > lim || (rows > 0 && stride > 0 && rows > lim / stride);
+}
 inline bool overlap(const Range &a, const Range &b) { return a.lo < b.hi && b.lo < a.hi && a.lo != a.hi && b.lo != b.hi; }
 
 // shape / dtype / pointer checks shared by the two prune calls and nm_compress
@@ -38,6 +44,7 @@ int check_tensor(const char *fn, const void *g, int64_t T, int64_t O, int64_t ld
     if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16 (pad with zero rows)", fn, (long long)T);
     if (O % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld is not a multiple of 8 (pad with zero columns)", fn, (long long)O);
+    if (too_big(T, O) || too_big(T, ld)) return fail(NM_ERR_SHAPE, "%s: %s is larger than 2^58 elements", fn, what);
     if (T == 0 || O == 0) return NM_OK;
     if (!g) return fail(NM_ERR_NULL, "%s: %s is NULL", fn, what);
     if (ld < O) return fail(NM_ERR_SHAPE, "%s: row stride %lld of %s is smaller than O=%lld", fn, (long long)ld, what, (long long)O);
@@ -60,7 +67,7 @@ int check_outputs(const char *fn, const void *in, int64_t T, int64_t O, int64_t 
     if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm))
         return fail(NM_ERR_ALIAS, "%s: input, vals and meta must not overlap", fn);
     if (dense) {
-        if (ldd < O) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld", fn, (long long)ldd, (long long)O);
+        if (ldd < O || too_big(T, ldd)) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld (or beyond 2^58 elements)", fn, (long long)ldd, (long long)O);
         if (!aligned16(dense) || (ldd * es) % 16) return fail(NM_ERR_ALIGN, "%s: dense_out needs a 16-byte aligned base and row stride", fn);
         Range rd = range_of(dense, ((T - 1) * ldd + O) * es, "dense_out");
         if (overlap(rd, rin) || overlap(rd, rv) || overlap(rd, rm))
@@ -151,7 +158,7 @@ int mvue_prune_4of8_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int
     Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta32, T / 16 * O * 4, "meta32");
     if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm)) return fail(NM_ERR_ALIAS, "%s: g, vals and meta32 must not overlap", fn);
     if (dense_out) {
-        if (ldd < O) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld", fn, (long long)ldd, (long long)O);
+        if (ldd < O || too_big(T, ldd)) return fail(NM_ERR_SHAPE, "%s: ldd=%lld is smaller than O=%lld (or beyond 2^58 elements)", fn, (long long)ldd, (long long)O);
         if (!aligned16(dense_out) || (ldd * es) % 16) return fail(NM_ERR_ALIGN, "%s: dense_out needs a 16-byte aligned base and row stride", fn);
         Range rd = range_of(dense_out, ((T - 1) * ldd + O) * es, "dense_out");
         if (overlap(rd, rin) || overlap(rd, rv) || overlap(rd, rm)) return fail(NM_ERR_ALIAS, "%s: dense_out must not overlap g, vals or meta32", fn);
@@ -167,6 +174,7 @@ static int prune_transposed(const char *fn, int est, const void *gT, int64_t T, 
     if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16 (pad with zero tokens)", fn, (long long)T);
     if (O % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld is not a multiple of 8 (pad with zero rows)", fn, (long long)O);
+    if (too_big(O, T) || too_big(O, ldt)) return fail(NM_ERR_SHAPE, "%s: gT is larger than 2^58 elements", fn);
     if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
     if (!gT || !vals || !meta) return fail(NM_ERR_NULL, "%s: gT, vals and meta must not be NULL", fn);
     if (ldt < T) return fail(NM_ERR_SHAPE, "%s: row stride %lld of gT is smaller than T=%lld", fn, (long long)ldt, (long long)T);
@@ -221,6 +229,8 @@ static int update_gemm_checked(const char *fn, bool static_scratch, const void *
     if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16", fn, (long long)T);
     if (O % 8 || I % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld and I=%lld must be multiples of 8", fn, (long long)O, (long long)I);
+    if (too_big(T, O) || too_big(T, I) || too_big(T, ldh) || too_big(O, I) || too_big(O, lddw))
+        return fail(NM_ERR_SHAPE, "%s: a tensor is larger than 2^58 elements", fn);
     if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
     if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
     const int64_t es = esize(dtype);
@@ -295,6 +305,8 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
     if (!row_shift) return fail(NM_ERR_NULL, "%s: row_shift is NULL", fn);
     if (T % 16) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 16", fn, (long long)T);
     if (O % 8 || cb % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld and cb=%lld must be multiples of 8", fn, (long long)O, (long long)cb);
+    if (too_big(T, O) || too_big(T + 64, 32 * cb) || too_big(T + 64, ldx) || too_big(O, 32 * cb) || too_big(O, lddw))
+        return fail(NM_ERR_SHAPE, "%s: a tensor is larger than 2^58 elements", fn);
     if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
     const int64_t I = cb * n_shift;
     if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
@@ -369,6 +381,8 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
     if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
     if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32", fn, (long long)T);
     if (O % 8 || I % 16) return fail(NM_ERR_SHAPE, "%s: O=%lld must be a multiple of 8 and I=%lld of 16", fn, (long long)O, (long long)I);
+    if (too_big(T, O) || too_big(T, I) || too_big(T, ldh) || too_big(O, I) || too_big(O, lddw))
+        return fail(NM_ERR_SHAPE, "%s: a tensor is larger than 2^58 elements", fn);
     if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
     if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
     if (!dW) return fail(NM_ERR_NULL, "%s: dW is NULL", fn);
@@ -410,6 +424,8 @@ int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, cons
     if (!row_shift) return fail(NM_ERR_NULL, "%s: row_shift is NULL", fn);
     if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32", fn, (long long)T);
     if (O % 8 || cb % 16) return fail(NM_ERR_SHAPE, "%s: O=%lld must be a multiple of 8 and cb=%lld of 16", fn, (long long)O, (long long)cb);
+    if (too_big(T, O) || too_big(T + 64, 32 * cb) || too_big(T + 64, ldx) || too_big(O, 32 * cb) || too_big(O, lddw))
+        return fail(NM_ERR_SHAPE, "%s: a tensor is larger than 2^58 elements", fn);
     if (!(beta == 0.0f || beta == 1.0f)) return fail(NM_ERR_UNSUPPORTED, "%s: beta must be 0 or 1", fn);
     const int64_t I = cb * n_shift;
     if (O == 0 || I == 0) { g_err[0] = 0; return NM_OK; }
