@@ -30,6 +30,7 @@
 
 #include "nm_internal.h"
 #include "smfmac_common.h"
+#include "gemm_plan.h"
 
 namespace nm {
 
@@ -659,20 +660,11 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
     bool small = false;
     if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
         p.shape = 0; p.tm = 256; p.tn = 256;
-        // Large problems: the 384 x 256 kernel moves 21 % fewer operand bytes per product and is ~10 % faster per
-        // product, but a GPU-wide round of its tiles takes 1.34 times as long, and a partly filled last round costs
-        // as much as a full one.  So the rows are split: the first mt tile rows go to the tall kernel, the rest to
-        // the 256 x 256 kernel, mt chosen to minimise the summed cost of whole rounds (mt = 0: no tall launch).
-        const int64_t tn = (I + 255) / 256;
-        double best = 1e300;
-        int64_t best_mt = 0;
-        for (int64_t mt = 0; !shifted && mt <= (O + 383) / 384; ++mt) {
-            const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
-            const double cost = 1.34 * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
-            if (cost < best - 1e-9) { best = cost; best_mt = mt; }
-        }
-        p.tall_tiles_m = (int)best_mt;
-        p.tall_rows = std::min<int64_t>(O, best_mt * 384);
+        // Large problems: rows split between the 384 x 256 kernel (21 % fewer operand bytes per product, ~10 % faster
+        // per product, a round of its tiles 1.34 times as long) and the 256 x 256 kernel
+        const RowSplit rs = split_rows_tall(O, I, 1.34, !shifted);
+        p.tall_tiles_m = rs.tall_tiles_m;
+        p.tall_rows = rs.tall_rows;
     }
     else if (shifted && O <= 64 && I > 128) { p.shape = 2; p.tm = 64; p.tn = 256; small = true; }
     else { p.shape = 1; p.tm = 128; p.tn = 128; small = true; }
@@ -701,24 +693,21 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
         slabs = (int)s_one;
         if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two) < cost(s_one)) slabs = (int)s_two;
     }
-    const int64_t gps = whole_trips((groups + slabs - 1) / slabs);           // whole trips of six LDS stages
-    p.groups_per_slab = gps;
-    p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
+    p.slabs = slabs;
+    p.groups_per_slab = slab_groups(groups, p.slabs, 12);                    // whole trips of six LDS stages (2 groups each)
     return p;
 }
 
 size_t update_gemm_smfmac_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
-    const Plan p = make_plan(T, O, I);
-    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+    return splitk_workspace_bytes(make_plan(T, O, I).slabs, O, I);
 }
 
 size_t update_gemm_smfmac_shifted_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
-    const Plan p = make_plan(T, O, I, true);
-    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+    return splitk_workspace_bytes(make_plan(T, O, I, true).slabs, O, I);
 }
 
 hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
@@ -727,10 +716,10 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
 {
     const Plan p = make_plan(T, O, I);
     const int accumulate = beta != 0.f;
-    float *out = dW;
-    int64_t ldo = lddw, slab_stride = 0;
-    int acc_flag = accumulate;
-    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; }
+    const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
+    float *out = tg.out;
+    const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
+    const int acc_flag = tg.accumulate;
     if (p.tall_rows > 0) {
         dim3 tall_grid((unsigned)(p.tall_tiles_m * p.tiles_n), 1, 1);
         hipLaunchKernelGGL(update_gemm_smfmac_tall_kernel, tall_grid, dim3(512), 0, st, (const uint16_t *)vals, meta, (const uint16_t *)h,
@@ -764,17 +753,12 @@ hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *m
     const int64_t I = cb * n;
     if (O == 0 || I == 0) return hipSuccess;
     const Plan p = make_plan(T, O, I, true);
-    ShiftArg sh{};
-    sh.cb = (int)cb; sh.n = n; sh.margin = 0;
-    for (int j = 0; j < n; ++j) {
-        sh.rows[j] = (int)rows[j];
-        sh.margin = std::max(sh.margin, (int)(rows[j] < 0 ? -rows[j] : rows[j]));
-    }
+    const ShiftArg sh = make_shift_arg(cb, rows, n);
     const int accumulate = beta != 0.f;
-    float *out = dW;
-    int64_t ldo = lddw, slab_stride = 0;
-    int acc_flag = accumulate;
-    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; }
+    const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
+    float *out = tg.out;
+    const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
+    const int acc_flag = tg.accumulate;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_kernel<WM, WN, AB, BB, true>), grid, dim3(WM * WN * 64), 0, st,              \

@@ -26,6 +26,7 @@
 
 #include "nm_internal.h"
 #include "smfmac_common.h"
+#include "gemm_plan.h"
 
 namespace nm {
 
@@ -587,20 +588,11 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I, bool shifted = false
     if (O <= 64) { p.shape = 2; p.tm = 64; }
     else if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
         p.shape = 0; p.tm = 256;
-        // rows split between the 384 x 256 and the 256 x 256 kernel as in the 16-bit path: fewer operand bytes per
-        // product on the taller tile, but a GPU-wide round of it takes TALL_ROUND times as long and a partly
-        // filled last round costs a full one; the split minimises the summed cost of whole rounds
-        constexpr double TALL_ROUND = 1.36;       // measured: 412 us against 302 us per round
-        const int64_t tn = (I + 255) / 256;
-        double best = 1e300;
-        int64_t best_mt = 0;
-        for (int64_t mt = 0; !shifted && mt <= (O + 383) / 384; ++mt) {
-            const int64_t left = O - std::min<int64_t>(O, mt * 384), m256 = (left + 255) / 256;
-            const double cost = TALL_ROUND * (double)((mt * tn + CUS - 1) / CUS) + (double)((m256 * tn + CUS - 1) / CUS);
-            if (cost < best - 1e-9) { best = cost; best_mt = mt; }
-        }
-        p.tall_tiles_m = (int)best_mt;
-        p.tall_rows = std::min<int64_t>(O, best_mt * 384);
+        // rows split between the 384 x 256 and the 256 x 256 kernel as in the 16-bit path; a round of tall tiles takes
+        // 1.36 times as long here (measured: 412 us against 302 us per round)
+        const RowSplit rs = split_rows_tall(O, I, 1.36, !shifted);
+        p.tall_tiles_m = rs.tall_tiles_m;
+        p.tall_rows = rs.tall_rows;
     }
     else { p.shape = 1; p.tm = 128; }
     p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
@@ -615,19 +607,15 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I, bool shifted = false
         if (slabs > max_slabs) slabs = (int)max_slabs;
         if (slabs < 1) slabs = 1;
     }
-    int64_t gps = (groups + slabs - 1) / slabs;
-    gps = (gps + 11) / 12 * 12;                                        // whole trips of six LDS stages
-    if (gps < 12) gps = 12;
-    p.groups_per_slab = gps;
-    p.slabs = groups > 0 ? (int)((groups + gps - 1) / gps) : 1;
+    p.slabs = slabs;
+    p.groups_per_slab = slab_groups(groups, p.slabs, 12);              // whole trips of six LDS stages (2 groups each)
     return p;
 }
 
 size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
-    const PlanQ8 p = make_plan_q8(T, O, I);
-    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+    return splitk_workspace_bytes(make_plan_q8(T, O, I).slabs, O, I);
 }
 
 hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
@@ -637,11 +625,11 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
     if (O == 0 || I == 0) return hipSuccess;
     const PlanQ8 p = make_plan_q8(T, O, I);
     const int accumulate = beta != 0.f;
-    float *out = dW;
-    int64_t ldo = lddw, slab_stride = 0;
-    int acc_flag = accumulate;
-    float k_alpha = alpha;
-    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; k_alpha = 1.0f; }
+    const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
+    float *out = tg.out;
+    const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
+    const int acc_flag = tg.accumulate;
+    const float k_alpha = p.slabs > 1 ? 1.0f : alpha;              // partial sums are scaled once, in the second pass
     if (p.tall_rows > 0) {
         hipLaunchKernelGGL(update_gemm_smfmac_q8_tall_kernel, dim3((unsigned)(p.tall_tiles_m * p.tiles_n)), dim3(512), 0, st,
                            vals8, meta32, h8, ldh, out, ldo, T / 32, O, I, p.tall_tiles_m, p.tiles_n, acc_flag, k_alpha, p.tall_rows);
@@ -667,8 +655,7 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
 size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
-    const PlanQ8 p = make_plan_q8(T, O, I, true);
-    return p.slabs > 1 ? (size_t)p.slabs * (size_t)O * (size_t)I * sizeof(float) : 0;
+    return splitk_workspace_bytes(make_plan_q8(T, O, I, true).slabs, O, I);
 }
 
 // dW = beta*dW + alpha * decompress(vals8, meta32)^T [x8 shifted by rows[0] | x8 shifted by rows[1] | ...]
@@ -679,18 +666,13 @@ hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *m
     const int64_t I = cb * n;
     if (O == 0 || I == 0) return hipSuccess;
     const PlanQ8 p = make_plan_q8(T, O, I, true);
-    ShiftArg sh{};
-    sh.cb = (int)cb; sh.n = n; sh.margin = 0;
-    for (int j = 0; j < n; ++j) {
-        sh.rows[j] = (int)rows[j];
-        sh.margin = std::max(sh.margin, (int)(rows[j] < 0 ? -rows[j] : rows[j]));
-    }
+    const ShiftArg sh = make_shift_arg(cb, rows, n);
     const int accumulate = beta != 0.f;
-    float *out = dW;
-    int64_t ldo = lddw, slab_stride = 0;
-    int acc_flag = accumulate;
-    float k_alpha = alpha;
-    if (p.slabs > 1) { out = (float *)workspace; ldo = I; slab_stride = O * I; acc_flag = 0; k_alpha = 1.0f; }
+    const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
+    float *out = tg.out;
+    const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
+    const int acc_flag = tg.accumulate;
+    const float k_alpha = p.slabs > 1 ? 1.0f : alpha;              // partial sums are scaled once, in the second pass
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB, true>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, x8, \
