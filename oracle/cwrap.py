@@ -112,6 +112,12 @@ def lib():
         _lib.oracle_prune_4of8_approx.restype = i32
         _lib.oracle_nm_decompress_4of8.argtypes = [vp, vp, i64, i64, i32, vp, i64]
         _lib.oracle_nm_decompress_4of8.restype = None
+        _lib.oracle_pow2_scale.argtypes = [vp, i64, i64, i64, i32, flt]
+        _lib.oracle_pow2_scale.restype = flt
+        _lib.oracle_e4m3_rne.argtypes = [flt]
+        _lib.oracle_e4m3_rne.restype = u8
+        _lib.oracle_cast_e4m3.argtypes = [vp, i64, i64, i64, i32, flt, vp, i64]
+        _lib.oracle_cast_e4m3.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -480,3 +486,21 @@ def nm_decompress_4of8(vals: np.ndarray, meta32: np.ndarray) -> np.ndarray:
     dense = np.zeros((G * 16, O), dtype=vals.dtype)
     lib().oracle_nm_decompress_4of8(_p(vals), _p(meta32), G * 16, O, _dt(vals), _p(dense), O)
     return dense
+
+
+# ---- per-tensor power-of-two scale and the activations' e4m3 cast of the 8-bit path
+
+def pow2_scale(t: np.ndarray, top: float) -> float:
+    R, Cc = t.shape
+    return float(lib().oracle_pow2_scale(_p(t), R, Cc, t.strides[0] // t.itemsize, _dt(t), C.c_float(top)))
+
+
+def e4m3_rne(x: float) -> int:
+    return int(lib().oracle_e4m3_rne(C.c_float(x)))
+
+
+def cast_e4m3(h: np.ndarray, scale: float) -> np.ndarray:
+    R, Cc = h.shape
+    h8 = np.zeros((R, Cc), dtype=np.uint8)
+    lib().oracle_cast_e4m3(_p(h), R, Cc, h.strides[0] // h.itemsize, _dt(h), C.c_float(scale), _p(h8), Cc)
+    return h8

@@ -885,6 +885,59 @@ void oracle_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32,
 }
 
 /* ------------------------------------------------------------------------- */
+/* Per-tensor scale and the activations' 8-bit cast for the 8-bit path (Sec. 5,  */
+/* 8-bit rows; the paper gives no scale rule).  Reading: one power-of-two scale  */
+/* per tensor from its current maximum magnitude, the largest s = 2^e with       */
+/* s * max|t| <= top (a power of two multiplies without rounding, so the scale   */
+/* itself adds no error); e is kept in [-126, 126] so that s and 1/s are normal  */
+/* binary32 numbers; an all-zero tensor, or one whose maximum is not finite,     */
+/* gets s = 1.  `top` is the largest magnitude the 8-bit format may be asked to  */
+/* hold: 448 for e4m3 activations, 57344 / 4 (2:4) or 57344 / 2 (1:2) for e5m2   */
+/* gradients, whose kept values are at most the sum of their block's magnitudes. */
+/* ------------------------------------------------------------------------- */
+float oracle_pow2_scale(const void *t, int64_t R, int64_t C, int64_t ld, int dt, float top)
+{
+    /* the maximum over the bit patterns of |t|: they order like the magnitudes, with infinity and every NaN on top */
+    uint32_t mb = 0;
+    for (int64_t r = 0; r < R; ++r)
+        for (int64_t c = 0; c < C; ++c) {
+            uint32_t b = float_to_bits(load_elem(t, dt, r * ld + c)) & 0x7FFFFFFFu;
+            if (b > mb) mb = b;
+        }
+    const float m = bits_to_float(mb);
+    if (mb == 0 || mb >= 0x7F800000u || !(top > 0.0f) || !isfinite(top)) return 1.0f;
+    int em, et;
+    double fm = frexp((double)m, &em), ft = frexp((double)top, &et);      /* x = f * 2^e, f in [0.5, 1) */
+    int e = et - em - (ft >= fm ? 0 : 1);                                  /* largest e with 2^e * m <= top */
+    if (e > 126) e = 126;
+    if (e < -126) e = -126;
+    return (float)ldexp(1.0, e);
+}
+
+/* binary32 -> e4m3 (OCP), round to nearest, ties to even; magnitudes above 448 saturate to 448; NaN -> 0x7F */
+uint8_t oracle_e4m3_rne(float x)
+{
+    uint8_t sign = (uint8_t)(float_to_bits(x) >> 31 << 7);
+    if (isnan(x)) return (uint8_t)(sign | 0x7F);
+    double m = fabs((double)x);
+    if (m >= 448.0) return (uint8_t)(sign | 0x7E);
+    int c = 0;
+    while (c < 0x7E && oracle_e4m3_value((uint8_t)(c + 1)) <= m) ++c;       /* codes 0..0x7E ascend with magnitude */
+    double lo = oracle_e4m3_value((uint8_t)c), hi = oracle_e4m3_value((uint8_t)(c + 1));
+    double dl = m - lo, dh = hi - m;
+    if (dh < dl || (dh == dl && (c & 1))) ++c;                               /* nearest; a tie goes to the even code */
+    return (uint8_t)(sign | (uint8_t)c);
+}
+
+/* h8[r][c] = e4m3(fl(h[r][c] * scale)): one binary32 product, then the rounding above */
+void oracle_cast_e4m3(const void *h, int64_t R, int64_t C, int64_t ld, int dt, float scale, uint8_t *h8, int64_t ld8)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t r = 0; r < R; ++r)
+        for (int64_t c = 0; c < C; ++c) h8[r * ld8 + c] = oracle_e4m3_rne(load_elem(h, dt, r * ld + c) * scale);
+}
+
+/* ------------------------------------------------------------------------- */
 /* Greedy N:M (the "Greedy" rows of the 1:2 ablation table in Sec. 4.1 and of   */
 /* the result tables in Sec. 5): keep the n largest magnitudes of the block,    */
 /* values unchanged.  Deterministic and biased -- the comparison method, not    */

@@ -259,3 +259,66 @@ def test_q8_prune_1of2_is_unbiased_over_seeds(oracle):
     assert np.all(np.abs(mean - g64) <= tol)
     big = a * partner > 0
     assert np.abs(mean - g64)[big].max() > 0              # (and it is a random estimate, not a copy)
+
+
+# ---- per-tensor scale and the e4m3 cast of the activations (the 8-bit layers compute both in the library)
+
+def test_e4m3_cast_against_a_library_cast(oracle):
+    """torch's float8_e4m3fn cast rounds to nearest even on the same grid; compared on random values of every
+    exponent in range, on every code's exact value, and on the midpoints between neighbouring codes (ties)"""
+    import torch
+    rng = np.random.default_rng(0)
+    xs = [np.float32(s * m * 2.0 ** e) for e in range(-12, 9) for m in rng.uniform(1, 2, 40) for s in (-1, 1)]
+    grid = sorted(oracle.e4m3_value(c) for c in range(0x7F))
+    xs += [np.float32(v) for v in grid] + [np.float32(-v) for v in grid]
+    xs += [np.float32((a + b) / 2) for a, b in zip(grid[:-1], grid[1:])]                 # exact midpoints (representable in binary32)
+    xs = np.array([x for x in xs if abs(x) <= 448.0], dtype=np.float32)
+    want = torch.from_numpy(xs).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    got = np.array([oracle.e4m3_rne(float(x)) for x in xs], dtype=np.uint8)
+    zero = xs == 0
+    assert np.array_equal(got[~zero], want[~zero])
+    assert all(oracle.e4m3_value(int(c)) == 0.0 for c in got[zero])
+    # beyond the largest finite value the cast saturates; NaN stays NaN
+    assert oracle.e4m3_rne(449.0) == 0x7E and oracle.e4m3_rne(-1e30) == 0xFE and oracle.e4m3_rne(float("inf")) == 0x7E
+    assert oracle.e4m3_rne(float("nan")) & 0x7F == 0x7F
+    # every code is a fixed point
+    for c in range(0x7F):
+        assert oracle.e4m3_rne(oracle.e4m3_value(c)) == c
+
+
+def test_pow2_scale_is_the_largest_power_of_two_that_fits(oracle):
+    rng = np.random.default_rng(1)
+    for top in (448.0, 57344.0 / 4.0, 57344.0 / 2.0, 1.0):
+        for _ in range(300):
+            t = (rng.standard_normal((3, 8)) * np.exp2(rng.uniform(-40, 40))).astype(np.float32)
+            s = oracle.pow2_scale(t, top)
+            m = float(np.abs(t).max())
+            assert s == 2.0 ** round(np.log2(s))                                     # a power of two
+            assert s * m <= top and 2.0 * s * m > top                               # the largest that fits
+    # exact powers of two on the boundary, bf16 input, padded stride
+    t = np.zeros((2, 16), dtype=np.float32); t[1, 3] = -7.0
+    assert oracle.pow2_scale(t, 448.0) == 64.0 and oracle.pow2_scale(t, 447.9) == 32.0
+    assert oracle.pow2_scale(t[:, :8], 448.0) == 64.0
+    assert oracle.pow2_scale(synth.f32_to_bf16_bits(t), 448.0) == 64.0
+    # degenerate tensors: scale 1
+    assert oracle.pow2_scale(np.zeros((2, 8), dtype=np.float32), 448.0) == 1.0
+    bad = np.ones((2, 8), dtype=np.float32); bad[0, 0] = np.inf
+    assert oracle.pow2_scale(bad, 448.0) == 1.0
+    bad[0, 0] = np.nan
+    assert oracle.pow2_scale(bad, 448.0) == 1.0
+    # the exponent is clamped so that the scale and its inverse stay normal numbers
+    assert oracle.pow2_scale(np.full((1, 8), 1e-44, dtype=np.float32), 448.0) == 2.0 ** 126
+    assert oracle.pow2_scale(np.full((1, 8), 3e38, dtype=np.float32), 2.0 ** -20) == 2.0 ** -126
+
+
+def test_cast_e4m3_tensor(oracle):
+    import torch
+    w = synth.Workload("h8", 48, 40, 8, "bf16", "2:4", 0.0, 1.0, 0.0)
+    h = synth.make_h(synth.Workload("h8", 48, 8, 40, "bf16", "2:4", 0.0, 1.0, 0.0), seed=3)
+    s = oracle.pow2_scale(h, 448.0)
+    h8 = oracle.cast_e4m3(h, s)
+    want = (torch.from_numpy(synth.bf16_to_f32(h)) * s).to(torch.float8_e4m3fn).view(torch.uint8).numpy()
+    nz = synth.bf16_to_f32(h) != 0
+    assert np.array_equal(h8[nz], want[nz])
+    dec = np.array([oracle.e4m3_value(int(c)) for c in h8.ravel()]).reshape(h8.shape)
+    assert np.abs(dec).max() <= 448.0 and np.abs(dec).max() > 224.0                 # the scale uses the top binade
