@@ -267,6 +267,42 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
 size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
 
 /*
+ * Per-tensor scales of the 8-bit path without a host round trip (Sec. 5, 8-bit rows; the paper fixes no scale rule:
+ * this library uses one power-of-two scale per tensor from its current maximum magnitude).
+ *
+ * nm_q8_scale writes a SCALE RECORD, four floats in device memory (16-byte aligned):
+ *     rec[0] = s    the largest power of two with s * max|t| <= top, exponent kept in [-126, 126];
+ *                   1 for an all-zero tensor or a maximum that is not finite
+ *     rec[1] = 1/s  rec[2] = the bit pattern of max|t|   rec[3] = 0 (scratch of the record's consumer, see below)
+ * t: [R x C] of NM_F32 or NM_BF16, row stride ld, C % 8 == 0.  top: the largest magnitude the 8-bit format is to
+ * hold: 448 for e4m3 activations; 57344/4 for e5m2 gradients pruned 2:4 and 57344/2 for 1:2 (a kept value is at most
+ * the sum of its block's magnitudes).  Three small kernels on the stream; the maximum is an order-independent atomic,
+ * so the record is reproducible.
+ *
+ * nm_cast_e4m3: h8[r][c] = e4m3(h[r][c] * rec[0]) -- one binary32 product, round to nearest even, magnitudes beyond
+ * 448 saturate to 448 -- for the activations of nm_update_gemm_q8.  C % 16 == 0, ld8 % 16 == 0 (bytes).
+ *
+ * The _ds ("device scale") forms of the 8-bit entry points read their scales from such records instead of host
+ * arguments: mvue_prune_*_q8_ds multiplies kept values by rec[0]; nm_update_gemm_q8*_ds uses
+ * alpha = rec_g[1] * rec_h[1], which a one-thread kernel of the call leaves in rec_h[3] for its GEMM kernels (so two
+ * GEMM calls that may run at the same time must not share an activation record).  Everything else as the
+ * host-scale forms.
+ */
+int nm_q8_scale(const void *t, int64_t R, int64_t C, int64_t ld, int dtype, float top, float *scale_rec, void *hip_stream);
+int nm_cast_e4m3(const void *h, int64_t R, int64_t C, int64_t ld, int dtype, const float *scale_rec,
+                 uint8_t *h8, int64_t ld8, void *hip_stream);
+int mvue_prune_2of4_q8_ds(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                          uint64_t seed, uint32_t stream_id, int mode, const float *scale_rec,
+                          uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+int mvue_prune_1of2_q8_ds(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
+                          uint64_t seed, uint32_t stream_id, const float *scale_rec,
+                          uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+int nm_update_gemm_q8_ds(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh,
+                         float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I,
+                         const float *scale_rec_g, float *scale_rec_h, float beta,
+                         void *workspace, size_t workspace_bytes, void *hip_stream);
+
+/*
  * The 8-bit update GEMM with the dense operand as row-shifted views (nm_update_gemm_shifted for the operands of
  * nm_update_gemm_q8: the paper's 8-bit rows are convolutional networks):
  *     dW[O x n_shift*cb] = beta*dW + alpha * decompress(vals8, meta32)^T h8,   h8[t][j*cb + c] = x8[(t + row_shift[j])*ldx + c].
@@ -276,6 +312,11 @@ int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, cons
                               const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
                               float alpha, float beta, void *workspace, size_t workspace_bytes, void *hip_stream);
 size_t nm_update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift);
+/* ... with alpha = scale_rec_g[1] * scale_rec_x[1] read on the device (see nm_q8_scale) */
+int nm_update_gemm_q8_shifted_ds(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                                 const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                                 const float *scale_rec_g, float *scale_rec_x, float beta,
+                                 void *workspace, size_t workspace_bytes, void *hip_stream);
 
 /* Message of the last error on this thread ("" if none).  Static storage; do not free. */
 const char *nm_last_error(void);

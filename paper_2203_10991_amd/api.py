@@ -66,6 +66,18 @@ def load():
     lib.mvue_prune_1of2_q8.restype = i32
     lib.nm_update_gemm_q8.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, f32, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_workspace.argtypes = [i64, i64, i64]
+    lib.nm_q8_scale.argtypes = [vp, i64, i64, i64, i32, f32, vp, vp]
+    lib.nm_q8_scale.restype = i32
+    lib.nm_cast_e4m3.argtypes = [vp, i64, i64, i64, i32, vp, vp, i64, vp]
+    lib.nm_cast_e4m3.restype = i32
+    lib.mvue_prune_2of4_q8_ds.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, vp]
+    lib.mvue_prune_2of4_q8_ds.restype = i32
+    lib.mvue_prune_1of2_q8_ds.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, vp]
+    lib.mvue_prune_1of2_q8_ds.restype = i32
+    lib.nm_update_gemm_q8_ds.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, vp, vp, f32, vp, sz, vp]
+    lib.nm_update_gemm_q8_ds.restype = i32
+    lib.nm_update_gemm_q8_shifted_ds.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, vp, vp, f32, vp, sz, vp]
+    lib.nm_update_gemm_q8_shifted_ds.restype = i32
     for f in (lib.mvue_prune_1of2, lib.mvue_prune_2of4, lib.nm_compress, lib.nm_update_gemm, lib.mvue_prune_2of4_q8,
               lib.nm_update_gemm_q8):
         f.restype = i32
@@ -289,7 +301,7 @@ def alloc_compressed_q8(T: int, O: int, device) -> Tuple[torch.Tensor, torch.Ten
             torch.empty((T // 32, O), dtype=torch.int32, device=device))
 
 
-def mvue_prune_2of4_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, scale: float = 1.0,
+def mvue_prune_2of4_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, scale=1.0,
                        vals8=None, meta32=None):
     """MVUE 2:4 prune of g[T x O] along T with kept values scaled and rounded stochastically to e5m2.  Returns (vals8, meta32)."""
     lib = load()
@@ -299,12 +311,16 @@ def mvue_prune_2of4_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode:
     ldg = _rowmajor(g, "g")
     if vals8 is None or meta32 is None:
         vals8, meta32 = alloc_compressed_q8(T - T % 32, O, g.device)
-    _check(lib.mvue_prune_2of4_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, float(scale),
-                                  _ptr(vals8), _ptr(meta32), _stream(g)))
+    if isinstance(scale, torch.Tensor):          # a scale record in device memory (nm_q8_scale)
+        _check(lib.mvue_prune_2of4_q8_ds(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, _ptr(scale),
+                                         _ptr(vals8), _ptr(meta32), _stream(g)))
+    else:
+        _check(lib.mvue_prune_2of4_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, mode, float(scale),
+                                      _ptr(vals8), _ptr(meta32), _stream(g)))
     return vals8, meta32
 
 
-def mvue_prune_1of2_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, scale: float = 1.0, vals8=None, meta32=None):
+def mvue_prune_1of2_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, scale=1.0, vals8=None, meta32=None):
     """MVUE 1:2 prune of g[T x O] along T with kept values scaled and rounded stochastically to e5m2.  Returns (vals8, meta32)."""
     lib = load()
     if not g.is_cuda:
@@ -313,8 +329,12 @@ def mvue_prune_1of2_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, scale
     ldg = _rowmajor(g, "g")
     if vals8 is None or meta32 is None:
         vals8, meta32 = alloc_compressed_q8(T - T % 32, O, g.device)
-    _check(lib.mvue_prune_1of2_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, float(scale),
-                                  _ptr(vals8), _ptr(meta32), _stream(g)))
+    if isinstance(scale, torch.Tensor):
+        _check(lib.mvue_prune_1of2_q8_ds(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, _ptr(scale),
+                                         _ptr(vals8), _ptr(meta32), _stream(g)))
+    else:
+        _check(lib.mvue_prune_1of2_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, float(scale),
+                                      _ptr(vals8), _ptr(meta32), _stream(g)))
     return vals8, meta32
 
 
@@ -340,9 +360,34 @@ def nm_update_gemm_q8(vals8: torch.Tensor, meta32: torch.Tensor, h8: torch.Tenso
     if need and (workspace is None or workspace.numel() * workspace.element_size() < need):
         workspace = torch.empty(need, dtype=torch.uint8, device=h8.device)
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
-    _check(lib.nm_update_gemm_q8(_ptr(vals8), _ptr(meta32), _ptr(h8), ldh, _ptr(dW), lddw, T, O, I, float(alpha),
-                                 float(beta), _ptr(workspace), wbytes, _stream(h8)))
+    if isinstance(alpha, tuple):                 # two scale records in device memory: alpha = rec_g[1] * rec_h[1]
+        _check(lib.nm_update_gemm_q8_ds(_ptr(vals8), _ptr(meta32), _ptr(h8), ldh, _ptr(dW), lddw, T, O, I, _ptr(alpha[0]),
+                                        _ptr(alpha[1]), float(beta), _ptr(workspace), wbytes, _stream(h8)))
+    else:
+        _check(lib.nm_update_gemm_q8(_ptr(vals8), _ptr(meta32), _ptr(h8), ldh, _ptr(dW), lddw, T, O, I, float(alpha),
+                                     float(beta), _ptr(workspace), wbytes, _stream(h8)))
     return dW
+
+
+def nm_q8_scale(t: torch.Tensor, top: float, rec: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """Scale record (device float[4] = s, 1/s, bits of max|t|, 0) of a 2-D tensor: s the largest power of two with
+    s * max|t| <= top.  Nothing returns to the host."""
+    lib = load()
+    R, Cc = t.shape
+    if rec is None:
+        rec = torch.empty(4, dtype=torch.float32, device=t.device)
+    _check(lib.nm_q8_scale(_ptr(t), R, Cc, _rowmajor(t, "t"), _dtype_code(t), float(top), _ptr(rec), _stream(t)))
+    return rec
+
+
+def nm_cast_e4m3(h: torch.Tensor, rec: torch.Tensor, h8: Optional[torch.Tensor] = None) -> torch.Tensor:
+    """h8 (uint8 e4m3 codes) = e4m3(h * rec[0]), round to nearest even."""
+    lib = load()
+    R, Cc = h.shape
+    if h8 is None:
+        h8 = torch.empty((R, Cc), dtype=torch.uint8, device=h.device)
+    _check(lib.nm_cast_e4m3(_ptr(h), R, Cc, _rowmajor(h, "h"), _dtype_code(h), _ptr(rec), _ptr(h8), _rowmajor(h8, "h8"), _stream(h)))
+    return h8
 
 
 def nm_update_gemm_shifted(vals: torch.Tensor, meta: torch.Tensor, x_full: torch.Tensor, margin: int, shifts,
@@ -400,6 +445,10 @@ def nm_update_gemm_q8_shifted(vals8: torch.Tensor, meta32: torch.Tensor, x8_full
     wbytes = 0 if workspace is None else workspace.numel() * workspace.element_size()
     sh = (C.c_int64 * n)(*[int(v) for v in shifts])
     xp = x8_full.data_ptr() + margin * ldx
-    _check(lib.nm_update_gemm_q8_shifted(_ptr(vals8), _ptr(meta32), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O, float(alpha),
-                                         float(beta), _ptr(workspace), wbytes, _stream(x8_full)))
+    if isinstance(alpha, tuple):
+        _check(lib.nm_update_gemm_q8_shifted_ds(_ptr(vals8), _ptr(meta32), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O, _ptr(alpha[0]),
+                                                _ptr(alpha[1]), float(beta), _ptr(workspace), wbytes, _stream(x8_full)))
+    else:
+        _check(lib.nm_update_gemm_q8_shifted(_ptr(vals8), _ptr(meta32), xp, ldx, Cb, sh, n, _ptr(dW), lddw, T, O, float(alpha),
+                                             float(beta), _ptr(workspace), wbytes, _stream(x8_full)))
     return dW

@@ -10,7 +10,6 @@ There is no fallback: tensors must live on the GPU and the HIP library must be b
 """
 from __future__ import annotations
 
-import math
 from dataclasses import dataclass
 from typing import Optional
 
@@ -33,12 +32,29 @@ class NMConfig:
     # on the sparse 16-bit path
     precision: str = "native"
     step: int = 0              # iteration counter; advance() once per optimizer step
+    # True: the layer that owns this configuration advances `step` itself after every backward pass (the default
+    # configuration a layer makes for itself: a drop-in layer then draws fresh samples every `reuse_every`
+    # iterations without any call from the training loop).  False: the caller calls advance() once per iteration,
+    # e.g. when several layers share one configuration object.
+    auto_advance: bool = False
 
     def current_seed(self) -> int:
         return self.seed + self.step // max(1, self.reuse_every)
 
     def advance(self) -> None:
         self.step += 1
+
+
+_next_stream_id = 0
+
+
+def _own_config() -> NMConfig:
+    """The configuration of a layer that was given none: a random stream of its own (stream ids count up over the
+    layers of the process) that moves on by itself after every backward pass."""
+    global _next_stream_id
+    cfg = NMConfig(stream_id=_next_stream_id, auto_advance=True)
+    _next_stream_id += 1
+    return cfg
 
 
 def _update_gemm(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Tensor:
@@ -95,25 +111,21 @@ def _conv_update_shifted(gy: torch.Tensor, x: torch.Tensor, k: int, cfg: NMConfi
     g2[:rows] = gr
     shifts = [(ky - pad) * wp + (kx - pad) for ky in range(k) for kx in range(k)]
     if q8:
-        sg, sh = pow2_scale(g2, 57344.0 / 4.0), pow2_scale(x_full, 448.0)
-        x8 = (x_full.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8)
+        # scales and the e4m3 cast are the library's: the scale records stay in device memory (no host read-back)
+        sg, sh = api.nm_q8_scale(g2, 57344.0 / 4.0), api.nm_q8_scale(x_full, 448.0)
+        x8 = api.nm_cast_e4m3(x_full, sh)
         v8, m32 = api.mvue_prune_2of4_q8(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
-        dW = api.nm_update_gemm_q8_shifted(v8, m32, x8, margin, shifts, alpha=1.0 / (sg * sh))
+        dW = api.nm_update_gemm_q8_shifted(v8, m32, x8, margin, shifts, alpha=(sg, sh))
     else:
         vals, meta, _ = api.mvue_prune_2of4(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode)
         dW = api.nm_update_gemm_shifted(vals, meta, x_full, margin, shifts)          # [O, (ky, kx, c)]
     return dW.reshape(O, k, k, C).permute(0, 3, 1, 2).contiguous()
 
 
-def pow2_scale(t: torch.Tensor, top: float) -> float:
-    """largest power of two s with s * max|t| <= top (1.0 for an all-zero tensor); reads the maximum back to the host"""
-    m = float(t.abs().max())
-    return 1.0 if m == 0.0 or not math.isfinite(m) else 2.0 ** math.floor(math.log2(top / m))
-
-
 def _update_gemm_q8(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.Tensor:
-    """The 8-bit update phase: per-tensor power-of-two scales from the current maxima (a kept value is at most the
-    sum of its block's magnitudes, hence the factor 4 or 2), activations cast to e4m3 by torch, everything else in the library."""
+    """The 8-bit update phase, all of it in the library: per-tensor power-of-two scales from the current maxima (a kept
+    value is at most the sum of its block's magnitudes, hence the factor 4 or 2) as device-side records, the e4m3 cast
+    of the activations, the prune and the GEMM.  No value returns to the host."""
     if cfg.nm not in ("2:4", "1:2"):
         raise ValueError(f"unknown N:M pattern {cfg.nm!r}")
     T, O = g2.shape
@@ -124,14 +136,15 @@ def _update_gemm_q8(g2: torch.Tensor, h2: torch.Tensor, cfg: NMConfig) -> torch.
     if pad:
         g2 = F.pad(g2, (0, 0, 0, pad))
         h2 = F.pad(h2, (0, 0, 0, pad))
-    sg = pow2_scale(g2, 57344.0 / (4.0 if cfg.nm == "2:4" else 2.0))    # (1:2: the sum of a pair's magnitudes)
-    sh = pow2_scale(h2, 448.0)
-    h8 = (h2.float() * sh).to(torch.float8_e4m3fn).view(torch.uint8)
+    g2, h2 = g2.contiguous(), h2.contiguous()
+    sg = api.nm_q8_scale(g2, 57344.0 / (4.0 if cfg.nm == "2:4" else 2.0))    # (1:2: the sum of a pair's magnitudes)
+    sh = api.nm_q8_scale(h2, 448.0)
+    h8 = api.nm_cast_e4m3(h2, sh)
     if cfg.nm == "1:2":
-        v8, m32 = api.mvue_prune_1of2_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, scale=sg)
+        v8, m32 = api.mvue_prune_1of2_q8(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, scale=sg)
     else:
-        v8, m32 = api.mvue_prune_2of4_q8(g2.contiguous(), seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
-    return api.nm_update_gemm_q8(v8, m32, h8, alpha=1.0 / (sg * sh))
+        v8, m32 = api.mvue_prune_2of4_q8(g2, seed=cfg.current_seed(), stream_id=cfg.stream_id, mode=cfg.mode, scale=sg)
+    return api.nm_update_gemm_q8(v8, m32, h8, alpha=(sg, sh))
 
 
 class _NMLinearFn(torch.autograd.Function):
@@ -149,6 +162,8 @@ class _NMLinearFn(torch.autograd.Function):
         if ctx.needs_input_grad[1]:
             dW = _update_gemm(gy.reshape(-1, gy.shape[-1]), x.reshape(-1, x.shape[-1]), ctx.cfg).to(weight.dtype)
         db = gy.reshape(-1, gy.shape[-1]).sum(0) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        if ctx.cfg.auto_advance:
+            ctx.cfg.advance()
         return dx, dW, db, None
 
 
@@ -157,7 +172,7 @@ class NMLinear(torch.nn.Linear):
 
     def __init__(self, in_features: int, out_features: int, bias: bool = True, cfg: Optional[NMConfig] = None, **kw):
         super().__init__(in_features, out_features, bias=bias, **kw)
-        self.cfg = cfg or NMConfig()
+        self.cfg = cfg or _own_config()
 
     def forward(self, x):
         return _NMLinearFn.apply(x, self.weight, self.bias, self.cfg)
@@ -194,6 +209,8 @@ class _NMConv2dFn(torch.autograd.Function):
                 g2 = gy.reshape(gy.shape[0], O, -1).transpose(1, 2).reshape(-1, O)
                 dW = _update_gemm(g2, h2, ctx.cfg).reshape(O, C, kh, kw).to(weight.dtype)
         db = gy.sum((0, 2, 3)) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        if ctx.cfg.auto_advance:
+            ctx.cfg.advance()
         return dx, dW, db, None, None, None, None
 
 
@@ -207,7 +224,7 @@ class NMConv2d(torch.nn.Conv2d):
         super().__init__(*args, **kw)
         if self.groups != 1 or self.padding_mode != "zeros" or isinstance(self.padding, str):
             raise ValueError("NMConv2d supports groups=1 with numeric zero padding")
-        self.cfg = cfg or NMConfig()
+        self.cfg = cfg or _own_config()
 
     def forward(self, x):
         return _NMConv2dFn.apply(x, self.weight, self.bias, self.stride, self.padding, self.dilation, self.cfg)

@@ -600,8 +600,9 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_tall_kernel(
 template <int R>
 __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restrict__ part, int slabs, int64_t slab_stride,
                                                            float *__restrict__ out, int64_t ldo, int64_t O, int64_t I, int accumulate,
-                                                           float alpha)
+                                                           AlphaArg al)
 {
+    const float alpha = alpha_of(al);
     const int64_t n4 = O * (I / 4);
     const int r = threadIdx.x % R;
     const int64_t idx = (int64_t)blockIdx.x * (256 / R) + threadIdx.x / R;
@@ -628,7 +629,7 @@ __global__ __launch_bounds__(256) void splitk_reduce_kernel(const float *__restr
 
 // dW = (accumulate ? dW : 0) + alpha * sum over the slabs of [slabs][O][I] partial sums (row stride I), in slab order
 hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
-                                int accumulate, float alpha, hipStream_t st)
+                                int accumulate, AlphaArg alpha, hipStream_t st)
 {
     const int64_t n4 = O * (I / 4);
     if (slabs >= 12)

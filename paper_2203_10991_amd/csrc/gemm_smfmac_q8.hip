@@ -62,6 +62,18 @@ __device__ __forceinline__ void store_acc_scaled(float *p, float v, float alpha)
     asm volatile("v_accvgpr_read_b32 %0, %2\n\tv_mul_f32 %0, %0, %3\n\tglobal_store_dword %1, %0, off"
                  : "=&v"(t) : "v"(p), "a"(v), "v"(alpha) : "memory");
 }
+// The (accumulate, alpha) argument pair of the kernels also carries the device-scale form without another kernel
+// argument (the 384 x 256 kernel has no register to spare for one): accumulate bit 0 = add to what is there, bit 1 =
+// "the scale is in device memory", and then the other 62 bits of the pair are the address of that binary32 value
+// (4-byte aligned: low 30 bits in accumulate[31:2], high 32 bits in alpha's bit pattern).  Decoded in the epilogue only.
+__device__ __forceinline__ float decode_alpha(int accumulate, float alpha)
+{
+    if (accumulate & 2) {
+        const uint64_t addr = ((uint64_t)__float_as_uint(alpha) << 32) | (uint32_t)(accumulate & ~3);
+        return *(const float *)addr;
+    }
+    return alpha;
+}
 template <int OFFSET> __device__ __forceinline__ u32x2 lds_read_tr8(uint32_t addr)
 {
     u32x2 r;
@@ -308,6 +320,7 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
 #pragma unroll
         for (int b = 0; b < BB; ++b) acc_settled(acc[a][b]);
     __builtin_amdgcn_sched_barrier(0);
+    const float alpha_v = decode_alpha(accumulate, alpha);
     const int64_t o0 = m0 + wm * (AB * 32);
 #pragma unroll
     for (int a = 0; a < AB; ++a)
@@ -319,8 +332,8 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_q8_kernel(
                 const int64_t row = o0 + AB * (8 * (r >> 2) + 4 * (lane >> 5) + (r & 3)) + a;   // block a holds rows a, AB+a, ...
                 if (row < O && col < I) {
                     float *p = out + row * ldo + col;
-                    if (accumulate) *p = *p + acc[a][b][r] * alpha;
-                    else store_acc_scaled(p, acc[a][b][r], alpha);
+                    if (accumulate & 1) *p = *p + acc[a][b][r] * alpha_v;
+                    else store_acc_scaled(p, acc[a][b][r], alpha_v);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -550,6 +563,8 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_q8_tall_kernel(
         for (int b = 0; b < BB; ++b) acc_settled<(a >= 4)>(acc[a][b]);
     });
     __builtin_amdgcn_sched_barrier(0);
+    const float alpha_v = decode_alpha(accumulate, alpha);
+    __builtin_amdgcn_sched_barrier(0);
     static_for<AB>([&](auto a_c) {
         constexpr int a = decltype(a_c)::value;
 #pragma unroll
@@ -561,9 +576,9 @@ __global__ __launch_bounds__(512) void update_gemm_smfmac_q8_tall_kernel(
                 const int64_t row = m0 + wm * 192 + 6 * mr + a;
                 if (row < o_end && col < I) {
                     float *p = out + row * ldo + col;
-                    if (accumulate) *p = *p + acc[a][b][r] * alpha;
-                    else if constexpr (a >= 4) *p = acc[a][b][r] * alpha;
-                    else store_acc_scaled(p, acc[a][b][r], alpha);
+                    if (accumulate & 1) *p = *p + acc[a][b][r] * alpha_v;
+                    else if constexpr (a >= 4) *p = acc[a][b][r] * alpha_v;
+                    else store_acc_scaled(p, acc[a][b][r], alpha_v);
                 }
             }
             __builtin_amdgcn_sched_barrier(0);       // one block at a time
@@ -612,6 +627,27 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I, bool shifted = false
     return p;
 }
 
+// alpha = rec_a[1] * rec_b[1], left in rec_b[3] (the consumer's scratch slot of a scale record) for the kernels
+__global__ void q8_alpha_product_kernel(const float *rec_a, float *rec_b)
+{
+    if (threadIdx.x == 0) rec_b[3] = rec_a[1] * rec_b[1];
+}
+
+// the (accumulate, alpha) pair the kernels take: host scale, or the address of the device scale (see decode_alpha)
+struct AlphaPair { int acc; float alpha; };
+static AlphaPair encode_alpha(int accumulate, const AlphaArg &al, hipStream_t st)
+{
+    if (!al.inv_a) return AlphaPair{accumulate, al.value};
+    float *slot = const_cast<float *>(al.inv_b) + 3;
+    hipLaunchKernelGGL(q8_alpha_product_kernel, dim3(1), dim3(64), 0, st, al.inv_a, const_cast<float *>(al.inv_b));
+    const uint64_t addr = (uint64_t)(uintptr_t)slot;
+    AlphaPair p;
+    p.acc = (int)((uint32_t)addr | 2u | (uint32_t)(accumulate & 1));
+    const uint32_t hi = (uint32_t)(addr >> 32);
+    __builtin_memcpy(&p.alpha, &hi, 4);
+    return p;
+}
+
 size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
 {
     if (T <= 0 || O <= 0 || I <= 0) return 0;
@@ -619,7 +655,7 @@ size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
 }
 
 hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
-                                 int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace,
+                                 int64_t lddw, int64_t T, int64_t O, int64_t I, AlphaArg alpha, float beta, void *workspace,
                                  hipStream_t st)
 {
     if (O == 0 || I == 0) return hipSuccess;
@@ -628,8 +664,10 @@ hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, c
     const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
     float *out = tg.out;
     const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
-    const int acc_flag = tg.accumulate;
-    const float k_alpha = p.slabs > 1 ? 1.0f : alpha;              // partial sums are scaled once, in the second pass
+    // partial sums are scaled once, in the second pass; otherwise the kernels scale, by a host or a device value
+    const AlphaPair ap = p.slabs > 1 ? AlphaPair{tg.accumulate, 1.0f} : encode_alpha(tg.accumulate, alpha, st);
+    const int acc_flag = ap.acc;
+    const float k_alpha = ap.alpha;
     if (p.tall_rows > 0) {
         hipLaunchKernelGGL(update_gemm_smfmac_q8_tall_kernel, dim3((unsigned)(p.tall_tiles_m * p.tiles_n)), dim3(512), 0, st,
                            vals8, meta32, h8, ldh, out, ldo, T / 32, O, I, p.tall_tiles_m, p.tiles_n, acc_flag, k_alpha, p.tall_rows);
@@ -661,7 +699,7 @@ size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I)
 // dW = beta*dW + alpha * decompress(vals8, meta32)^T [x8 shifted by rows[0] | x8 shifted by rows[1] | ...]
 hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
                                          const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,
-                                         float alpha, float beta, void *workspace, hipStream_t st)
+                                         AlphaArg alpha, float beta, void *workspace, hipStream_t st)
 {
     const int64_t I = cb * n;
     if (O == 0 || I == 0) return hipSuccess;
@@ -671,8 +709,10 @@ hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *m
     const OutTarget tg = splitk_target(p.slabs, dW, lddw, workspace, O, I, accumulate);
     float *out = tg.out;
     const int64_t ldo = tg.ldo, slab_stride = tg.slab_stride;
-    const int acc_flag = tg.accumulate;
-    const float k_alpha = p.slabs > 1 ? 1.0f : alpha;              // partial sums are scaled once, in the second pass
+    // partial sums are scaled once, in the second pass; otherwise the kernels scale, by a host or a device value
+    const AlphaPair ap = p.slabs > 1 ? AlphaPair{tg.accumulate, 1.0f} : encode_alpha(tg.accumulate, alpha, st);
+    const int acc_flag = ap.acc;
+    const float k_alpha = ap.alpha;
     dim3 grid((unsigned)(p.tiles_m * p.tiles_n), 1, (unsigned)p.slabs);
 #define NM_LAUNCH(WM, WN, AB, BB)                                                                                     \
     hipLaunchKernelGGL((update_gemm_smfmac_q8_kernel<WM, WN, AB, BB, true>), grid, dim3(WM * WN * 64), 0, st, vals8, meta32, x8, \

@@ -337,11 +337,15 @@ int nm_update_gemm_shifted(const void *vals, const uint16_t *meta, const void *x
 }
 
 static int prune_q8(const char *fn, int est, const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed,
-                    uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+                    uint32_t stream_id, float scale, const float *scale_dev, bool device_scale, uint8_t *vals8, uint32_t *meta32,
+                    void *hip_stream)
 {
     if (int rc = check_tensor(fn, g, T, O, ldg, dtype, "g")) return rc;
     if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32 (pad with zero rows)", fn, (long long)T);
-    if (!(scale > 0.0f) || !(scale < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: scale must be positive and finite", fn);
+    if (device_scale) {
+        if (!scale_dev) return fail(NM_ERR_NULL, "%s: the scale record is NULL", fn);
+        if (!aligned16(scale_dev)) return fail(NM_ERR_ALIGN, "%s: the scale record needs a 16-byte aligned base", fn);
+    } else if (!(scale > 0.0f) || !(scale < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: scale must be positive and finite", fn);
     if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
     if (!vals8 || !meta32) return fail(NM_ERR_NULL, "%s: vals8 and meta32 must not be NULL", fn);
     if (!aligned16(vals8) || !aligned16(meta32)) return fail(NM_ERR_ALIGN, "%s: vals8 and meta32 need 16-byte aligned bases", fn);
@@ -349,8 +353,12 @@ static int prune_q8(const char *fn, int est, const void *g, int64_t T, int64_t O
     Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
     if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm))
         return fail(NM_ERR_ALIAS, "%s: g, vals8 and meta32 must not overlap", fn);
-    return launched(fn, nm::launch_prune_q8(dtype, est, g, T, O, ldg, seed, stream_id, scale, vals8, meta32,
-                                            (hipStream_t)hip_stream));
+    if (device_scale) {
+        Range rs = range_of(scale_dev, 16, "scale record");
+        if (overlap(rs, rv) || overlap(rs, rm)) return fail(NM_ERR_ALIAS, "%s: the scale record must not overlap an output", fn);
+    }
+    return launched(fn, nm::launch_prune_q8(dtype, est, g, T, O, ldg, seed, stream_id, scale, device_scale ? scale_dev : nullptr,
+                                            vals8, meta32, (hipStream_t)hip_stream));
 }
 
 int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
@@ -358,13 +366,66 @@ int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dty
 {
     if (mode != 0 && mode != 1)
         return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_q8: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
-    return prune_q8("mvue_prune_2of4_q8", mode, g, T, O, ldg, dtype, seed, stream_id, scale, vals8, meta32, hip_stream);
+    return prune_q8("mvue_prune_2of4_q8", mode, g, T, O, ldg, dtype, seed, stream_id, scale, nullptr, false, vals8, meta32, hip_stream);
+}
+
+int mvue_prune_2of4_q8_ds(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                          int mode, const float *scale_rec, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_q8_ds: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
+    return prune_q8("mvue_prune_2of4_q8_ds", mode, g, T, O, ldg, dtype, seed, stream_id, 1.0f, scale_rec, true, vals8, meta32, hip_stream);
+}
+
+int mvue_prune_1of2_q8_ds(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
+                          const float *scale_rec, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    return prune_q8("mvue_prune_1of2_q8_ds", 3, g, T, O, ldg, dtype, seed, stream_id, 1.0f, scale_rec, true, vals8, meta32, hip_stream);
+}
+
+int nm_q8_scale(const void *t, int64_t R, int64_t C, int64_t ld, int dtype, float top, float *scale_rec, void *hip_stream)
+{
+    const char *fn = "nm_q8_scale";
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (R < 0 || C < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (C % 8) return fail(NM_ERR_SHAPE, "%s: C=%lld is not a multiple of 8", fn, (long long)C);
+    if (too_big(R, C) || too_big(R, ld)) return fail(NM_ERR_SHAPE, "%s: the tensor is larger than 2^58 elements", fn);
+    if (!(top > 0.0f) || !(top < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: top must be positive and finite", fn);
+    if (!scale_rec) return fail(NM_ERR_NULL, "%s: the scale record is NULL", fn);
+    if (!aligned16(scale_rec)) return fail(NM_ERR_ALIGN, "%s: the scale record needs a 16-byte aligned base", fn);
+    if (R > 0 && C > 0) {
+        if (!t) return fail(NM_ERR_NULL, "%s: t is NULL", fn);
+        if (ld < C) return fail(NM_ERR_SHAPE, "%s: row stride %lld is smaller than C=%lld", fn, (long long)ld, (long long)C);
+        if (!aligned16(t) || (ld * esize(dtype)) % 16) return fail(NM_ERR_ALIGN, "%s: t needs a 16-byte aligned base and row stride", fn);
+        if (overlap(range_of(t, ((R - 1) * ld + C) * esize(dtype), "t"), range_of(scale_rec, 16, "scale record")))
+            return fail(NM_ERR_ALIAS, "%s: the scale record must not overlap t", fn);
+    }
+    return launched(fn, nm::launch_q8_scale(dtype, t, R, C, ld, top, scale_rec, (hipStream_t)hip_stream));
+}
+
+int nm_cast_e4m3(const void *h, int64_t R, int64_t C, int64_t ld, int dtype, const float *scale_rec, uint8_t *h8, int64_t ld8,
+                 void *hip_stream)
+{
+    const char *fn = "nm_cast_e4m3";
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (R < 0 || C < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (C % 16) return fail(NM_ERR_SHAPE, "%s: C=%lld is not a multiple of 16", fn, (long long)C);
+    if (too_big(R, C) || too_big(R, ld) || too_big(R, ld8)) return fail(NM_ERR_SHAPE, "%s: a tensor is larger than 2^58 elements", fn);
+    if (R == 0 || C == 0) { g_err[0] = 0; return NM_OK; }
+    if (!h || !h8 || !scale_rec) return fail(NM_ERR_NULL, "%s: h, h8 and the scale record must not be NULL", fn);
+    if (ld < C || ld8 < C) return fail(NM_ERR_SHAPE, "%s: a row stride is smaller than C=%lld", fn, (long long)C);
+    if (!aligned16(h) || (ld * esize(dtype)) % 16 || !aligned16(h8) || ld8 % 16 || !aligned16(scale_rec))
+        return fail(NM_ERR_ALIGN, "%s: h, h8 (bases and row strides) and the scale record need 16-byte alignment", fn);
+    Range rh = range_of(h, ((R - 1) * ld + C) * esize(dtype), "h"), r8 = range_of(h8, (R - 1) * ld8 + C, "h8");
+    Range rs = range_of(scale_rec, 16, "scale record");
+    if (overlap(rh, r8) || overlap(rs, r8)) return fail(NM_ERR_ALIAS, "%s: h8 must not overlap h or the scale record", fn);
+    return launched(fn, nm::launch_cast_e4m3(dtype, h, R, C, ld, scale_rec, h8, ld8, (hipStream_t)hip_stream));
 }
 
 int mvue_prune_1of2_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
                        float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
 {
-    return prune_q8("mvue_prune_1of2_q8", 3, g, T, O, ldg, dtype, seed, stream_id, scale, vals8, meta32, hip_stream);
+    return prune_q8("mvue_prune_1of2_q8", 3, g, T, O, ldg, dtype, seed, stream_id, scale, nullptr, false, vals8, meta32, hip_stream);
 }
 
 size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
@@ -373,11 +434,20 @@ size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I)
     return nm::update_gemm_q8_workspace(T, O, I);
 }
 
-int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW, int64_t lddw,
-                      int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace, size_t workspace_bytes,
-                      void *hip_stream)
+// scale records of the _ds entry points: present, aligned, clear of the output
+static int check_scale_recs(const char *fn, const float *a, const float *b, const Range &rd)
 {
-    const char *fn = "nm_update_gemm_q8";
+    if (!a || !b) return fail(NM_ERR_NULL, "%s: a scale record is NULL", fn);
+    if (!aligned16(a) || !aligned16(b)) return fail(NM_ERR_ALIGN, "%s: the scale records need 16-byte aligned bases", fn);
+    if (overlap(range_of(a, 16, "scale record"), rd) || overlap(range_of(b, 16, "scale record"), rd))
+        return fail(NM_ERR_ALIAS, "%s: dW must not overlap a scale record", fn);
+    return NM_OK;
+}
+
+static int update_gemm_q8_checked(const char *fn, const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh,
+                                  float *dW, int64_t lddw, int64_t T, int64_t O, int64_t I, nm::AlphaArg alpha, bool device_scale,
+                                  float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
     if (T < 0 || O < 0 || I < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
     if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32", fn, (long long)T);
     if (O % 8 || I % 16) return fail(NM_ERR_SHAPE, "%s: O=%lld must be a multiple of 8 and I=%lld of 16", fn, (long long)O, (long long)I);
@@ -404,8 +474,25 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
         if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
     if (int rc = check_workspace(fn, nm::update_gemm_q8_workspace(T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
+    if (device_scale) if (int rc = check_scale_recs(fn, alpha.inv_a, alpha.inv_b, rd)) return rc;
     return launched(fn, nm::launch_update_gemm_q8(vals8, meta32, h8, ldh, dW, lddw, T, O, I, alpha, beta, workspace,
                                                   (hipStream_t)hip_stream));
+}
+
+int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW, int64_t lddw,
+                      int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace, size_t workspace_bytes,
+                      void *hip_stream)
+{
+    return update_gemm_q8_checked("nm_update_gemm_q8", vals8, meta32, h8, ldh, dW, lddw, T, O, I, nm::AlphaArg(alpha), false, beta,
+                                  workspace, workspace_bytes, hip_stream);
+}
+
+int nm_update_gemm_q8_ds(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW, int64_t lddw,
+                         int64_t T, int64_t O, int64_t I, const float *scale_rec_g, float *scale_rec_h, float beta,
+                         void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return update_gemm_q8_checked("nm_update_gemm_q8_ds", vals8, meta32, h8, ldh, dW, lddw, T, O, I,
+                                  nm::AlphaArg(1.0f, scale_rec_g, scale_rec_h), true, beta, workspace, workspace_bytes, hip_stream);
 }
 
 size_t nm_update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t cb, int n_shift)
@@ -414,11 +501,11 @@ size_t nm_update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t cb, int
     return nm::update_gemm_q8_shifted_workspace(T, O, cb * n_shift);
 }
 
-int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
-                              const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
-                              float alpha, float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
+static int update_gemm_q8_shifted_checked(const char *fn, const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx,
+                                          int64_t cb, const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T,
+                                          int64_t O, nm::AlphaArg alpha, bool device_scale, float beta, void *workspace,
+                                          size_t workspace_bytes, void *hip_stream)
 {
-    const char *fn = "nm_update_gemm_q8_shifted";
     if (T < 0 || O < 0 || cb < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
     if (n_shift < 1 || n_shift > 32) return fail(NM_ERR_SHAPE, "%s: n_shift=%d must be 1..32", fn, n_shift);
     if (!row_shift) return fail(NM_ERR_NULL, "%s: row_shift is NULL", fn);
@@ -451,8 +538,27 @@ int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, cons
         if (overlap(rd, rin[0]) || overlap(rd, rin[1]) || overlap(rd, rin[2])) return fail(NM_ERR_ALIAS, "%s: dW must not overlap an input", fn);
     }
     if (int rc = check_workspace(fn, nm::update_gemm_q8_shifted_workspace(T, O, I), workspace, workspace_bytes, rd, rin, n_in)) return rc;
+    if (device_scale) if (int rc = check_scale_recs(fn, alpha.inv_a, alpha.inv_b, rd)) return rc;
     return launched(fn, nm::launch_update_gemm_q8_shifted(vals8, meta32, x8, ldx, cb, row_shift, n_shift, dW, lddw, T, O, alpha,
                                                           beta, workspace, (hipStream_t)hip_stream));
+}
+
+int nm_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                              const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                              float alpha, float beta, void *workspace, size_t workspace_bytes, void *hip_stream)
+{
+    return update_gemm_q8_shifted_checked("nm_update_gemm_q8_shifted", vals8, meta32, x8, ldx, cb, row_shift, n_shift, dW, lddw, T, O,
+                                          nm::AlphaArg(alpha), false, beta, workspace, workspace_bytes, hip_stream);
+}
+
+int nm_update_gemm_q8_shifted_ds(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
+                                 const int64_t *row_shift, int n_shift, float *dW, int64_t lddw, int64_t T, int64_t O,
+                                 const float *scale_rec_g, float *scale_rec_x, float beta, void *workspace,
+                                 size_t workspace_bytes, void *hip_stream)
+{
+    return update_gemm_q8_shifted_checked("nm_update_gemm_q8_shifted_ds", vals8, meta32, x8, ldx, cb, row_shift, n_shift, dW, lddw, T, O,
+                                          nm::AlphaArg(1.0f, scale_rec_g, scale_rec_x), true, beta, workspace, workspace_bytes,
+                                          hip_stream);
 }
 
 const char *nm_last_error(void) { return g_err; }

@@ -9,6 +9,15 @@
 
 namespace nm {
 
+// Output scale of the 8-bit update GEMM: a host value, or (inv_a != nullptr) value * inv_a[1] * inv_b[1] with the two
+// factors read on the device -- element [1] of a scale record written by launch_q8_scale is the inverse scale; the
+// GEMM launchers leave that product in inv_b[3] (the record's scratch slot) for their kernels.
+struct AlphaArg {
+    float value;
+    const float *inv_a, *inv_b;
+    AlphaArg(float v = 1.0f, const float *a = nullptr, const float *b = nullptr) : value(v), inv_a(a), inv_b(b) {}
+};
+
 hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st);
 
@@ -51,21 +60,28 @@ hipError_t launch_update_gemm_f32_split(const void *vals, const uint16_t *meta, 
                                         hipStream_t st);
 size_t update_gemm_f32_split_workspace(int64_t T, int64_t O, int64_t I);
 hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t lddw, int64_t O, int64_t I,
-                                int accumulate, float alpha, hipStream_t st);
+                                int accumulate, AlphaArg alpha, hipStream_t st);
 
 // 8-bit path: 2:4 prune with e5m2 output (stochastic rounding) in 32-token groups, and its update GEMM
 // dW = beta*dW + alpha * decompress(vals8, meta32)^T h8  (vals8 e5m2, h8 e4m3)
 hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
-                           uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st);
+                           uint32_t stream_id, float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32, hipStream_t st);
 hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
-                                 int64_t lddw, int64_t T, int64_t O, int64_t I, float alpha, float beta, void *workspace,
+                                 int64_t lddw, int64_t T, int64_t O, int64_t I, AlphaArg alpha, float beta, void *workspace,
                                  hipStream_t st);
 size_t update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
 // ... with h8 given as n row-shifted views of one [rows x cb] matrix x8
 hipError_t launch_update_gemm_q8_shifted(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *x8, int64_t ldx, int64_t cb,
                                          const int64_t *rows, int n, float *dW, int64_t lddw, int64_t T, int64_t O,
-                                         float alpha, float beta, void *workspace, hipStream_t st);
+                                         AlphaArg alpha, float beta, void *workspace, hipStream_t st);
 size_t update_gemm_q8_shifted_workspace(int64_t T, int64_t O, int64_t I);
+
+// 8-bit path, per-tensor scale and activation cast (q8_scale.hip).  rec: device float[4] = {s, 1/s, bits of max|t|, 0}
+// with s the largest power of two such that s * max|t| <= top (1 for an all-zero or non-finite tensor).
+hipError_t launch_q8_scale(int dt, const void *t, int64_t R, int64_t C, int64_t ld, float top, float *rec, hipStream_t st);
+// h8 = e4m3(h * rec[0]), round to nearest even, magnitudes beyond 448 saturate
+hipError_t launch_cast_e4m3(int dt, const void *h, int64_t R, int64_t C, int64_t ld, const float *rec, uint8_t *h8, int64_t ld8,
+                            hipStream_t st);
 
 // The library's static device scratch array (nm_static.hip): its size, and its address on the current device
 // (looked up once per device; no allocation).

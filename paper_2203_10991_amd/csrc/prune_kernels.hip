@@ -411,8 +411,9 @@ __device__ __forceinline__ uint32_t sr_e5m2_into(uint32_t word, float x, uint32_
 template <int DT, int EST>
 __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
-    float scale, uint8_t *__restrict__ vals8, uint32_t *__restrict__ meta32)
+    float scale, const float *__restrict__ scale_dev, uint8_t *__restrict__ vals8, uint32_t *__restrict__ meta32)
 {
+    if (scale_dev) scale = scale_dev[0];            // the scale as a device value (element 0 of a scale record)
     constexpr int VEC = Row<DT>::VEC;
     constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
     const int64_t ncg = O / VEC;
@@ -520,20 +521,20 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
 
 template <int DT, int EST>
 static hipError_t launch_prune_q8_t(const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed, uint32_t stream_id,
-                                    float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
+                                    float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
 {
     const int64_t groups = T / 32, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
     hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, vals8, meta32);
+                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
     return hipGetLastError();
 }
 
 hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
-                           uint32_t stream_id, float scale, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
+                           uint32_t stream_id, float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
 {
-#define NM_PRUNE8(DT, EST) launch_prune_q8_t<DT, EST>(g, T, O, ldg, seed, stream_id, scale, vals8, meta32, st)
+#define NM_PRUNE8(DT, EST) launch_prune_q8_t<DT, EST>(g, T, O, ldg, seed, stream_id, scale, scale_dev, vals8, meta32, st)
     // est: 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2
     if (dt == NM_DT_F32) return est == 3 ? NM_PRUNE8(NM_DT_F32, 3) : est == 1 ? NM_PRUNE8(NM_DT_F32, 1) : NM_PRUNE8(NM_DT_F32, 0);
     return est == 3 ? NM_PRUNE8(NM_DT_BF16, 3) : est == 1 ? NM_PRUNE8(NM_DT_BF16, 1) : NM_PRUNE8(NM_DT_BF16, 0);

@@ -7,6 +7,8 @@
 #include <type_traits>
 #include <utility>
 
+#include "nm_internal.h"     // AlphaArg
+
 namespace nm {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
@@ -181,6 +183,12 @@ __device__ __forceinline__ void tile_of_workgroup(int bid_, int tiles_m, int til
             tn = in_band / band_rows;
         }
     }
+}
+
+// the output scale of a kernel: a host value, or that value times two inverse scales read from device memory
+__device__ __forceinline__ float alpha_of(const AlphaArg &al)
+{
+    return al.inv_a ? al.value * al.inv_a[1] * al.inv_b[1] : al.value;
 }
 
 // The dense operand as row-shifted views of one [rows x cb] matrix (a convolution's im2col matrix that is never

@@ -16,6 +16,7 @@
 
 static int g_launches = 0;
 namespace nm {
+struct AlphaArg { float value; const float *inv_a, *inv_b; };      // layout of the library's own (passed by value)
 hipError_t launch_prune(int, int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint16_t *, void *, int64_t,
                         hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_prune_transposed(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint16_t *,
@@ -23,18 +24,20 @@ hipError_t launch_prune_transposed(int, int, const void *, int64_t, int64_t, int
 hipError_t launch_prune_4of8_approx(int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint32_t *, void *, int64_t,
                                     hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_compress(int, int, const void *, int64_t, int64_t, int64_t, void *, uint16_t *, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
-hipError_t launch_prune_q8(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, float, uint8_t *, uint32_t *,
+hipError_t launch_prune_q8(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, float, const float *, uint8_t *, uint32_t *,
                            hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_q8_scale(int, const void *, int64_t, int64_t, int64_t, float, float *, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_cast_e4m3(int, const void *, int64_t, int64_t, int64_t, const float *, uint8_t *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_update_gemm(int, const void *, const uint16_t *, const void *, int64_t, float *, int64_t, int64_t, int64_t, int64_t, float,
                               void *, size_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_update_gemm_q8(const uint8_t *, const uint32_t *, const uint8_t *, int64_t, float *, int64_t, int64_t, int64_t, int64_t,
-                                 float, float, void *, hipStream_t) { ++g_launches; return hipSuccess; }
+                                 AlphaArg, float, void *, hipStream_t) { ++g_launches; return hipSuccess; }
 static int64_t read_rows(const int64_t *rows, int n) { int64_t s = 0; for (int j = 0; j < n; ++j) s += rows[j]; return s; }
 hipError_t launch_update_gemm_smfmac_shifted(const void *, const uint16_t *, const void *, int64_t, int64_t, const int64_t *rows, int n, float *,
                                              int64_t, int64_t, int64_t, float, void *, hipStream_t)
 { ++g_launches; return read_rows(rows, n) == INT64_MIN ? hipErrorUnknown : hipSuccess; }
 hipError_t launch_update_gemm_q8_shifted(const uint8_t *, const uint32_t *, const uint8_t *, int64_t, int64_t, const int64_t *rows, int n,
-                                         float *, int64_t, int64_t, int64_t, float, float, void *, hipStream_t)
+                                         float *, int64_t, int64_t, int64_t, AlphaArg, float, void *, hipStream_t)
 { ++g_launches; return read_rows(rows, n) == INT64_MIN ? hipErrorUnknown : hipSuccess; }
 // split-K whenever there are few output tiles, as the real plans do (sizes only matter to the checks)
 size_t update_gemm_workspace(int, int64_t T, int64_t O, int64_t I) { return O * I <= 1 << 20 && T >= 1024 ? (size_t)(2 * O * I * 4) : 0; }
@@ -95,6 +98,28 @@ int main()
     EXPECT(nm_update_gemm_shifted(vals, m16, x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, NM_BF16, 0.f, ws, wsb_conv, nullptr), NM_OK);
     EXPECT(nm_update_gemm_q8_shifted((const uint8_t *)vals, m32, (const uint8_t *)x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, 1.f, 0.f, ws, wsb_conv,
                                      nullptr), NM_OK);
+    // device-side scales of the 8-bit path
+    alignas(16) static float rec_g[4], rec_h[4];
+    EXPECT(nm_q8_scale(g, T, O, O, NM_BF16, 448.f, rec_g, nullptr), NM_OK);
+    EXPECT(nm_q8_scale(g, T, O, O, NM_F32, 57344.f / 4.f, rec_h, nullptr), NM_OK);
+    EXPECT(nm_cast_e4m3(h, T, I, I, NM_BF16, rec_h, (uint8_t *)x, I, nullptr), NM_OK);
+    EXPECT(mvue_prune_2of4_q8_ds(g, T, O, O, NM_BF16, 1, 2, 0, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);
+    EXPECT(mvue_prune_1of2_q8_ds(g, T, O, O, NM_BF16, 1, 2, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);
+    EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, rec_g, rec_h, 0.f, ws, wsb, nullptr), NM_OK);
+    EXPECT(nm_update_gemm_q8_shifted_ds((const uint8_t *)vals, m32, (const uint8_t *)x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, rec_g, rec_h, 0.f,
+                                        ws, wsb_conv, nullptr), NM_OK);
+    EXPECT(nm_q8_scale(g, T, O, O, NM_BF16, 0.f, rec_g, nullptr), NM_ERR_SHAPE);
+    EXPECT(nm_q8_scale(g, T, O + 4, O + 4, NM_BF16, 1.f, rec_g, nullptr), NM_ERR_SHAPE);
+    EXPECT(nm_q8_scale(g, T, O, O, NM_BF16, 1.f, nullptr, nullptr), NM_ERR_NULL);
+    EXPECT(nm_q8_scale(g, T, O, O, NM_BF16, 1.f, (float *)((char *)g + 64), nullptr), NM_ERR_ALIAS);
+    EXPECT(nm_q8_scale(g, huge, huge, huge, NM_BF16, 1.f, rec_g, nullptr), NM_ERR_SHAPE);
+    EXPECT(nm_cast_e4m3(h, T, I + 8, I + 8, NM_BF16, rec_h, (uint8_t *)x, I + 8, nullptr), NM_ERR_SHAPE);
+    EXPECT(nm_cast_e4m3(h, T, I, I, NM_BF16, rec_h, (uint8_t *)h + 32, I, nullptr), NM_ERR_ALIAS);
+    EXPECT(nm_cast_e4m3(h, T, I, I, NM_BF16, nullptr, (uint8_t *)x, I, nullptr), NM_ERR_NULL);
+    EXPECT(mvue_prune_2of4_q8_ds(g, T, O, O, NM_BF16, 1, 2, 0, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_NULL);
+    EXPECT(mvue_prune_2of4_q8_ds(g, T, O, O, NM_BF16, 1, 2, 0, rec_g + 1, (uint8_t *)vals, m32, nullptr), NM_ERR_ALIGN);
+    EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, rec_g, nullptr, 0.f, ws, wsb, nullptr), NM_ERR_NULL);
+    EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, dW + 4, rec_h, 0.f, ws, wsb, nullptr), NM_ERR_ALIAS);
     // empty problems do nothing and need no pointers
     EXPECT(mvue_prune_2of4(nullptr, 0, O, O, NM_BF16, 0, 0, 0, nullptr, nullptr, nullptr, 0, nullptr), NM_OK);
     EXPECT(mvue_prune_4of8_approx(nullptr, T, 0, 0, NM_BF16, 0, 0, nullptr, nullptr, nullptr, 0, nullptr), NM_OK);
