@@ -198,3 +198,26 @@ def make_device(w: Workload, seed: int = 0, device: str = "cuda:0", rows_per_pas
             x = torch.where(keep, x.abs(), torch.zeros((), device=device))
         h[a:b] = x.to(tdt)
     return g, h
+
+
+def make_device_from_host(w: Workload, seed: int = 0, device: str = "cuda:0", threads: int = 8, rows_per_pass: int = 4096):
+    """(g, h) of ``w`` on ``device`` from the HOST recipe (numpy PCG64, the arrays make_g / make_h return), drawn and
+    copied in row slabs: the device tensors equal what a test or the CPU oracle gets from make_g / make_h for the same
+    seed, element for element."""
+    import torch
+
+    tdt = torch.float32 if w.dtype == "f32" else torch.bfloat16
+    g = torch.empty((w.T, w.O), dtype=tdt, device=device)
+    h = torch.empty((w.T, w.I), dtype=tdt, device=device)
+
+    def put(dst, a):
+        if w.dtype == "f32":
+            dst.copy_(torch.from_numpy(a))
+        else:
+            dst.view(torch.int16).copy_(torch.from_numpy(a.view(np.int16)))
+
+    for a in range(0, w.T, rows_per_pass):
+        b = min(a + rows_per_pass, w.T)
+        put(g[a:b], make_g(w, seed, rows=(a, b), threads=threads))
+        put(h[a:b], make_h(w, seed, rows=(a, b), threads=threads))
+    return g, h
