@@ -118,6 +118,8 @@ def lib():
         _lib.oracle_e4m3_rne.restype = u8
         _lib.oracle_cast_e4m3.argtypes = [vp, i64, i64, i64, i32, flt, vp, i64]
         _lib.oracle_cast_e4m3.restype = None
+        _lib.oracle_act_backward.argtypes = [vp, i64, vp, i64, i64, i64, i32, vp, i64]
+        _lib.oracle_act_backward.restype = None
         _lib.oracle_num_threads.argtypes = []
         _lib.oracle_num_threads.restype = i32
     return _lib
@@ -504,3 +506,13 @@ def cast_e4m3(h: np.ndarray, scale: float) -> np.ndarray:
     h8 = np.zeros((R, Cc), dtype=np.uint8)
     lib().oracle_cast_e4m3(_p(h), R, Cc, h.strides[0] // h.itemsize, _dt(h), C.c_float(scale), _p(h8), Cc)
     return h8
+
+
+# ---- the producer of the neural gradient: g = u * d elementwise (eq. (2): d = f'(z), u = W^T g_next), rounded to the dtype
+
+def act_backward(u: np.ndarray, d: np.ndarray) -> np.ndarray:
+    assert u.shape == d.shape and u.dtype == d.dtype
+    T, O = u.shape
+    g = np.zeros((T, O), dtype=u.dtype)
+    lib().oracle_act_backward(_p(u), u.strides[0] // u.itemsize, _p(d), d.strides[0] // d.itemsize, T, O, _dt(u), _p(g), O)
+    return g

@@ -938,6 +938,24 @@ void oracle_cast_e4m3(const void *h, int64_t R, int64_t C, int64_t ld, int dt, f
 }
 
 /* ------------------------------------------------------------------------- */
+/* The producer of the neural gradient (eq. (2)): g_l = Diag(f'(z_l)) W^T g_{l+1}. */
+/* The matrix product u = W^T g_{l+1} is a dense GEMM the method leaves alone;     */
+/* the last step that makes g_l is the elementwise product with the activation's  */
+/* derivative d = f'(z_l).  Plain definition: one binary32 product per element,   */
+/* rounded to the storage type -- that rounded tensor is the neural gradient the  */
+/* next layer's backward GEMM reads and the prune of this layer's update phase    */
+/* applies to.                                                                    */
+/* ------------------------------------------------------------------------- */
+void oracle_act_backward(const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O, int dt,
+                         void *g, int64_t ldg)
+{
+    #pragma omp parallel for schedule(static)
+    for (int64_t t = 0; t < T; ++t)
+        for (int64_t o = 0; o < O; ++o)
+            store_elem(g, dt, t * ldg + o, load_elem(u, dt, t * ldu + o) * load_elem(d, dt, t * ldd + o));
+}
+
+/* ------------------------------------------------------------------------- */
 /* Greedy N:M (the "Greedy" rows of the 1:2 ablation table in Sec. 4.1 and of   */
 /* the result tables in Sec. 5): keep the n largest magnitudes of the block,    */
 /* values unchanged.  Deterministic and biased -- the comparison method, not    */
