@@ -233,6 +233,10 @@ def main():
     ap.add_argument("--g-layout", default="token-major", choices=["token-major", "transposed"],
                     help="transposed: the gradient arrives as g^T [O x T] (tokens contiguous) and is pruned by "
                          "mvue_prune_2of4_t; 2:4 workloads in their own dtype only")
+    ap.add_argument("--fused-producer", action="store_true",
+                    help="the prune fused into the producer of the neural gradient (eq. (2)): the workload's tensor is taken as "
+                         "u = W^T g_next, a ReLU-like derivative d is drawn beside it, and the step's first kernel forms g = u*d, "
+                         "writes it dense and prunes it in one pass (mvue_prune_*_producer); its own dtype, token-major only")
     ap.add_argument("--device-inputs", action="store_true",
                     help="draw the tensors with torch's generator on the device (same recipe, another bit stream) instead of "
                          "the seeded numpy recipe on the host that the tests and the oracle use")
@@ -312,6 +316,14 @@ def main():
     if q8 and (w.dtype != "bf16" or w.T % 32):
         print("bench.py: --precision q8 runs the bf16 workloads whose token count is a multiple of 32", file=sys.stderr)
         sys.exit(2)
+    producer = None
+    if args.fused_producer:
+        if q8 or conv or transposed:
+            print("bench.py: --fused-producer runs the token-major path in the workload's own dtype", file=sys.stderr)
+            sys.exit(2)
+        gen = torch.Generator(device=dev); gen.manual_seed(1)
+        d_act = (torch.rand((w.T, w.O), generator=gen, device=dev) < 0.7).to(g.dtype)        # ReLU'(z): 70 % of the units active
+        producer = dict(d=d_act, g_out=torch.empty_like(g))
     dW = torch.empty((w.O, w.I), dtype=torch.float32, device=dev)
     if q8:
         # activations cast to e4m3 once, outside the timed region (they arrive in 8 bits from the forward pass);
@@ -345,6 +357,9 @@ def main():
                 nm.mvue_prune_1of2_q8(g, seed=seed, stream_id=0, scale=g_scale, vals8=vals, meta32=meta)
             else:
                 nm.mvue_prune_2of4_q8(g, seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=vals, meta32=meta)
+        elif producer:
+            nm.mvue_prune_producer(g, producer["d"], nm=w.nm, seed=seed, stream_id=0, mode=1 if approx else 0,
+                                   g_out=producer["g_out"], vals=vals, meta=meta)
         else:
             prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
         if evs: evs[1].record()
@@ -368,10 +383,29 @@ def main():
     prune_bytes = w.T * w.O * 2 + w.T * w.O // 2 + w.T * w.O // 8 if q8 else w.prune_bytes
     if conv:
         prune_bytes = conv["T"] * w.O * 25 // 8          # the padded grid's rows
+    if producer:                                         # read u and d, write g, vals and meta
+        prune_bytes = w.T * w.O * w.elem_bytes * 3 + w.T * w.O * w.elem_bytes // 2 + w.T * w.O // 8
     f32 = w.dtype == "f32" and not q8 and not x3
     # binary32 operands: dense fp32 MFMA (no sparse fp32 instruction exists; every product is executed)
     gemm_peak = SPARSE_FP8_PEAK_TFLOPS if q8 else DENSE_FP32_PEAK_TFLOPS if f32 else SPARSE_PEAK_TFLOPS
-    tname = w.name + ("_bf16x3" if x3 else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
+    unfused = None
+    if producer:
+        # context: the same work as two kernels, the framework's activation backward (g = u*d) and then the prune
+        gtmp = torch.empty_like(g)
+        for _ in range(3):
+            torch.mul(g, producer["d"], out=gtmp); prune(gtmp, seed=0, stream_id=0, vals=vals, meta=meta)
+        torch.cuda.synchronize()
+        ev = [torch.cuda.Event(enable_timing=True) for _ in range(3)]
+        tm = tp = 0.0
+        for _ in range(10):
+            ev[0].record(); torch.mul(g, producer["d"], out=gtmp); ev[1].record()
+            prune(gtmp, seed=0, stream_id=0, vals=vals, meta=meta); ev[2].record()
+            torch.cuda.synchronize()
+            tm += ev[0].elapsed_time(ev[1]) / 10; tp += ev[1].elapsed_time(ev[2]) / 10
+        unfused = {"what": "torch.mul(u, d) then the separate prune call (two kernels, g written and read back)",
+                   "mul_ms": tm, "prune_ms": tp, "fused_ms": prune_ms, "speedup": (tm + tp) / prune_ms}
+        del gtmp
+    tname = w.name + ("_producer" if producer else "_bf16x3" if x3 else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -382,6 +416,7 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f8" if q8 else "bf16x3" if x3 else ("bf16" if w.dtype == "bf16" else "f32"), "data": "synthetic",
         "inputs": inputs,
+        **({"producer_unfused_context": unfused} if unfused else {}),
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
                    "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0,
                    "precision": "e5m2 kept values (stochastic rounding) x e4m3 activations" if q8 else
@@ -406,11 +441,13 @@ def main():
                              ("peak = published dense fp32 MFMA peak (binary32 operands are expanded and multiplied densely)" if f32 else
                               "dense-equivalent; peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
                               " MFMA peak (4:2 sparse MFMA executes half the products)")},
-        "roofline_prune": {"kernel": "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
+        "roofline_prune": {"kernel": "prune_producer_kernel (g = u*d formed, written dense and pruned in one pass)" if producer else
+                           "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
                            "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(tname, "prune"),
-                           "note": f"algorithmic bytes {prune_bytes} per launch: read g, write T/2 values and T/16 index words per column; "
+                           "note": f"algorithmic bytes {prune_bytes} per launch: " + ("read u and d, write g, " if producer else "read g, ") +
+                                   "write T/2 values and T/16 index words per column; "
                                    "the kernel is bound by its vector ALU work (97 % of the vector-ALU issue slots busy, "
                                    "profiles/sq_counters_prune_c5_decoder_mlp_2of4.txt); the same loads and stores without arithmetic "
                                    "reach 5.6 TB/s = 0.70 of the HBM peak on this device"},

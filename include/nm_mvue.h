@@ -121,6 +121,25 @@ int mvue_prune_1of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     void *vals, uint16_t *meta, void *dense_out, int64_t ldd, void *hip_stream);
 
 /*
+ * MVUE prune fused into the PRODUCER of the neural gradient (eq. (2): g_l = Diag(f'(z_l)) W^T g_{l+1}; the dense
+ * product u = W^T g_{l+1} is a GEMM the method leaves alone, the last step that makes g_l is the elementwise product
+ * with the activation's derivative d = f'(z_l)).  One pass forms g_l = u * d (one binary32 product per element,
+ * rounded to nearest even in `dtype`), writes it dense to g_out -- the next layer's backward GEMM reads it -- and
+ * prunes + compresses it from registers, so g_l is never read back: 2 of the 3.125 bytes per element a separate
+ * prune call moves (bf16) disappear.  vals and meta equal mvue_prune_2of4 / mvue_prune_1of2 of g_out for the same
+ * (seed, stream_id, mode), bit for bit.
+ *   u, d       [T x O] of `dtype`, row strides ldu, ldd     g_out  [T x O] of `dtype`, row stride ldg
+ * (On this device the matrix pipeline idles while a GEMM epilogue selects -- ~90 vector instructions per quad -- so
+ * the fusion point is this elementwise step and not the GEMM's own epilogue.)
+ */
+int mvue_prune_2of4_producer(const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O, int dtype,
+                             uint64_t seed, uint32_t stream_id, int mode,
+                             void *g_out, int64_t ldg, void *vals, uint16_t *meta, void *hip_stream);
+int mvue_prune_1of2_producer(const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O, int dtype,
+                             uint64_t seed, uint32_t stream_id,
+                             void *g_out, int64_t ldg, void *vals, uint16_t *meta, void *hip_stream);
+
+/*
  * approx-MVUE 4:8 prune + compress (appendix, "Additional sparsity results": the approximate 2:4 method of Sec. 4.4
  * carried over to more elements).  Of every block of eight consecutive tokens of a column four elements are drawn one
  * after the other without replacement, each with probability |a_j| / (sum of the magnitudes not yet drawn), and kept

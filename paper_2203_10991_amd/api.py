@@ -38,6 +38,10 @@ def load():
     lib.mvue_prune_2of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
     lib.mvue_prune_1of4.restype = i32
+    lib.mvue_prune_2of4_producer.argtypes = [vp, i64, vp, i64, i64, i64, i32, u64, u32, i32, vp, i64, vp, vp, vp]
+    lib.mvue_prune_2of4_producer.restype = i32
+    lib.mvue_prune_1of2_producer.argtypes = [vp, i64, vp, i64, i64, i64, i32, u64, u32, vp, i64, vp, vp, vp]
+    lib.mvue_prune_1of2_producer.restype = i32
     lib.mvue_prune_4of8_approx.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, i64, vp]
     lib.mvue_prune_4of8_approx.restype = i32
     lib.nm_prune_greedy.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, i64, vp]
@@ -162,6 +166,28 @@ def mvue_prune_2of4(g: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: in
                     dense_out=None, want_dense: bool = False):
     """Optimal MVUE 2:4 prune + compress of g[T x O] along T.  Returns (vals, meta, dense_out or None)."""
     return _prune("2of4", g, seed, stream_id, mode, vals, meta, dense_out, want_dense)
+
+
+def mvue_prune_producer(u: torch.Tensor, d: torch.Tensor, nm: str = "2:4", seed: int = 0, stream_id: int = 0, mode: int = 0,
+                        g_out=None, vals=None, meta=None):
+    """g = u * d (eq. (2): d = f'(z), u = W^T g_next) written dense, and its MVUE prune + compress, in one pass.
+    Returns (g_out, vals, meta)."""
+    lib = load()
+    if not (u.is_cuda and d.is_cuda) or u.shape != d.shape or u.dtype != d.dtype:
+        raise ValueError("u and d must be GPU tensors of one shape and dtype")
+    T, O = u.shape
+    if g_out is None:
+        g_out = torch.empty((T, O), dtype=u.dtype, device=u.device)
+    if vals is None or meta is None:
+        vals, meta = alloc_compressed(T - T % 16, O, u.dtype, u.device)
+    if nm == "1:2":
+        rc = lib.mvue_prune_1of2_producer(_ptr(u), _rowmajor(u, "u"), _ptr(d), _rowmajor(d, "d"), T, O, _dtype_code(u), seed, stream_id,
+                                          _ptr(g_out), _rowmajor(g_out, "g_out"), _ptr(vals), _ptr(meta), _stream(u))
+    else:
+        rc = lib.mvue_prune_2of4_producer(_ptr(u), _rowmajor(u, "u"), _ptr(d), _rowmajor(d, "d"), T, O, _dtype_code(u), seed, stream_id,
+                                          mode, _ptr(g_out), _rowmajor(g_out, "g_out"), _ptr(vals), _ptr(meta), _stream(u))
+    _check(rc)
+    return g_out, vals, meta
 
 
 def mvue_prune_4of8_approx(g: torch.Tensor, seed: int = 0, stream_id: int = 0, vals=None, meta32=None, dense_out=None,

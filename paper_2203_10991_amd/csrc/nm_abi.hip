@@ -167,6 +167,45 @@ int mvue_prune_4of8_approx(const void *g, int64_t T, int64_t O, int64_t ldg, int
                                                      (hipStream_t)hip_stream));
 }
 
+static int prune_producer(const char *fn, int m, int est, const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O,
+                          int dtype, uint64_t seed, uint32_t stream_id, void *g_out, int64_t ldg, void *vals, uint16_t *meta,
+                          void *hip_stream)
+{
+    if (int rc = check_tensor(fn, u, T, O, ldu, dtype, "u")) return rc;
+    if (int rc = check_tensor(fn, d, T, O, ldd, dtype, "d")) return rc;
+    if (int rc = check_tensor(fn, g_out, T, O, ldg, dtype, "g_out")) return rc;
+    if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
+    if (!vals || !meta) return fail(NM_ERR_NULL, "%s: vals and meta must not be NULL", fn);
+    if (!aligned16(vals) || !aligned16(meta)) return fail(NM_ERR_ALIGN, "%s: vals and meta need 16-byte aligned bases", fn);
+    const int64_t es = esize(dtype);
+    const Range ru = range_of(u, ((T - 1) * ldu + O) * es, "u"), rdd = range_of(d, ((T - 1) * ldd + O) * es, "d");
+    const Range rg = range_of(g_out, ((T - 1) * ldg + O) * es, "g_out");
+    const Range rv = range_of(vals, T / 2 * O * es, "vals"), rm = range_of(meta, T / 16 * O * 2, "meta");
+    if (overlap(rg, ru) || overlap(rg, rdd) || overlap(rv, ru) || overlap(rv, rdd) || overlap(rm, ru) || overlap(rm, rdd) ||
+        overlap(rg, rv) || overlap(rg, rm) || overlap(rv, rm))
+        return fail(NM_ERR_ALIAS, "%s: g_out, vals and meta must not overlap each other or an input", fn);
+    return launched(fn, nm::launch_prune_producer(dtype, m, est, u, ldu, d, ldd, T, O, seed, stream_id, g_out, ldg, vals, meta,
+                                                  (hipStream_t)hip_stream));
+}
+
+int mvue_prune_2of4_producer(const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O, int dtype,
+                             uint64_t seed, uint32_t stream_id, int mode, void *g_out, int64_t ldg, void *vals, uint16_t *meta,
+                             void *hip_stream)
+{
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_producer: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
+    return prune_producer("mvue_prune_2of4_producer", 4, mode, u, ldu, d, ldd, T, O, dtype, seed, stream_id, g_out, ldg, vals, meta,
+                          hip_stream);
+}
+
+int mvue_prune_1of2_producer(const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O, int dtype,
+                             uint64_t seed, uint32_t stream_id, void *g_out, int64_t ldg, void *vals, uint16_t *meta,
+                             void *hip_stream)
+{
+    return prune_producer("mvue_prune_1of2_producer", 2, 0, u, ldu, d, ldd, T, O, dtype, seed, stream_id, g_out, ldg, vals, meta,
+                          hip_stream);
+}
+
 static int prune_transposed(const char *fn, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed,
                             uint32_t stream_id, void *vals, uint16_t *meta, void *hip_stream)
 {

@@ -21,6 +21,11 @@ struct AlphaArg {
 hipError_t launch_prune(int dt, int m, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                         uint32_t stream_id, void *vals, uint16_t *meta, void *dense, int64_t ldd, hipStream_t st);
 
+// prune fused into the producer of the neural gradient: g_l = u * d (eq. (2): d = f'(z_l), u = W^T g_{l+1}) is written
+// dense to gout and pruned + compressed in the same pass
+hipError_t launch_prune_producer(int dt, int m, int est, const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O,
+                                 uint64_t seed, uint32_t stream_id, void *gout, int64_t ldgo, void *vals, uint16_t *meta, hipStream_t st);
+
 // the same prunes for a gradient stored transposed: gT [O x T], row stride ldt (est 0 optimal 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2)
 hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
                                    uint32_t stream_id, void *vals, uint16_t *meta, hipStream_t st);

@@ -233,12 +233,36 @@ __device__ __forceinline__ void select_greedy_2of4(typename Key<DT>::type k1, ty
 // ------------------------------------------------------------------------------------
 // M = 2: MVUE 1:2; M = 4: EST = 0 the optimal MVUE 2:4, 1 approx-MVUE 2:4, 2 MVUE 1:4; EST = 4 (either M): Greedy;
 // DENSE: also write theta(g)
-template <int DT, int M, int EST, bool DENSE>
+// PROD: the kernel is also the PRODUCER of the neural gradient (eq. (2): g_l = Diag(f'(z_l)) W^T g_{l+1}): g_ holds
+// u = W^T g_{l+1} (the dense backward GEMM's output) and dense_ / ldd the derivative factor d = f'(z_l); each row of
+// g_l = u * d (one binary32 product per element, rounded to the storage type) is formed in registers, written once to
+// gout_ -- the next layer's backward GEMM needs it dense -- and pruned from there: g_l is never read back.
+struct ProdArg { const void *d; int64_t ldd; void *gout; int64_t ldgo; };
+
+template <int DT>
+__device__ __forceinline__ uint4 producer_row(const uint4 &u, const uint4 &d)
+{
+    uint4 r;
+    if constexpr (DT == NM_DT_F32) {
+        r.x = __float_as_uint(__uint_as_float(u.x) * __uint_as_float(d.x)); r.y = __float_as_uint(__uint_as_float(u.y) * __uint_as_float(d.y));
+        r.z = __float_as_uint(__uint_as_float(u.z) * __uint_as_float(d.z)); r.w = __float_as_uint(__uint_as_float(u.w) * __uint_as_float(d.w));
+    } else {
+        auto mul2 = [](uint32_t a, uint32_t b) {
+            return pack_bf16_rne(__uint_as_float(a << 16) * __uint_as_float(b << 16),
+                                 __uint_as_float(a & 0xffff0000u) * __uint_as_float(b & 0xffff0000u));
+        };
+        r.x = mul2(u.x, d.x); r.y = mul2(u.y, d.y); r.z = mul2(u.z, d.z); r.w = mul2(u.w, d.w);
+    }
+    return r;
+}
+
+template <int DT, int M, int EST, bool DENSE, bool PROD = false>
 __device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
     uint32_t key0, uint32_t key1, uint32_t stream_id,
-    void *__restrict__ vals_, uint16_t *__restrict__ meta_, void *__restrict__ dense_, int64_t ldd)
+    void *__restrict__ vals_, uint16_t *__restrict__ meta_, void *__restrict__ dense_, int64_t ldd, ProdArg pa = ProdArg{})
 {
+    static_assert(!(PROD && DENSE), "the producer form writes g_l, not theta(g_l)");
     constexpr int VEC = Row<DT>::VEC;
     constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
     const int64_t ncg = O / VEC;
@@ -252,8 +276,23 @@ __device__ __forceinline__ void prune_compress_body(
     // address keeps those loads from being hoisted): their latency hides under the arithmetic of the rows already
     // here, and fewer registers are live at once, so one more wave fits each SIMD.
     uint4 rows[16];
+    const char *dp_in = nullptr;
+    char *gop = nullptr;
+    if constexpr (PROD) {
+        dp_in = (const char *)pa.d + ((G * 16) * pa.ldd + col0) * ESZ;
+        gop = (char *)pa.gout + ((G * 16) * pa.ldgo + col0) * ESZ;
+    }
+    auto fetch_rows = [&](const char *base, const char *dbase, int first) {
 #pragma unroll
-    for (int r = 0; r < 8; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
+        for (int r = first; r < first + 8; ++r) {
+            rows[r] = *(const uint4 *)(base + (int64_t)r * ldg * ESZ);
+            if constexpr (PROD) {
+                rows[r] = producer_row<DT>(rows[r], *(const uint4 *)(dbase + (int64_t)r * pa.ldd * ESZ));
+                *(uint4 *)(gop + (int64_t)r * pa.ldgo * ESZ) = rows[r];
+            }
+        }
+    };
+    fetch_rows(gp, dp_in, 0);
 
     // kept values per column in the slot order of the group format, as stored: binary32 words, or bf16 pairs
     // (slots 2i, 2i+1) packed as soon as a block row is decided, which keeps the live registers low
@@ -272,10 +311,9 @@ __device__ __forceinline__ void prune_compress_body(
 #pragma unroll
     for (int b = 0; b < BLOCK_ROWS; ++b) {
         if (b == 1) {
-            const char *gp2 = gp;
+            const char *gp2 = gp, *dp2 = dp_in;
             asm volatile("" : "+v"(gp2));               // an address the compiler cannot see through
-#pragma unroll
-            for (int r = 8; r < 16; ++r) rows[r] = *(const uint4 *)(gp2 + (int64_t)r * ldg * ESZ);
+            fetch_rows(gp2, dp2, 8);
         }
         const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
         // one uniform per block: four blocks share a Philox call (counter blk/4, last counter word 0);
@@ -376,6 +414,13 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
     void *__restrict__ vals, uint16_t *__restrict__ meta, void *__restrict__ dense, int64_t ldd)
 {
     prune_compress_body<DT, M, EST, DENSE>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, dense, ldd);
+}
+template <int DT, int M, int EST>
+__global__ __launch_bounds__(256) void prune_producer_kernel(
+    const void *__restrict__ u, int64_t n_groups, int64_t O, int64_t ldu, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals, uint16_t *__restrict__ meta, ProdArg pa)
+{
+    prune_compress_body<DT, M, EST, false, true>(u, n_groups, O, ldu, key0, key1, stream_id, vals, meta, nullptr, 0, pa);
 }
 // The bf16 optimal-2:4 kernel without the dense output needs 98 registers as the compiler would have it, two more
 // than let a fifth wave onto each SIMD; asked for five waves it fits 96 without spilling.
@@ -786,6 +831,24 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     else
         hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, false>), dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
+    return hipGetLastError();
+}
+
+// g_l = u * d written to gout, and its prune + compress, in one pass.  m = 2: MVUE 1:2; m = 4: est 0 optimal / 1 approx-MVUE 2:4
+hipError_t launch_prune_producer(int dt, int m, int est, const void *u, int64_t ldu, const void *d, int64_t ldd, int64_t T, int64_t O,
+                                 uint64_t seed, uint32_t stream_id, void *gout, int64_t ldgo, void *vals, uint16_t *meta, hipStream_t st)
+{
+    const int64_t groups = T / 16, threads = groups * (O / (dt == NM_DT_F32 ? 4 : 8));
+    if (threads == 0) return hipSuccess;
+    const int64_t blocks = (threads + 255) / 256;
+    if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
+    const ProdArg pa{d, ldd, gout, ldgo};
+#define NM_PROD(DT, M, EST)                                                                                             \
+    hipLaunchKernelGGL((prune_producer_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st, u, groups, O, ldu,   \
+                       (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, pa)
+    if (dt == NM_DT_F32) { if (m == 2) NM_PROD(NM_DT_F32, 2, 0); else if (est == 1) NM_PROD(NM_DT_F32, 4, 1); else NM_PROD(NM_DT_F32, 4, 0); }
+    else { if (m == 2) NM_PROD(NM_DT_BF16, 2, 0); else if (est == 1) NM_PROD(NM_DT_BF16, 4, 1); else NM_PROD(NM_DT_BF16, 4, 0); }
+#undef NM_PROD
     return hipGetLastError();
 }
 

@@ -19,6 +19,8 @@ namespace nm {
 struct AlphaArg { float value; const float *inv_a, *inv_b; };      // layout of the library's own (passed by value)
 hipError_t launch_prune(int, int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint16_t *, void *, int64_t,
                         hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_prune_producer(int, int, int, const void *, int64_t, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *,
+                                 int64_t, void *, uint16_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_prune_transposed(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint16_t *,
                                    hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_prune_4of8_approx(int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, void *, uint32_t *, void *, int64_t,
@@ -98,6 +100,15 @@ int main()
     EXPECT(nm_update_gemm_shifted(vals, m16, x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, NM_BF16, 0.f, ws, wsb_conv, nullptr), NM_OK);
     EXPECT(nm_update_gemm_q8_shifted((const uint8_t *)vals, m32, (const uint8_t *)x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, 1.f, 0.f, ws, wsb_conv,
                                      nullptr), NM_OK);
+    // prune fused into the producer of g
+    EXPECT(mvue_prune_2of4_producer(g, O, h, O, T, O, NM_BF16, 1, 2, 0, dense, O, vals, m16, nullptr), NM_OK);
+    EXPECT(mvue_prune_1of2_producer(g, O, h, O, T, O, NM_F32, 1, 2, dense, O, vals, m16, nullptr), NM_OK);
+    EXPECT(mvue_prune_2of4_producer(g, O, h, O, T, O, NM_BF16, 1, 2, 3, dense, O, vals, m16, nullptr), NM_ERR_UNSUPPORTED);
+    EXPECT(mvue_prune_2of4_producer(g, O, nullptr, O, T, O, NM_BF16, 1, 2, 0, dense, O, vals, m16, nullptr), NM_ERR_NULL);
+    EXPECT(mvue_prune_2of4_producer(g, O, h, O, T, O, NM_BF16, 1, 2, 0, g, O, vals, m16, nullptr), NM_ERR_ALIAS);
+    EXPECT(mvue_prune_2of4_producer(g, O, h, O, T, O, NM_BF16, 1, 2, 0, dense, O, (char *)h + 64, m16, nullptr), NM_ERR_ALIAS);
+    EXPECT(mvue_prune_2of4_producer(g, O, h, O - 8, T, O, NM_BF16, 1, 2, 0, dense, O, vals, m16, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_producer(g, huge, h, huge, huge, O, NM_BF16, 1, 2, 0, dense, huge, vals, m16, nullptr), NM_ERR_SHAPE);
     // device-side scales of the 8-bit path
     alignas(16) static float rec_g[4], rec_h[4];
     EXPECT(nm_q8_scale(g, T, O, O, NM_BF16, 448.f, rec_g, nullptr), NM_OK);
