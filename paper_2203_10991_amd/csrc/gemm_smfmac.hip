@@ -344,8 +344,8 @@ __global__ __launch_bounds__(WM * WN * 64) void update_gemm_smfmac_kernel(
 // MFMA 6, row fragment a after MFMA 7+a, column fragment 1 after MFMA 12.
 //
 // Rows of a wave's 192-row block are interleaved so that the index words a lane needs are adjacent in
-// the natural `meta` order: accumulator blocks 0-3 hold rows 4m+a of the first 128 rows (m = row inside
-// the block), blocks 4-5 rows 128 + 2m + (a-4).
+// the natural `meta` order: accumulator block a holds rows 6m + a of the wave's 192 rows (m = row inside
+// the block), so a lane's six index words are 12 consecutive bytes.
 // LDS image of a stage: h tile [32][256] bf16 (swizzled as above) | vals [2 groups][384 slots] x 16 B
 // (slot 192*wm + 32*a + m) | meta [2 groups][384 rows] x 2 B; five stages rotate.
 // ------------------------------------------------------------------------------------
