@@ -342,31 +342,54 @@ def main():
         need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, g.dtype, x3)
     ws = torch.empty(max(need, 16), dtype=torch.uint8, device=dev)
 
-    def gemm():
+    # Small workloads: consecutive steps use different copies of every buffer, enough of them to exceed the 256 MB
+    # last-level cache twice over, so that no step finds its operands in a cache the previous step filled.
+    def tensors_of(b):
+        ts = [b["g"], b["h"], b["vals"], b["meta"], b["dW"], b["ws"]]
+        if b["conv"]:
+            ts.append(b["conv"]["x_full"])
+        if b["producer"]:
+            ts += [b["producer"]["d"], b["producer"]["g_out"]]
+        return [t for t in ts if t is not None]
+    sets = [dict(g=g, h=h, vals=vals, meta=meta, dW=dW, ws=ws, conv=conv, producer=producer)]
+    set_bytes = sum(t.numel() * t.element_size() for t in tensors_of(sets[0]))
+    n_sets = 1 if set_bytes >= (512 << 20) else min(64, -(-(768 << 20) // set_bytes))
+    for _ in range(n_sets - 1):
+        b = {k: (v.clone() if torch.is_tensor(v) else v) for k, v in sets[0].items()}
         if conv:
-            nm.nm_update_gemm_shifted(vals, meta, conv["x_full"], conv["margin"], conv["shifts"], dW=dW, beta=0.0, workspace=ws)
+            b["conv"] = dict(conv, x_full=conv["x_full"].clone())
+        if producer:
+            b["producer"] = dict(d=producer["d"].clone(), g_out=torch.empty_like(producer["g_out"]))
+        sets.append(b)
+
+    def gemm(b=None):
+        b = b or sets[0]
+        if b["conv"]:
+            c = b["conv"]
+            nm.nm_update_gemm_shifted(b["vals"], b["meta"], c["x_full"], c["margin"], c["shifts"], dW=b["dW"], beta=0.0, workspace=b["ws"])
         elif q8:
-            nm.nm_update_gemm_q8(vals, meta, h, dW=dW, alpha=(g_scale, h_scale), beta=0.0, workspace=ws)
+            nm.nm_update_gemm_q8(b["vals"], b["meta"], b["h"], dW=b["dW"], alpha=(g_scale, h_scale), beta=0.0, workspace=b["ws"])
         else:
-            nm.nm_update_gemm(vals, meta, h, dW=dW, beta=0.0, workspace=ws, f32_as_bf16x3=x3)
+            nm.nm_update_gemm(b["vals"], b["meta"], b["h"], dW=b["dW"], beta=0.0, workspace=b["ws"], f32_as_bf16x3=x3)
 
     def step(seed, evs=None):
+        b = sets[seed % n_sets]
         if evs: evs[0].record()
         if q8:
             if w.nm == "1:2":
-                nm.mvue_prune_1of2_q8(g, seed=seed, stream_id=0, scale=g_scale, vals8=vals, meta32=meta)
+                nm.mvue_prune_1of2_q8(b["g"], seed=seed, stream_id=0, scale=g_scale, vals8=b["vals"], meta32=b["meta"])
             else:
-                nm.mvue_prune_2of4_q8(g, seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=vals, meta32=meta)
-        elif producer:
-            nm.mvue_prune_producer(g, producer["d"], nm=w.nm, seed=seed, stream_id=0, mode=1 if approx else 0,
-                                   g_out=producer["g_out"], vals=vals, meta=meta)
+                nm.mvue_prune_2of4_q8(b["g"], seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=b["vals"], meta32=b["meta"])
+        elif b["producer"]:
+            nm.mvue_prune_producer(b["g"], b["producer"]["d"], nm=w.nm, seed=seed, stream_id=0, mode=1 if approx else 0,
+                                   g_out=b["producer"]["g_out"], vals=b["vals"], meta=b["meta"])
         else:
-            prune(g, seed=seed, stream_id=0, vals=vals, meta=meta)
+            prune(b["g"], seed=seed, stream_id=0, vals=b["vals"], meta=b["meta"])
         if evs: evs[1].record()
-        gemm()
+        gemm(b)
         if evs: evs[2].record()
 
-    for i in range(args.warmup):
+    for i in range(max(args.warmup, n_sets if n_sets > 1 else 0)):      # every copy is touched before the clock starts
         step(i)
     torch.cuda.synchronize()
     events = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(args.steps)]
@@ -416,6 +439,9 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": "f8" if q8 else "bf16x3" if x3 else ("bf16" if w.dtype == "bf16" else "f32"), "data": "synthetic",
         "inputs": inputs,
+        "cache": (f"cold: consecutive steps rotate over {n_sets} copies of every buffer ({set_bytes / 2**20:.0f} MiB each, "
+                  f"{n_sets * set_bytes / 2**20:.0f} MiB in all, against a 256 MB last-level cache)" if n_sets > 1 else
+                  f"one buffer set of {set_bytes / 2**20:.0f} MiB: more than the 256 MB last-level cache holds"),
         **({"producer_unfused_context": unfused} if unfused else {}),
         "config": {"workload": f"{w.name}: MVUE {w.nm} along tokens, g[{w.T}x{w.O}] h[{w.T}x{w.I}] dW[{w.O}x{w.I}] fp32 accumulate",
                    "T": w.T, "O": w.O, "I": w.I, "estimator": ("approx-MVUE " if approx else "MVUE ") + w.nm, "seed": 0,
@@ -540,6 +566,7 @@ def main():
         del src, dst
     if not args.no_cpu_baseline:
         del g, h, vals, meta, dW, ws
+        sets.clear()
         torch.cuda.empty_cache()
         out["cpu_baseline"] = cpu_baseline_q8(w, approx) if q8 else cpu_baseline(w, approx)
     print(json.dumps(out))
