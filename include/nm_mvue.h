@@ -228,7 +228,7 @@ size_t nm_update_gemm_workspace(int64_t T, int64_t O, int64_t I, int dtype);
  * nm_update_gemm for callers that cannot allocate device memory or carry a workspace: code under HIP graph
  * capture, tight serving loops, harnesses that forbid hipMalloc.  Same arguments, checks, kernels and results as
  * nm_update_gemm, without the workspace pair: the split-K partial sums go to a static device array inside the
- * library (nm_update_gemm_static_max() bytes, 32 MiB, held by every GPU the library runs on until the process
+ * library (nm_update_gemm_static_max() bytes, 64 MiB, held by every GPU the library runs on until the process
  * ends).  The call allocates and frees nothing.  A problem whose nm_update_gemm_workspace() exceeds that size
  * returns NM_ERR_WORKSPACE (nothing is enqueued); problems that need no workspace are unlimited.
  * All calls on one GPU share the array: two calls that may run at the same time on one GPU (different streams,

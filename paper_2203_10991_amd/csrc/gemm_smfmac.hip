@@ -677,22 +677,44 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
     // the cheaper one by a measured cost model: microseconds per 32-token stage of a 128 x 128 tile (0.14 alone on
     // its CU, rising to 0.18 with all CUs busy; 0.32 when two share a CU), never less than one pass over the operands
     // at 4.5 TB/s, plus the second pass over the partial sums.
+    // Then the same problem on 256 x 256 tiles, cut into as many slabs as keep it to one workgroup per CU: half the
+    // operand bytes per product, more partial sums.  The two are compared with the stage costs measured on operands
+    // that are not in any cache, as a training step finds them (128 x 128: 0.19-0.25 us, 0.42 with two on a CU;
+    // 256 x 256: 0.44-0.56 us plus 3 us of pipeline fill): the small tile loses more to cold operands than the large.
+    // The large tile has to win by 15 %: its plan writes two to three times the partial sums and leaves no CU to a
+    // kernel that runs beside it (layers replayed from a graph with parallel branches measure 5 % slower with it
+    // where the margin is smaller).
     auto whole_trips = [](int64_t gps) { gps = (gps + 11) / 12 * 12; return gps < 12 ? (int64_t)12 : gps; };
     int slabs = 1;
     if (small && groups >= 48) {
         const int64_t max_s = std::max<int64_t>(1, groups / 24);               // at least 384 tokens per slab
-        auto cost = [&](int64_t sl) {
+        auto second_pass = [&](int64_t sl) { return sl > 1 ? 4.0 + (double)(sl + 1) * (double)O * (double)I * 4.0 / 3.5e6 : 0.0; };
+        const double stream = (double)T * ((double)I * 2.0 + (double)O * 1.125) / 4.5e6;
+        auto cost = [&](int64_t sl, bool cold) {
             const int64_t wgs = tiles * sl, stages = whole_trips((groups + sl - 1) / sl) / 2;
-            const double t_stage = wgs <= CUS ? 0.14 + 0.04 * (double)wgs / CUS : 0.32;
+            const double fill = (double)wgs / CUS;
+            const double t_stage = cold ? (wgs <= CUS ? 0.19 + 0.06 * fill : 0.42) : (wgs <= CUS ? 0.14 + 0.04 * fill : 0.32);
             const double rounds = wgs <= CUS ? 1.0 : (double)((wgs + 2 * CUS - 1) / (2 * CUS));
-            const double second_pass = sl > 1 ? 4.0 + (double)(sl + 1) * (double)O * (double)I * 4.0 / 3.5e6 : 0.0;
-            const double stream = (double)T * ((double)I * 2.0 + (double)O * 1.125) / 4.5e6;
-            return std::max(rounds * (double)stages * t_stage, stream) + second_pass;
+            return std::max(rounds * (double)stages * t_stage, stream) + second_pass(sl);
         };
         const int64_t s_one = std::min(max_s, std::max<int64_t>(1, CUS / tiles));
         const int64_t s_two = std::min(max_s, std::max<int64_t>(1, 2 * CUS / tiles));
         slabs = (int)s_one;
-        if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two) < cost(s_one)) slabs = (int)s_two;
+        if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two, false) < cost(s_one, false)) slabs = (int)s_two;
+        if (p.shape == 1 && !shifted) {
+            const int64_t tiles0 = (O + 255) / 256 * ((I + 255) / 256);
+            const int64_t s0 = std::min(max_s, std::max<int64_t>(1, CUS / tiles0));
+            const int64_t wgs = tiles0 * s0, stages = whole_trips((groups + s0 - 1) / s0) / 2;
+            const double rounds = (double)((wgs + CUS - 1) / CUS);
+            const double t_stage = 0.44 + 0.12 * (double)std::min<int64_t>(wgs, CUS) / CUS;
+            const double cost0 = std::max(rounds * (double)stages * t_stage + 3.0, stream) + second_pass(s0);
+            if (cost0 < 0.85 * cost(slabs, true)) {
+                p.shape = 0; p.tm = 256; p.tn = 256;
+                p.tiles_m = (int)((O + 255) / 256);
+                p.tiles_n = (int)((I + 255) / 256);
+                slabs = (int)s0;
+            }
+        }
     }
     p.slabs = slabs;
     p.groups_per_slab = slab_groups(groups, p.slabs, 12);                    // whole trips of six LDS stages (2 groups each)

@@ -12,7 +12,7 @@
 
 namespace nm {
 
-constexpr size_t STATIC_SCRATCH_BYTES = (size_t)32 << 20;       // 32 MiB per GPU
+constexpr size_t STATIC_SCRATCH_BYTES = (size_t)64 << 20;       // 64 MiB per GPU
 constexpr int MAX_DEVICES = 64;
 
 // In host code this name is a stand-in for the symbol, not a device address: it is only ever used inside HIP_SYMBOL().

@@ -68,6 +68,16 @@ def test_large_tile_kernels_and_their_tile_maps(nm, oracle, T, O, I):
     run_case(nm, oracle, synth.Workload(f"big{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T)
 
 
+@pytest.mark.parametrize("T,O,I,slabs,beta", [(6416, 2296, 2040, 3, 0.0), (16400, 2296, 760, 9, 1.0)])
+def test_large_tiles_with_split_k(nm, oracle, T, O, I, slabs, beta):
+    """Mid-sized problems (fewer than 256 tiles of 256 x 256, a long reduction) run on the 256 x 256 kernel with the
+    token axis cut into slabs: ragged last tile row and column, a ragged last slab, and the second pass over the
+    partial sums.  The slab count identifies the plan (256 // tiles of 256 x 256; the 128 x 128 plan would take fewer)."""
+    need = nm.nm_update_gemm_workspace(T, O, I, torch.bfloat16)
+    assert need == slabs * O * I * 4
+    run_case(nm, oracle, synth.Workload(f"mid{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T, beta=beta)
+
+
 @pytest.mark.parametrize("dtype", ["f32", "bf16"])
 def test_beta_one_accumulates(nm, oracle, dtype):
     run_case(nm, oracle, synth.Workload("beta", 16 * 20, 8 * 21, 8 * 19, dtype, "2:4", 0.0, 2.0, 0.3), seed=2, beta=1.0)

@@ -142,6 +142,14 @@ def test_update_gemm_q8_large_tile_kernel(nm, oracle, T, O, I):
     gemm_case(nm, oracle, T, O, I, seed=T, sample=12)
 
 
+@pytest.mark.parametrize("T,O,I,slabs,beta", [(4128, 2040, 2000, 4, 0.0), (2080, 2296, 3056, 2, 1.0)])
+def test_update_gemm_q8_large_tiles_with_split_k(nm, oracle, T, O, I, slabs, beta):
+    """mid-sized problems (48 to 255 tiles of 256 x 256) run on the 256 x 256 kernel with the token axis cut into
+    slabs: ragged last tile row and column, ragged last slab, scale applied in the second pass"""
+    assert nm.nm_update_gemm_q8_workspace(T, O, I) == slabs * O * I * 4
+    gemm_case(nm, oracle, T, O, I, seed=T, beta=beta, sample=10)
+
+
 def test_update_gemm_q8_beta_one_large_tile(nm, oracle):
     gemm_case(nm, oracle, 128, 16 * 256, 16 * 256, seed=3, beta=1.0, sample=8)
 

@@ -24,9 +24,10 @@ def test_static_scratch_entry_point_matches_the_workspace_one(oracle):
     import paper_2203_10991_amd as nm
     nm.load()
     limit = nm.nm_update_gemm_static_max()
-    assert limit == 32 << 20
-    # first call: a split-K problem (ViT proj shape: 36 tiles of 128 x 128, several slabs); second: a smaller one
-    shapes = [synth.scaled(synth.WORKLOADS["c4_vit_proj_2of4"], name="static_first"),
+    assert limit == 64 << 20
+    # first call: a split-K problem whose partial sums fill the array to the last byte (the transformer-MLP shape:
+    # 64 tiles of 256 x 256, four slabs); second: a smaller one on the other tile shape
+    shapes = [synth.scaled(synth.WORKLOADS["c2_mlp_1of2"], name="static_first"),
               synth.Workload("static_second", 16 * 150, 8 * 41, 8 * 35, "bf16", "2:4", 0.0, 2.0, 0.3)]
     for k, w in enumerate(shapes):
         need = nm.nm_update_gemm_workspace(w.T, w.O, w.I, torch.bfloat16)
@@ -76,7 +77,7 @@ def test_static_scratch_entry_point_rejects_what_does_not_fit():
     import paper_2203_10991_amd as nm
     nm.load()
     # a split-K problem whose partial sums exceed the array: rejected on the host, nothing enqueued, dW untouched
-    T, O, I = 12608, 768, 768
+    T, O, I = 12608, 1536, 1536
     need = nm.nm_update_gemm_workspace(T, O, I, torch.float32)
     assert need > nm.nm_update_gemm_static_max(), need
     v, m = nm.alloc_compressed(T, O, torch.float32, DEV)
