@@ -474,7 +474,7 @@ def main():
                            "traffic": read_traffic(tname, "prune"),
                            "note": f"algorithmic bytes {prune_bytes} per launch: " + ("read u and d, write g, " if producer else "read g, ") +
                                    "write T/2 values and T/16 index words per column; "
-                                   "the kernel is bound by its vector ALU work (97 % of the vector-ALU issue slots busy, "
+                                   "the kernel's vector ALU work takes as long as its memory traffic and the two overlap to within 10 % ("
                                    "profiles/sq_counters_prune_c5_decoder_mlp_2of4.txt); the same loads and stores without arithmetic "
                                    "reach 5.6 TB/s = 0.70 of the HBM peak on this device"},
     }

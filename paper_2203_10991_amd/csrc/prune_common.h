@@ -30,6 +30,53 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
     out[0] = c0; out[1] = c1; out[2] = c2; out[3] = c3;
 }
 
+// The same function for a call whose counter words 1-3 are wave-uniform, like the key (the high half of the call
+// index, the stream and the domain word: only the low half of the call index differs between lanes).  Then half of
+// round 1, a multiply and an xor of round 2 and an xor of round 3 are scalar work; the result is the same word for word.
+__device__ __forceinline__ void philox4x32_10_uniform_c123(uint32_t c0, uint32_t c1u, uint32_t c2u, uint32_t c3u,
+                                                           uint32_t k0, uint32_t k1, uint32_t (&out)[4])
+{
+    constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
+    // round 1: c1, c2, c3 uniform
+    const uint64_t q1 = (uint64_t)M1 * c2u;                             // scalar
+    const uint32_t a0 = (uint32_t)(q1 >> 32) ^ c1u ^ k0;                // scalar
+    const uint32_t a1 = (uint32_t)q1;                                   // scalar
+    const uint64_t q0 = (uint64_t)M0 * c0;
+    const uint32_t a2 = (uint32_t)(q0 >> 32) ^ (c3u ^ k1);
+    const uint32_t a3 = (uint32_t)q0;
+    k0 += W0; k1 += W1;
+    // round 2: c0, c1 uniform
+    const uint64_t r0 = (uint64_t)M0 * a0;                              // scalar
+    const uint64_t r1 = (uint64_t)M1 * a2;
+    const uint32_t b0 = (uint32_t)(r1 >> 32) ^ (a1 ^ k0);
+    const uint32_t b1 = (uint32_t)r1;
+    const uint32_t b2 = a3 ^ ((uint32_t)(r0 >> 32) ^ k1);
+    const uint32_t b3 = (uint32_t)r0;                                   // scalar
+    k0 += W0; k1 += W1;
+    // round 3: c3 uniform
+    const uint64_t s0 = (uint64_t)M0 * b0;
+    const uint64_t s1 = (uint64_t)M1 * b2;
+    uint32_t d0 = (uint32_t)(s1 >> 32) ^ b1 ^ k0;
+    uint32_t d1 = (uint32_t)s1;
+    uint32_t d2 = (uint32_t)(s0 >> 32) ^ (b3 ^ k1);
+    uint32_t d3 = (uint32_t)s0;
+    k0 += W0; k1 += W1;
+#pragma unroll
+    for (int r = 3; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)M0 * d0;
+        const uint64_t p1 = (uint64_t)M1 * d2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ d1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ d3 ^ k1;
+        d1 = (uint32_t)p1;
+        d3 = (uint32_t)p0;
+        d0 = n0;
+        d2 = n2;
+        k0 += W0;
+        k1 += W1;
+    }
+    out[0] = d0; out[1] = d1; out[2] = d2; out[3] = d3;
+}
+
 __device__ __forceinline__ float word_to_eps(uint32_t word)
 {
     return (float)(word >> 8) * 0x1p-24f;      // 24-bit uniform in [0,1), exact

@@ -78,6 +78,23 @@ template <typename K> __device__ __forceinline__ void order2(K &a, K &b)
     a = lo;
     b = hi;
 }
+// ascending sort of four distinct keys.  64-bit keys: the 5-comparator network.  32-bit keys: the two middle keys
+// come from three-input instructions -- with x <= X and y <= Y the sorted pairs and m = min(X, Y) >= min(x, y), the
+// second key is the median and the third the maximum of {x, y, m} -- nine operations instead of ten.
+__device__ __forceinline__ void sort4(uint64_t &k1, uint64_t &k2, uint64_t &k3, uint64_t &k4)
+{
+    order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
+}
+__device__ __forceinline__ void sort4(uint32_t &k1, uint32_t &k2, uint32_t &k3, uint32_t &k4)
+{
+    order2(k1, k2); order2(k3, k4);
+    const uint32_t x = k1, X = k2, y = k3, Y = k4;
+    const uint32_t m = X < Y ? X : Y;
+    k1 = x < y ? x : y;
+    k4 = X < Y ? Y : X;
+    asm("v_med3_u32 %0, %1, %2, %3" : "=v"(k2) : "v"(x), "v"(y), "v"(m));
+    asm("v_max3_u32 %0, %1, %2, %3" : "=v"(k3) : "v"(x), "v"(y), "v"(m));
+}
 
 // out0/out1: kept values in ascending position; nib = pos0 | pos1 << 2.  Straight-line code: the case
 // analysis and the walk over the pair probabilities are lane masks and selects, no divergent branch.
@@ -86,7 +103,7 @@ __device__ __forceinline__ void select_2of4(typename Key<DT>::type k1, typename 
                                             typename Key<DT>::type k4, uint32_t word, float &out0, float &out1, uint32_t &nib)
 {
     typedef Key<DT> KT;
-    order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
+    sort4(k1, k2, k3, k4);
     const float a1 = KT::mag(k1), a2 = KT::mag(k2), a3 = KT::mag(k3), a4 = KT::mag(k4);
 
     const float s12 = a1 + a2;
@@ -219,7 +236,7 @@ __device__ __forceinline__ void select_greedy_2of4(typename Key<DT>::type k1, ty
                                                    typename Key<DT>::type k4, float &out0, float &out1, uint32_t &nib)
 {
     typedef Key<DT> KT;
-    order2(k1, k2); order2(k3, k4); order2(k1, k3); order2(k2, k4); order2(k2, k3);
+    sort4(k1, k2, k3, k4);
     const float va = KT::with_sign(KT::mag(k3), k3), vb = KT::with_sign(KT::mag(k4), k4);
     const uint32_t pa = KT::pos(k3), pb = KT::pos(k4);
     const bool swap = pa > pb;
@@ -256,7 +273,9 @@ __device__ __forceinline__ uint4 producer_row(const uint4 &u, const uint4 &d)
     return r;
 }
 
-template <int DT, int M, int EST, bool DENSE, bool PROD = false>
+// HI0: the caller guarantees that every Philox call index of the launch is below 2^32 (the launcher checks the
+// tensor's size): counter words 1-3 are then wave-uniform and the generator's first rounds run partly on the scalar unit.
+template <int DT, int M, int EST, bool DENSE, bool PROD = false, bool HI0 = false>
 __device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
     uint32_t key0, uint32_t key1, uint32_t stream_id,
@@ -308,6 +327,11 @@ __device__ __forceinline__ void prune_compress_body(
 
     constexpr int BLOCK_ROWS = 16 / M;       // pair rows (8) or quad rows (4) in the group
     float held[VEC];                         // 1:2: the kept value of the even pair row, until its partner is known
+    // one uniform per block: four blocks share a Philox call (counter blk/4, last counter word 0);
+    // approx-MVUE draws twice: two blocks share a call (counter blk/2, last counter word 1)
+    constexpr int WPB = EST == 1 ? 2 : 1;            // words per block
+    constexpr int CTR_SHIFT = EST == 1 ? 1 : 2;
+    constexpr uint32_t DOMAIN = EST == 1 ? 1u : 0u;
 #pragma unroll
     for (int b = 0; b < BLOCK_ROWS; ++b) {
         if (b == 1) {
@@ -316,16 +340,14 @@ __device__ __forceinline__ void prune_compress_body(
             fetch_rows(gp2, dp2, 8);
         }
         const uint64_t blk0 = (uint64_t)(G * BLOCK_ROWS + b) * (uint64_t)O + (uint64_t)col0;
-        // one uniform per block: four blocks share a Philox call (counter blk/4, last counter word 0);
-        // approx-MVUE draws twice: two blocks share a call (counter blk/2, last counter word 1)
-        constexpr int WPB = EST == 1 ? 2 : 1;            // words per block
         uint32_t words[VEC * WPB];
         if constexpr (EST != 4) {
 #pragma unroll
             for (int q = 0; q < VEC * WPB / 4; ++q) {
-                const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
+                const uint64_t ctr = (blk0 >> CTR_SHIFT) + q;
                 uint32_t w4[4];
-                philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
+                if constexpr (HI0) philox4x32_10_uniform_c123((uint32_t)ctr, 0u, stream_id, DOMAIN, key0, key1, w4);
+                else philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, DOMAIN, key0, key1, w4);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
             }
@@ -428,7 +450,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
     const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
     void *__restrict__ vals, uint16_t *__restrict__ meta)
 {
-    prune_compress_body<NM_DT_BF16, 4, 0, false>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
+    prune_compress_body<NM_DT_BF16, 4, 0, false, false, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
 }
 
 // ------------------------------------------------------------------------------------
@@ -825,7 +847,7 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     if (dense)
         hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
-    else if (DT == NM_DT_BF16 && M == 4 && EST == 0)
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34))     // call indices (block / 4) below 2^32
         hipLaunchKernelGGL(prune_compress_bf16_2of4_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
     else
