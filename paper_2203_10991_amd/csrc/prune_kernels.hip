@@ -475,12 +475,17 @@ __device__ __forceinline__ uint32_t sr_e5m2_into(uint32_t word, float x, uint32_
     return (uint32_t)__builtin_amdgcn_cvt_sr_bf8_f32(c, (int)r_top, (int)word, BYTE);
 }
 
-template <int DT, int EST>
+// HI0: every Philox call index of the launch is below 2^32 (checked by the launcher), see prune_compress_body
+template <int DT, int EST, bool HI0>
 __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
     float scale, const float *__restrict__ scale_dev, uint8_t *__restrict__ vals8, uint32_t *__restrict__ meta32)
 {
     if (scale_dev) scale = scale_dev[0];            // the scale as a device value (element 0 of a scale record)
+    auto philox = [&](uint64_t ctr, uint32_t domain, uint32_t (&w4)[4]) {
+        if constexpr (HI0) philox4x32_10_uniform_c123((uint32_t)ctr, 0u, stream_id, domain, key0, key1, w4);
+        else philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, domain, key0, key1, w4);
+    };
     constexpr int VEC = Row<DT>::VEC;
     constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
     const int64_t ncg = O / VEC;
@@ -522,10 +527,10 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
                 for (int q = 0; q < VEC / 4; ++q) {
                     const uint64_t ctr = (pblk0 >> 2) + q;
                     uint32_t w4[4];
-                    philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 0u, key0, key1, w4);
+                    philox(ctr, 0u, w4);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) sel[4 * q + j] = w4[j];
-                    philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 2u, key0, key1, w4);
+                    philox(ctr, 2u, w4);
 #pragma unroll
                     for (int j = 0; j < 4; ++j) rnd1[4 * q + j] = w4[j];
                 }
@@ -547,7 +552,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
         for (int q = 0; q < VEC * WPB / 4; ++q) {
             const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + q;
             uint32_t w4[4];
-            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, w4);
+            philox(ctr, EST == 1 ? 1u : 0u, w4);
 #pragma unroll
             for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
         }
@@ -555,7 +560,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
         for (int q = 0; q < VEC / 4; ++q) {
             const uint64_t ctr = (blk0 >> 2) + q;
             uint32_t w4[4];
-            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 2u, key0, key1, w4);
+            philox(ctr, 2u, w4);
 #pragma unroll
             for (int j = 0; j < 4; ++j) rnd[4 * q + j] = w4[j];
         }
@@ -593,8 +598,13 @@ static hipError_t launch_prune_q8_t(const void *g, int64_t T, int64_t O, int64_t
     const int64_t groups = T / 32, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
+    // every call index is at most T*O/8 + 3: below 2^32 for tensors of up to 2^33 elements
+    if ((uint64_t)T * (uint64_t)O <= ((uint64_t)1 << 33))
+        hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, true>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
+    else
+        hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, false>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
     return hipGetLastError();
 }
 
