@@ -598,13 +598,17 @@ static hipError_t launch_prune_q8_t(const void *g, int64_t T, int64_t O, int64_t
     const int64_t groups = T / 32, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
-    // every call index is at most T*O/8 + 3: below 2^32 for tensors of up to 2^33 elements
-    if ((uint64_t)T * (uint64_t)O <= ((uint64_t)1 << 33))
-        hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, true>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
-    else
-        hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, false>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
+    // The bf16 optimal-2:4 kernel has a form for launches whose call indices (at most T*O/16 + 1) all lie below 2^32 (2^35 elements is a safe bound);
+    // the other instances run the general code, which the larger tensors take too.
+    if constexpr (DT == NM_DT_BF16 && EST == 0) {
+        if ((uint64_t)T * (uint64_t)O <= ((uint64_t)1 << 35)) {
+            hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, true>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                               g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
+            return hipGetLastError();
+        }
+    }
+    hipLaunchKernelGGL((prune_compress_q8_kernel<DT, EST, false>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                       g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
     return hipGetLastError();
 }
 
