@@ -536,6 +536,27 @@ def main():
         del src, dst
     except Exception as e:
         out["roofline_prune"]["device_copy_GBps_measured"] = None
+    # The same read:write mix as the 16-bit prune + compress (16 bytes in, 9 out) streamed by a kernel that does nothing
+    # else, fully contiguous instructions, over the same number of bytes: what this mix reaches on this machine.
+    if w.dtype == "bf16" and not (q8 or producer or conv):
+        try:
+            n_blk = max(1, (w.T * w.O * 2) // 65536)
+            src = torch.ones(n_blk * 16384, dtype=torch.int32, device=dev)
+            dst = torch.empty(n_blk * 9216, dtype=torch.int32, device=dev)
+            for _ in range(3):
+                nm.nm_rw_mix_probe(src, dst, n_blk)
+            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            e0.record()
+            for _ in range(10):
+                nm.nm_rw_mix_probe(src, dst, n_blk)
+            e1.record()
+            torch.cuda.synchronize()
+            mix_gbps = 10 * n_blk * (65536 + 36864) / (e0.elapsed_time(e1) * 1e-3) / 1e9
+            out["roofline_prune"]["same_mix_stream_GBps_measured"] = mix_gbps
+            out["roofline_prune"]["frac_of_same_mix_stream"] = prune_gbps / mix_gbps
+            del src, dst
+        except Exception as e:
+            out["roofline_prune"]["same_mix_stream_GBps_measured"] = None
     # Context, not the product path: the vendor library's DENSE update GEMM g^T h on the unpruned gradient, same
     # tensors and dtype (what the update phase costs without the method).  Not run under a profiler's counters.
     if not (conv or q8 or transposed or args.pmc_calibration) and g is not None and h is not None:

@@ -286,6 +286,16 @@ int nm_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_
 size_t nm_update_gemm_q8_workspace(int64_t T, int64_t O, int64_t I);
 
 /*
+ * Measurement aid (no passage of the paper: a benchmark's yardstick).  Streams n_blocks * 64 KiB from src and writes
+ * n_blocks * 36 KiB to dst with fully contiguous 4 KiB instructions -- the 16:9 read:write mix of the 16-bit
+ * prune + compress (Sec. 4: the gradient in, half the values and 1/16 index words out) -- so that the prune kernel's
+ * rate can be stated against what this mix reaches on the device.  With src and dst as arrays of 16-byte words,
+ * block b and t = 0..255:  dst[(9b + k)*256 + t] = src[(16b + k)*256 + t] XOR src[(16b + k + 7)*256 + t], k = 0..8.
+ * src, dst: device pointers, 16-byte aligned, not overlapping; the caller owns both.  Errors as everywhere.
+ */
+int nm_rw_mix_probe(const void *src, void *dst, int64_t n_blocks, void *hip_stream);
+
+/*
  * Per-tensor scales of the 8-bit path without a host round trip (Sec. 5, 8-bit rows; the paper fixes no scale rule:
  * this library uses one power-of-two scale per tensor from its current maximum magnitude).
  *

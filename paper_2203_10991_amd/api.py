@@ -46,6 +46,8 @@ def load():
     lib.mvue_prune_4of8_approx.restype = i32
     lib.nm_prune_greedy.argtypes = [vp, i64, i64, i64, i32, i32, i32, vp, vp, vp, i64, vp]
     lib.nm_prune_greedy.restype = i32
+    lib.nm_rw_mix_probe.argtypes = [vp, vp, i64, vp]
+    lib.nm_rw_mix_probe.restype = i32
     lib.mvue_prune_2of4_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, vp, vp, vp]
     lib.mvue_prune_2of4_t.restype = i32
     lib.mvue_prune_1of2_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp]
@@ -414,6 +416,15 @@ def nm_cast_e4m3(h: torch.Tensor, rec: torch.Tensor, h8: Optional[torch.Tensor] 
         h8 = torch.empty((R, Cc), dtype=torch.uint8, device=h.device)
     _check(lib.nm_cast_e4m3(_ptr(h), R, Cc, _rowmajor(h, "h"), _dtype_code(h), _ptr(rec), _ptr(h8), _rowmajor(h8, "h8"), _stream(h)))
     return h8
+
+
+def nm_rw_mix_probe(src: torch.Tensor, dst: torch.Tensor, n_blocks: int) -> None:
+    """Measurement aid: streams n_blocks * 64 KiB from src and writes n_blocks * 36 KiB to dst (the 16:9 read:write mix of
+    the 16-bit prune + compress, contiguous 4 KiB instructions).  src, dst: contiguous device tensors of any dtype."""
+    lib = load()
+    if src.numel() * src.element_size() < n_blocks * 65536 or dst.numel() * dst.element_size() < n_blocks * 36864:
+        raise ValueError("nm_rw_mix_probe: src needs 64 KiB and dst 36 KiB per block")
+    _check(lib.nm_rw_mix_probe(_ptr(src), _ptr(dst), n_blocks, _stream(src)))
 
 
 def nm_update_gemm_shifted(vals: torch.Tensor, meta: torch.Tensor, x_full: torch.Tensor, margin: int, shifts,

@@ -442,6 +442,19 @@ int nm_q8_scale(const void *t, int64_t R, int64_t C, int64_t ld, int dtype, floa
     return launched(fn, nm::launch_q8_scale(dtype, t, R, C, ld, top, scale_rec, (hipStream_t)hip_stream));
 }
 
+int nm_rw_mix_probe(const void *src, void *dst, int64_t n_blocks, void *hip_stream)
+{
+    const char *fn = "nm_rw_mix_probe";
+    if (n_blocks < 0) return fail(NM_ERR_SHAPE, "%s: negative size", fn);
+    if (n_blocks > 0x7fffffffll) return fail(NM_ERR_SHAPE, "%s: more than 2^31 - 1 blocks", fn);
+    if (n_blocks == 0) { g_err[0] = 0; return NM_OK; }
+    if (!src || !dst) return fail(NM_ERR_NULL, "%s: src and dst must not be NULL", fn);
+    if (!aligned16(src) || !aligned16(dst)) return fail(NM_ERR_ALIGN, "%s: src and dst need 16-byte alignment", fn);
+    if (overlap(range_of(src, n_blocks * 65536, "src"), range_of(dst, n_blocks * 36864, "dst")))
+        return fail(NM_ERR_ALIAS, "%s: dst must not overlap src", fn);
+    return launched(fn, nm::launch_rw_mix_probe(src, dst, n_blocks, (hipStream_t)hip_stream));
+}
+
 int nm_cast_e4m3(const void *h, int64_t R, int64_t C, int64_t ld, int dtype, const float *scale_rec, uint8_t *h8, int64_t ld8,
                  void *hip_stream)
 {

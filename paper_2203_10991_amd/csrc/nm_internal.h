@@ -87,6 +87,8 @@ hipError_t launch_q8_scale(int dt, const void *t, int64_t R, int64_t C, int64_t 
 // h8 = e4m3(h * rec[0]), round to nearest even, magnitudes beyond 448 saturate
 hipError_t launch_cast_e4m3(int dt, const void *h, int64_t R, int64_t C, int64_t ld, const float *rec, uint8_t *h8, int64_t ld8,
                             hipStream_t st);
+// measurement aid: streams 64 KB in and 36 KB out per block (the 16-bit prune's read:write mix)
+hipError_t launch_rw_mix_probe(const void *src, void *dst, int64_t n_blocks, hipStream_t st);
 
 // The library's static device scratch array (nm_static.hip): its size, and its address on the current device
 // (looked up once per device; no allocation).

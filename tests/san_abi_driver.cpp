@@ -30,6 +30,7 @@ hipError_t launch_prune_q8(int, int, const void *, int64_t, int64_t, int64_t, ui
                            hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_q8_scale(int, const void *, int64_t, int64_t, int64_t, float, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_cast_e4m3(int, const void *, int64_t, int64_t, int64_t, const float *, uint8_t *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_rw_mix_probe(const void *, void *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_update_gemm(int, const void *, const uint16_t *, const void *, int64_t, float *, int64_t, int64_t, int64_t, int64_t, float,
                               void *, size_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_update_gemm_q8(const uint8_t *, const uint32_t *, const uint8_t *, int64_t, float *, int64_t, int64_t, int64_t, int64_t,
@@ -131,6 +132,14 @@ int main()
     EXPECT(mvue_prune_2of4_q8_ds(g, T, O, O, NM_BF16, 1, 2, 0, rec_g + 1, (uint8_t *)vals, m32, nullptr), NM_ERR_ALIGN);
     EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, rec_g, nullptr, 0.f, ws, wsb, nullptr), NM_ERR_NULL);
     EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, dW + 4, rec_h, 0.f, ws, wsb, nullptr), NM_ERR_ALIAS);
+    // the read/write-mix probe (pointers are never dereferenced on the host)
+    EXPECT(nm_rw_mix_probe(g, (char *)g + (1ll << 40), 3, nullptr), NM_OK);
+    EXPECT(nm_rw_mix_probe(g, (char *)g + 65536, 1, nullptr), NM_OK);
+    EXPECT(nm_rw_mix_probe(g, (char *)g + 65536, 2, nullptr), NM_ERR_ALIAS);
+    EXPECT(nm_rw_mix_probe(g, nullptr, 1, nullptr), NM_ERR_NULL);
+    EXPECT(nm_rw_mix_probe((char *)g + 4, (char *)g + (1ll << 40), 1, nullptr), NM_ERR_ALIGN);
+    EXPECT(nm_rw_mix_probe(g, g, -1, nullptr), NM_ERR_SHAPE);
+    EXPECT(nm_rw_mix_probe(nullptr, nullptr, 0, nullptr), NM_OK);
     // empty problems do nothing and need no pointers
     EXPECT(mvue_prune_2of4(nullptr, 0, O, O, NM_BF16, 0, 0, 0, nullptr, nullptr, nullptr, 0, nullptr), NM_OK);
     EXPECT(mvue_prune_4of8_approx(nullptr, T, 0, 0, NM_BF16, 0, 0, nullptr, nullptr, nullptr, 0, nullptr), NM_OK);
