@@ -32,12 +32,13 @@ __device__ __forceinline__ void philox4x32_10(uint32_t c0, uint32_t c1, uint32_t
 
 // The same function for a call whose counter words 1-3 are wave-uniform, like the key (the high half of the call
 // index, the stream and the domain word: only the low half of the call index differs between lanes).  Then half of
-// round 1, a multiply and an xor of round 2 and an xor of round 3 are scalar work; the result is the same word for word.
+// the generator's first iteration, a multiply and an xor of its second and an xor of its third are scalar work; the
+// result is the same word for word.
 __device__ __forceinline__ void philox4x32_10_uniform_c123(uint32_t c0, uint32_t c1u, uint32_t c2u, uint32_t c3u,
                                                            uint32_t k0, uint32_t k1, uint32_t (&out)[4])
 {
     constexpr uint32_t M0 = 0xD2511F53u, M1 = 0xCD9E8D57u, W0 = 0x9E3779B9u, W1 = 0xBB67AE85u;
-    // round 1: c1, c2, c3 uniform
+    // first of the ten iterations: c1, c2, c3 uniform
     const uint64_t q1 = (uint64_t)M1 * c2u;                             // scalar
     const uint32_t a0 = (uint32_t)(q1 >> 32) ^ c1u ^ k0;                // scalar
     const uint32_t a1 = (uint32_t)q1;                                   // scalar
@@ -45,7 +46,7 @@ __device__ __forceinline__ void philox4x32_10_uniform_c123(uint32_t c0, uint32_t
     const uint32_t a2 = (uint32_t)(q0 >> 32) ^ (c3u ^ k1);
     const uint32_t a3 = (uint32_t)q0;
     k0 += W0; k1 += W1;
-    // round 2: c0, c1 uniform
+    // second iteration: c0, c1 uniform
     const uint64_t r0 = (uint64_t)M0 * a0;                              // scalar
     const uint64_t r1 = (uint64_t)M1 * a2;
     const uint32_t b0 = (uint32_t)(r1 >> 32) ^ (a1 ^ k0);
@@ -53,7 +54,7 @@ __device__ __forceinline__ void philox4x32_10_uniform_c123(uint32_t c0, uint32_t
     const uint32_t b2 = a3 ^ ((uint32_t)(r0 >> 32) ^ k1);
     const uint32_t b3 = (uint32_t)r0;                                   // scalar
     k0 += W0; k1 += W1;
-    // round 3: c3 uniform
+    // third iteration: c3 uniform
     const uint64_t s0 = (uint64_t)M0 * b0;
     const uint64_t s1 = (uint64_t)M1 * b2;
     uint32_t d0 = (uint32_t)(s1 >> 32) ^ b1 ^ k0;
