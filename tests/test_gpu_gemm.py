@@ -139,6 +139,18 @@ def test_update_gemm_random_shapes(nm, oracle, T, O, I):
     run_case(nm, oracle, synth.Workload(f"r{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T + O + I)
 
 
+def _random_mid_shapes(n, seed):
+    rng = np.random.default_rng(seed)
+    return [(int(rng.integers(200, 900)) * 16, int(rng.integers(100, 400)) * 8, int(rng.integers(100, 400)) * 8) for _ in range(n)]
+
+
+@pytest.mark.parametrize("T,O,I", _random_mid_shapes(5, 31))
+def test_update_gemm_random_mid_sized_shapes(nm, oracle, T, O, I):
+    """seeded random mid-sized problems (tens of tiles of 256 x 256, thousands of tokens): the plans that choose between
+    128 x 128 and 256 x 256 tiles with split-K, ragged in every dimension, against the oracle"""
+    run_case(nm, oracle, synth.Workload(f"m{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T + O + I)
+
+
 @pytest.mark.parametrize("dtype", ["bf16", "f32", "q8"])
 @pytest.mark.parametrize("T,O,I", [(4096, 64, 576), (12608 - 12608 % 32, 768, 768), (2048, 1000, 528), (32 * 300, 256, 2304)])
 def test_update_gemm_is_bitwise_reproducible(nm, dtype, T, O, I):
