@@ -178,6 +178,59 @@ class NMLinear(torch.nn.Linear):
         return _NMLinearFn.apply(x, self.weight, self.bias, self.cfg)
 
 
+class _NMLinearReLUFn(torch.autograd.Function):
+    """y = relu(x W^T + b).  In the backward pass the neural gradient of the linear part, g = gy * relu'(z) (the
+    elementwise step of eq. (2)), is formed, written dense and pruned in ONE pass by the library
+    (mvue_prune_*_producer): g is never read back for the prune.  dx and db use the dense g, as in the paper."""
+
+    @staticmethod
+    def forward(ctx, x, weight, bias, cfg):
+        y = F.relu(F.linear(x, weight, bias))
+        ctx.save_for_backward(x, weight, y)               # relu'(z) = [y > 0]
+        ctx.cfg, ctx.has_bias = cfg, bias is not None
+        return y
+
+    @staticmethod
+    def backward(ctx, gy):
+        x, weight, y = ctx.saved_tensors
+        cfg = ctx.cfg
+        O = weight.shape[0]
+        u2 = gy.reshape(-1, O)
+        d2 = (y.reshape(-1, O) > 0).to(gy.dtype)
+        h2 = x.reshape(-1, x.shape[-1])
+        T = u2.shape[0]
+        fused = (cfg.precision == "native" and cfg.nm in ("1:2", "2:4") and u2.is_cuda and O % 8 == 0 and h2.shape[1] % 8 == 0
+                 and u2.dtype == h2.dtype and u2.dtype in (torch.float32, torch.bfloat16) and ctx.needs_input_grad[1])
+        if fused:
+            pad = (-T) % 16
+            if pad:                                       # zero rows prune to zeros and add nothing to dW
+                u2, d2, h2 = F.pad(u2, (0, 0, 0, pad)), F.pad(d2, (0, 0, 0, pad)), F.pad(h2, (0, 0, 0, pad))
+            g2, vals, meta = api.mvue_prune_producer(u2.contiguous(), d2.contiguous(), nm=cfg.nm, seed=cfg.current_seed(),
+                                                     stream_id=cfg.stream_id, mode=cfg.mode)
+            dW = api.nm_update_gemm(vals, meta, h2.contiguous()).to(weight.dtype)
+            g2 = g2[:T]
+        else:                                             # 8-bit and three-term modes: separate product, then the usual path
+            g2 = u2 * d2
+            dW = _update_gemm(g2, h2, cfg).to(weight.dtype) if ctx.needs_input_grad[1] else None
+        dx = (g2 @ weight).reshape(x.shape) if ctx.needs_input_grad[0] else None
+        db = g2.sum(0) if ctx.has_bias and ctx.needs_input_grad[2] else None
+        if cfg.auto_advance:
+            cfg.advance()
+        return dx, dW, db, None
+
+
+class NMLinearReLU(torch.nn.Linear):
+    """Linear followed by ReLU as one module, so that the activation's backward and the prune of the neural gradient
+    are one kernel (the prune fused into the producer of g_l, eq. (2))."""
+
+    def __init__(self, in_features: int, out_features: int, bias: bool = True, cfg: Optional[NMConfig] = None, **kw):
+        super().__init__(in_features, out_features, bias=bias, **kw)
+        self.cfg = cfg or _own_config()
+
+    def forward(self, x):
+        return _NMLinearReLUFn.apply(x, self.weight, self.bias, self.cfg)
+
+
 class _NMConv2dFn(torch.autograd.Function):
     @staticmethod
     def forward(ctx, x, weight, bias, stride, padding, dilation, cfg):

@@ -52,6 +52,41 @@ def test_linear_update_phase_matches_oracle(oracle, dtype, nmode, mode, precisio
     assert not torch.equal(w1, layer.weight.grad)
 
 
+@pytest.mark.parametrize("dtype,nmode,mode", [(torch.bfloat16, "2:4", 0), (torch.bfloat16, "1:2", 0), (torch.float32, "2:4", 1)])
+def test_linear_relu_fuses_the_activation_backward_with_the_prune(oracle, dtype, nmode, mode):
+    """NMLinearReLU: g = gy * relu'(z) and its prune come from one library call (eq. (2)'s elementwise step as the
+    producer).  dW against the oracle's producer step + prune + binary64 GEMM; dx, db against torch's dense backward of
+    relu(linear(x))."""
+    from paper_2203_10991_amd.autograd import NMConfig, NMLinearReLU
+    torch.manual_seed(3)
+    B, S, I, O = 2, 53, 48, 64                      # T = 106: padded to 112 inside
+    cfg = NMConfig(nm=nmode, mode=mode, seed=11, stream_id=4)
+    layer = NMLinearReLU(I, O, bias=True, cfg=cfg, device=DEV, dtype=dtype)
+    x = torch.randn(B, S, I, device=DEV, dtype=dtype, requires_grad=True)
+    gy = (torch.randn(B, S, O, device=DEV) * torch.exp(2 * torch.randn(B, S, O, device=DEV))).to(dtype)
+    y = layer(x)
+    y.backward(gy)
+    ref = torch.nn.Linear(I, O, device=DEV, dtype=dtype)
+    ref.load_state_dict(layer.state_dict())
+    x2 = x.detach().clone().requires_grad_(True)
+    y2 = torch.relu(ref(x2))
+    y2.backward(gy)
+    assert torch.equal(y, y2)
+    assert torch.equal(x.grad, x2.grad) and torch.equal(layer.bias.grad, ref.bias.grad)
+    # update phase against the oracle
+    pad = (0, 0, 0, 6)
+    u2 = torch.nn.functional.pad(gy.reshape(-1, O), pad)
+    d2 = torch.nn.functional.pad((y.detach().reshape(-1, O) > 0).to(dtype), pad)
+    h2 = torch.nn.functional.pad(x.detach().reshape(-1, I), pad)
+    g2 = oracle.act_backward(bits(u2), bits(d2))
+    oprune = oracle.prune_1of2 if nmode == "1:2" else (oracle.prune_2of4_approx if mode else oracle.prune_2of4)
+    ov, om, _ = oprune(g2, 11, 4)
+    want, wabs = oracle.update_gemm(ov, om, bits(h2))
+    got = layer.weight.grad.double().cpu().numpy()
+    tol = 1e-5 if dtype == torch.float32 else 1e-2          # (bf16: dW itself is rounded to bf16 by the layer)
+    assert (np.abs(got - want) <= tol * np.maximum(wabs, np.abs(want))).all()
+
+
 def test_conv2d_update_phase_matches_oracle(oracle):
     from paper_2203_10991_amd.autograd import NMConfig, NMConv2d
     torch.manual_seed(1)
@@ -151,7 +186,7 @@ def test_training_with_pruned_update_phase_tracks_dense_training():
             opt.step()
             for c in cfgs:
                 c.advance()
-            losses.append(float(loss))
+            losses.append(float(loss.detach()))
         return losses
 
     dense_net, _ = make(torch.nn.Linear)
