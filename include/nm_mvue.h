@@ -90,6 +90,9 @@ int mvue_prune_1of2(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
  * that section.  No ranking, six binary32 divisions per quad.  A zero is never drawn while a
  * non-zero remains; padding falls on the lowest-index zeros.
  * Any other mode returns NM_ERR_UNSUPPORTED.  Arguments as mvue_prune_1of2.
+ * Non-finite values (every prune of this header): infinities and sums that overflow go through the same formulas in
+ * IEEE arithmetic and the result is still a pure function of the arguments; a NaN makes the kept values of its block NaN,
+ * and which positions of that block are kept is unspecified.
  */
 int mvue_prune_2of4(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype,
                     uint64_t seed, uint32_t stream_id, int mode,

@@ -112,6 +112,19 @@ def test_edge_values_bit_exact(nm, oracle, dtype, nmode):
         check_case(nm, oracle, _edge_tensor(dtype), nmode, seed, 0)
 
 
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("nmode", ["1:2", "2:4", "2:4a", "1:4"])
+def test_overflowing_sums_and_infinities_bit_exact(nm, oracle, dtype, nmode):
+    """values whose block sums overflow binary32, and infinities: both sides follow IEEE arithmetic through the same
+    formulas, so masks and values still agree bit for bit (a NaN in a block is outside the contract: the block's kept
+    values are NaN on both sides, which positions carry them is unspecified)"""
+    base = [0.0, 1.0, -3.0, 1e37, 3.3e38, -3.3e38, 2.5e38, 1.7e38, 9e37, 3.4e38, 1.2e38, np.inf, -np.inf, 7.0, 1e30]
+    g = np.random.default_rng(1).choice(np.array(base, dtype=np.float32), size=(64, 256))
+    g = g if dtype == "f32" else synth.f32_to_bf16_bits(g)
+    for seed in range(3):
+        check_case(nm, oracle, g, nmode, seed, 0)
+
+
 def test_empty_and_error_paths_on_device(nm):
     g = torch.zeros((0, 64), dtype=torch.bfloat16, device=DEV)
     v, m, _ = nm.mvue_prune_2of4(g)
