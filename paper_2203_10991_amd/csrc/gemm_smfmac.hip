@@ -658,7 +658,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
     const int CUS = 256;
     p.tall_rows = 0; p.tall_tiles_m = 0;
     // shape 0: 256x256 (8 waves), shape 1: 128x128 (4 waves, two workgroups fit a CU), shape 2: 64x256 (4 waves, one per CU),
-    // shape 3: 256x128 (4 waves, one per CU)
+    // shape 3: 256x128 (8 waves, one per CU)
     bool small = false;
     if ((O + 255) / 256 * ((I + 255) / 256) >= CUS) {
         p.shape = 0; p.tm = 256; p.tn = 256;
@@ -685,9 +685,9 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
     // The large tile has to win by 15 %: its plan writes two to three times the partial sums and leaves no CU to a
     // kernel that runs beside it (layers replayed from a graph with parallel branches measure 5 % slower with it
     // where the margin is smaller).
-    // Between the two sits a 256 x 128 tile on 4 waves (one workgroup per CU, 102 KB of LDS: 0.35 us per stage cold, a
-    // third fewer operand bytes per product than 128 x 128): it takes the ViT-sized layers (qkv, fc1, fc2: 11-15 % faster
-    // cold and warm at the same or a little more workspace) when predicted 5 % faster.
+    // Between the two sits a 256 x 128 tile on 8 waves (one workgroup per CU, 102 KB of LDS: 0.30-0.365 us per stage cold, a
+    // third fewer operand bytes per product than 128 x 128; the same tile on 4 waves measured 2-9 % slower): it takes the
+    // ViT-sized layers (qkv, fc1, fc2) at the same or a little more workspace when predicted 5 % faster.
     auto whole_trips = [](int64_t gps) { gps = (gps + 11) / 12 * 12; return gps < 12 ? (int64_t)12 : gps; };
     int slabs = 1;
     if (small && groups >= 48) {
@@ -706,18 +706,20 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
         slabs = (int)s_one;
         if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two, false) < cost(s_one, false)) slabs = (int)s_two;
         if (p.shape == 1 && !shifted) {
-            // one workgroup per CU at most on the larger tiles; cost of `tl` tiles cut into `sl` slabs at `t_stage` us per stage
-            auto one_per_cu = [&](int64_t tl, double t_stage_alone, double t_stage_full, int64_t &sl) {
+            // one workgroup per CU at most on the larger tiles: cost of `tl` tiles cut into as many slabs as fit, at
+            // t_lo us per stage up to a `knee` share of the CUs in use, rising linearly to t_hi with all of them
+            auto one_per_cu = [&](int64_t tl, double t_lo, double t_hi, double knee, int64_t &sl) {
                 sl = std::min(max_s, std::max<int64_t>(1, CUS / tl));
                 const int64_t wgs = tl * sl, stages = whole_trips((groups + sl - 1) / sl) / 2;
                 const double rounds = (double)((wgs + CUS - 1) / CUS);
-                const double t_stage = t_stage_alone + (t_stage_full - t_stage_alone) * (double)std::min<int64_t>(wgs, CUS) / CUS;
+                const double fill = (double)std::min<int64_t>(wgs, CUS) / CUS;
+                const double t_stage = t_lo + (t_hi - t_lo) * std::max(0.0, (fill - knee) / (1.0 - knee));
                 return std::max(rounds * (double)stages * t_stage + 3.0, stream) + second_pass(sl);
             };
             const double cost1 = cost(slabs, true);
             int64_t s0 = 1, s3 = 1;
-            const double cost0 = one_per_cu((O + 255) / 256 * ((I + 255) / 256), 0.44, 0.56, s0);     // 256 x 256, 8 waves
-            const double cost3 = one_per_cu((O + 255) / 256 * ((I + 127) / 128), 0.35, 0.35, s3);     // 256 x 128, 4 waves
+            const double cost0 = one_per_cu((O + 255) / 256 * ((I + 255) / 256), 0.44, 0.56, 0.0, s0);       // 256 x 256, 8 waves
+            const double cost3 = one_per_cu((O + 255) / 256 * ((I + 127) / 128), 0.30, 0.365, 0.75, s3);     // 256 x 128, 8 waves
             // (with fewer than 32 of its tiles the 256 x 128 plan needs more than eight slabs and measured slower than predicted)
             const int64_t tiles3 = (O + 255) / 256 * ((I + 127) / 128);
             const bool take0 = cost0 < 0.85 * cost1, take3 = tiles3 >= 32 && cost3 < 0.95 * cost1;
@@ -774,7 +776,7 @@ hipError_t launch_update_gemm_smfmac(const void *vals, const uint16_t *meta, con
                        meta, (const uint16_t *)h, ldh, out, ldo, slab_stride, T / 16, p.groups_per_slab, O, I,         \
                        p.tiles_m, p.tiles_n, acc_flag, p.tall_rows, O, ShiftArg{})
         if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
-        else if (p.shape == 3) NM_LAUNCH(2, 2, 4, 2);
+        else if (p.shape == 3) NM_LAUNCH(4, 2, 2, 2);
         else NM_LAUNCH(2, 2, 2, 2);
 #undef NM_LAUNCH
     }

@@ -68,14 +68,15 @@ def test_large_tile_kernels_and_their_tile_maps(nm, oracle, T, O, I):
     run_case(nm, oracle, synth.Workload(f"big{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T)
 
 
-@pytest.mark.parametrize("T,O,I,slabs,beta", [(6416, 2296, 2040, 3, 0.0), (16400, 2296, 760, 9, 1.0), (10784, 2472, 888, 3, 1.0)])
+@pytest.mark.parametrize("T,O,I,slabs,beta", [(8208, 3064, 1528, 3, 0.0), (16400, 2296, 760, 4, 1.0), (10784, 2472, 888, 3, 1.0), (6416, 2296, 2040, 0, 0.0)])
 def test_large_tiles_with_split_k(nm, oracle, T, O, I, slabs, beta):
     """Mid-sized problems (fewer than 256 tiles of 256 x 256, a long reduction) run on the 256 x 256 kernel with the
     token axis cut into slabs: ragged last tile row and column, a ragged last slab, and the second pass over the
-    partial sums.  The slab count identifies the plan of the first two (256 // tiles of 256 x 256; the 128 x 128 plan
-    would take fewer); the third is a size the plan gives to 256 x 128 tiles (70 of them, three slabs), here with beta = 1."""
+    partial sums.  The slab count identifies the plan of the first (256 // tiles of 256 x 256 = 3; the other plans would
+    take one slab); the next two are sizes the plan gives to 256 x 128 tiles cut into slabs (54 and 70 tiles), with
+    beta = 1; the last to 144 tiles of 256 x 128 in one pass."""
     need = nm.nm_update_gemm_workspace(T, O, I, torch.bfloat16)
-    assert need == slabs * O * I * 4
+    assert need == (slabs * O * I * 4 if slabs > 1 else 0)
     run_case(nm, oracle, synth.Workload(f"mid{T}x{O}x{I}", T, O, I, "bf16", "2:4", 0.0, 2.0, 0.3), seed=T, beta=beta)
 
 
