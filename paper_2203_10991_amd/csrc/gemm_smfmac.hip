@@ -705,7 +705,7 @@ static Plan make_plan(int64_t T, int64_t O, int64_t I, bool shifted = false)
         const int64_t s_two = std::min(max_s, std::max<int64_t>(1, 2 * CUS / tiles));
         slabs = (int)s_one;
         if (p.shape == 1 && tiles * s_two >= 3 * CUS / 2 && cost(s_two, false) < cost(s_one, false)) slabs = (int)s_two;
-        if (p.shape == 1 && !shifted) {
+        if (p.shape == 1) {
             // one workgroup per CU at most on the larger tiles: cost of `tl` tiles cut into as many slabs as fit, at
             // t_lo us per stage up to a `knee` share of the CUs in use, rising linearly to t_hi with all of them
             auto one_per_cu = [&](int64_t tl, double t_lo, double t_hi, double knee, int64_t &sl) {
@@ -808,6 +808,7 @@ hipError_t launch_update_gemm_smfmac_shifted(const void *vals, const uint16_t *m
                        p.groups_per_slab, O, I, p.tiles_m, p.tiles_n, acc_flag, (int64_t)0, O, sh)
     if (p.shape == 0) NM_LAUNCH(2, 4, 4, 2);
     else if (p.shape == 1) NM_LAUNCH(2, 2, 2, 2);
+    else if (p.shape == 3) NM_LAUNCH(4, 2, 2, 2);
     else NM_LAUNCH(1, 4, 2, 2);
 #undef NM_LAUNCH
     hipError_t e = hipGetLastError();

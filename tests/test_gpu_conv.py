@@ -45,7 +45,8 @@ def make_case(N, H, W, C, O, k, seed):
                                          (3, 14, 14, 64, 64, 3),       # ResNet-like block, few tiles: split-K path
                                          (2, 9, 11, 24, 200, 3),       # ragged rows and columns (C not a power of two)
                                          (2, 8, 8, 16, 40, 5),         # 5x5 taps: 25 views
-                                         (1, 20, 20, 32, 72, 1)])      # 1x1: one view, no shift
+                                         (1, 20, 20, 32, 72, 1),       # 1x1: one view, no shift
+                                         (8, 14, 14, 256, 504, 3)])    # 2 x 18 tiles of 256 x 128 (the mid-sized plan), ragged rows
 def test_shifted_gemm_matches_oracle(nm, oracle, N, H, W, C, O, k):
     x_full, g, T, margin, shifts = make_case(N, H, W, C, O, k, seed=H + C + k)
     ov, om, _ = oracle.prune_2of4(g, 5, 1)
