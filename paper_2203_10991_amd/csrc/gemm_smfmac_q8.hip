@@ -610,11 +610,14 @@ static PlanQ8 make_plan_q8(int64_t T, int64_t O, int64_t I, bool shifted = false
         p.tall_tiles_m = rs.tall_tiles_m;
         p.tall_rows = rs.tall_rows;
     }
-    // Mid-sized problems (48 to 255 tiles of 256 x 256) stay on the 256 x 256 kernel, the token axis cut into slabs up
-    // to one workgroup per CU: measured on operands that are in no cache, it is 13 % (64 tiles, four slabs) to 38 %
-    // (192 tiles, one slab) faster than 128 x 256 tiles, which need twice the bytes of `h` per product and, beyond 256
-    // tiles, a second round.  Below that the two measure alike and the smaller tile needs fewer partial sums.
-    else if (!shifted && (O + 255) / 256 * ((I + 255) / 256) >= 48) { p.shape = 0; p.tm = 256; }
+    // Mid-sized problems stay on the 256 x 256 kernel once 128 x 256 tiles would need a second round (more than 256 of
+    // them): measured on operands that are in no cache, 144 and 192 tiles of 256 x 256 in one round are 14-32 % faster
+    // than twice as many 128 x 256 tiles, which need twice the bytes of `h` per product.  Up to 256 tiles of 128 x 256
+    // (cut into slabs until every CU has one) the smaller tile on 8 waves is the faster one (5-20 %).
+    // With a long reduction (16384 tokens or more) the larger tile also wins from 48 tiles on (the transformer-MLP
+    // shape, 64 tiles in four slabs: 78 against 89 us cold): the second pass over its partial sums weighs less.
+    else if (!shifted && ((O + 127) / 128 * ((I + 255) / 256) > CUS ||
+                          (T >= 16384 && (O + 255) / 256 * ((I + 255) / 256) >= 48))) { p.shape = 0; p.tm = 256; }
     else { p.shape = 1; p.tm = 128; }
     p.tiles_m = (int)((O - p.tall_rows + p.tm - 1) / p.tm);
     p.tiles_n = (int)((I + 255) / 256);

@@ -142,11 +142,13 @@ def test_update_gemm_q8_large_tile_kernel(nm, oracle, T, O, I):
     gemm_case(nm, oracle, T, O, I, seed=T, sample=12)
 
 
-@pytest.mark.parametrize("T,O,I,slabs,beta", [(4128, 2040, 2000, 4, 0.0), (2080, 2296, 3056, 2, 1.0)])
-def test_update_gemm_q8_large_tiles_with_split_k(nm, oracle, T, O, I, slabs, beta):
-    """mid-sized problems (48 to 255 tiles of 256 x 256) run on the 256 x 256 kernel with the token axis cut into
-    slabs: ragged last tile row and column, ragged last slab, scale applied in the second pass"""
-    assert nm.nm_update_gemm_q8_workspace(T, O, I) == slabs * O * I * 4
+@pytest.mark.parametrize("T,O,I,slabs,beta", [(4128, 2040, 2000, 2, 0.0), (2080, 2296, 4080, 0, 1.0), (16416, 2040, 2000, 4, 0.0)])
+def test_update_gemm_q8_mid_sized_plans(nm, oracle, T, O, I, slabs, beta):
+    """mid-sized problems: up to 256 tiles of 128 x 256 run on that tile with the token axis cut into slabs (here 128
+    tiles, two slabs, the scale applied in the second pass); beyond that on 256 x 256 tiles in one round (here 144
+    tiles), and so do 48 tiles or more under a long reduction (here 64 tiles in four slabs); ragged last tile row and
+    column, ragged last slab"""
+    assert nm.nm_update_gemm_q8_workspace(T, O, I) == (slabs * O * I * 4 if slabs > 1 else 0)
     gemm_case(nm, oracle, T, O, I, seed=T, beta=beta, sample=10)
 
 
