@@ -174,7 +174,7 @@ def vit_sweep(args, nm, synth, torch, dev):
 
     ms_forked = {}
     same = True
-    for nb in (2, 4):
+    for nb in (2, 4, 8):
         ms_forked[nb], ok = forked_graph(nb)
         same = same and ok
     best = min([ms_chain] + [v for v in ms_forked.values() if v is not None]) if same else ms_chain
@@ -199,7 +199,7 @@ def vit_sweep(args, nm, synth, torch, dev):
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "bf16", "data": "synthetic",
         "config": {"workload": "c4_vit_sweep: ViT-Base-shaped update GEMMs (qkv, proj, fc1, fc2) at 64 x 197 tokens, MVUE 1:2 and 2:4",
                    "shapes": len(layers), "seed": 0,
-                   "launch": "one HIP graph per step, the fastest of a chain and graphs of two and four parallel branches whose "
+                   "launch": "one HIP graph per step, the fastest of a chain and graphs of two, four and eight parallel branches whose "
                              "replays reproduce the chain's dW bit for bit (ms_per_step_graph_chain, ms_per_step_graph_branches; "
                              "eager launches: ms_per_step_eager)"},
         "ms_per_step_eager": ms_eager, "ms_per_step_graph_chain": ms_chain,
