@@ -457,7 +457,7 @@ def main():
                                "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
                                "update_gemm_smfmac_q8_tall_kernel + update_gemm_smfmac_q8_kernel (rows split as in the 16-bit path)" if q8 else
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "
-                               "between the 384x256 and the 256x256 tile kernel)" + (" x 6 partial products, + split3_bf16_kernel" if x3 else ""),
+                               "between the 384x256 and the 256x256 tile kernel)" + (" over the six partial products stacked along the token axis, + split3_bf16_kernel" if x3 else ""),
                      "bound": "mfma", "achieved": gemm_tflops * (6.0 if x3 else 1.0),
                      "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops * (6.0 if x3 else 1.0) / gemm_peak,
                      "traffic": read_traffic(w.name if transposed else tname, "gemm"),

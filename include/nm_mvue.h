@@ -193,8 +193,10 @@ int nm_compress(const void *dense, int64_t T, int64_t O, int64_t ld, int dtype, 
  * NM_F32_BF16X3: the same binary32 tensors, but each value is split into three bf16 terms (24 significant bits)
  * and the six partial products of first and second order run on the sparse 16-bit path, accumulated in binary32:
  * |error| below 2^-22 of the sum of absolute products plus the accumulation's own rounding, at less than half the
- * time of NM_F32.  It needs a larger workspace (the six bf16 planes live there).  A non-finite operand value makes the
- * results it touches non-finite, but an infinity may come out as a NaN.
+ * time of NM_F32.  It needs a larger workspace: six bf16 copies of each operand live there, stacked along the token
+ * axis so that one run of the 16-bit kernels sums the six products (6 x (T/2*O + T*I) x 2 bytes, plus the index
+ * words six times).  A non-finite operand value makes the results it touches non-finite, but an infinity may come out
+ * as a NaN.
  *   workspace    device scratch of at least nm_update_gemm_workspace(T,O,I,dtype) bytes
  *                (split-K partial sums); may be NULL when that size is 0.
  * O and ldh may not exceed 2^21 (NM_ERR_UNSUPPORTED): the kernels reach a few hundred rows of h

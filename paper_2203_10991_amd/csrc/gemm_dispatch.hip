@@ -19,7 +19,7 @@ hipError_t launch_update_gemm(int dt, const void *vals, const uint16_t *meta, co
     (void)workspace_bytes;
     // bf16: 4:2 sparse MFMA.  binary32: gfx950's sparse matrix instructions take 16- and 8-bit operands only,
     // so the operand is expanded on its way into LDS and multiplied on the dense fp32 MFMA path.
-    // binary32 as three bf16 terms: six runs of the sparse 16-bit kernels.
+    // binary32 as three bf16 terms: the six partial products as one run of the sparse 16-bit kernels.
     if (dt == NM_DT_F32_BF16X3) return launch_update_gemm_f32_split(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);
     if (dt == NM_DT_BF16) return launch_update_gemm_smfmac(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);
     return launch_update_gemm_f32(vals, meta, h, ldh, dW, lddw, T, O, I, beta, workspace, st);

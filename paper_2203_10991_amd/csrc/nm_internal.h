@@ -59,7 +59,8 @@ hipError_t launch_update_gemm_f32(const void *vals, const uint16_t *meta, const 
                                   hipStream_t st);
 size_t update_gemm_f32_workspace(int64_t T, int64_t O, int64_t I);
 
-// binary32 operands split into three bf16 terms each, six runs of the 16-bit sparse GEMM (gemm_f32_split.hip)
+// binary32 operands split into three bf16 terms each, the six partial products as one run of the 16-bit sparse GEMM over
+// operands stacked along the token axis (gemm_f32_split.hip)
 hipError_t launch_update_gemm_f32_split(const void *vals, const uint16_t *meta, const void *h, int64_t ldh, float *dW,
                                         int64_t lddw, int64_t T, int64_t O, int64_t I, float beta, void *workspace,
                                         hipStream_t st);
