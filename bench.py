@@ -294,8 +294,8 @@ def main():
         g = gT
         prune = lambda g_, **kw: nm.mvue_prune_2of4_t(g_, mode=1 if approx else 0, **kw)
     if args.conv_implicit:
-        if w.name != "c3_conv_2of4" or q8:
-            print("bench.py: --conv-implicit runs the bf16 c3_conv_2of4 layer only", file=sys.stderr)
+        if w.name != "c3_conv_2of4":
+            print("bench.py: --conv-implicit runs the c3_conv_2of4 layer only (16-bit, or --precision q8)", file=sys.stderr)
             sys.exit(2)
         # ResNet-50 stage-1 3x3 convolution at batch 256: rows of g are (n, y, x); its activations are one [T x 64]
         # tensor of the workload's recipe.  Both are placed on the zero-padded grid once, outside the timed region
@@ -303,7 +303,7 @@ def main():
         N, H, W, C, k = 256, 56, 56, 64, 3
         Hp, Wp = H + 2, W + 2
         rows = N * Hp * Wp
-        Tp = (rows + 15) // 16 * 16
+        Tp = (rows + 31) // 32 * 32          # whole token groups of either format
         margin = Wp + 1
         x_full = torch.zeros((Tp + 2 * margin, C), dtype=g.dtype, device=dev)
         x_full[margin:margin + rows].view(N, Hp, Wp, C)[:, 1:-1, 1:-1] = h[:, :C].reshape(N, H, W, C)
@@ -313,7 +313,7 @@ def main():
         conv = dict(x_full=x_full, margin=margin, shifts=shifts, T=Tp)
         del h
         g, h = g_pad, None
-    if q8 and (w.dtype != "bf16" or w.T % 32):
+    if q8 and (w.dtype != "bf16" or g.shape[0] % 32):
         print("bench.py: --precision q8 runs the bf16 workloads whose token count is a multiple of 32", file=sys.stderr)
         sys.exit(2)
     producer = None
@@ -330,10 +330,16 @@ def main():
         # gradient scale: a power of two that keeps every kept value below the largest e5m2
         # (both by the library: per-tensor power-of-two scales as device-side records, nothing returns to the host)
         g_scale = nm.nm_q8_scale(g, 57344.0 / (2.0 if w.nm == "1:2" else 4.0))
-        h_scale = nm.nm_q8_scale(h, 448.0)
-        h = nm.nm_cast_e4m3(h, h_scale)
-        vals, meta = nm.alloc_compressed_q8(w.T, w.O, dev)
-        need = nm.nm_update_gemm_q8_workspace(w.T, w.O, w.I)
+        if conv:
+            h_scale = nm.nm_q8_scale(conv["x_full"], 448.0)
+            conv["x_full"] = nm.nm_cast_e4m3(conv["x_full"], h_scale)
+            vals, meta = nm.alloc_compressed_q8(conv["T"], w.O, dev)
+            need = int(nm.load().nm_update_gemm_q8_shifted_workspace(conv["T"], w.O, 64, len(conv["shifts"])))
+        else:
+            h_scale = nm.nm_q8_scale(h, 448.0)
+            h = nm.nm_cast_e4m3(h, h_scale)
+            vals, meta = nm.alloc_compressed_q8(w.T, w.O, dev)
+            need = nm.nm_update_gemm_q8_workspace(w.T, w.O, w.I)
     elif conv:
         vals, meta = nm.alloc_compressed(conv["T"], w.O, g.dtype, dev)
         need = int(nm.load().nm_update_gemm_shifted_workspace(conv["T"], w.O, 64, len(conv["shifts"])))
@@ -364,7 +370,11 @@ def main():
 
     def gemm(b=None):
         b = b or sets[0]
-        if b["conv"]:
+        if b["conv"] and q8:
+            c = b["conv"]
+            nm.nm_update_gemm_q8_shifted(b["vals"], b["meta"], c["x_full"], c["margin"], c["shifts"], dW=b["dW"], alpha=(g_scale, h_scale),
+                                         beta=0.0, workspace=b["ws"])
+        elif b["conv"]:
             c = b["conv"]
             nm.nm_update_gemm_shifted(b["vals"], b["meta"], c["x_full"], c["margin"], c["shifts"], dW=b["dW"], beta=0.0, workspace=b["ws"])
         elif q8:
@@ -405,7 +415,7 @@ def main():
     flops = w.flops_dense_equiv
     prune_bytes = w.T * w.O * 2 + w.T * w.O // 2 + w.T * w.O // 8 if q8 else w.prune_bytes
     if conv:
-        prune_bytes = conv["T"] * w.O * 25 // 8          # the padded grid's rows
+        prune_bytes = conv["T"] * w.O * (21 if q8 else 25) // 8          # the padded grid's rows
     if producer:                                         # read u and d, write g, vals and meta
         prune_bytes = w.T * w.O * w.elem_bytes * 3 + w.T * w.O * w.elem_bytes // 2 + w.T * w.O // 8
     f32 = w.dtype == "f32" and not q8 and not x3
@@ -428,7 +438,7 @@ def main():
         unfused = {"what": "torch.mul(u, d) then the separate prune call (two kernels, g written and read back)",
                    "mul_ms": tm, "prune_ms": tp, "fused_ms": prune_ms, "speedup": (tm + tp) / prune_ms}
         del gtmp
-    tname = w.name + ("_producer" if producer else "_bf16x3" if x3 else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
+    tname = w.name + ("_producer" if producer else "_bf16x3" if x3 else "_q8_shifted" if q8 and conv else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -454,6 +464,7 @@ def main():
         "gemm_TFLOPs_dense_equiv": gemm_tflops, ("gemm_pct_fp32_mfma_peak" if f32 else "gemm_pct_smfmac_peak"): 100.0 * gemm_tflops / gemm_peak,
         "gemm_ms": gemm_ms,
         "roofline": {"kernel": "update_gemm_f32_mfma_kernel (+ splitk_reduce_kernel when the plan splits the token axis)" if f32 else
+                               "update_gemm_smfmac_q8_kernel<1,4,2,2,shifted>" if conv and q8 else
                                "update_gemm_smfmac_kernel<1,4,2,2,shifted>" if conv else
                                "update_gemm_smfmac_q8_tall_kernel + update_gemm_smfmac_q8_kernel (rows split as in the 16-bit path)" if q8 else
                                "update_gemm_smfmac_tall_kernel + update_gemm_smfmac_kernel (one nm_update_gemm call: rows split "

@@ -112,6 +112,7 @@ hipError_t launch_update_gemm_f32_split(const void *vals, const uint16_t *meta, 
         db.seg[k] = b + k * b_elems; db.plane[k] = TERM_B[k];
     }
     const int64_t na = a_elems / 4, nb = T * (I / 4), nm16 = m_bytes / 16;
+    if ((na + 255) / 256 > 0x7fffffffll || (nb + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;   // one thread per 4 values
     hipLaunchKernelGGL(split3_bf16_kernel, dim3((unsigned)((na + 255) / 256)), dim3(256), 0, st, (const float *)vals,
                        (int64_t)1, a_elems, a_elems, da);
     hipLaunchKernelGGL(split3_bf16_kernel, dim3((unsigned)((nb + 255) / 256)), dim3(256), 0, st, (const float *)h, T, I, ldh, db);
