@@ -286,8 +286,8 @@ def main():
     conv = None
     transposed = args.g_layout == "transposed"
     if transposed:
-        if w.nm != "2:4" or q8 or args.conv_implicit:
-            print("bench.py: --g-layout transposed runs 2:4 workloads in their own dtype, materialised operands", file=sys.stderr)
+        if w.nm != "2:4" or args.conv_implicit:
+            print("bench.py: --g-layout transposed runs 2:4 workloads (16-bit or --precision q8), materialised operands", file=sys.stderr)
             sys.exit(2)
         gT = g.t().contiguous()                 # outside the timed region: a producer would have written g^T
         del g
@@ -313,7 +313,7 @@ def main():
         conv = dict(x_full=x_full, margin=margin, shifts=shifts, T=Tp)
         del h
         g, h = g_pad, None
-    if q8 and (w.dtype != "bf16" or g.shape[0] % 32):
+    if q8 and (w.dtype != "bf16" or w.T % 32 if transposed else (w.dtype != "bf16" or g.shape[0] % 32)):
         print("bench.py: --precision q8 runs the bf16 workloads whose token count is a multiple of 32", file=sys.stderr)
         sys.exit(2)
     producer = None
@@ -388,6 +388,8 @@ def main():
         if q8:
             if w.nm == "1:2":
                 nm.mvue_prune_1of2_q8(b["g"], seed=seed, stream_id=0, scale=g_scale, vals8=b["vals"], meta32=b["meta"])
+            elif transposed:
+                nm.mvue_prune_2of4_q8_t(b["g"], seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=b["vals"], meta32=b["meta"])
             else:
                 nm.mvue_prune_2of4_q8(b["g"], seed=seed, stream_id=0, mode=1 if approx else 0, scale=g_scale, vals8=b["vals"], meta32=b["meta"])
         elif b["producer"]:
@@ -438,7 +440,7 @@ def main():
         unfused = {"what": "torch.mul(u, d) then the separate prune call (two kernels, g written and read back)",
                    "mul_ms": tm, "prune_ms": tp, "fused_ms": prune_ms, "speedup": (tm + tp) / prune_ms}
         del gtmp
-    tname = w.name + ("_producer" if producer else "_bf16x3" if x3 else "_q8_shifted" if q8 and conv else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
+    tname = w.name + ("_producer" if producer else "_bf16x3" if x3 else "_q8_shifted" if q8 and conv else "_q8_transposed" if q8 and transposed else "_q8" if q8 else "_shifted" if conv else "_transposed" if transposed else "")
     prune_gbps = prune_bytes / (prune_ms * 1e-3) / 1e9
     gemm_tflops = flops / (gemm_ms * 1e-3) / 1e12
     out = {
@@ -471,7 +473,7 @@ def main():
                                "between the 384x256 and the 256x256 tile kernel)" + (" over the six partial products stacked along the token axis, + split3_bf16_kernel" if x3 else ""),
                      "bound": "mfma", "achieved": gemm_tflops * (6.0 if x3 else 1.0),
                      "peak": gemm_peak, "unit": "TFLOP/s", "frac": gemm_tflops * (6.0 if x3 else 1.0) / gemm_peak,
-                     "traffic": read_traffic(w.name if transposed else tname, "gemm"),
+                     "traffic": read_traffic((w.name + ("_q8" if q8 else "")) if transposed else tname, "gemm"),
                      "note": ("six partial products: achieved = 6 x 2*T*O*I / time of the whole call (splits included), against the "
                               "sparse bf16 peak; gemm_TFLOPs_dense_equiv counts 2*T*O*I once (binary32-equivalent); " if x3 else "") +
                              "flops 2*T*O*I per call; time = HIP events around the call's kernels; " +
@@ -479,6 +481,7 @@ def main():
                               "dense-equivalent; peak = 2 x published dense " + ("fp8" if q8 else "bf16") +
                               " MFMA peak (4:2 sparse MFMA executes half the products)")},
         "roofline_prune": {"kernel": "prune_producer_kernel (g = u*d formed, written dense and pruned in one pass)" if producer else
+                           "prune_compress_q8_t_kernel" if q8 and transposed else
                            "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
                            "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,

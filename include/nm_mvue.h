@@ -279,6 +279,20 @@ int mvue_prune_1of2_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dty
                        uint8_t *vals8, uint32_t *meta32, void *hip_stream);
 
 /*
+ * The 8-bit prunes for a gradient stored transposed (gT [O x T], tokens contiguous, row stride ldt elements; see
+ * mvue_prune_2of4_t): same selection, scaling, rounding, random streams and block indices, so vals8 and meta32 equal
+ * what mvue_prune_2of4_q8 / mvue_prune_1of2_q8 write for the transposed tensor, bit for bit.  The scale: scale_rec
+ * (device, a record of nm_q8_scale, 16-byte aligned) when it is not NULL -- the kept values are multiplied by
+ * scale_rec[0] and `scale` is ignored --, else the host value `scale` (> 0, finite).  T a multiple of 32, O of 8.
+ */
+int mvue_prune_2of4_q8_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype,
+                         uint64_t seed, uint32_t stream_id, int mode, float scale, const float *scale_rec,
+                         uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+int mvue_prune_1of2_q8_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype,
+                         uint64_t seed, uint32_t stream_id, float scale, const float *scale_rec,
+                         uint8_t *vals8, uint32_t *meta32, void *hip_stream);
+
+/*
  * Update GEMM (eq. (3)) on the 8-bit operands:
  *     dW[O x I] = beta*dW + alpha * decompress(vals8, meta32)^T h8,   beta in {0, 1},
  * h8 [T x I] e4m3 with row stride ldh (bytes = elements), products exact and accumulation in binary32

@@ -80,6 +80,10 @@ def load():
     lib.mvue_prune_2of4_q8_ds.restype = i32
     lib.mvue_prune_1of2_q8_ds.argtypes = [vp, i64, i64, i64, i32, u64, u32, vp, vp, vp, vp]
     lib.mvue_prune_1of2_q8_ds.restype = i32
+    lib.mvue_prune_2of4_q8_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, i32, f32, vp, vp, vp, vp]
+    lib.mvue_prune_2of4_q8_t.restype = i32
+    lib.mvue_prune_1of2_q8_t.argtypes = [vp, i64, i64, i64, i32, u64, u32, f32, vp, vp, vp, vp]
+    lib.mvue_prune_1of2_q8_t.restype = i32
     lib.nm_update_gemm_q8_ds.argtypes = [vp, vp, vp, i64, vp, i64, i64, i64, i64, vp, vp, f32, vp, sz, vp]
     lib.nm_update_gemm_q8_ds.restype = i32
     lib.nm_update_gemm_q8_shifted_ds.argtypes = [vp, vp, vp, i64, i64, vp, i32, vp, i64, i64, i64, vp, vp, f32, vp, sz, vp]
@@ -363,6 +367,36 @@ def mvue_prune_1of2_q8(g: torch.Tensor, seed: int = 0, stream_id: int = 0, scale
     else:
         _check(lib.mvue_prune_1of2_q8(_ptr(g), T, O, ldg, _dtype_code(g), seed, stream_id, float(scale),
                                       _ptr(vals8), _ptr(meta32), _stream(g)))
+    return vals8, meta32
+
+
+def _prune_q8_transposed(gT: torch.Tensor, vals8, meta32, scale):
+    if not gT.is_cuda:
+        raise ValueError("gT must live on the GPU")
+    O, T = gT.shape
+    ldt = _rowmajor(gT, "gT")
+    if vals8 is None or meta32 is None:
+        vals8, meta32 = alloc_compressed_q8(T - T % 32, O, gT.device)
+    rec = scale if isinstance(scale, torch.Tensor) else None          # a scale record in device memory (nm_q8_scale)
+    return O, T, ldt, vals8, meta32, (1.0 if rec is not None else float(scale)), rec
+
+
+def mvue_prune_2of4_q8_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, mode: int = 0, scale=1.0, vals8=None, meta32=None):
+    """mvue_prune_2of4_q8 for a gradient stored transposed: gT is [O x T], tokens contiguous.  Returns (vals8, meta32), equal to
+    mvue_prune_2of4_q8(gT.t().contiguous(), ...) bit for bit."""
+    lib = load()
+    O, T, ldt, vals8, meta32, s, rec = _prune_q8_transposed(gT, vals8, meta32, scale)
+    _check(lib.mvue_prune_2of4_q8_t(_ptr(gT), T, O, ldt, _dtype_code(gT), seed, stream_id, mode, s, _ptr(rec), _ptr(vals8),
+                                    _ptr(meta32), _stream(gT)))
+    return vals8, meta32
+
+
+def mvue_prune_1of2_q8_t(gT: torch.Tensor, seed: int = 0, stream_id: int = 0, scale=1.0, vals8=None, meta32=None):
+    """mvue_prune_1of2_q8 for a gradient stored transposed (gT [O x T])."""
+    lib = load()
+    O, T, ldt, vals8, meta32, s, rec = _prune_q8_transposed(gT, vals8, meta32, scale)
+    _check(lib.mvue_prune_1of2_q8_t(_ptr(gT), T, O, ldt, _dtype_code(gT), seed, stream_id, s, _ptr(rec), _ptr(vals8), _ptr(meta32),
+                                    _stream(gT)))
     return vals8, meta32
 
 

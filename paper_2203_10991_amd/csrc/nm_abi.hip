@@ -400,6 +400,51 @@ static int prune_q8(const char *fn, int est, const void *g, int64_t T, int64_t O
                                             vals8, meta32, (hipStream_t)hip_stream));
 }
 
+static int prune_q8_transposed(const char *fn, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed,
+                               uint32_t stream_id, float scale, const float *scale_rec, uint8_t *vals8, uint32_t *meta32,
+                               void *hip_stream)
+{
+    if (dtype != NM_F32 && dtype != NM_BF16) return fail(NM_ERR_DTYPE, "%s: dtype %d is not NM_F32 (0) or NM_BF16 (1)", fn, dtype);
+    if (T < 0 || O < 0) return fail(NM_ERR_SHAPE, "%s: negative size T=%lld O=%lld", fn, (long long)T, (long long)O);
+    if (T % 32) return fail(NM_ERR_SHAPE, "%s: T=%lld is not a multiple of 32 (pad with zero tokens)", fn, (long long)T);
+    if (O % 8) return fail(NM_ERR_SHAPE, "%s: O=%lld is not a multiple of 8 (pad with zero rows)", fn, (long long)O);
+    if (too_big(O, T) || too_big(O, ldt)) return fail(NM_ERR_SHAPE, "%s: gT is larger than 2^58 elements", fn);
+    if (scale_rec) {
+        if (!aligned16(scale_rec)) return fail(NM_ERR_ALIGN, "%s: the scale record needs a 16-byte aligned base", fn);
+    } else if (!(scale > 0.0f) || !(scale < __builtin_inff())) return fail(NM_ERR_SHAPE, "%s: scale must be positive and finite", fn);
+    if (T == 0 || O == 0) { g_err[0] = 0; return NM_OK; }
+    if (!gT || !vals8 || !meta32) return fail(NM_ERR_NULL, "%s: gT, vals8 and meta32 must not be NULL", fn);
+    if (ldt < T) return fail(NM_ERR_SHAPE, "%s: row stride %lld of gT is smaller than T=%lld", fn, (long long)ldt, (long long)T);
+    const int64_t es = esize(dtype);
+    if (!aligned16(gT) || (ldt * es) % 16 || !aligned16(vals8) || !aligned16(meta32))
+        return fail(NM_ERR_ALIGN, "%s: gT (base and row stride), vals8 and meta32 need 16-byte alignment", fn);
+    Range rin = range_of(gT, ((O - 1) * ldt + T) * es, "gT");
+    Range rv = range_of(vals8, T / 2 * O, "vals8"), rm = range_of(meta32, T / 32 * O * 4, "meta32");
+    if (overlap(rin, rv) || overlap(rin, rm) || overlap(rv, rm)) return fail(NM_ERR_ALIAS, "%s: gT, vals8 and meta32 must not overlap", fn);
+    if (scale_rec) {
+        Range rs = range_of(scale_rec, 16, "scale record");
+        if (overlap(rs, rv) || overlap(rs, rm)) return fail(NM_ERR_ALIAS, "%s: the scale record must not overlap an output", fn);
+    }
+    return launched(fn, nm::launch_prune_q8_transposed(dtype, est, gT, T, O, ldt, seed, stream_id, scale_rec ? 1.0f : scale, scale_rec,
+                                                       vals8, meta32, (hipStream_t)hip_stream));
+}
+
+int mvue_prune_2of4_q8_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id, int mode,
+                         float scale, const float *scale_rec, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    if (mode != 0 && mode != 1)
+        return fail(NM_ERR_UNSUPPORTED, "mvue_prune_2of4_q8_t: unknown mode %d (0 = optimal MVUE, 1 = approx-MVUE)", mode);
+    return prune_q8_transposed("mvue_prune_2of4_q8_t", mode, gT, T, O, ldt, dtype, seed, stream_id, scale, scale_rec, vals8, meta32,
+                               hip_stream);
+}
+
+int mvue_prune_1of2_q8_t(const void *gT, int64_t T, int64_t O, int64_t ldt, int dtype, uint64_t seed, uint32_t stream_id, float scale,
+                         const float *scale_rec, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
+{
+    return prune_q8_transposed("mvue_prune_1of2_q8_t", 3, gT, T, O, ldt, dtype, seed, stream_id, scale, scale_rec, vals8, meta32,
+                               hip_stream);
+}
+
 int mvue_prune_2of4_q8(const void *g, int64_t T, int64_t O, int64_t ldg, int dtype, uint64_t seed, uint32_t stream_id,
                        int mode, float scale, uint8_t *vals8, uint32_t *meta32, void *hip_stream)
 {

@@ -72,6 +72,10 @@ hipError_t launch_splitk_reduce(const float *part, int slabs, float *dW, int64_t
 // dW = beta*dW + alpha * decompress(vals8, meta32)^T h8  (vals8 e5m2, h8 e4m3)
 hipError_t launch_prune_q8(int dt, int est, const void *g, int64_t T, int64_t O, int64_t ldg, uint64_t seed,
                            uint32_t stream_id, float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32, hipStream_t st);
+// ... of a gradient stored transposed (gT [O x T], tokens contiguous)
+hipError_t launch_prune_q8_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
+                                      uint32_t stream_id, float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32,
+                                      hipStream_t st);
 hipError_t launch_update_gemm_q8(const uint8_t *vals8, const uint32_t *meta32, const uint8_t *h8, int64_t ldh, float *dW,
                                  int64_t lddw, int64_t T, int64_t O, int64_t I, AlphaArg alpha, float beta, void *workspace,
                                  hipStream_t st);

@@ -763,6 +763,145 @@ hipError_t launch_prune_transposed(int dt, int est, const void *gT, int64_t T, i
 }
 
 // ------------------------------------------------------------------------------------
+// The 8-bit prune of a gradient stored TRANSPOSED (gT [O x T], tokens contiguous): selection, kept values, scaling and
+// stochastic rounding as in prune_compress_q8_kernel, with the same random streams and block indices, so the output
+// equals that kernel's on the transposed tensor bit for bit.  Same workgroup shape as prune_compress_t_kernel with
+// 32-token groups: a thread owns one (column, group), loads the group's 32 tokens as one contiguous piece (64 or 128
+// bytes), decides its eight quads (sixteen pairs), and the 16 codes and the index word go through LDS so that the
+// stores run along o.
+// ------------------------------------------------------------------------------------
+template <int DT, int EST>
+__global__ __launch_bounds__(256) void prune_compress_q8_t_kernel(
+    const void *__restrict__ gT_, int64_t n_groups, int64_t O, int64_t ldt, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    float scale, const float *__restrict__ scale_dev, uint8_t *__restrict__ vals8, uint32_t *__restrict__ meta32)
+{
+    if (scale_dev) scale = scale_dev[0];
+    constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
+    constexpr int VW = 32 * ESZ / 4;                       // 32-bit words of a group's 32 tokens: 16 (bf16) or 32 (fp32)
+    __shared__ uint32_t kept_s[16][16][5];                 // [group][column][word] (+1: no bank conflicts on the way in)
+    __shared__ uint32_t meta_s[16][16];
+    const int tid = threadIdx.x, oi = tid >> 4, gi = tid & 15;
+    const int64_t gblocks = (n_groups + 15) / 16;          // consecutive workgroups walk along the tokens of the same 16 columns
+    const int64_t ob = (int64_t)blockIdx.x / gblocks, gb = (int64_t)blockIdx.x % gblocks;
+    const int64_t o = ob * 16 + oi, G = gb * 16 + gi;
+    const bool live = o < O && G < n_groups;
+
+    uint32_t w[VW];
+#pragma unroll
+    for (int j = 0; j < VW; ++j) w[j] = 0;
+    if (live) {
+        const uint4 *src = (const uint4 *)((const char *)gT_ + (o * ldt + G * 32) * ESZ);
+#pragma unroll
+        for (int j = 0; j < VW / 4; ++j) { const uint4 v = src[j]; w[4 * j] = v.x; w[4 * j + 1] = v.y; w[4 * j + 2] = v.z; w[4 * j + 3] = v.w; }
+    }
+    auto elem_bits = [&](int t) -> uint32_t {             // token t of the group as binary32 bits
+        if constexpr (DT == NM_DT_F32) return w[t];
+        else return (t & 1) ? (w[t >> 1] & 0xffff0000u) : (w[t >> 1] << 16);
+    };
+    // Random words, shared as in prune_compress_t_kernel: a wave holds 4 columns x 16 groups; lane (a, gi) makes the
+    // calls of block rows a, a + 4, ... of group gi for the wave's four columns -- the selection words (last counter
+    // word 0, or 1 with two calls for approx-MVUE) and the rounding words (last counter word 2) -- and leaves them in LDS.
+    constexpr int RB = EST == 3 ? 16 : 8;                  // block rows of a group: 16 pair rows (1:2) or 8 quad rows
+    constexpr int SELW = EST == 1 ? 8 : 4;                 // selection words per block row of four columns
+    constexpr int WPC = SELW + 4;                          // + their four rounding words
+    __shared__ __attribute__((aligned(16))) uint32_t rnd_s[4][RB][16][WPC];      // [wave][block row][group][word]
+    {
+        const int wave = tid >> 6, a = oi & 3;
+#pragma unroll
+        for (int rb = 0; rb < RB / 4; ++rb) {
+            const int b = a + 4 * rb;
+            const uint64_t blk0 = (uint64_t)(G * RB + b) * (uint64_t)O + (uint64_t)(o - a);
+            uint32_t r4[4];
+#pragma unroll
+            for (int c = 0; c < SELW / 4; ++c) {
+                const uint64_t ctr = (blk0 >> (EST == 1 ? 1 : 2)) + c;
+                philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, EST == 1 ? 1u : 0u, key0, key1, r4);
+                *(uint4 *)&rnd_s[wave][b][gi][4 * c] = make_uint4(r4[0], r4[1], r4[2], r4[3]);
+            }
+            const uint64_t ctr = blk0 >> 2;
+            philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, 2u, key0, key1, r4);
+            *(uint4 *)&rnd_s[wave][b][gi][SELW] = make_uint4(r4[0], r4[1], r4[2], r4[3]);
+        }
+    }
+    __syncthreads();
+    uint32_t md = 0;
+    uint32_t kept[4] = {0u, 0u, 0u, 0u};
+    const int col = oi & 3;
+    static_for<8>([&](auto i_c) {                           // quad i of the group: tokens 4i .. 4i+3, codes 2i and 2i+1
+        constexpr int i = decltype(i_c)::value;
+        float v0, v1; uint32_t nib, r0, r1;                 // r0, r1: rounding bits of the two kept values, in the top half
+        if constexpr (EST == 3) {
+            const uint32_t *ra = rnd_s[tid >> 6][2 * i][gi], *rb = rnd_s[tid >> 6][2 * i + 1][gi];
+            uint32_t k0, k1;
+            select_1of2(__uint_as_float(elem_bits(4 * i)), __uint_as_float(elem_bits(4 * i + 1)), ra[col], k0, v0);
+            select_1of2(__uint_as_float(elem_bits(4 * i + 2)), __uint_as_float(elem_bits(4 * i + 3)), rb[col], k1, v1);
+            nib = k0 | ((2u | k1) << 2);
+            r0 = ra[SELW + col] << 16;                      // each pair block rounds with the low half of its own word
+            r1 = rb[SELW + col] << 16;
+        } else {
+            const uint32_t *rw = rnd_s[tid >> 6][i][gi];
+            if constexpr (EST == 1) {
+                const uint2 wab = *(const uint2 *)&rw[2 * col];
+                select_2of4_approx(__uint_as_float(elem_bits(4 * i)), __uint_as_float(elem_bits(4 * i + 1)),
+                                   __uint_as_float(elem_bits(4 * i + 2)), __uint_as_float(elem_bits(4 * i + 3)), wab.x, wab.y, v0, v1, nib);
+            } else {
+                uint4 e[4];                                 // one-element "rows": the element sits where column 0 of a row would
+#pragma unroll
+                for (int p = 0; p < 4; ++p) {
+                    const uint32_t b = elem_bits(4 * i + p);
+                    e[p] = make_uint4(DT == NM_DT_F32 ? b : (b >> 16), 0u, 0u, 0u);
+                }
+                select_2of4<DT>(Key<DT>::make(e[0], 0, 0), Key<DT>::make(e[1], 0, 1), Key<DT>::make(e[2], 0, 2), Key<DT>::make(e[3], 0, 3),
+                                rw[col], v0, v1, nib);
+            }
+            const uint32_t r = rw[SELW + col];
+            r0 = r << 16;
+            r1 = r & 0xffff0000u;
+        }
+        kept[i / 2] = sr_e5m2_into<2 * (i & 1)>(kept[i / 2], v0 * scale, r0);
+        kept[i / 2] = sr_e5m2_into<2 * (i & 1) + 1>(kept[i / 2], v1 * scale, r1);
+        md |= nib << (4 * i);
+    });
+#pragma unroll
+    for (int j = 0; j < 4; ++j) kept_s[gi][oi][j] = kept[j];
+    meta_s[gi][oi] = md;
+    __syncthreads();
+    // second half: thread (group gj, column oj) stores what thread (oj, gj) computed: 16 threads write one token group's run along o
+    const int gj = tid >> 4, oj = tid & 15;
+    const int64_t o2 = ob * 16 + oj, G2 = gb * 16 + gj;
+    if (o2 < O && G2 < n_groups) {
+        *(uint4 *)(vals8 + (G2 * O + o2) * 16) = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
+        meta32[G2 * O + o2] = meta_s[gj][oj];
+    }
+}
+
+template <int DT, int EST>
+static hipError_t launch_prune_q8_t_t(const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed, uint32_t stream_id, float scale,
+                                      const float *scale_dev, uint8_t *vals8, uint32_t *meta32, hipStream_t st)
+{
+    const int64_t groups = T / 32;
+    if (groups == 0 || O == 0) return hipSuccess;
+    const int64_t blocks = ((groups + 15) / 16) * ((O + 15) / 16);
+    if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
+    hipLaunchKernelGGL((prune_compress_q8_t_kernel<DT, EST>), dim3((unsigned)blocks), dim3(256), 0, st, gT, groups, O, ldt, (uint32_t)seed,
+                       (uint32_t)(seed >> 32), stream_id, scale, scale_dev, vals8, meta32);
+    return hipGetLastError();
+}
+
+hipError_t launch_prune_q8_transposed(int dt, int est, const void *gT, int64_t T, int64_t O, int64_t ldt, uint64_t seed,
+                                      uint32_t stream_id, float scale, const float *scale_dev, uint8_t *vals8, uint32_t *meta32,
+                                      hipStream_t st)
+{
+    // est: 0 optimal MVUE 2:4, 1 approx-MVUE 2:4, 3 MVUE 1:2
+#define NM_T8_CASE(DT_, EST_) \
+    if (dt == DT_ && est == EST_) return launch_prune_q8_t_t<DT_, EST_>(gT, T, O, ldt, seed, stream_id, scale, scale_dev, vals8, meta32, st)
+    NM_T8_CASE(NM_DT_F32, 0); NM_T8_CASE(NM_DT_F32, 1); NM_T8_CASE(NM_DT_F32, 3);
+    NM_T8_CASE(NM_DT_BF16, 0); NM_T8_CASE(NM_DT_BF16, 1); NM_T8_CASE(NM_DT_BF16, 3);
+#undef NM_T8_CASE
+    return hipErrorInvalidValue;
+}
+
+// ------------------------------------------------------------------------------------
 // nm_compress: dense n:m tensor -> group format.  Same thread tiling as above.
 // ------------------------------------------------------------------------------------
 template <int DT, int M>

@@ -28,6 +28,8 @@ hipError_t launch_prune_4of8_approx(int, const void *, int64_t, int64_t, int64_t
 hipError_t launch_compress(int, int, const void *, int64_t, int64_t, int64_t, void *, uint16_t *, int32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_prune_q8(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, float, const float *, uint8_t *, uint32_t *,
                            hipStream_t) { ++g_launches; return hipSuccess; }
+hipError_t launch_prune_q8_transposed(int, int, const void *, int64_t, int64_t, int64_t, uint64_t, uint32_t, float, const float *, uint8_t *,
+                                      uint32_t *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_q8_scale(int, const void *, int64_t, int64_t, int64_t, float, float *, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_cast_e4m3(int, const void *, int64_t, int64_t, int64_t, const float *, uint8_t *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
 hipError_t launch_rw_mix_probe(const void *, void *, int64_t, hipStream_t) { ++g_launches; return hipSuccess; }
@@ -90,6 +92,8 @@ int main()
         EXPECT(nm_compress(dense, T, O, O, dt, 2, 4, vals, m16, nullptr, nullptr), NM_OK);
         EXPECT(mvue_prune_2of4_q8(g, T, O, O, dt, 1, 2, 0, 0.5f, (uint8_t *)vals, m32, nullptr), NM_OK);
         EXPECT(mvue_prune_1of2_q8(g, T, O, O, dt, 1, 2, 0.5f, (uint8_t *)vals, m32, nullptr), NM_OK);
+        EXPECT(mvue_prune_2of4_q8_t(g, T, O, T, dt, 1, 2, 1, 0.5f, nullptr, (uint8_t *)vals, m32, nullptr), NM_OK);
+        EXPECT(mvue_prune_1of2_q8_t(g, T, O, T, dt, 1, 2, 0.5f, nullptr, (uint8_t *)vals, m32, nullptr), NM_OK);
         EXPECT(nm_update_gemm(vals, m16, h, I, dW, I, T, O, I, dt, 0.f, ws, wsb, nullptr), NM_OK);
         EXPECT(nm_update_gemm_static(vals, m16, h, I, dW, I, T, O, I, dt, 1.f, nullptr), NM_OK);
     }
@@ -117,6 +121,8 @@ int main()
     EXPECT(nm_cast_e4m3(h, T, I, I, NM_BF16, rec_h, (uint8_t *)x, I, nullptr), NM_OK);
     EXPECT(mvue_prune_2of4_q8_ds(g, T, O, O, NM_BF16, 1, 2, 0, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);
     EXPECT(mvue_prune_1of2_q8_ds(g, T, O, O, NM_BF16, 1, 2, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);
+    EXPECT(mvue_prune_2of4_q8_t(g, T, O, T, NM_BF16, 1, 2, 0, -1.f, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);     // the record wins
+    EXPECT(mvue_prune_1of2_q8_t(g, T, O, T, NM_BF16, 1, 2, 0.f, rec_g, (uint8_t *)vals, m32, nullptr), NM_OK);
     EXPECT(nm_update_gemm_q8_ds((const uint8_t *)vals, m32, (const uint8_t *)h, I, dW, I, T, O, I, rec_g, rec_h, 0.f, ws, wsb, nullptr), NM_OK);
     EXPECT(nm_update_gemm_q8_shifted_ds((const uint8_t *)vals, m32, (const uint8_t *)x0, cb, cb, shifts, 9, dW, 9 * cb, T, O, rec_g, rec_h, 0.f,
                                         ws, wsb_conv, nullptr), NM_OK);
@@ -166,6 +172,12 @@ int main()
     EXPECT(mvue_prune_2of4_t(g, T, O, T - 16, NM_BF16, 0, 0, 0, vals, m16, nullptr), NM_ERR_SHAPE);
     EXPECT(mvue_prune_2of4_q8(g, T + 16, O, O, NM_BF16, 0, 0, 0, 1.f, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
     EXPECT(mvue_prune_2of4_q8(g, T, O, O, NM_BF16, 0, 0, 0, -1.f, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_q8_t(g, T, O, T, NM_BF16, 0, 0, 0, -1.f, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_q8_t(g, T, O, T - 32, NM_BF16, 0, 0, 0, 1.f, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_q8_t(g, T + 16, O, T + 16, NM_BF16, 0, 0, 0, 1.f, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_q8_t(g, T, O, T, NM_BF16, 0, 0, 2, 1.f, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_UNSUPPORTED);
+    EXPECT(mvue_prune_1of2_q8_t(g, T, O, T, NM_BF16, 0, 0, 1.f, nullptr, nullptr, m32, nullptr), NM_ERR_NULL);
+    EXPECT(mvue_prune_1of2_q8_t(g, T, O, T, NM_BF16, 0, 0, 1.f, nullptr, (uint8_t *)g, m32, nullptr), NM_ERR_ALIAS);
     EXPECT(nm_update_gemm(vals, m16, h, I, dW, I, T, O, I, NM_BF16, 0.5f, ws, wsb, nullptr), NM_ERR_UNSUPPORTED);
     EXPECT(nm_update_gemm(vals, m16, h, I, dW, I, T, O, I, NM_BF16, 0.f, ws, wsb - 1, nullptr), NM_ERR_WORKSPACE);
     EXPECT(nm_update_gemm(vals, m16, h, I, dW, I, T, O, I, NM_BF16, 0.f, nullptr, 0, nullptr), NM_ERR_WORKSPACE);
@@ -188,6 +200,7 @@ int main()
     EXPECT(mvue_prune_4of8_approx(g, huge, huge, huge, NM_F32, 0, 0, vals, m32, dense, huge, nullptr), NM_ERR_SHAPE);
     EXPECT(mvue_prune_2of4_t(g, huge, O, huge, NM_BF16, 0, 0, 0, vals, m16, nullptr), NM_ERR_SHAPE);
     EXPECT(mvue_prune_2of4_q8(g, huge, huge, huge, NM_BF16, 0, 0, 0, 1.f, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
+    EXPECT(mvue_prune_2of4_q8_t(g, huge, huge, huge, NM_BF16, 0, 0, 0, 1.f, nullptr, (uint8_t *)vals, m32, nullptr), NM_ERR_SHAPE);
     EXPECT(nm_compress(dense, huge, huge, huge, NM_F32, 2, 4, vals, m16, nullptr, nullptr), NM_ERR_SHAPE);
     EXPECT(nm_update_gemm(vals, m16, h, I, dW, I, huge, O, I, NM_BF16, 0.f, ws, wsb, nullptr), NM_ERR_SHAPE);
     EXPECT(nm_update_gemm(vals, m16, h, I, dW, huge, T, O, I, NM_BF16, 0.f, ws, wsb, nullptr), NM_ERR_SHAPE);

@@ -29,7 +29,7 @@ def declared_functions():
 def test_every_declared_symbol_is_exported(lib):
     names = declared_functions()
     assert set(names) >= {"mvue_prune_1of2", "mvue_prune_2of4", "nm_compress", "nm_update_gemm",
-                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of2_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "mvue_prune_1of2_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
+                          "nm_update_gemm_workspace", "nm_last_error", "nm_version", "mvue_prune_2of4_q8", "mvue_prune_1of2_q8", "mvue_prune_1of4", "mvue_prune_2of4_t", "mvue_prune_1of2_t", "mvue_prune_2of4_q8_t", "mvue_prune_1of2_q8_t", "nm_update_gemm_shifted", "nm_update_gemm_shifted_workspace", "nm_update_gemm_q8_shifted",
                           "nm_update_gemm_q8_shifted_workspace",
                           "nm_update_gemm_q8", "nm_update_gemm_q8_workspace"}
     for n in names:

@@ -1,6 +1,7 @@
 """GPU parity of mvue_prune_2of4_t and mvue_prune_1of2_t (gradient stored transposed, tokens contiguous) through the C ABI:
 vals and meta equal the CPU oracle's prune of the transposed tensor bit for bit, and so equal what
-mvue_prune_2of4 writes for it; the compressed operand then feeds the same update GEMM."""
+mvue_prune_2of4 writes for it; the compressed operand then feeds the same update GEMM.  The same for the 8-bit
+prunes (mvue_prune_2of4_q8_t, mvue_prune_1of2_q8_t) against the oracle's 8-bit prune of the transposed tensor."""
 import numpy as np
 import pytest
 import torch
@@ -114,3 +115,68 @@ def test_transposed_prune_empty_and_errors(nm):
         nm.mvue_prune_2of4_t(torch.zeros((12, 32), dtype=torch.bfloat16, device=DEV))    # O not a multiple of 8
     with pytest.raises(nm.NmError):
         nm.mvue_prune_2of4_t(torch.zeros((8, 32), dtype=torch.bfloat16, device=DEV), mode=2)
+
+
+Q8_SHAPES = [(32, 8), (32 * 19, 8 * 29), (32 * 3, 8 * 64 + 8), (32 * 17, 16), (32 * 33, 1024), (32 * 70, 8 * 3)]
+
+
+def _fit_scale(g):
+    f = g if g.dtype == np.float32 else synth.bf16_to_f32(g)
+    return float(2.0 ** np.floor(np.log2(57344.0 / (4.0 * max(float(np.abs(f).max()), 1e-30)))))
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("mode", [0, 1])
+@pytest.mark.parametrize("shape", Q8_SHAPES)
+def test_transposed_q8_prune_bit_exact(nm, oracle, dtype, mode, shape):
+    T, O = shape
+    print(f"case q8 dtype={dtype} mode={mode} T={T} O={O}", flush=True)
+    w = synth.Workload("t", T, O, 16, dtype, "2:4", 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O + 3)
+    scale = _fit_scale(g)
+    seed, stream = 0x91 + (7 << 40), 6
+    ov, om = oracle.prune_2of4_q8(g, seed=seed, stream_id=stream, mode=mode, scale=scale)
+    v, m = nm.mvue_prune_2of4_q8_t(to_dev(np.ascontiguousarray(g.T)), seed=seed, stream_id=stream, mode=mode, scale=scale)
+    torch.cuda.synchronize()
+    hv, hm = v.cpu().numpy(), m.cpu().numpy().view(np.uint32)
+    assert first_mismatch(hm, om) is None, ("meta32", first_mismatch(hm, om))
+    assert first_mismatch(hv, ov) is None, ("vals8", first_mismatch(hv, ov))
+    # the token-major entry point on the same tensor, and the scale as a device record
+    v2, m2 = nm.mvue_prune_2of4_q8(to_dev(g), seed=seed, stream_id=stream, mode=mode, scale=scale)
+    assert torch.equal(m2, m) and torch.equal(v2, v)
+    rec = torch.tensor([scale, 1.0 / scale, 0.0, 0.0], dtype=torch.float32, device=DEV)
+    v3, m3 = nm.mvue_prune_2of4_q8_t(to_dev(np.ascontiguousarray(g.T)), seed=seed, stream_id=stream, mode=mode, scale=rec)
+    assert torch.equal(m3, m) and torch.equal(v3, v)
+
+
+@pytest.mark.parametrize("dtype", ["f32", "bf16"])
+@pytest.mark.parametrize("shape", Q8_SHAPES)
+def test_transposed_q8_prune_1of2_bit_exact(nm, oracle, dtype, shape):
+    T, O = shape
+    print(f"case q8 1:2 dtype={dtype} T={T} O={O}", flush=True)
+    w = synth.Workload("t", T, O, 16, dtype, "1:2", 0.0, 2.5, 0.3)
+    g = synth.make_g(w, seed=T + O + 4)
+    scale = 2.0 * _fit_scale(g)
+    seed, stream = 0x93 + (9 << 40), 1
+    ov, om = oracle.prune_1of2_q8(g, seed=seed, stream_id=stream, scale=scale)
+    v, m = nm.mvue_prune_1of2_q8_t(to_dev(np.ascontiguousarray(g.T)), seed=seed, stream_id=stream, scale=scale)
+    torch.cuda.synchronize()
+    hv, hm = v.cpu().numpy(), m.cpu().numpy().view(np.uint32)
+    assert first_mismatch(hm, om) is None, ("meta32", first_mismatch(hm, om))
+    assert first_mismatch(hv, ov) is None, ("vals8", first_mismatch(hv, ov))
+    v2, m2 = nm.mvue_prune_1of2_q8(to_dev(g), seed=seed, stream_id=stream, scale=scale)
+    assert torch.equal(m2, m) and torch.equal(v2, v)
+
+
+def test_transposed_q8_prune_row_stride(nm, oracle):
+    """row stride larger than T; saturating scale"""
+    T, O = 32 * 5, 24
+    w = synth.Workload("t", T, O, 16, "bf16", "2:4", 0.0, 3.0, 0.5)
+    g = synth.make_g(w, seed=9)
+    wide = torch.zeros((O, T + 40), dtype=torch.bfloat16, device=DEV)
+    wide[:, :T] = to_dev(np.ascontiguousarray(g.T))
+    for scale in (_fit_scale(g), 64.0 * _fit_scale(g)):
+        ov, om = oracle.prune_2of4_q8(g, seed=4, stream_id=2, mode=0, scale=scale)
+        v, m = nm.mvue_prune_2of4_q8_t(wide[:, :T], seed=4, stream_id=2, scale=scale)
+        torch.cuda.synchronize()
+        assert np.array_equal(m.cpu().numpy().view(np.uint32), om) and np.array_equal(v.cpu().numpy(), ov)
