@@ -1,7 +1,7 @@
 """GPU parity at the benchmark's full size (large decoder-MLP workload, MVUE 2:4, bf16), in the launch
 configuration bench.py times.  The tensors are drawn on the device, copied to the host, and the CPU
 oracle computes its own prune output from them:
-  * vals / meta of the whole tensor: bit for bit;
+  * vals / meta of the whole tensor: bit for bit (token-major and transposed layout, 16-bit and 8-bit);
   * dW: 4096 sampled entries as fp64 dot products over all tokens, one full 256x256 output tile, and a
     Freivalds identity  dW x  ==  theta(g)^T (h x)  for random x (covers every entry).
 """
@@ -41,6 +41,20 @@ def case(oracle):
 def test_full_tensor_masks_and_values_bit_exact(case):
     assert np.array_equal(to_host(case["meta"]), case["om"])
     assert np.array_equal(to_host(case["vals"]), case["ov"])
+
+
+def test_full_tensor_transposed_layout_bit_exact(case):
+    """mvue_prune_2of4_t on g^T of the full-size tensor: the whole compressed output equals the oracle's."""
+    import paper_2203_10991_amd as nm
+    w = case["w"]
+    g, _ = synth.make_device(w, seed=0, device=DEV)            # the same tensor as the fixture's (seeded generator)
+    gT = g.t().contiguous()
+    del g
+    vals, meta = nm.mvue_prune_2of4_t(gT, seed=0, stream_id=0)
+    torch.cuda.synchronize()
+    del gT
+    assert np.array_equal(to_host(meta), case["om"])
+    assert np.array_equal(to_host(vals), case["ov"])
 
 
 def test_full_tensor_approx_mvue_bit_exact(case, oracle):
@@ -127,6 +141,15 @@ def test_full_size_q8_path(case, oracle):
     del g_host
     assert np.array_equal(m32.cpu().numpy().view(np.uint32), om)
     assert np.array_equal(v8.cpu().numpy(), ov)
+    # the transposed-layout 8-bit prune of the same tensor, in the launch configuration bench.py times
+    g, _ = synth.make_device(w, seed=0, device=DEV)
+    gT = g.t().contiguous()
+    del g
+    v8t, m32t = nm.mvue_prune_2of4_q8_t(gT, seed=3, stream_id=1, mode=0, scale=scale)
+    torch.cuda.synchronize()
+    del gT
+    assert torch.equal(m32t, m32) and torch.equal(v8t, v8)
+    del v8t, m32t
     h8_host = h8.cpu().numpy()
     rng = np.random.default_rng(2)
     oi = np.stack([rng.integers(0, w.O, size=2048), rng.integers(0, w.I, size=2048)], axis=1)
