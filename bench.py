@@ -483,14 +483,16 @@ def main():
         "roofline_prune": {"kernel": "prune_producer_kernel (g = u*d formed, written dense and pruned in one pass)" if producer else
                            "prune_compress_q8_t_kernel" if q8 and transposed else
                            "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
-                           "prune_compress_bf16_2of4_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_kernel", "bound": "hbm", "achieved": prune_gbps,
+                           "prune_compress_bf16_2of4_stream_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else
+                           "prune_compress_kernel" if (w.dtype == "bf16" and w.nm == "1:2") else "prune_compress_stream_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(tname, "prune"),
                            "note": f"algorithmic bytes {prune_bytes} per launch: " + ("read u and d, write g, " if producer else "read g, ") +
                                    "write T/2 values and T/16 index words per column; "
-                                   "the kernel's vector ALU work takes as long as its memory traffic and the two overlap to within 10 % ("
-                                   "profiles/sq_counters_prune_c5_decoder_mlp_2of4.txt); the same loads and stores without arithmetic "
-                                   "reach 5.6 TB/s = 0.70 of the HBM peak on this device"},
+                                   "the kernel's vector ALU work takes as long as its memory traffic ("
+                                   "profiles/sq_counters_prune_c5_decoder_mlp_2of4.txt); streaming (non-temporal) loads and stores; the same "
+                                   "read:write mix without arithmetic reaches 5.8-5.9 TB/s = 0.73 of the HBM peak on this device "
+                                   "(same_mix_stream_GBps_measured is this run's figure)"},
     }
     # Sustained shader clock and board power while the GEMM runs (best effort, driver's management interface):
     # a queue of back-to-back launches is sampled from the host.  MFMA-heavy kernels run below the 2.4 GHz the

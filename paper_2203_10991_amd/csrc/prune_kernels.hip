@@ -275,7 +275,20 @@ __device__ __forceinline__ uint4 producer_row(const uint4 &u, const uint4 &d)
 
 // HI0: the caller guarantees that every Philox call index of the launch is below 2^32 (the launcher checks the
 // tensor's size): counter words 1-3 are then wave-uniform and the generator's first rounds run partly on the scalar unit.
-template <int DT, int M, int EST, bool DENSE, bool PROD = false, bool HI0 = false>
+// Streaming (non-temporal) forms of a 16-byte load and store
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+__device__ __forceinline__ uint4 load_stream(const void *p)
+{
+    const u32x4_t t = __builtin_nontemporal_load((const u32x4_t *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ void store_stream(void *p, const uint4 &v)
+{
+    const u32x4_t t = {v.x, v.y, v.z, v.w};
+    __builtin_nontemporal_store(t, (u32x4_t *)p);
+}
+
+template <int DT, int M, int EST, bool DENSE, bool PROD = false, bool HI0 = false, bool NT = false>
 __device__ __forceinline__ void prune_compress_body(
     const void *__restrict__ g_, int64_t n_groups, int64_t O, int64_t ldg,
     uint32_t key0, uint32_t key1, uint32_t stream_id,
@@ -286,7 +299,7 @@ __device__ __forceinline__ void prune_compress_body(
     constexpr int ESZ = DT == NM_DT_F32 ? 4 : 2;
     const int64_t ncg = O / VEC;
     const int64_t n = (int64_t)blockIdx.x * 256 + threadIdx.x;
-    if (n >= n_groups * ncg) return;
+    if (n >= n_groups * ncg) return;                 // (NT: the launcher has checked that the thread count is a multiple of 64: whole waves leave)
     const int64_t G = n / ncg;
     const int64_t col0 = (n - G * ncg) * VEC;
 
@@ -304,10 +317,16 @@ __device__ __forceinline__ void prune_compress_body(
     auto fetch_rows = [&](const char *base, const char *dbase, int first) {
 #pragma unroll
         for (int r = first; r < first + 8; ++r) {
-            rows[r] = *(const uint4 *)(base + (int64_t)r * ldg * ESZ);
+            if constexpr (NT) rows[r] = load_stream(base + (int64_t)r * ldg * ESZ);
+            else rows[r] = *(const uint4 *)(base + (int64_t)r * ldg * ESZ);
             if constexpr (PROD) {
-                rows[r] = producer_row<DT>(rows[r], *(const uint4 *)(dbase + (int64_t)r * pa.ldd * ESZ));
-                *(uint4 *)(gop + (int64_t)r * pa.ldgo * ESZ) = rows[r];
+                if constexpr (NT) {
+                    rows[r] = producer_row<DT>(rows[r], load_stream(dbase + (int64_t)r * pa.ldd * ESZ));
+                    store_stream(gop + (int64_t)r * pa.ldgo * ESZ, rows[r]);
+                } else {
+                    rows[r] = producer_row<DT>(rows[r], *(const uint4 *)(dbase + (int64_t)r * pa.ldd * ESZ));
+                    *(uint4 *)(gop + (int64_t)r * pa.ldgo * ESZ) = rows[r];
+                }
             }
         }
     };
@@ -332,6 +351,7 @@ __device__ __forceinline__ void prune_compress_body(
     constexpr int WPB = EST == 1 ? 2 : 1;            // words per block
     constexpr int CTR_SHIFT = EST == 1 ? 1 : 2;
     constexpr uint32_t DOMAIN = EST == 1 ? 1u : 0u;
+    [[maybe_unused]] const uint32_t ctr0 = (uint32_t)(((uint64_t)(G * BLOCK_ROWS) * (uint64_t)O + (uint64_t)col0) >> CTR_SHIFT);   // call index of block row 0
 #pragma unroll
     for (int b = 0; b < BLOCK_ROWS; ++b) {
         if (b == 1) {
@@ -346,7 +366,8 @@ __device__ __forceinline__ void prune_compress_body(
             for (int q = 0; q < VEC * WPB / 4; ++q) {
                 const uint64_t ctr = (blk0 >> CTR_SHIFT) + q;
                 uint32_t w4[4];
-                if constexpr (HI0) philox4x32_10_uniform_c123((uint32_t)ctr, 0u, stream_id, DOMAIN, key0, key1, w4);
+                // HI0: the call index fits 32 bits, and block row b adds b * O (a multiple of 8) to the block index
+                if constexpr (HI0) philox4x32_10_uniform_c123(ctr0 + (uint32_t)b * (uint32_t)(O >> CTR_SHIFT) + (uint32_t)q, 0u, stream_id, DOMAIN, key0, key1, w4);
                 else philox4x32_10((uint32_t)ctr, (uint32_t)(ctr >> 32), stream_id, DOMAIN, key0, key1, w4);
 #pragma unroll
                 for (int j = 0; j < 4; ++j) words[4 * q + j] = w4[j];
@@ -385,23 +406,57 @@ __device__ __forceinline__ void prune_compress_body(
     }
 
     // ---- kept values: 8 per column, VEC columns contiguous = 128 bytes per thread
-    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;
+    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;            // = vals_ + 128 n: a wave's 64 threads own 8 KB in a row
+    [[maybe_unused]] uint16_t *mp_late = nullptr;
+    // Streaming stores want whole lines per instruction: the wave's 8 KB go through its own 8 KB of LDS, written as
+    // each thread holds them (eight 16-byte pieces at a stride of 128 bytes; piece c of lane l at slot 8l + (c ^ l%8),
+    // which spreads the lanes over the banks) and read back so that store k covers bytes [1024 k, 1024 k + 1024).
+    // Only a full wave does this (the last wave of the launch may have lost lanes at the top).
+    if constexpr (NT) {
+        __shared__ __attribute__((aligned(1024))) char xs[4 * 8192];
+        uint32_t tid = threadIdx.x;
+        asm volatile("" : "+v"(tid) : "v"(kept[VEC - 1][KW - 1]));       // (the addresses below are formed here, after the last block, not carried through the kernel)
+        const uint32_t lane = tid & 63u, wave_lds = (tid >> 6) * 8192;
+        const int64_t n_late = (int64_t)blockIdx.x * 256 + tid;          // = n
+        // byte address of piece p of this lane: 128 lane + 16 (p ^ lane%8) = (128 lane + 16 (lane%8)) ^ 16 p
+        const uint32_t wr = wave_lds + lane * 128 + (lane & 7) * 16;
+#pragma unroll
+        for (int c = 0; c < VEC; ++c)
+#pragma unroll
+            for (int j = 0; j < KW / 4; ++j) {
+                const int piece = c * (KW / 4) + j;
+                *(uint4 *)(xs + (wr ^ (uint32_t)(piece * 16))) = make_uint4(kept[c][4 * j], kept[c][4 * j + 1], kept[c][4 * j + 2], kept[c][4 * j + 3]);
+            }
+        __builtin_amdgcn_wave_barrier();
+        // store k, lane l: piece l%8 of the wave's thread 8k + l/8, which sits at slot 8 (8k + l/8) + (l%8 ^ l/8)
+        char *wave_base = (char *)vals_ + (n_late - lane) * 128;
+        mp_late = meta_ + n_late * VEC;                                   // (G O + col0 = n VEC)
+        const uint32_t rd = wave_lds + (8 * (lane >> 3) + ((lane & 7) ^ (lane >> 3))) * 16;
+#pragma unroll
+        for (int k = 0; k < 8; ++k) store_stream(wave_base + (1024 * k + 16 * lane), *(const uint4 *)(xs + rd + 1024 * k));
+    } else {
 #pragma unroll
     for (int c = 0; c < VEC; ++c)
 #pragma unroll
         for (int j = 0; j < KW / 4; ++j)
             ((uint4 *)vp)[c * (KW / 4) + j] = make_uint4(kept[c][4 * j], kept[c][4 * j + 1], kept[c][4 * j + 2], kept[c][4 * j + 3]);
+    }
     // ---- index words
-    uint16_t *mp = meta_ + (G * O + col0);
+    uint16_t *mp = NT ? mp_late : meta_ + (G * O + col0);
     if (VEC == 8) {
         uint4 o;
         o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
         o.z = md[4 % VEC] | (md[5 % VEC] << 16); o.w = md[6 % VEC] | (md[7 % VEC] << 16);
-        *(uint4 *)mp = o;
+        if constexpr (NT) store_stream(mp, o);
+        else *(uint4 *)mp = o;
     } else {
         uint2 o;
         o.x = md[0] | (md[1] << 16); o.y = md[2] | (md[3] << 16);
-        *(uint2 *)mp = o;
+        if constexpr (NT) {
+            typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+            const u32x2_t t = {o.x, o.y};
+            __builtin_nontemporal_store(t, (u32x2_t *)mp);
+        } else *(uint2 *)mp = o;
     }
 
     // ---- optional dense theta(g)
@@ -437,12 +492,21 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 {
     prune_compress_body<DT, M, EST, DENSE>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, dense, ldd);
 }
+// The streaming form (no dense output): its 32 KB of LDS let five workgroups onto a CU, so five waves per SIMD is
+// what the registers are budgeted for (four for the instances that need more than 96).
 template <int DT, int M, int EST>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DT == NM_DT_BF16 && (EST == 1 || (M == 2 && EST == 0))) ? 4 : 5, 5))) void prune_compress_stream_kernel(
+    const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals, uint16_t *__restrict__ meta)
+{
+    prune_compress_body<DT, M, EST, false, false, false, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
+}
+template <int DT, int M, int EST, bool NT>
 __global__ __launch_bounds__(256) void prune_producer_kernel(
     const void *__restrict__ u, int64_t n_groups, int64_t O, int64_t ldu, uint32_t key0, uint32_t key1, uint32_t stream_id,
     void *__restrict__ vals, uint16_t *__restrict__ meta, ProdArg pa)
 {
-    prune_compress_body<DT, M, EST, false, true>(u, n_groups, O, ldu, key0, key1, stream_id, vals, meta, nullptr, 0, pa);
+    prune_compress_body<DT, M, EST, false, true, false, NT>(u, n_groups, O, ldu, key0, key1, stream_id, vals, meta, nullptr, 0, pa);
 }
 // The bf16 optimal-2:4 kernel without the dense output needs 98 registers as the compiler would have it, two more
 // than let a fifth wave onto each SIMD; asked for five waves it fits 96 without spilling.
@@ -451,6 +515,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) voi
     void *__restrict__ vals, uint16_t *__restrict__ meta)
 {
     prune_compress_body<NM_DT_BF16, 4, 0, false, false, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
+}
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(5, 5))) void prune_compress_bf16_2of4_stream_kernel(
+    const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
+    void *__restrict__ vals, uint16_t *__restrict__ meta)
+{
+    prune_compress_body<NM_DT_BF16, 4, 0, false, false, true, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
 }
 
 // ------------------------------------------------------------------------------------
@@ -728,11 +798,10 @@ __global__ __launch_bounds__(256) void prune_compress_t_kernel(
     const int64_t o2 = ob * 16 + oj, G2 = gb * 16 + gj;
     if (o2 < O && G2 < n_groups) {
         uint32_t *dst = (uint32_t *)((char *)vals_ + ((G2 * O + o2) * 8) * ESZ);
-        if constexpr (KW == 4) *(uint4 *)dst = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
-        else {
-            ((uint4 *)dst)[0] = make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]);
-            ((uint4 *)dst)[1] = make_uint4(kept_s[gj][oj][4], kept_s[gj][oj][5], kept_s[gj][oj][6], kept_s[gj][oj][7]);
-        }
+        // streaming stores (16 threads write whole lines; measured 1.5 % faster than plain ones; streaming LOADS of the
+        // 32- or 64-byte pieces a thread reads measured no faster)
+        store_stream(dst, make_uint4(kept_s[gj][oj][0], kept_s[gj][oj][1], kept_s[gj][oj][2], kept_s[gj][oj][3]));
+        if constexpr (KW == 8) store_stream(dst + 4, make_uint4(kept_s[gj][oj][4], kept_s[gj][oj][5], kept_s[gj][oj][6], kept_s[gj][oj][7]));
         meta_[G2 * O + o2] = meta_s[gj][oj];
     }
 }
@@ -1000,8 +1069,17 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     if (dense)
         hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
-    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34))     // call indices (block / 4) below 2^32
+    // The streaming kernels store through whole waves: they take the launches whose thread count is a multiple of 64.
+    // (MVUE 1:2 on bf16 is bound by its sixteen generator calls per thread, gains nothing from them and needs more
+    // registers in that form: it stays on the plain kernel.)
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34) && threads % 64 == 0)     // call indices (block / 4) below 2^32
+        hipLaunchKernelGGL(prune_compress_bf16_2of4_stream_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34))
         hipLaunchKernelGGL(prune_compress_bf16_2of4_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
+                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
+    else if (threads % 64 == 0 && !(DT == NM_DT_BF16 && M == 2 && EST == 0))
+        hipLaunchKernelGGL((prune_compress_stream_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st,
                            g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
     else
         hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, false>), dim3((unsigned)blocks), dim3(256), 0, st,
@@ -1018,9 +1096,16 @@ hipError_t launch_prune_producer(int dt, int m, int est, const void *u, int64_t 
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
     const ProdArg pa{d, ldd, gout, ldgo};
+    // whole waves only on the streaming form (its stores go through the whole wave)
 #define NM_PROD(DT, M, EST)                                                                                             \
-    hipLaunchKernelGGL((prune_producer_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st, u, groups, O, ldu,   \
-                       (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, pa)
+    do {                                                                                                                \
+        if (threads % 64 == 0)                                                                                          \
+            hipLaunchKernelGGL((prune_producer_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st, u, groups, O, ldu,  \
+                               (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, pa);                      \
+        else                                                                                                            \
+            hipLaunchKernelGGL((prune_producer_kernel<DT, M, EST, false>), dim3((unsigned)blocks), dim3(256), 0, st, u, groups, O, ldu, \
+                               (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, pa);                      \
+    } while (0)
     if (dt == NM_DT_F32) { if (m == 2) NM_PROD(NM_DT_F32, 2, 0); else if (est == 1) NM_PROD(NM_DT_F32, 4, 1); else NM_PROD(NM_DT_F32, 4, 0); }
     else { if (m == 2) NM_PROD(NM_DT_BF16, 2, 0); else if (est == 1) NM_PROD(NM_DT_BF16, 4, 1); else NM_PROD(NM_DT_BF16, 4, 0); }
 #undef NM_PROD
