@@ -277,9 +277,17 @@ __device__ __forceinline__ uint4 producer_row(const uint4 &u, const uint4 &d)
 // tensor's size): counter words 1-3 are then wave-uniform and the generator's first rounds run partly on the scalar unit.
 // Streaming (non-temporal) forms of a 16-byte load and store
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+// (the pointers are to global memory; said explicitly, because an address that went through an opaque asm statement
+// would otherwise be loaded from with the generic form, which counts as an LDS operation too)
+#define NM_GLOBAL __attribute__((address_space(1)))
 __device__ __forceinline__ uint4 load_stream(const void *p)
 {
-    const u32x4_t t = __builtin_nontemporal_load((const u32x4_t *)p);
+    const u32x4_t t = __builtin_nontemporal_load((const NM_GLOBAL u32x4_t *)p);
+    return make_uint4(t.x, t.y, t.z, t.w);
+}
+__device__ __forceinline__ uint4 load_global(const void *p)
+{
+    const u32x4_t t = *(const NM_GLOBAL u32x4_t *)p;
     return make_uint4(t.x, t.y, t.z, t.w);
 }
 __device__ __forceinline__ void store_stream(void *p, const uint4 &v)
@@ -318,13 +326,13 @@ __device__ __forceinline__ void prune_compress_body(
 #pragma unroll
         for (int r = first; r < first + 8; ++r) {
             if constexpr (NT) rows[r] = load_stream(base + (int64_t)r * ldg * ESZ);
-            else rows[r] = *(const uint4 *)(base + (int64_t)r * ldg * ESZ);
+            else rows[r] = load_global(base + (int64_t)r * ldg * ESZ);
             if constexpr (PROD) {
                 if constexpr (NT) {
                     rows[r] = producer_row<DT>(rows[r], load_stream(dbase + (int64_t)r * pa.ldd * ESZ));
                     store_stream(gop + (int64_t)r * pa.ldgo * ESZ, rows[r]);
                 } else {
-                    rows[r] = producer_row<DT>(rows[r], *(const uint4 *)(dbase + (int64_t)r * pa.ldd * ESZ));
+                    rows[r] = producer_row<DT>(rows[r], load_global(dbase + (int64_t)r * pa.ldd * ESZ));
                     *(uint4 *)(gop + (int64_t)r * pa.ldgo * ESZ) = rows[r];
                 }
             }
@@ -569,7 +577,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
     // as its quads are decided, through an address the compiler cannot see through (keeps the loads where they are)
     uint4 rows[16];
 #pragma unroll
-    for (int r = 0; r < 8; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ldg * ESZ);
+    for (int r = 0; r < 8; ++r) rows[r] = load_global(gp + (int64_t)r * ldg * ESZ);
 
     uint32_t kept[VEC][4];        // 16 e5m2 codes per column
     uint32_t md[VEC];
@@ -583,7 +591,7 @@ __global__ __launch_bounds__(256) void prune_compress_q8_kernel(
             const char *gp2 = gp;
             asm volatile("" : "+v"(gp2));
 #pragma unroll
-            for (int r = 0; r < 8; ++r) rows[(first + r) % 16] = *(const uint4 *)(gp2 + (int64_t)(first + r) * ldg * ESZ);
+            for (int r = 0; r < 8; ++r) rows[(first + r) % 16] = load_global(gp2 + (int64_t)(first + r) * ldg * ESZ);
         }
         constexpr int R0 = (4 * b) % 16;
         if constexpr (EST == 3) {
