@@ -483,8 +483,7 @@ def main():
         "roofline_prune": {"kernel": "prune_producer_kernel (g = u*d formed, written dense and pruned in one pass)" if producer else
                            "prune_compress_q8_t_kernel" if q8 and transposed else
                            "prune_compress_q8_kernel" if q8 else "prune_compress_t_kernel" if transposed else
-                           "prune_compress_bf16_2of4_stream_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else
-                           "prune_compress_kernel" if (w.dtype == "bf16" and w.nm == "1:2") else "prune_compress_stream_kernel", "bound": "hbm", "achieved": prune_gbps,
+                           "prune_compress_bf16_2of4_stream_kernel" if (w.dtype == "bf16" and w.nm == "2:4" and not approx) else "prune_compress_stream_kernel", "bound": "hbm", "achieved": prune_gbps,
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": prune_gbps / HBM_PEAK_GBPS,
                            "traffic": read_traffic(tname, "prune"),
                            "note": f"algorithmic bytes {prune_bytes} per launch: " + ("read u and d, write g, " if producer else "read g, ") +

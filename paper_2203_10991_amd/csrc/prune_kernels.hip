@@ -502,12 +502,13 @@ __global__ __launch_bounds__(256) void prune_compress_kernel(
 }
 // The streaming form (no dense output): its 32 KB of LDS let five workgroups onto a CU, so five waves per SIMD is
 // what the registers are budgeted for (four for the instances that need more than 96).
-template <int DT, int M, int EST>
+// HI0: every Philox call index of the launch is below 2^32, which the launcher has checked.
+template <int DT, int M, int EST, bool HI0>
 __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((DT == NM_DT_BF16 && (EST == 1 || (M == 2 && EST == 0))) ? 4 : 5, 5))) void prune_compress_stream_kernel(
     const void *__restrict__ g, int64_t n_groups, int64_t O, int64_t ldg, uint32_t key0, uint32_t key1, uint32_t stream_id,
     void *__restrict__ vals, uint16_t *__restrict__ meta)
 {
-    prune_compress_body<DT, M, EST, false, false, false, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
+    prune_compress_body<DT, M, EST, false, false, HI0, true>(g, n_groups, O, ldg, key0, key1, stream_id, vals, meta, nullptr, 0);
 }
 template <int DT, int M, int EST, bool NT>
 __global__ __launch_bounds__(256) void prune_producer_kernel(
@@ -1074,24 +1075,23 @@ static hipError_t launch_prune_t(const void *g, int64_t T, int64_t O, int64_t ld
     if (threads == 0) return hipSuccess;
     const int64_t blocks = (threads + 255) / 256;
     if (blocks > 0x7fffffffll) return hipErrorInvalidConfiguration;
-    if (dense)
-        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
     // The streaming kernels store through whole waves: they take the launches whose thread count is a multiple of 64.
-    // (MVUE 1:2 on bf16 is bound by its sixteen generator calls per thread, gains nothing from them and needs more
-    // registers in that form: it stays on the plain kernel.)
-    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34) && threads % 64 == 0)     // call indices (block / 4) below 2^32
-        hipLaunchKernelGGL(prune_compress_bf16_2of4_stream_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
-    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && (uint64_t)(T / 4) * (uint64_t)O <= ((uint64_t)1 << 34))
-        hipLaunchKernelGGL(prune_compress_bf16_2of4_kernel, dim3((unsigned)blocks), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
-    else if (threads % 64 == 0 && !(DT == NM_DT_BF16 && M == 2 && EST == 0))
-        hipLaunchKernelGGL((prune_compress_stream_kernel<DT, M, EST>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta);
-    else
-        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, false>), dim3((unsigned)blocks), dim3(256), 0, st,
-                           g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta, dense, ldd);
+    // hi0: every call index (block / 4, or block / 2 for approx-MVUE's two words per block) lies below 2^32
+    const bool hi0 = EST != 4 && (uint64_t)(T / M) * (uint64_t)O <= ((uint64_t)1 << (EST == 1 ? 33 : 34));
+    const dim3 grid((unsigned)blocks);
+#define NM_ARGS g, groups, O, ldg, (uint32_t)seed, (uint32_t)(seed >> 32), stream_id, vals, meta
+    if (dense)
+        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, true>), grid, dim3(256), 0, st, NM_ARGS, dense, ldd);
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && hi0 && threads % 64 == 0)
+        hipLaunchKernelGGL(prune_compress_bf16_2of4_stream_kernel, grid, dim3(256), 0, st, NM_ARGS);
+    else if (DT == NM_DT_BF16 && M == 4 && EST == 0 && hi0)
+        hipLaunchKernelGGL(prune_compress_bf16_2of4_kernel, grid, dim3(256), 0, st, NM_ARGS);
+    else if (threads % 64 == 0) {
+        if (hi0) hipLaunchKernelGGL((prune_compress_stream_kernel<DT, M, EST, true>), grid, dim3(256), 0, st, NM_ARGS);
+        else hipLaunchKernelGGL((prune_compress_stream_kernel<DT, M, EST, false>), grid, dim3(256), 0, st, NM_ARGS);
+    } else
+        hipLaunchKernelGGL((prune_compress_kernel<DT, M, EST, false>), grid, dim3(256), 0, st, NM_ARGS, dense, ldd);
+#undef NM_ARGS
     return hipGetLastError();
 }
 
