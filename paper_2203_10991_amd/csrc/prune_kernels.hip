@@ -419,7 +419,8 @@ __device__ __forceinline__ void prune_compress_body(
     // Streaming stores want whole lines per instruction: the wave's 8 KB go through its own 8 KB of LDS, written as
     // each thread holds them (eight 16-byte pieces at a stride of 128 bytes; piece c of lane l at slot 8l + (c ^ l%8),
     // which spreads the lanes over the banks) and read back so that store k covers bytes [1024 k, 1024 k + 1024).
-    // Only a full wave does this (the last wave of the launch may have lost lanes at the top).
+    // Every lane of the wave is here (the launcher sends only launches made of whole waves to the streaming kernels), and
+    // a wave's LDS operations execute in order, so the reads below see the writes above without a workgroup barrier.
     if constexpr (NT) {
         __shared__ __attribute__((aligned(1024))) char xs[4 * 8192];
         uint32_t tid = threadIdx.x;
