@@ -117,11 +117,12 @@ __device__ __forceinline__ void select_2of4(typename Key<DT>::type k1, typename 
     // Case 3: D = a1+a2+a3, partner of a4 is a1 / a2 / a3; expressed in the same chain.
     const float t = word_to_eps(word) * (case12 ? s + s : s123);
     const float c13 = u - a4;                                                   // counts in case 1 only
-    const float c14 = case12 ? 4.0f * a1 : a1;
+    const float f4 = case12 ? 4.0f : 1.0f;                                     // (one select for both scaled thresholds: the products are exact)
+    const float c14 = f4 * a1;
     const float d34 = s123 - a4;
     const float n23 = case1 ? (fmaf(2.0f, a2, a3) - a4) : (d34 + d34);
     const float c23 = 4.0f * a1 + n23;                                          // counts in cases 1-2 only
-    const float c24 = case12 ? 4.0f * s12 : s12;
+    const float c24 = f4 * s12;
 
     // the first threshold above t decides the pair: 13, 14, 23, 24, else 34 (case 3: 14, 24, else 34)
     const bool lt13 = case1 & (t < c13), lt14 = t < c14, lt23 = case12 & (t < c23), lt24 = t < c24;
