@@ -984,7 +984,24 @@ hipError_t launch_prune_q8_transposed(int dt, int est, const void *gT, int64_t T
 // ------------------------------------------------------------------------------------
 // nm_compress: dense n:m tensor -> group format.  Same thread tiling as above.
 // ------------------------------------------------------------------------------------
-template <int DT, int M>
+// The per-wave transpose of prune_compress_body as a function: every lane of the wave hands in the eight 16-byte pieces
+// it would have stored at vals + 128 n (n = its thread number in the launch); the wave stores them as eight streaming
+// stores of 1 KB of whole lines each.  xs: the workgroup's 32 KB of LDS.  Whole waves only.
+__device__ __forceinline__ void store_wave_pieces_stream(void *vals_, char *xs, const uint4 (&piece)[8])
+{
+    const uint32_t tid = threadIdx.x, lane = tid & 63u, wave_lds = (tid >> 6) * 8192;
+    const uint32_t wr = wave_lds + lane * 128 + (lane & 7) * 16;         // piece p at slot 8 lane + (p ^ lane % 8)
+#pragma unroll
+    for (int p = 0; p < 8; ++p) *(uint4 *)(xs + (wr ^ (uint32_t)(p * 16))) = piece[p];
+    __builtin_amdgcn_wave_barrier();
+    const int64_t n = (int64_t)blockIdx.x * 256 + tid;
+    char *wave_base = (char *)vals_ + (n - lane) * 128;
+    const uint32_t rd = wave_lds + (8 * (lane >> 3) + ((lane & 7) ^ (lane >> 3))) * 16;
+#pragma unroll
+    for (int k = 0; k < 8; ++k) store_stream(wave_base + (1024 * k + 16 * lane), *(const uint4 *)(xs + rd + 1024 * k));
+}
+
+template <int DT, int M, bool NT = false>
 __global__ __launch_bounds__(256) void compress_kernel(
     const void *__restrict__ d_, int64_t n_groups, int64_t O, int64_t ld,
     void *__restrict__ vals_, uint16_t *__restrict__ meta_, int32_t *__restrict__ bad)
@@ -999,16 +1016,19 @@ __global__ __launch_bounds__(256) void compress_kernel(
     const char *gp = (const char *)d_ + ((G * 16) * ld + col0) * ESZ;
     uint4 rows[16];
 #pragma unroll
-    for (int r = 0; r < 16; ++r) rows[r] = *(const uint4 *)(gp + (int64_t)r * ld * ESZ);
+    for (int r = 0; r < 16; ++r) rows[r] = NT ? load_stream(gp + (int64_t)r * ld * ESZ) : load_global(gp + (int64_t)r * ld * ESZ);
 
-    float kept[VEC][8];
+    constexpr int KW = DT == NM_DT_F32 ? 8 : 4;      // stored words per column: binary32 values, or bf16 pairs packed at once
+    uint32_t kept[VEC][KW];
     uint32_t md[VEC];
     int nbad = 0;
 #pragma unroll
-    for (int c = 0; c < VEC; ++c) {
-        md[c] = 0;
+    for (int c = 0; c < VEC; ++c) md[c] = 0;
+    // quad row by quad row (the rows of a finished one are dead), one quad at a time
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
+    for (int i = 0; i < 4; ++i) {
+#pragma unroll
+        for (int c = 0; c < VEC; ++c) {
             float x[4];
 #pragma unroll
             for (int p = 0; p < 4; ++p) x[p] = Row<DT>::get(rows[4 * i + p], c);
@@ -1016,10 +1036,15 @@ __global__ __launch_bounds__(256) void compress_kernel(
             if (M == 4) {
                 const uint32_t nz = (x[0] != 0.0f ? 1u : 0u) | (x[1] != 0.0f ? 2u : 0u) |
                                     (x[2] != 0.0f ? 4u : 0u) | (x[3] != 0.0f ? 8u : 0u);
+                // straight-line: fewer than two non-zeros are padded with the lowest zero positions (one if one is
+                // missing, two if both are)
                 uint32_t taken = nz;
-                if (__popc(taken) > 2) ++nbad;
-                if (__popc(taken) < 2) taken |= (~taken) & (uint32_t)(-(int)(~taken & 0xfu)) & 0xfu;   // lowest zero
-                if (__popc(taken) < 2) taken |= (~taken) & (uint32_t)(-(int)(~taken & 0xfu)) & 0xfu;
+                const int cnt = __popc(nz);
+                nbad += cnt > 2 ? 1 : 0;
+                const uint32_t z1 = ~taken & 0xfu;
+                taken |= cnt < 2 ? (z1 & (0u - z1)) : 0u;                  // lowest zero
+                const uint32_t z2 = ~taken & 0xfu;
+                taken |= cnt < 1 ? (z2 & (0u - z2)) : 0u;
                 p0 = (uint32_t)__ffs((int)taken) - 1u;
                 taken &= taken - 1u;
                 p1 = (uint32_t)__ffs((int)taken) - 1u;
@@ -1029,28 +1054,29 @@ __global__ __launch_bounds__(256) void compress_kernel(
                 p0 = (n1 & !n0) ? 1u : 0u;
                 p1 = (n3 & !n2) ? 3u : 2u;
             }
-            kept[c][2 * i] = p0 == 0 ? x[0] : p0 == 1 ? x[1] : p0 == 2 ? x[2] : x[3];
-            kept[c][2 * i + 1] = p1 == 0 ? x[0] : p1 == 1 ? x[1] : p1 == 2 ? x[2] : x[3];
+            // (two levels of selects on the position's bits: written as a chain of comparisons the compiler made branches of it)
+            const uint32_t u0 = __float_as_uint(x[0]), u1 = __float_as_uint(x[1]), u2 = __float_as_uint(x[2]), u3 = __float_as_uint(x[3]);
+            const uint32_t k0 = (p0 & 2u) ? ((p0 & 1u) ? u3 : u2) : ((p0 & 1u) ? u1 : u0);
+            const uint32_t k1 = (p1 & 2u) ? ((p1 & 1u) ? u3 : u2) : ((p1 & 1u) ? u1 : u0);
+            if constexpr (DT == NM_DT_F32) { kept[c][2 * i] = k0; kept[c][2 * i + 1] = k1; }
+            else kept[c][i] = (k0 >> 16) | (k1 & 0xffff0000u);        // values are bf16 already: the upper half is exact
             md[c] |= (p0 | (p1 << 2)) << (4 * i);
+            __builtin_amdgcn_sched_barrier(0);
         }
     }
-    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;
-    if (DT == NM_DT_F32) {
+    char *vp = (char *)vals_ + ((G * O + col0) * 8) * ESZ;            // = vals_ + 128 n
+    uint4 piece[8];                                                   // the thread's 128 bytes of vals
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {
-            ((float4 *)vp)[2 * c] = make_float4(kept[c][0], kept[c][1], kept[c][2], kept[c][3]);
-            ((float4 *)vp)[2 * c + 1] = make_float4(kept[c][4], kept[c][5], kept[c][6], kept[c][7]);
-        }
+    for (int c = 0; c < VEC; ++c)
+#pragma unroll
+        for (int j = 0; j < KW / 4; ++j)
+            piece[c * (KW / 4) + j] = make_uint4(kept[c][4 * j], kept[c][4 * j + 1], kept[c][4 * j + 2], kept[c][4 * j + 3]);
+    if constexpr (NT) {
+        __shared__ __attribute__((aligned(1024))) char xs[4 * 8192];
+        store_wave_pieces_stream(vals_, xs, piece);
     } else {
 #pragma unroll
-        for (int c = 0; c < VEC; ++c) {           // values are bf16 already: the upper half is exact
-            uint4 o;
-            o.x = (__float_as_uint(kept[c][0]) >> 16) | (__float_as_uint(kept[c][1]) & 0xffff0000u);
-            o.y = (__float_as_uint(kept[c][2]) >> 16) | (__float_as_uint(kept[c][3]) & 0xffff0000u);
-            o.z = (__float_as_uint(kept[c][4]) >> 16) | (__float_as_uint(kept[c][5]) & 0xffff0000u);
-            o.w = (__float_as_uint(kept[c][6]) >> 16) | (__float_as_uint(kept[c][7]) & 0xffff0000u);
-            ((uint4 *)vp)[c] = o;
-        }
+        for (int p = 0; p < 8; ++p) ((uint4 *)vp)[p] = piece[p];
     }
     uint16_t *mp = meta_ + (G * O + col0);
     if (VEC == 8) {
@@ -1143,8 +1169,12 @@ static hipError_t launch_compress_t(const void *d, int64_t T, int64_t O, int64_t
     const int64_t groups = T / 16, threads = groups * (O / Row<DT>::VEC);
     if (threads == 0) return hipSuccess;
     if ((threads + 255) / 256 > 0x7fffffffll) return hipErrorInvalidConfiguration;
-    hipLaunchKernelGGL((compress_kernel<DT, M>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
-                       d, groups, O, ld, vals, meta, bad);
+    if (threads % 64 == 0)          // whole waves: streaming loads, stores of whole lines through the per-wave transpose
+        hipLaunchKernelGGL((compress_kernel<DT, M, true>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           d, groups, O, ld, vals, meta, bad);
+    else
+        hipLaunchKernelGGL((compress_kernel<DT, M, false>), dim3((unsigned)((threads + 255) / 256)), dim3(256), 0, st,
+                           d, groups, O, ld, vals, meta, bad);
     return hipGetLastError();
 }
 
